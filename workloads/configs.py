@@ -1,0 +1,58 @@
+"""The five benchmark configurations (synthetic stand-ins shaped like the paper's workloads).
+
+Config 2 is shaped like the binary density-estimation sets / binarised 28x28
+digits of Sec. 4.1, config 3 like 28x28 grey images, config 4 like the 32x32x3
+street-number images and config 5 like a 64x64x3 crop of the face images of
+Sec. 4.2.  None of those datasets is used: every sample is drawn from a seeded
+mixture, see generate.py.
+"""
+BERNOULLI = 0
+GAUSSIAN = 1
+
+CONFIGS = [
+    dict(
+        name="cfg1_rat_d8_k4",
+        structure=dict(kind="rat", D=8, depth=3, R=2),
+        K=4, channels=1, family=BERNOULLI, B=64,
+        leaf_range=(0.1, 0.9),
+        data=dict(kind="bernoulli_iid", p=0.5),
+        mask=None,
+    ),
+    dict(
+        name="cfg2_rat_d784_k10",
+        structure=dict(kind="rat", D=784, depth=8, R=10),
+        K=10, channels=1, family=BERNOULLI, B=100,
+        leaf_range=(0.05, 0.95),
+        data=dict(kind="bernoulli_mixture", components=10, lo=0.05, hi=0.95),
+        mask=None,
+    ),
+    dict(
+        name="cfg3_pd_28x28_k16",
+        structure=dict(kind="pd", H=28, W=28, deltas=[7], axes=3),
+        K=16, channels=1, family=GAUSSIAN, B=256,
+        leaf_range=(0.0, 1.0),
+        data=dict(kind="gaussian_mixture", components=20, std=0.1),
+        mask=dict(kind="shared", observed_fraction=0.7),
+    ),
+    dict(
+        name="cfg4_pd_32x32x3_k40",
+        structure=dict(kind="pd", H=32, W=32, deltas=[8], axes=3),
+        K=40, channels=3, family=GAUSSIAN, B=128,
+        leaf_range=(0.0, 1.0),
+        data=dict(kind="gaussian_mixture", components=50, std=0.1),
+        mask=None,
+    ),
+    dict(
+        name="cfg5_pd_64x64x3_k20",
+        structure=dict(kind="pd", H=64, W=64, deltas=[16, 8], axes=3),
+        K=20, channels=3, family=GAUSSIAN, B=64,
+        leaf_range=(0.0, 1.0),
+        data=dict(kind="gaussian_mixture", components=100, std=0.1),
+        mask=dict(kind="shared", observed_fraction=0.5),
+    ),
+]
+
+
+def get_config(i):
+    """i is 1-based, as in the configuration list."""
+    return CONFIGS[i - 1]
