@@ -1,0 +1,197 @@
+/*
+ * einet.h - C ABI of libeinet: Einsum Networks (arxiv 2004.06231) on one MI355X.
+ *
+ * The library evaluates a vectorised probabilistic circuit layer by layer in
+ * the log domain (Sec. 3.2-3.4 of the paper) and accumulates the expected
+ * sufficient statistics of EM (Sec. 3.5).  Every step runs in hand-written
+ * HIP kernels for gfx950; the library allocates no device memory: the caller
+ * asks for the sizes, allocates, and binds the buffers.
+ *
+ * Conventions
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP
+ *     device memory on the current device; the comment of every argument
+ *     says which.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Compute calls only enqueue work on it and return; they never
+ *     synchronise.  Calls on one handle must be issued in order on one
+ *     stream (they share the handle's workspace).
+ *   - Every function returning int returns EINET_OK (0) or a negative
+ *     EINET_ERR_* code; nothing throws or aborts across the boundary.
+ *     einet_last_error() gives a human-readable reason.
+ *   - Vector length: every region holds K entries, except the root region,
+ *     which holds one (K_out = 1).
+ *
+ * Structure numbering (fixed so that an independent implementation builds the
+ * identical graph from the same arguments):
+ *   Random binary trees (Sec. 4.1): region 0 is the root over variables
+ *   0..D-1.  Replica r is a complete binary tree of split depth `depth`; its
+ *   node with heap index h (root 1, children 2h, 2h+1), h >= 2, is region
+ *   1 + r*(2^(depth+1)-2) + (h-2); the split of heap node h < 2^depth is
+ *   partition r*(2^depth-1) + (h-1).  A scope (sorted ascending, n entries) is
+ *   shuffled by Fisher-Yates, t = n-1..1: swap a[t], a[u mod (t+1)], u drawn
+ *   from SplitMix64 started at state seed ^ (0xD1B54A32D192ED03*(r+1)) ^
+ *   (0x8CB92BA72F3D8DD7*h) (64-bit wrap); the first n/2 entries (sorted) form
+ *   the left child, the others the right child.  Leaves of replica r use leaf
+ *   parameter replica r.
+ *   Poon-Domingos (Sec. 4.2): variable y*width + x is pixel (y, x); regions
+ *   are rectangles, region 0 the image; rectangles are processed in creation
+ *   order; the step of a rectangle is the first entry of `deltas` that cuts
+ *   it on an allowed axis; cuts along y (ascending) come before cuts along x;
+ *   each cut is one partition (top or left part = left child); a rectangle
+ *   gets the next region number when first seen (left before right).  Leaf
+ *   regions take, in region order, the smallest replica index whose earlier
+ *   leaves do not overlap them (Sec. 3.4).
+ *
+ * Flat parameter buffer (float32, n_params entries), in this order:
+ *   W   for each partition n in order: [K_out(parent)][K][K], last index (the
+ *       right child's entry j) fastest; non-negative, each [K][K] block sums
+ *       to one (Eq. 2)
+ *   v   for each region with C_s > 1 partitions, in region order:
+ *       [K_out][C_s] mixing weights, private per entry k (App. B)
+ *   phi [D][channels][R][T][K] expectation parameters of the leaves
+ *       (Sec. 3.4): Bernoulli T=1: p; Gaussian T=2: (E[x], E[x^2])
+ * Flat statistics buffer (float32, n_stats entries):
+ *   Nw, Nv, num with the shapes of W, v, phi, then den [D][R][K] and
+ *   tot [D][R][K]  (posterior mass of a leaf entry over observed samples /
+ *   over all samples).
+ */
+#ifndef EINET_H
+#define EINET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct einet einet_t;
+
+enum {
+    EINET_OK = 0,
+    EINET_ERR_INVALID_ARG = -1,
+    EINET_ERR_BAD_STRUCTURE = -2,
+    EINET_ERR_NOT_BOUND = -3,
+    EINET_ERR_BATCH_TOO_LARGE = -4,
+    EINET_ERR_HIP = -5
+};
+
+enum { EINET_STRUCTURE_RAT = 0, EINET_STRUCTURE_PD = 1 };
+enum { EINET_LEAF_BERNOULLI = 0, EINET_LEAF_GAUSSIAN = 1 };
+enum { EINET_MASK_NONE = 0, EINET_MASK_SHARED = 1, EINET_MASK_PER_SAMPLE = 2 };
+enum { EINET_AXIS_Y = 1, EINET_AXIS_X = 2 };
+#define EINET_MAX_DELTAS 8
+
+/* Description of a model; plain data, read only during einet_create. */
+typedef struct einet_spec {
+    int32_t structure;     /* EINET_STRUCTURE_* */
+    int32_t K;             /* entries per sum / leaf vector (Sec. 3.1), 1..64 */
+    int32_t channels;      /* values per variable; the leaf factorises over them (Sec. 4.2) */
+    int32_t leaf_family;   /* EINET_LEAF_* */
+    int32_t max_batch;     /* largest B any later call will pass */
+    /* random binary trees */
+    int32_t num_vars;      /* D */
+    int32_t depth;         /* split depth, 2^depth leaves per replica */
+    int32_t num_replica;   /* R trees mixed at the root */
+    uint64_t seed;
+    /* Poon-Domingos */
+    int32_t height, width;
+    int32_t num_deltas;    /* 1..EINET_MAX_DELTAS */
+    int32_t deltas[EINET_MAX_DELTAS];
+    int32_t axes;          /* EINET_AXIS_Y | EINET_AXIS_X; X alone = vertical cuts only */
+} einet_spec;
+
+/* Read-only view of the compiled structure; all pointers are host memory
+ * owned by the handle and valid until einet_destroy. */
+typedef struct einet_structure_view {
+    int32_t num_vars, num_regions, num_partitions, num_replica;
+    int32_t num_layers;               /* einsum layers (= product layers of Algorithm 1) */
+    int32_t K, channels, num_suff_stats;
+    const int32_t* scope_ptr;         /* [num_regions+1] CSR into scope_var */
+    const int32_t* scope_var;         /* variables of each region, ascending */
+    const int32_t* region_replica;    /* [num_regions] replica of a leaf region, -1 otherwise */
+    const int32_t* partition;         /* [num_partitions][3] = parent region, left region, right region */
+    const int32_t* layer_ptr;         /* [num_layers+1] CSR into layer_partition, bottom layer first */
+    const int32_t* layer_partition;   /* partitions of each einsum layer, ascending */
+    const int64_t* w_offset;          /* [num_partitions] offset (floats) of W[n] in the parameter buffer */
+    const int64_t* v_offset;          /* [num_regions] offset of v[s], -1 if the region has < 2 partitions */
+    int64_t phi_offset;               /* offset of phi in the parameter buffer (= of num in the statistics) */
+    int64_t den_offset, tot_offset;   /* offsets in the statistics buffer */
+} einet_structure_view;
+
+/* Builds the region graph (Sec. 3.1; generators of Sec. 4.1 / 4.2), assigns
+ * leaf replicas (Sec. 3.4), orders it in topological layers (Algorithm 1) and
+ * splits sums with several children into simple sums plus a mixing layer
+ * (App. B).  Host work only.  spec: host.  *out receives a handle owned by the
+ * library (release with einet_destroy).  Errors: EINET_ERR_INVALID_ARG for
+ * out-of-range fields, EINET_ERR_BAD_STRUCTURE when the structure cannot be
+ * built (a one-variable scope would have to split; no delta cuts the image). */
+int einet_create(const einet_spec* spec, einet_t** out);
+
+/* Frees the handle and its host tables.  Never touches caller buffers. */
+void einet_destroy(einet_t* h);
+
+/* Reason of the last error on this handle (or of the last failed
+ * einet_create when h is NULL).  Host string owned by the library. */
+const char* einet_last_error(const einet_t* h);
+
+/* Sizes the caller must allocate on the device: n_params and n_stats in
+ * float32 elements, workspace in bytes (index tables, derived leaf constants,
+ * activation and posterior arenas for max_batch samples).  All outputs: host. */
+int einet_sizes(const einet_t* h, size_t* n_params, size_t* n_stats, size_t* workspace_bytes);
+
+/* Fills *view (host) with pointers into the handle's host tables. */
+int einet_structure(const einet_t* h, einet_structure_view* view);
+
+/* Registers the caller's device buffers (params: n_params floats, stats:
+ * n_stats floats, workspace: workspace_bytes, 256-byte aligned) and uploads
+ * the index tables into the workspace on `stream`, synchronising once.  The
+ * buffers stay owned by the caller and must outlive every later call.  The
+ * parameter buffer may be uninitialised at this point; call einet_refresh
+ * after writing it. */
+int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_dev, void* stream);
+
+/* Recomputes what the kernels derive from the parameters (per leaf entry:
+ * log p, log(1-p), or mean, -1/(2 var), -log(2 pi var)/2; Sec. 3.4) after the
+ * caller has written the parameter buffer.  einet_em_update does it itself. */
+int einet_refresh(einet_t* h, void* stream);
+
+/* log P(x) per sample: leaf layer (Sec. 3.4), einsum layers with the
+ * log-einsum-exp stabilisation (Eq. 4-5), mixing layers (App. B).
+ *   x_dev     device, [B][D][channels] float32 (Bernoulli: 0.0 / 1.0)
+ *   mask_dev  device uint8, 1 = observed, 0 = integrated out (a marginalised
+ *             variable's leaf factor is 1; Sec. 2): NULL with EINET_MASK_NONE,
+ *             [D] with EINET_MASK_SHARED, [B][D] with EINET_MASK_PER_SAMPLE
+ *   logp_dev  device, [B] float32, written
+ * The conditional of Eq. 1 is einet_logp(mask = q|e) - einet_logp(mask = e).
+ * Errors: EINET_ERR_NOT_BOUND, EINET_ERR_BATCH_TOO_LARGE (B > max_batch),
+ * EINET_ERR_INVALID_ARG (B < 1, bad mask_mode, NULL pointers), EINET_ERR_HIP. */
+int einet_logp(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int B,
+               float* logp_dev, void* stream);
+
+/* E-step on one batch (Eq. 6): forward pass as einet_logp, then the top-down
+ * pass that yields n = w * dlogP/dw for every sum weight and the posterior
+ * p = dlogP/dlogL of every leaf entry, summed over the batch and ADDED to the
+ * bound statistics buffer (p*T(x) into num, p over observed samples into den,
+ * p over all samples into tot).  Batch reductions use no atomics: results are
+ * bit-reproducible.  logp_dev may be NULL. */
+int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int B,
+                        float* logp_dev, void* stream);
+
+/* M-step (Eq. 7) blended with step size `step` in (0,1] (Eq. 8-9):
+ *   weights: hat = Nw / sum_ij Nw per (n,k) (kept if the sum is 0), floored at
+ *            w_floor and renormalised, w <- (1-step) w + step hat; v likewise;
+ *   leaves : hat = (num + (tot-den) phi) / tot (kept if tot is 0; equals
+ *            num/den when nothing was masked), phi <- (1-step) phi + step hat;
+ *            Bernoulli p clipped to [1e-6, 1-1e-6]; Gaussian variance
+ *            E[x^2]-E[x]^2 projected to [min_var, max_var] (Sec. 4.2).
+ * Zeroes the statistics and refreshes the derived leaf constants. */
+int einet_em_update(einet_t* h, float step, float min_var, float max_var, float w_floor, void* stream);
+
+/* Zeroes the statistics buffer. */
+int einet_em_reset(einet_t* h, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EINET_H */

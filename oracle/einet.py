@@ -311,3 +311,17 @@ class OracleEiNet:
         parts += [stats["Nv"][s].ravel() for s in sorted(stats["Nv"])]
         parts += [stats["num"].ravel(), stats["den"].ravel(), stats["tot"].ravel()]
         return np.concatenate(parts)
+
+    def stats_from_flat(self, flat):
+        """Inverse of stats_to_flat."""
+        flat = np.asarray(flat, dtype=np.float64)
+        lay, st = self.layout, self.zero_stats()
+        assert flat.size == lay.n_stats
+        for n, w in enumerate(self.W):
+            st["Nw"][n] = flat[lay.w_off[n]: lay.w_off[n] + w.size].reshape(w.shape).copy()
+        for s, v in self.v.items():
+            st["Nv"][s] = flat[lay.v_off[s]: lay.v_off[s] + v.size].reshape(v.shape).copy()
+        st["num"] = flat[lay.phi_off: lay.n_params].reshape(self.phi.shape).copy()
+        st["den"] = flat[lay.den_off: lay.tot_off].reshape(st["den"].shape).copy()
+        st["tot"] = flat[lay.tot_off:].reshape(st["tot"].shape).copy()
+        return st

@@ -1,0 +1,270 @@
+"""ctypes binding of include/einet.h.  Argument marshalling only."""
+import ctypes as C
+import math
+import os
+
+import numpy as np
+
+from .build import LIB_PATH
+
+BERNOULLI, GAUSSIAN = 0, 1
+STRUCTURE_RAT, STRUCTURE_PD = 0, 1
+MASK_NONE, MASK_SHARED, MASK_PER_SAMPLE = 0, 1, 2
+MAX_DELTAS = 8
+
+EXPORTED_SYMBOLS = [
+    "einet_create", "einet_destroy", "einet_last_error", "einet_sizes", "einet_structure", "einet_bind",
+    "einet_refresh", "einet_logp", "einet_em_accumulate", "einet_em_update", "einet_em_reset",
+]
+
+
+class EinetError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"libeinet error {code}: {message}")
+        self.code = code
+
+
+class _Spec(C.Structure):
+    _fields_ = [("structure", C.c_int32), ("K", C.c_int32), ("channels", C.c_int32), ("leaf_family", C.c_int32),
+                ("max_batch", C.c_int32), ("num_vars", C.c_int32), ("depth", C.c_int32), ("num_replica", C.c_int32),
+                ("seed", C.c_uint64), ("height", C.c_int32), ("width", C.c_int32), ("num_deltas", C.c_int32),
+                ("deltas", C.c_int32 * MAX_DELTAS), ("axes", C.c_int32)]
+
+
+class _View(C.Structure):
+    _fields_ = [("num_vars", C.c_int32), ("num_regions", C.c_int32), ("num_partitions", C.c_int32),
+                ("num_replica", C.c_int32), ("num_layers", C.c_int32), ("K", C.c_int32), ("channels", C.c_int32),
+                ("num_suff_stats", C.c_int32),
+                ("scope_ptr", C.POINTER(C.c_int32)), ("scope_var", C.POINTER(C.c_int32)),
+                ("region_replica", C.POINTER(C.c_int32)), ("partition", C.POINTER(C.c_int32)),
+                ("layer_ptr", C.POINTER(C.c_int32)), ("layer_partition", C.POINTER(C.c_int32)),
+                ("w_offset", C.POINTER(C.c_int64)), ("v_offset", C.POINTER(C.c_int64)),
+                ("phi_offset", C.c_int64), ("den_offset", C.c_int64), ("tot_offset", C.c_int64)]
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libeinet.so (built in-tree by build.build_library); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built; run __graft_entry__.build() first (no CPU fallback exists)")
+    # torch ships its own HIP runtime; load it first so that the library resolves libamdhip64 to the same
+    # copy and shares torch's device context, streams and allocations
+    import torch  # noqa: F401
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, f32 = C.c_void_p, C.c_int, C.c_float
+    lib.einet_create.argtypes = [C.POINTER(_Spec), C.POINTER(vp)]
+    lib.einet_destroy.argtypes = [vp]
+    lib.einet_destroy.restype = None
+    lib.einet_last_error.argtypes = [vp]
+    lib.einet_last_error.restype = C.c_char_p
+    lib.einet_sizes.argtypes = [vp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+    lib.einet_structure.argtypes = [vp, C.POINTER(_View)]
+    lib.einet_bind.argtypes = [vp, vp, vp, vp, vp]
+    lib.einet_refresh.argtypes = [vp, vp]
+    lib.einet_logp.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.einet_em_accumulate.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.einet_em_update.argtypes = [vp, f32, f32, f32, f32, vp]
+    lib.einet_em_reset.argtypes = [vp, vp]
+    _lib = lib
+    return lib
+
+
+def _make_spec(spec, K, channels, family, max_batch, seed):
+    s = _Spec()
+    s.K, s.channels, s.leaf_family, s.max_batch = K, channels, family, max_batch
+    if spec["kind"] == "rat":
+        s.structure = STRUCTURE_RAT
+        s.num_vars, s.depth, s.num_replica, s.seed = spec["D"], spec["depth"], spec["R"], seed
+    elif spec["kind"] == "pd":
+        s.structure = STRUCTURE_PD
+        s.height, s.width = spec["H"], spec["W"]
+        deltas = list(spec["deltas"])
+        s.num_deltas = len(deltas)
+        for i, d in enumerate(deltas[:MAX_DELTAS]):
+            s.deltas[i] = d
+        s.axes = spec.get("axes", 3)
+    else:
+        raise ValueError(spec["kind"])
+    return s
+
+
+class EiNet:
+    """A model handle plus the torch tensors that back its device buffers."""
+
+    def __init__(self, structure, K, channels, family, max_batch, seed=0):
+        self._lib = load_library()
+        self._h = C.c_void_p()
+        spec = _make_spec(structure, K, channels, family, max_batch, seed)
+        rc = self._lib.einet_create(C.byref(spec), C.byref(self._h))
+        if rc != 0:
+            raise EinetError(rc, self._lib.einet_last_error(None).decode())
+        n_p, n_s, ws = C.c_size_t(), C.c_size_t(), C.c_size_t()
+        self._check(self._lib.einet_sizes(self._h, C.byref(n_p), C.byref(n_s), C.byref(ws)))
+        self.n_params, self.n_stats, self.workspace_bytes = n_p.value, n_s.value, ws.value
+        self.K, self.channels, self.family, self.max_batch = K, channels, family, max_batch
+        self.params = self.stats = self.workspace = None
+        self._structure = None
+
+    def _check(self, rc):
+        if rc != 0:
+            raise EinetError(rc, self._lib.einet_last_error(self._h).decode())
+
+    def close(self):
+        if self._h:
+            self._lib.einet_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ------------------------------------------------------------- structure (host only)
+    def structure(self):
+        if self._structure is not None:
+            return self._structure
+        v = _View()
+        self._check(self._lib.einet_structure(self._h, C.byref(v)))
+
+        def arr(ptr, n, dtype):
+            return np.ctypeslib.as_array(ptr, shape=(n,)).astype(dtype).copy() if n else np.zeros(0, dtype)
+
+        scope_ptr = arr(v.scope_ptr, v.num_regions + 1, np.int64)
+        layer_ptr = arr(v.layer_ptr, v.num_layers + 1, np.int64)
+        self._structure = dict(
+            num_vars=v.num_vars, num_regions=v.num_regions, num_partitions=v.num_partitions,
+            num_replica=v.num_replica, num_layers=v.num_layers, K=v.K, channels=v.channels, T=v.num_suff_stats,
+            scope_ptr=scope_ptr, scope_var=arr(v.scope_var, int(scope_ptr[-1]), np.int64),
+            region_replica=arr(v.region_replica, v.num_regions, np.int64),
+            partition=arr(v.partition, 3 * v.num_partitions, np.int64).reshape(-1, 3),
+            layer_ptr=layer_ptr, layer_partition=arr(v.layer_partition, int(layer_ptr[-1]), np.int64),
+            w_offset=arr(v.w_offset, v.num_partitions, np.int64), v_offset=arr(v.v_offset, v.num_regions, np.int64),
+            phi_offset=v.phi_offset, den_offset=v.den_offset, tot_offset=v.tot_offset)
+        return self._structure
+
+    def weight_blocks(self):
+        """(offset, rows, row_len) of every normalised weight block, for the seeded parameter generator."""
+        st = self.structure()
+        n_parts = np.bincount(st["partition"][:, 0], minlength=st["num_regions"])
+        blocks = []
+        for n in range(st["num_partitions"]):
+            parent = st["partition"][n, 0]
+            blocks.append((int(st["w_offset"][n]), 1 if parent == 0 else self.K, self.K * self.K))
+        for s in range(st["num_regions"]):
+            if st["v_offset"][s] >= 0:
+                blocks.append((int(st["v_offset"][s]), 1 if s == 0 else self.K, int(n_parts[s])))
+        return blocks
+
+    # ------------------------------------------------------------- device side
+    def bind(self, device="cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: libeinet has no CPU path")
+        self._torch = torch
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.params = torch.zeros(self.n_params, dtype=torch.float32, device=self.device)
+        self.stats = torch.zeros(self.n_stats, dtype=torch.float32, device=self.device)
+        self.workspace = torch.zeros(self.workspace_bytes, dtype=torch.uint8, device=self.device)
+        self._check(self._lib.einet_bind(self._h, self.params.data_ptr(), self.stats.data_ptr(),
+                                         self.workspace.data_ptr(), self._stream()))
+        return self
+
+    def _stream(self):
+        return C.c_void_p(self._torch.cuda.current_stream().cuda_stream)
+
+    def set_params(self, flat):
+        torch = self._torch
+        t = torch.as_tensor(np.asarray(flat, dtype=np.float32)) if not torch.is_tensor(flat) else flat
+        assert t.numel() == self.n_params
+        self.params.copy_(t.to(self.device, non_blocking=False))
+        self.refresh()
+
+    def refresh(self):
+        self._check(self._lib.einet_refresh(self._h, self._stream()))
+
+    def _mask_args(self, mask, B):
+        if mask is None:
+            return None, MASK_NONE
+        assert mask.dtype == self._torch.uint8 and mask.is_cuda and mask.is_contiguous()
+        if mask.dim() == 1:
+            return C.c_void_p(mask.data_ptr()), MASK_SHARED
+        assert mask.shape[0] == B
+        return C.c_void_p(mask.data_ptr()), MASK_PER_SAMPLE
+
+    def logp(self, x, mask=None, out=None):
+        """x: cuda float32 [B, D, channels]; mask: cuda uint8 [D] or [B, D] (1 = observed) or None."""
+        torch = self._torch
+        assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous() and x.dim() == 3
+        B = x.shape[0]
+        if out is None:
+            out = torch.empty(B, dtype=torch.float32, device=self.device)
+        m, mode = self._mask_args(mask, B)
+        self._check(self._lib.einet_logp(self._h, x.data_ptr(), m, mode, B, out.data_ptr(), self._stream()))
+        return out
+
+    def em_accumulate(self, x, mask=None, logp=None):
+        torch = self._torch
+        assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous() and x.dim() == 3
+        B = x.shape[0]
+        m, mode = self._mask_args(mask, B)
+        lp = None if logp is None else C.c_void_p(logp.data_ptr())
+        self._check(self._lib.einet_em_accumulate(self._h, x.data_ptr(), m, mode, B, lp, self._stream()))
+        return logp
+
+    def em_update(self, step=1.0, min_var=0.0, max_var=math.inf, w_floor=0.0):
+        self._check(self._lib.einet_em_update(self._h, step, min_var, max_var, w_floor, self._stream()))
+
+    def em_reset(self):
+        self._check(self._lib.einet_em_reset(self._h, self._stream()))
+
+
+# The C names, for callers who prefer the flat interface.
+def einet_create(structure, K, channels, family, max_batch, seed=0):
+    return EiNet(structure, K, channels, family, max_batch, seed)
+
+
+def einet_destroy(m):
+    m.close()
+
+
+def einet_last_error(m):
+    return load_library().einet_last_error(m._h if m is not None else None).decode()
+
+
+def einet_sizes(m):
+    return m.n_params, m.n_stats, m.workspace_bytes
+
+
+def einet_structure(m):
+    return m.structure()
+
+
+def einet_bind(m, device="cuda:0"):
+    return m.bind(device)
+
+
+def einet_refresh(m):
+    m.refresh()
+
+
+def einet_logp(m, x, mask=None, out=None):
+    return m.logp(x, mask, out)
+
+
+def einet_em_accumulate(m, x, mask=None, logp=None):
+    return m.em_accumulate(x, mask, logp)
+
+
+def einet_em_update(m, step=1.0, min_var=0.0, max_var=math.inf, w_floor=0.0):
+    m.em_update(step, min_var, max_var, w_floor)
+
+
+def einet_em_reset(m):
+    m.em_reset()

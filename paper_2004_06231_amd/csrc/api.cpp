@@ -1,0 +1,315 @@
+// C ABI of libeinet (see include/einet.h): argument checks, workspace layout,
+// and the per-layer launch sequence.  No device memory is allocated here.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/einet.h"
+#include "kernels.hpp"
+#include "structure.hpp"
+
+using namespace einet_impl;
+
+struct einet {
+    einet_spec spec{};
+    RegionGraph graph;
+    Plan plan;
+    mutable std::string err;
+
+    // workspace layout (bytes from the start of the workspace)
+    std::vector<int32_t> blob;      // all index tables, concatenated
+    size_t off_theta = 0, off_A = 0, off_G = 0, off_Gp = 0, ws_bytes = 0;
+    struct TableOffsets {
+        size_t ein_left, ein_right, ein_out, ein_kout, ein_woff, mix_node, mix_kout, mix_cptr, mix_child, mix_voff,
+            leaf_node, leaf_replica, leaf_sptr, leaf_var, lv_leaf, lv_var, rb_node, rb_kout, rb_mix, rb_pptr,
+            rb_pslot, row_off, row_len;
+    } to{};
+
+    bool bound = false;
+    float* params = nullptr;
+    float* stats = nullptr;
+    char* ws = nullptr;
+    DevTables dt{};
+};
+
+namespace {
+
+std::string g_create_error;
+
+size_t append(std::vector<int32_t>& blob, const std::vector<int32_t>& v) {
+    while (blob.size() % 64) blob.push_back(0);   // 256-byte alignment of every table
+    size_t off = blob.size();
+    blob.insert(blob.end(), v.begin(), v.end());
+    if (v.empty()) blob.push_back(0);
+    return off;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+int fail(const einet_t* h, int code, const std::string& msg) {
+    if (h) h->err = msg;
+    else g_create_error = msg;
+    return code;
+}
+
+int check_hip(const einet_t* h, const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(h, EINET_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+    return EINET_OK;
+}
+
+Dims dims_of(const einet_t* h, int B) {
+    Dims d;
+    d.B = B;
+    d.D = h->graph.num_vars;
+    d.C = h->plan.C;
+    d.R = h->graph.num_replica;
+    d.K = h->plan.K;
+    d.T = h->plan.T;
+    d.TD = h->plan.TD;
+    d.family = h->plan.family;
+    return d;
+}
+
+int check_batch_args(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, int B) {
+    if (!h) return EINET_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
+    if (B < 1) return fail(h, EINET_ERR_INVALID_ARG, "B must be at least 1");
+    if (B > h->spec.max_batch) return fail(h, EINET_ERR_BATCH_TOO_LARGE, "B exceeds max_batch given to einet_create");
+    if (!x) return fail(h, EINET_ERR_INVALID_ARG, "x_dev is NULL");
+    if (mask_mode != EINET_MASK_NONE && mask_mode != EINET_MASK_SHARED && mask_mode != EINET_MASK_PER_SAMPLE)
+        return fail(h, EINET_ERR_INVALID_ARG, "unknown mask_mode");
+    if ((mask_mode != EINET_MASK_NONE) != (mask != nullptr))
+        return fail(h, EINET_ERR_INVALID_ARG, "mask_dev must be NULL exactly when mask_mode is EINET_MASK_NONE");
+    return EINET_OK;
+}
+
+// Leaf layer, then einsum (+ mixing) layers bottom-up; fills the arena A.
+void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, const Dims& d, hipStream_t s) {
+    const Plan& p = h->plan;
+    float* A = reinterpret_cast<float*>(h->ws + h->off_A);
+    const float* theta = reinterpret_cast<const float*>(h->ws + h->off_theta);
+    launch_leaf_forward(h->dt, (int)p.leaf_node.size(), x, mask, mask_mode, theta, A, d, s);
+    for (int l = 0; l < p.num_layers; ++l) {
+        launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params, A, d,
+                              s);
+        launch_mixing_forward(h->dt, p.mix_layer_ptr[l], p.mix_layer_ptr[l + 1] - p.mix_layer_ptr[l], h->params, A, d,
+                              s);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int einet_create(const einet_spec* spec, einet_t** out) {
+    if (!spec || !out) return fail(nullptr, EINET_ERR_INVALID_ARG, "spec or out is NULL");
+    *out = nullptr;
+    if (spec->K < 1 || spec->K > 64) return fail(nullptr, EINET_ERR_INVALID_ARG, "K must be in 1..64");
+    if (spec->channels < 1) return fail(nullptr, EINET_ERR_INVALID_ARG, "channels must be at least 1");
+    if (spec->max_batch < 1) return fail(nullptr, EINET_ERR_INVALID_ARG, "max_batch must be at least 1");
+    if (spec->leaf_family != EINET_LEAF_BERNOULLI && spec->leaf_family != EINET_LEAF_GAUSSIAN)
+        return fail(nullptr, EINET_ERR_INVALID_ARG, "unknown leaf_family");
+    einet_t* h = new einet();
+    h->spec = *spec;
+    std::string err;
+    bool ok = false;
+    if (spec->structure == EINET_STRUCTURE_RAT) {
+        if (spec->num_vars < 2 || spec->depth < 1 || spec->depth > 24 || spec->num_replica < 1) {
+            delete h;
+            return fail(nullptr, EINET_ERR_INVALID_ARG, "random binary trees need num_vars >= 2, depth in 1..24, num_replica >= 1");
+        }
+        ok = build_rat(spec->num_vars, spec->depth, spec->num_replica, spec->seed, h->graph, err);
+    } else if (spec->structure == EINET_STRUCTURE_PD) {
+        bool good = spec->height >= 1 && spec->width >= 1 && spec->num_deltas >= 1 &&
+                    spec->num_deltas <= EINET_MAX_DELTAS && (spec->axes & 3) && !(spec->axes & ~3);
+        for (int i = 0; good && i < spec->num_deltas; ++i) good = spec->deltas[i] >= 1;
+        if (!good) {
+            delete h;
+            return fail(nullptr, EINET_ERR_INVALID_ARG, "Poon-Domingos needs height, width >= 1, 1..8 positive deltas, axes in 1..3");
+        }
+        ok = build_pd(spec->height, spec->width, spec->deltas, spec->num_deltas, spec->axes, h->graph, err);
+    } else {
+        delete h;
+        return fail(nullptr, EINET_ERR_INVALID_ARG, "unknown structure kind");
+    }
+    if (ok) ok = compile_plan(h->graph, spec->K, spec->channels, spec->leaf_family, h->plan, err);
+    if (!ok) {
+        delete h;
+        return fail(nullptr, EINET_ERR_BAD_STRUCTURE, err);
+    }
+    // workspace layout
+    const Plan& p = h->plan;
+    auto& b = h->blob;
+    auto& t = h->to;
+    t.ein_left = append(b, p.ein_left);
+    t.ein_right = append(b, p.ein_right);
+    t.ein_out = append(b, p.ein_out);
+    t.ein_kout = append(b, p.ein_kout);
+    t.ein_woff = append(b, p.ein_woff);
+    t.mix_node = append(b, p.mix_node);
+    t.mix_kout = append(b, p.mix_kout);
+    t.mix_cptr = append(b, p.mix_cptr);
+    t.mix_child = append(b, p.mix_child);
+    t.mix_voff = append(b, p.mix_voff);
+    t.leaf_node = append(b, p.leaf_node);
+    t.leaf_replica = append(b, p.leaf_replica);
+    t.leaf_sptr = append(b, p.leaf_sptr);
+    t.leaf_var = append(b, p.leaf_var);
+    t.lv_leaf = append(b, p.lv_leaf);
+    t.lv_var = append(b, p.lv_var);
+    t.rb_node = append(b, p.rb_node);
+    t.rb_kout = append(b, p.rb_kout);
+    t.rb_mix = append(b, p.rb_mix);
+    t.rb_pptr = append(b, p.rb_pptr);
+    t.rb_pslot = append(b, p.rb_pslot);
+    t.row_off = append(b, p.row_off);
+    t.row_len = append(b, p.row_len);
+    const size_t K = p.K, mb = spec->max_batch;
+    size_t off = align256(b.size() * sizeof(int32_t));
+    h->off_theta = off;
+    off = align256(off + sizeof(float) * size_t(h->graph.num_vars) * p.C * h->graph.num_replica * p.TD * K);
+    h->off_A = off;
+    off = align256(off + sizeof(float) * size_t(p.num_nodes) * mb * K);
+    h->off_G = off;
+    off = align256(off + sizeof(float) * size_t(p.num_nodes) * mb * K);
+    h->off_Gp = off;
+    off = align256(off + sizeof(float) * 2 * p.ein_left.size() * mb * K);
+    h->ws_bytes = off;
+    *out = h;
+    return EINET_OK;
+}
+
+void einet_destroy(einet_t* h) { delete h; }
+
+const char* einet_last_error(const einet_t* h) { return h ? h->err.c_str() : g_create_error.c_str(); }
+
+int einet_sizes(const einet_t* h, size_t* n_params, size_t* n_stats, size_t* workspace_bytes) {
+    if (!h) return EINET_ERR_INVALID_ARG;
+    if (n_params) *n_params = (size_t)h->plan.n_params;
+    if (n_stats) *n_stats = (size_t)h->plan.n_stats;
+    if (workspace_bytes) *workspace_bytes = h->ws_bytes;
+    return EINET_OK;
+}
+
+int einet_structure(const einet_t* h, einet_structure_view* v) {
+    if (!h || !v) return EINET_ERR_INVALID_ARG;
+    const Plan& p = h->plan;
+    v->num_vars = h->graph.num_vars;
+    v->num_regions = (int32_t)h->graph.scope.size();
+    v->num_partitions = (int32_t)h->graph.partition.size();
+    v->num_replica = h->graph.num_replica;
+    v->num_layers = p.num_layers;
+    v->K = p.K;
+    v->channels = p.C;
+    v->num_suff_stats = p.T;
+    v->scope_ptr = p.scope_ptr.data();
+    v->scope_var = p.scope_var.data();
+    v->region_replica = h->graph.replica.data();
+    v->partition = p.partition_flat.data();
+    v->layer_ptr = p.layer_ptr.data();
+    v->layer_partition = p.layer_partition.data();
+    v->w_offset = p.w_offset.data();
+    v->v_offset = p.v_offset.data();
+    v->phi_offset = p.phi_offset;
+    v->den_offset = p.den_offset;
+    v->tot_offset = p.tot_offset;
+    return EINET_OK;
+}
+
+int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_dev, void* stream) {
+    if (!h) return EINET_ERR_INVALID_ARG;
+    if (!params_dev || !stats_dev || !workspace_dev) return fail(h, EINET_ERR_INVALID_ARG, "NULL device buffer");
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % 256) return fail(h, EINET_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(workspace_dev, h->blob.data(), h->blob.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(h, EINET_ERR_HIP, std::string("uploading index tables: ") + hipGetErrorString(e));
+    h->params = params_dev;
+    h->stats = stats_dev;
+    h->ws = static_cast<char*>(workspace_dev);
+    const int32_t* base = reinterpret_cast<const int32_t*>(h->ws);
+    const auto& t = h->to;
+    h->dt = DevTables{base + t.ein_left,  base + t.ein_right,    base + t.ein_out,   base + t.ein_kout,
+                      base + t.ein_woff,  base + t.mix_node,     base + t.mix_kout,  base + t.mix_cptr,
+                      base + t.mix_child, base + t.mix_voff,     base + t.leaf_node, base + t.leaf_replica,
+                      base + t.leaf_sptr, base + t.leaf_var,     base + t.lv_leaf,   base + t.lv_var,
+                      base + t.rb_node,   base + t.rb_kout,      base + t.rb_mix,    base + t.rb_pptr,
+                      base + t.rb_pslot,  base + t.row_off,      base + t.row_len};
+    h->bound = true;
+    return EINET_OK;
+}
+
+int einet_refresh(einet_t* h, void* stream) {
+    if (!h) return EINET_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
+    launch_leaf_derive(h->params + h->plan.phi_offset, reinterpret_cast<float*>(h->ws + h->off_theta), dims_of(h, 0),
+                       static_cast<hipStream_t>(stream));
+    return check_hip(h, "einet_refresh");
+}
+
+int einet_logp(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int B, float* logp_dev,
+               void* stream) {
+    int rc = check_batch_args(h, x_dev, mask_dev, mask_mode, B);
+    if (rc != EINET_OK) return rc;
+    if (!logp_dev) return fail(h, EINET_ERR_INVALID_ARG, "logp_dev is NULL");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dims d = dims_of(h, B);
+    forward(h, x_dev, mask_dev, mask_mode, d, s);
+    launch_copy_root(reinterpret_cast<const float*>(h->ws + h->off_A), logp_dev, d, s);
+    return check_hip(h, "einet_logp");
+}
+
+int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int B,
+                        float* logp_dev, void* stream) {
+    int rc = check_batch_args(h, x_dev, mask_dev, mask_mode, B);
+    if (rc != EINET_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dims d = dims_of(h, B);
+    const Plan& p = h->plan;
+    forward(h, x_dev, mask_dev, mask_mode, d, s);
+    const float* A = reinterpret_cast<const float*>(h->ws + h->off_A);
+    float* G = reinterpret_cast<float*>(h->ws + h->off_G);
+    float* Gp = reinterpret_cast<float*>(h->ws + h->off_Gp);
+    if (logp_dev) launch_copy_root(A, logp_dev, d, s);
+    // top-down: regions of sum layer l (root first), then the einsum items that feed them
+    for (int l = p.num_layers - 1, step = 0; l >= 0; --l, ++step) {
+        launch_region_backward(h->dt, p.rb_layer_ptr[step], p.rb_layer_ptr[step + 1] - p.rb_layer_ptr[step],
+                               step == 0, h->params, h->stats, A, G, Gp, d, s);
+        launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params,
+                               h->stats, A, G, Gp, d, s);
+    }
+    const int leaf_step = p.num_layers;
+    launch_region_backward(h->dt, p.rb_layer_ptr[leaf_step], p.rb_layer_ptr[leaf_step + 1] - p.rb_layer_ptr[leaf_step],
+                           false, h->params, h->stats, A, G, Gp, d, s);
+    launch_leaf_backward(h->dt, (int)p.lv_leaf.size(), x_dev, mask_dev, mask_mode, G, h->stats, p.phi_offset,
+                         p.den_offset, p.tot_offset, d, s);
+    return check_hip(h, "einet_em_accumulate");
+}
+
+int einet_em_update(einet_t* h, float step, float min_var, float max_var, float w_floor, void* stream) {
+    if (!h) return EINET_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
+    if (!(step > 0.f && step <= 1.f)) return fail(h, EINET_ERR_INVALID_ARG, "step must be in (0, 1]");
+    if (!(min_var >= 0.f) || !(max_var >= min_var) || !(w_floor >= 0.f))
+        return fail(h, EINET_ERR_INVALID_ARG, "need 0 <= min_var <= max_var and w_floor >= 0");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dims d = dims_of(h, 0);
+    const Plan& p = h->plan;
+    launch_update_rows(h->dt, (int)p.row_off.size(), h->params, h->stats, step, w_floor, s);
+    launch_update_leaves(h->params, h->stats, p.phi_offset, p.den_offset, p.tot_offset, step, min_var, max_var, d, s);
+    launch_fill(h->stats + p.den_offset, 0.f, p.n_stats - p.den_offset, s);
+    launch_leaf_derive(h->params + p.phi_offset, reinterpret_cast<float*>(h->ws + h->off_theta), d, s);
+    return check_hip(h, "einet_em_update");
+}
+
+int einet_em_reset(einet_t* h, void* stream) {
+    if (!h) return EINET_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
+    launch_fill(h->stats, 0.f, h->plan.n_stats, static_cast<hipStream_t>(stream));
+    return check_hip(h, "einet_em_reset");
+}
+
+}  // extern "C"

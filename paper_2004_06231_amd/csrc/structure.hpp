@@ -1,0 +1,62 @@
+// Host-side structure compiler: region graph -> layered execution plan.
+//
+// A vectorised circuit (Sec. 3.1) is kept as regions (sum or leaf vectors) and
+// partitions (binary product nodes, one parent region each).  The plan turns it
+// into the flat tables the kernels walk: one arena slot ("node") per region and
+// per simple sum (App. B), einsum layers bottom-up (Algorithm 1), mixing items,
+// and per region the list of partitions that feed its posterior top-down.
+#pragma once
+#include <array>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/einet.h"
+
+namespace einet_impl {
+
+struct RegionGraph {
+    int num_vars = 0;
+    int num_replica = 0;
+    std::vector<std::vector<int32_t>> scope;        // region -> ascending variables
+    std::vector<std::array<int32_t, 3>> partition;  // parent, left, right
+    std::vector<std::vector<int32_t>> parts_of;     // region -> its partitions, ascending
+    std::vector<int32_t> replica;                   // leaf region -> replica, else -1
+    bool is_leaf(int s) const { return parts_of[s].empty(); }
+};
+
+// Generators; return false and fill err when the structure cannot be built.
+bool build_rat(int D, int depth, int R, uint64_t seed, RegionGraph& g, std::string& err);
+bool build_pd(int H, int W, const int32_t* deltas, int n_deltas, int axes, RegionGraph& g, std::string& err);
+
+// Everything the device needs, as host vectors (uploaded verbatim by einet_bind).
+struct Plan {
+    int K = 0, C = 0, T = 0, TD = 0, family = 0;
+    int num_nodes = 0;      // regions + simple sums
+    int num_layers = 0;
+
+    // einsum items in execution order (bottom layer first); item e owns posterior slots 2e, 2e+1
+    std::vector<int32_t> ein_left, ein_right, ein_out, ein_kout, ein_woff;
+    std::vector<int32_t> ein_layer_ptr;             // [num_layers+1]
+    // mixing items, grouped by the layer whose einsum they follow
+    std::vector<int32_t> mix_node, mix_kout, mix_cptr, mix_child, mix_voff;
+    std::vector<int32_t> mix_layer_ptr;             // [num_layers+1]
+    // leaves
+    std::vector<int32_t> leaf_node, leaf_replica, leaf_sptr, leaf_var;
+    std::vector<int32_t> lv_leaf, lv_var;           // one entry per (leaf, variable of its scope)
+    // top-down items: sum layers from the root down, then the leaves
+    std::vector<int32_t> rb_node, rb_kout, rb_mix, rb_pptr, rb_pslot;
+    std::vector<int32_t> rb_layer_ptr;              // [num_layers+2]
+    // M-step rows (one per (n,k) and per (s,k))
+    std::vector<int32_t> row_off, row_len;
+
+    // ABI view data
+    std::vector<int32_t> scope_ptr, scope_var, layer_partition, layer_ptr, partition_flat;
+    std::vector<int64_t> w_offset, v_offset;
+    int64_t phi_offset = 0, den_offset = 0, tot_offset = 0;
+    int64_t n_params = 0, n_stats = 0;
+};
+
+bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& plan, std::string& err);
+
+}  // namespace einet_impl

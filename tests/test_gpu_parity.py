@@ -1,0 +1,189 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 oracle,
+element by element, on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2004_06231_amd as P
+import workloads
+from oracle.einet import BERNOULLI, GAUSSIAN
+from tests.common import make_oracle
+from tests.gpu_common import (gpu_config, gpu_model, dev, assert_logp_close, assert_stats_close)
+
+pytestmark = pytest.mark.gpu
+
+_cache = {}
+
+
+def config_case(i):
+    """Full-size configuration i: models, inputs and the oracle's E-step (computed once per session)."""
+    if i not in _cache:
+        cfg, oracle, m, flat, x, mask = gpu_config(i)
+        stats, logp = oracle.em_accumulate(x, None, chunk=16)          # EM runs on fully observed data
+        _cache[i] = dict(cfg=cfg, oracle=oracle, m=m, flat=flat, x=x, mask=mask,
+                         ref_stats=oracle.stats_to_flat(stats), ref_logp=logp)
+    return _cache[i]
+
+
+@pytest.mark.parametrize("i", [1, 2, 3, 4, 5])
+def test_logp_matches_oracle_on_benchmark_configs(i):
+    c = config_case(i)
+    print(f"config {i}: {c['cfg']['name']} B={c['x'].shape[0]}", flush=True)
+    got = c["m"].logp(dev(c["x"]))
+    worst = assert_logp_close(got, c["ref_logp"])
+    print(f"  worst relative logP error {worst:.2e}", flush=True)
+    if c["mask"] is not None:
+        ref = c["oracle"].logp(c["x"], c["mask"], chunk=32)
+        assert_logp_close(c["m"].logp(dev(c["x"]), dev(c["mask"])), ref)
+
+
+@pytest.mark.parametrize("i", [1, 2, 3, 4, 5])
+def test_em_statistics_match_oracle_on_benchmark_configs(i):
+    c = config_case(i)
+    m = c["m"]
+    m.em_reset()
+    lp = torch.empty(c["x"].shape[0], device="cuda")
+    m.em_accumulate(dev(c["x"]), None, lp)
+    assert_logp_close(lp, c["ref_logp"])
+    worst = assert_stats_close(m.stats, c["ref_stats"], c["oracle"].layout, m.n_params)
+    print(f"config {i}: worst normalised statistic errors {worst}", flush=True)
+    # accumulating again doubles every statistic (Eq. 7 sums over the data)
+    m.em_accumulate(dev(c["x"]))
+    assert_stats_close(m.stats, 2 * c["ref_stats"], c["oracle"].layout, m.n_params)
+    m.em_reset()
+    assert float(m.stats.abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("i", [1, 2, 3, 5])
+def test_em_update_matches_oracle(i):
+    c = config_case(i)
+    cfg, oracle, m = c["cfg"], c["oracle"], c["m"]
+    kw = dict(step=0.5, min_var=1e-6, max_var=1e-2, w_floor=1e-6) if cfg["family"] == GAUSSIAN else \
+        dict(step=1.0, w_floor=0.0)
+    m.set_params(c["flat"])
+    m.em_reset()
+    m.em_accumulate(dev(c["x"]))
+    m.em_update(**kw)
+    oracle.set_flat_params(c["flat"])
+    st = oracle.stats_from_flat(c["ref_stats"])          # the oracle's statistics of this batch (cached)
+    oracle.em_update(st, **kw)
+    ref = oracle.get_flat_params()
+    got = m.params.cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref)
+    assert np.all(err <= 1e-3 * np.abs(ref) + 1e-7), f"worst {err.max():.3e}"
+    assert float(m.stats.abs().max()) == 0.0                     # the update zeroes the accumulators
+    # the refreshed leaf constants are in use: logP under the new parameters
+    assert_logp_close(m.logp(dev(c["x"][:8])), oracle.logp(c["x"][:8]))
+    oracle.set_flat_params(c["flat"])
+    m.set_params(c["flat"])
+
+
+def test_conditional_logp_eq1_on_config5():
+    c = config_case(5)
+    D = c["x"].shape[1]
+    e = c["mask"].astype(np.uint8)                 # evidence: the seeded 50 % mask
+    q = (1 - e).astype(np.uint8)                   # query: all other pixels
+    x = c["x"][:16]
+    ref = c["oracle"].conditional_logp(x, q, e)
+    got = c["m"].logp(dev(x), dev(np.maximum(q, e))) - c["m"].logp(dev(x), dev(e))
+    err = np.abs(got.cpu().numpy() - ref)
+    # each of the two marginals meets its own bound; the difference inherits their sum
+    tol = 1e-4 * (np.abs(c["oracle"].logp(x, np.maximum(q, e))) + np.abs(c["oracle"].logp(x, e))) + 2e-5
+    assert np.all(err <= tol)
+
+
+SMALL = [
+    # spec, K, C, family, B
+    (dict(kind="rat", D=9, depth=2, R=1), 1, 1, BERNOULLI, 5),          # K = 1, no root mixing
+    (dict(kind="rat", D=16, depth=3, R=3), 3, 2, BERNOULLI, 17),        # ragged sample tile
+    (dict(kind="rat", D=20, depth=2, R=2), 5, 1, GAUSSIAN, 33),
+    (dict(kind="rat", D=12, depth=1, R=4), 7, 1, GAUSSIAN, 1),          # single sample
+    (dict(kind="rat", D=40, depth=3, R=2), 13, 1, GAUSSIAN, 70),
+    (dict(kind="rat", D=10, depth=2, R=1), 64, 1, BERNOULLI, 20),       # largest K
+    (dict(kind="pd", H=6, W=6, deltas=[2]), 6, 3, GAUSSIAN, 19),
+    (dict(kind="pd", H=8, W=4, deltas=[4, 2]), 9, 1, BERNOULLI, 40),
+    (dict(kind="pd", H=4, W=12, deltas=[4], axes=2), 17, 2, GAUSSIAN, 16),   # vertical cuts only
+]
+
+
+@pytest.mark.parametrize("spec,K,C,family,B", SMALL)
+@pytest.mark.parametrize("mask_kind", [None, "shared", "per_sample"])
+def test_small_shapes_logp_and_statistics(spec, K, C, family, B, mask_kind):
+    seed = 1000 + K
+    oracle, flat, rng = make_oracle(spec, K, C, family, seed, leaf_range=(0.1, 0.9))
+    D = oracle.g.num_vars
+    x = workloads.draw_data(rng, dict(kind="bernoulli_iid", p=0.4) if family == BERNOULLI
+                            else dict(kind="gaussian_mixture", components=3, std=0.3), B, D, C)
+    mask = workloads.draw_mask(rng, None if mask_kind is None else dict(kind=mask_kind, observed_fraction=0.6), B, D)
+    m = gpu_model(spec, K, C, family, B, seed, flat)
+    ref_stats, ref_logp = oracle.em_accumulate(x, mask)
+    assert_logp_close(m.logp(dev(x), dev(mask)), ref_logp)
+    lp = torch.empty(B, device="cuda")
+    m.em_accumulate(dev(x), dev(mask), lp)
+    assert_logp_close(lp, ref_logp)
+    assert_stats_close(m.stats, oracle.stats_to_flat(ref_stats), oracle.layout, m.n_params)
+    m.close()
+
+
+def test_smaller_batch_than_max_batch_and_determinism():
+    spec, K = dict(kind="pd", H=8, W=8, deltas=[4]), 10
+    oracle, flat, rng = make_oracle(spec, K, 1, GAUSSIAN, 77)
+    x = workloads.draw_data(rng, dict(kind="gaussian_mixture", components=4, std=0.2), 50, 64, 1)
+    m = gpu_model(spec, K, 1, GAUSSIAN, 50, 77, flat)
+    full = m.logp(dev(x)).clone()
+    part = m.logp(dev(x[:23]))
+    assert torch.equal(full[:23], part)                # samples are independent; layout does not leak
+    m.em_accumulate(dev(x))
+    s1 = m.stats.clone()
+    m.em_reset()
+    m.em_accumulate(dev(x))
+    assert torch.equal(s1, m.stats)                    # no atomics: bit-reproducible
+    with pytest.raises(P.EinetError) as e:
+        m.logp(dev(np.concatenate([x, x])))
+    assert e.value.code == -4
+    m.close()
+
+
+def test_everything_marginalised_gives_zero_and_impossible_evidence_gives_minus_inf():
+    spec, K = dict(kind="rat", D=8, depth=2, R=2), 4
+    oracle, flat, rng = make_oracle(spec, K, 1, BERNOULLI, 5)
+    x = workloads.draw_data(rng, dict(kind="bernoulli_iid", p=0.5), 6, 8, 1)
+    m = gpu_model(spec, K, 1, BERNOULLI, 6, 5, flat)
+    lp = m.logp(dev(x), dev(np.zeros(8, np.uint8))).cpu().numpy()
+    assert np.max(np.abs(lp)) < 1e-5
+    # p = 0 for every entry of variable 3 in every replica: x_3 = 1 has probability zero
+    lay = oracle.layout
+    phi = flat[lay.phi_off:].reshape(8, 1, 2, 1, K).copy()
+    phi[3] = 0.0
+    flat2 = flat.copy(); flat2[lay.phi_off:] = phi.ravel()
+    m.set_params(flat2)
+    x1 = x.copy(); x1[:, 3, 0] = 1.0
+    lp = m.logp(dev(x1)).cpu().numpy()
+    assert np.all(np.isneginf(lp))
+    # with valid parameters again the same handle gives finite values
+    m.set_params(flat)
+    assert_logp_close(m.logp(dev(x1)), oracle.logp(x1))
+    m.close()
+
+
+@pytest.mark.parametrize("family", [BERNOULLI, GAUSSIAN])
+def test_full_batch_em_is_monotone_on_gpu(family):
+    spec, K = dict(kind="rat", D=16, depth=3, R=3), 4
+    oracle, flat, rng = make_oracle(spec, K, 1, family, 31, leaf_range=(0.2, 0.8))
+    if family == BERNOULLI:
+        x = workloads.draw_data(rng, dict(kind="bernoulli_mixture", components=3, lo=0.1, hi=0.9), 200, 16, 1)
+    else:
+        x = workloads.draw_data(rng, dict(kind="gaussian_mixture", components=3, std=0.2), 200, 16, 1)
+    m = gpu_model(spec, K, 1, family, 200, 31, flat)
+    xd, lp = dev(x), torch.empty(200, device="cuda")
+    prev = -np.inf
+    for it in range(10):
+        m.em_accumulate(xd, None, lp)
+        ll = float(lp.double().sum())
+        assert ll >= prev - 1e-4 * abs(ll), (it, ll, prev)
+        prev = ll
+        m.em_update(step=1.0, min_var=1e-4)
+    # and the oracle, fed the parameters the GPU reached, agrees on the likelihood
+    oracle.set_flat_params(m.params.cpu().numpy())
+    assert_logp_close(m.logp(xd), oracle.logp(x))
+    m.close()

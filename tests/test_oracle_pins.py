@@ -391,3 +391,6 @@ def test_flat_round_trip_and_chunking():
     np.testing.assert_allclose(model.stats_to_flat(s1), model.stats_to_flat(s2), rtol=1e-12, atol=1e-15)
     np.testing.assert_allclose(lp1, lp2, rtol=0, atol=0)
     assert model.stats_to_flat(s1).size == model.layout.n_stats
+    back = model.stats_from_flat(model.stats_to_flat(s1))
+    np.testing.assert_array_equal(model.stats_to_flat(back), model.stats_to_flat(s1))
+    np.testing.assert_array_equal(back["num"], s1["num"])
