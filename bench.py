@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the EiNet hot path on one MI355X.
+
+A step is one full EM step on one resident batch of synthetic data: forward pass
+(leaf, einsum and mixing layers), top-down pass accumulating the expected
+statistics, and the M-step.  The workload is configuration 4 (Poon-Domingos
+structure on a 32x32x3 grid, step 8, K=40, Gaussian leaves, B=128), the largest of
+the five configurations in einsum work; the data stand in for 32x32 RGB images and
+are drawn from a seeded Gaussian mixture.
+
+Prints ONE JSON line: EM samples/s as `value`, plus logP samples/s, the per-kernel
+device times, the roofline of the dominant kernel, and the float64 oracle timed on
+a bounded sample of the same batch on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_MFMA_FP32_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
+WORKLOAD = 4
+
+
+def algorithmic_work(st, K, C, R, T, TD, B, D):
+    """Per step, per kernel class: (flop, bytes) the method itself needs (unpadded K, no
+    materialised outer products, every operand moved once)."""
+    part = st["partition"]
+    kout = [1 if p[0] == 0 else K for p in part]
+    n_children = {}
+    for p in part:
+        n_children[p[0]] = n_children.get(p[0], 0) + 1
+    mix = {s: c for s, c in n_children.items() if c > 1}
+    n_leaf = int((st["region_replica"] >= 0).sum())
+    w = {}
+    w["einsum_forward"] = (sum(2.0 * B * ko * K * K for ko in kout),
+                           sum(4.0 * ko * K * K + 4.0 * B * (2 * K + ko) for ko in kout))
+    # backward: W read, Nw read and written; L, R, A_out, G_out read; two posterior blocks written
+    w["einsum_backward"] = (sum(4.0 * B * ko * K * K for ko in kout),
+                            sum(12.0 * ko * K * K + 4.0 * B * (4 * K + 2 * ko) for ko in kout))
+    w["mixing_forward"] = (0.0, sum(4.0 * (c + 1) * B * (1 if s == 0 else K) for s, c in mix.items()))
+    w["leaf_forward"] = (0.0, 4.0 * B * D * C + 4.0 * D * C * R * TD * K + 4.0 * n_leaf * B * K)
+    w["leaf_backward"] = (0.0, 4.0 * B * D * C + 4.0 * n_leaf * B * K + 8.0 * (D * C * R * T * K + 2 * D * R * K))
+    n_param = float(st["phi_offset"]) + D * C * R * T * K
+    w["em_update"] = (0.0, 4.0 * 3 * n_param)       # read statistics and parameters, write parameters (+ zeroing)
+    n_regions = st["num_regions"]
+    w["region_backward"] = (0.0, 4.0 * B * K * (n_regions + 2 * len(part)))
+    return w
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; sharding over the batch with one all-reduce of the "
+              "statistics per M-step is described in DESIGN.md, not built. Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2004_06231_amd as P
+    import workloads
+
+    cfg = workloads.get_config(WORKLOAD)
+    seed = workloads.config_seed(WORKLOAD)
+    K, C, fam, B = cfg["K"], cfg["channels"], cfg["family"], cfg["B"]
+    m = P.EiNet(cfg["structure"], K, C, fam, B, seed).bind("cuda:0")
+    st = m.structure()
+    D, R, T = st["num_vars"], st["num_replica"], st["T"]
+    TD = 3 if fam == P.GAUSSIAN else 2
+    rng = np.random.default_rng(seed)
+    flat = workloads.draw_params(rng, m.n_params, m.weight_blocks(), int(st["phi_offset"]), (D, C, R, T, K), fam,
+                                 cfg["leaf_range"])
+    x_host = workloads.draw_data(rng, cfg["data"], B, D, C)
+    m.set_params(flat)
+    x = torch.as_tensor(x_host).cuda()
+    logp = torch.empty(B, dtype=torch.float32, device="cuda")
+    em_kw = dict(step=0.5, min_var=1e-6, max_var=1e-2, w_floor=1e-9)   # Sec. 4.2 settings
+
+    def em_step():
+        m.em_accumulate(x, None, logp)
+        m.em_update(**em_kw)
+
+    for _ in range(args.warmup):
+        em_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        em_step()
+    torch.cuda.synchronize()
+    t_em = time.perf_counter() - t0
+    ms_per_step = 1e3 * t_em / args.steps
+
+    # forward only
+    for _ in range(args.warmup):
+        m.logp(x, None, logp)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        m.logp(x, None, logp)
+    torch.cuda.synchronize()
+    t_lp = time.perf_counter() - t0
+
+    # per-kernel device time: the same steps again with a HIP event pair around every launch,
+    # recorded on the stream the kernels run on (separate pass: recording costs host time)
+    m.profile_enable(True)
+    for _ in range(args.steps):
+        em_step()
+    torch.cuda.synchronize()
+    prof = m.profile_read()
+    m.profile_enable(False)
+    work = algorithmic_work(st, K, C, R, T, TD, B, D)
+    kernels = {}
+    for name, (ms, launches) in prof.items():
+        if launches == 0:
+            continue
+        flop, byts = work[name]
+        per_step_us = 1e3 * ms / args.steps
+        kernels[name] = dict(us_per_step=round(per_step_us, 2), launches_per_step=launches // args.steps,
+                             tflops=round(flop / (per_step_us * 1e-6) / 1e12, 3),
+                             gbs=round(byts / (per_step_us * 1e-6) / 1e9, 1))
+    dom = max(kernels, key=lambda n: kernels[n]["us_per_step"])
+    flop, byts = work[dom]
+    n_launch = kernels[dom]["launches_per_step"]
+    avg_launch_s = kernels[dom]["us_per_step"] * 1e-6 / n_launch
+    # which roof binds the dominant kernel: the one that takes longer at peak
+    if flop / (PEAK_MFMA_FP32_TFLOPS * 1e12) >= byts / (PEAK_HBM_GBS * 1e9):
+        achieved = flop / n_launch / avg_launch_s / 1e12
+        roof = dict(bound="mfma", achieved=round(achieved, 3), peak=PEAK_MFMA_FP32_TFLOPS, unit="TFLOP/s",
+                    frac=round(achieved / PEAK_MFMA_FP32_TFLOPS, 4))
+    else:
+        achieved = byts / n_launch / avg_launch_s / 1e9
+        roof = dict(bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(achieved / PEAK_HBM_GBS, 4))
+    roof.update(kernel=dom, avg_launch_us=round(avg_launch_s * 1e6, 2), launches_per_step=n_launch,
+                algorithmic_flop_per_step=flop, algorithmic_bytes_per_step=byts, traffic=None,
+                timing="hip events around each launch, separate pass of the same steps")
+
+    out = {
+        "metric": "EM samples/sec (fwd+bwd+M-step)", "value": round(B * args.steps / t_em, 1), "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg["name"], "structure": "Poon-Domingos 32x32x3, delta 8", "K": K, "batch": B,
+                   "leaves": "gaussian", "em": em_kw},
+        "logp_samples_per_s": round(B * args.steps / t_lp, 1), "logp_ms_per_call": round(1e3 * t_lp / args.steps, 4),
+        "kernels": kernels,
+        "roofline": roof,
+    }
+
+    if not args.no_cpu_baseline:
+        # the float64 oracle, as it stands, on a bounded sample of the same batch
+        from tests.common import make_config
+        n_cpu = 16
+        _, oracle, _, xs, _ = make_config(WORKLOAD, batch=B)
+        assert np.array_equal(xs, x_host)
+        t0 = time.perf_counter()
+        stats, _ = oracle.em_accumulate(xs[:n_cpu], None, chunk=8)
+        oracle.em_update(stats, **em_kw)
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 3), "unit": "samples/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {n_cpu} of the {B} samples of {cfg['name']}, one EM step "
+                                         f"(float64 NumPy, single thread), {t_cpu:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

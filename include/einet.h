@@ -191,6 +191,18 @@ int einet_em_update(einet_t* h, float step, float min_var, float max_var, float 
 /* Zeroes the statistics buffer. */
 int einet_em_reset(einet_t* h, void* stream);
 
+/* Per-kernel timing for benchmarks (no passage of the paper: measurement aid).
+ * While enabled, every kernel launch of the compute calls above is bracketed
+ * by two HIP events recorded on the call's stream.  einet_profile_read
+ * synchronises those events, adds the elapsed times per kernel class, clears
+ * the record, and writes up to `capacity` classes: names[i] (host strings
+ * owned by the library), total_ms[i], launches[i]; *n_classes receives the
+ * number of classes.  All outputs: host.  Disabled by default; recording costs
+ * host time per launch, so throughput is measured with it off. */
+int einet_profile_enable(einet_t* h, int enable);
+int einet_profile_read(einet_t* h, int capacity, int* n_classes, const char** names, double* total_ms,
+                       int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,6 +15,7 @@ MAX_DELTAS = 8
 EXPORTED_SYMBOLS = [
     "einet_create", "einet_destroy", "einet_last_error", "einet_sizes", "einet_structure", "einet_bind",
     "einet_refresh", "einet_logp", "einet_em_accumulate", "einet_em_update", "einet_em_reset",
+    "einet_profile_enable", "einet_profile_read",
 ]
 
 
@@ -70,6 +71,9 @@ def load_library():
     lib.einet_em_accumulate.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.einet_em_update.argtypes = [vp, f32, f32, f32, f32, vp]
     lib.einet_em_reset.argtypes = [vp, vp]
+    lib.einet_profile_enable.argtypes = [vp, i32]
+    lib.einet_profile_read.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(C.c_char_p), C.POINTER(C.c_double),
+                                       C.POINTER(C.c_int64)]
     _lib = lib
     return lib
 
@@ -224,6 +228,17 @@ class EiNet:
     def em_reset(self):
         self._check(self._lib.einet_em_reset(self._h, self._stream()))
 
+    def profile_enable(self, enable=True):
+        self._check(self._lib.einet_profile_enable(self._h, 1 if enable else 0))
+
+    def profile_read(self):
+        """{kernel class: (total milliseconds, launches)} since the last read."""
+        cap = 16
+        n = C.c_int()
+        names, ms, cnt = (C.c_char_p * cap)(), (C.c_double * cap)(), (C.c_int64 * cap)()
+        self._check(self._lib.einet_profile_read(self._h, cap, C.byref(n), names, ms, cnt))
+        return {names[i].decode(): (ms[i], cnt[i]) for i in range(min(n.value, cap))}
+
 
 # The C names, for callers who prefer the flat interface.
 def einet_create(structure, K, channels, family, max_batch, seed=0):
@@ -268,3 +283,11 @@ def einet_em_update(m, step=1.0, min_var=0.0, max_var=math.inf, w_floor=0.0):
 
 def einet_em_reset(m):
     m.em_reset()
+
+
+def einet_profile_enable(m, enable=True):
+    m.profile_enable(enable)
+
+
+def einet_profile_read(m):
+    return m.profile_read()

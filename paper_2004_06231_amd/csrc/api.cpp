@@ -27,6 +27,11 @@ struct einet {
             rb_pslot, row_off, row_len;
     } to{};
 
+    // optional per-launch timing (einet_profile_*)
+    bool profiling = false;
+    struct Timed { int cls; hipEvent_t start, stop; };
+    std::vector<Timed> timed;
+
     bool bound = false;
     float* params = nullptr;
     float* stats = nullptr;
@@ -86,17 +91,44 @@ int check_batch_args(einet_t* h, const float* x, const uint8_t* mask, int mask_m
     return EINET_OK;
 }
 
+enum KernelClass { KC_LEAF_FWD, KC_EINSUM_FWD, KC_MIXING_FWD, KC_REGION_BWD, KC_EINSUM_BWD, KC_LEAF_BWD, KC_UPDATE, KC_COUNT };
+const char* const kKernelClassNames[KC_COUNT] = {"leaf_forward", "einsum_forward", "mixing_forward", "region_backward",
+                                                 "einsum_backward", "leaf_backward", "em_update"};
+
+// Runs `launch` (which enqueues kernels on s); when profiling, brackets it with two events.
+template <class F>
+void run(einet_t* h, int cls, hipStream_t s, F&& launch) {
+    if (!h->profiling) {
+        launch();
+        return;
+    }
+    einet::Timed t{cls, nullptr, nullptr};
+    if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) {
+        launch();
+        return;
+    }
+    (void)hipEventRecord(t.start, s);
+    launch();
+    (void)hipEventRecord(t.stop, s);
+    h->timed.push_back(t);
+}
+
 // Leaf layer, then einsum (+ mixing) layers bottom-up; fills the arena A.
 void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, const Dims& d, hipStream_t s) {
     const Plan& p = h->plan;
     float* A = reinterpret_cast<float*>(h->ws + h->off_A);
     const float* theta = reinterpret_cast<const float*>(h->ws + h->off_theta);
-    launch_leaf_forward(h->dt, (int)p.leaf_node.size(), x, mask, mask_mode, theta, A, d, s);
+    run(h, KC_LEAF_FWD, s, [&] { launch_leaf_forward(h->dt, (int)p.leaf_node.size(), x, mask, mask_mode, theta, A, d, s); });
     for (int l = 0; l < p.num_layers; ++l) {
-        launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params, A, d,
-                              s);
-        launch_mixing_forward(h->dt, p.mix_layer_ptr[l], p.mix_layer_ptr[l + 1] - p.mix_layer_ptr[l], h->params, A, d,
-                              s);
+        run(h, KC_EINSUM_FWD, s, [&] {
+            launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params, A,
+                                  d, s);
+        });
+        if (p.mix_layer_ptr[l + 1] > p.mix_layer_ptr[l])
+            run(h, KC_MIXING_FWD, s, [&] {
+                launch_mixing_forward(h->dt, p.mix_layer_ptr[l], p.mix_layer_ptr[l + 1] - p.mix_layer_ptr[l],
+                                      h->params, A, d, s);
+            });
     }
 }
 
@@ -182,7 +214,14 @@ int einet_create(const einet_spec* spec, einet_t** out) {
     return EINET_OK;
 }
 
-void einet_destroy(einet_t* h) { delete h; }
+void einet_destroy(einet_t* h) {
+    if (!h) return;
+    for (auto& t : h->timed) {
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+    }
+    delete h;
+}
 
 const char* einet_last_error(const einet_t* h) { return h ? h->err.c_str() : g_create_error.c_str(); }
 
@@ -276,16 +315,25 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
     if (logp_dev) launch_copy_root(A, logp_dev, d, s);
     // top-down: regions of sum layer l (root first), then the einsum items that feed them
     for (int l = p.num_layers - 1, step = 0; l >= 0; --l, ++step) {
-        launch_region_backward(h->dt, p.rb_layer_ptr[step], p.rb_layer_ptr[step + 1] - p.rb_layer_ptr[step],
-                               step == 0, h->params, h->stats, A, G, Gp, d, s);
-        launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params,
-                               h->stats, A, G, Gp, d, s);
+        run(h, KC_REGION_BWD, s, [&] {
+            launch_region_backward(h->dt, p.rb_layer_ptr[step], p.rb_layer_ptr[step + 1] - p.rb_layer_ptr[step],
+                                   step == 0, h->params, h->stats, A, G, Gp, d, s);
+        });
+        run(h, KC_EINSUM_BWD, s, [&] {
+            launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params,
+                                   h->stats, A, G, Gp, d, s);
+        });
     }
     const int leaf_step = p.num_layers;
-    launch_region_backward(h->dt, p.rb_layer_ptr[leaf_step], p.rb_layer_ptr[leaf_step + 1] - p.rb_layer_ptr[leaf_step],
-                           false, h->params, h->stats, A, G, Gp, d, s);
-    launch_leaf_backward(h->dt, (int)p.lv_leaf.size(), x_dev, mask_dev, mask_mode, G, h->stats, p.phi_offset,
-                         p.den_offset, p.tot_offset, d, s);
+    run(h, KC_REGION_BWD, s, [&] {
+        launch_region_backward(h->dt, p.rb_layer_ptr[leaf_step],
+                               p.rb_layer_ptr[leaf_step + 1] - p.rb_layer_ptr[leaf_step], false, h->params, h->stats,
+                               A, G, Gp, d, s);
+    });
+    run(h, KC_LEAF_BWD, s, [&] {
+        launch_leaf_backward(h->dt, (int)p.lv_leaf.size(), x_dev, mask_dev, mask_mode, G, h->stats, p.phi_offset,
+                             p.den_offset, p.tot_offset, d, s);
+    });
     return check_hip(h, "einet_em_accumulate");
 }
 
@@ -298,10 +346,13 @@ int einet_em_update(einet_t* h, float step, float min_var, float max_var, float 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Dims d = dims_of(h, 0);
     const Plan& p = h->plan;
-    launch_update_rows(h->dt, (int)p.row_off.size(), h->params, h->stats, step, w_floor, s);
-    launch_update_leaves(h->params, h->stats, p.phi_offset, p.den_offset, p.tot_offset, step, min_var, max_var, d, s);
-    launch_fill(h->stats + p.den_offset, 0.f, p.n_stats - p.den_offset, s);
-    launch_leaf_derive(h->params + p.phi_offset, reinterpret_cast<float*>(h->ws + h->off_theta), d, s);
+    run(h, KC_UPDATE, s, [&] {
+        launch_update_rows(h->dt, (int)p.row_off.size(), h->params, h->stats, step, w_floor, s);
+        launch_update_leaves(h->params, h->stats, p.phi_offset, p.den_offset, p.tot_offset, step, min_var, max_var, d,
+                             s);
+        launch_fill(h->stats + p.den_offset, 0.f, p.n_stats - p.den_offset, s);
+        launch_leaf_derive(h->params + p.phi_offset, reinterpret_cast<float*>(h->ws + h->off_theta), d, s);
+    });
     return check_hip(h, "einet_em_update");
 }
 
@@ -310,6 +361,38 @@ int einet_em_reset(einet_t* h, void* stream) {
     if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
     launch_fill(h->stats, 0.f, h->plan.n_stats, static_cast<hipStream_t>(stream));
     return check_hip(h, "einet_em_reset");
+}
+
+int einet_profile_enable(einet_t* h, int enable) {
+    if (!h) return EINET_ERR_INVALID_ARG;
+    h->profiling = enable != 0;
+    return EINET_OK;
+}
+
+int einet_profile_read(einet_t* h, int capacity, int* n_classes, const char** names, double* total_ms,
+                       int64_t* launches) {
+    if (!h || capacity < 0 || !n_classes) return EINET_ERR_INVALID_ARG;
+    double ms[KC_COUNT] = {0};
+    int64_t cnt[KC_COUNT] = {0};
+    int rc = EINET_OK;
+    for (auto& t : h->timed) {
+        float el = 0.f;
+        hipError_t e = hipEventSynchronize(t.stop);
+        if (e == hipSuccess) e = hipEventElapsedTime(&el, t.start, t.stop);
+        if (e != hipSuccess) rc = fail(h, EINET_ERR_HIP, std::string("reading profile events: ") + hipGetErrorString(e));
+        ms[t.cls] += el;
+        cnt[t.cls] += 1;
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+    }
+    h->timed.clear();
+    *n_classes = KC_COUNT;
+    for (int i = 0; i < KC_COUNT && i < capacity; ++i) {
+        if (names) names[i] = kKernelClassNames[i];
+        if (total_ms) total_ms[i] = ms[i];
+        if (launches) launches[i] = cnt[i];
+    }
+    return rc;
 }
 
 }  // extern "C"
