@@ -49,6 +49,7 @@ def algorithmic_work(st, K, C, R, T, TD, B, D):
     w["em_update"] = (0.0, 4.0 * 3 * n_param)       # read statistics and parameters, write parameters (+ zeroing)
     n_regions = st["num_regions"]
     w["region_backward"] = (0.0, 4.0 * B * K * (n_regions + 2 * len(part)))
+    w["mixing_backward"] = (0.0, sum(4.0 * (c + 2) * B * (1 if s == 0 else K) for s, c in mix.items()))
     return w
 
 

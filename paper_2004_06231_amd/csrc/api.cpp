@@ -20,11 +20,11 @@ struct einet {
 
     // workspace layout (bytes from the start of the workspace)
     std::vector<int32_t> blob;      // all index tables, concatenated
-    size_t off_theta = 0, off_A = 0, off_G = 0, off_Gp = 0, ws_bytes = 0;
+    size_t off_theta = 0, off_A = 0, off_amax = 0, off_G = 0, off_Gp = 0, ws_bytes = 0;
     struct TableOffsets {
-        size_t ein_left, ein_right, ein_out, ein_kout, ein_woff, mix_node, mix_kout, mix_cptr, mix_child, mix_voff,
-            leaf_node, leaf_replica, leaf_sptr, leaf_var, lv_leaf, lv_var, rb_node, rb_kout, rb_mix, rb_pptr,
-            rb_pslot, row_off, row_len;
+#define X(name) size_t name;
+        EINET_TABLES(X)
+#undef X
     } to{};
 
     // optional per-launch timing (einet_profile_*)
@@ -91,9 +91,9 @@ int check_batch_args(einet_t* h, const float* x, const uint8_t* mask, int mask_m
     return EINET_OK;
 }
 
-enum KernelClass { KC_LEAF_FWD, KC_EINSUM_FWD, KC_MIXING_FWD, KC_REGION_BWD, KC_EINSUM_BWD, KC_LEAF_BWD, KC_UPDATE, KC_COUNT };
+enum KernelClass { KC_LEAF_FWD, KC_EINSUM_FWD, KC_MIXING_FWD, KC_REGION_BWD, KC_EINSUM_BWD, KC_LEAF_BWD, KC_MIXING_BWD, KC_UPDATE, KC_COUNT };
 const char* const kKernelClassNames[KC_COUNT] = {"leaf_forward", "einsum_forward", "mixing_forward", "region_backward",
-                                                 "einsum_backward", "leaf_backward", "em_update"};
+                                                 "einsum_backward", "leaf_backward", "mixing_backward", "em_update"};
 
 // Runs `launch` (which enqueues kernels on s); when profiling, brackets it with two events.
 template <class F>
@@ -122,7 +122,7 @@ void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, con
     for (int l = 0; l < p.num_layers; ++l) {
         run(h, KC_EINSUM_FWD, s, [&] {
             launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params, A,
-                                  d, s);
+                                  reinterpret_cast<float*>(h->ws + h->off_amax), d, s);
         });
         if (p.mix_layer_ptr[l + 1] > p.mix_layer_ptr[l])
             run(h, KC_MIXING_FWD, s, [&] {
@@ -176,39 +176,21 @@ int einet_create(const einet_spec* spec, einet_t** out) {
     const Plan& p = h->plan;
     auto& b = h->blob;
     auto& t = h->to;
-    t.ein_left = append(b, p.ein_left);
-    t.ein_right = append(b, p.ein_right);
-    t.ein_out = append(b, p.ein_out);
-    t.ein_kout = append(b, p.ein_kout);
-    t.ein_woff = append(b, p.ein_woff);
-    t.mix_node = append(b, p.mix_node);
-    t.mix_kout = append(b, p.mix_kout);
-    t.mix_cptr = append(b, p.mix_cptr);
-    t.mix_child = append(b, p.mix_child);
-    t.mix_voff = append(b, p.mix_voff);
-    t.leaf_node = append(b, p.leaf_node);
-    t.leaf_replica = append(b, p.leaf_replica);
-    t.leaf_sptr = append(b, p.leaf_sptr);
-    t.leaf_var = append(b, p.leaf_var);
-    t.lv_leaf = append(b, p.lv_leaf);
-    t.lv_var = append(b, p.lv_var);
-    t.rb_node = append(b, p.rb_node);
-    t.rb_kout = append(b, p.rb_kout);
-    t.rb_mix = append(b, p.rb_mix);
-    t.rb_pptr = append(b, p.rb_pptr);
-    t.rb_pslot = append(b, p.rb_pslot);
-    t.row_off = append(b, p.row_off);
-    t.row_len = append(b, p.row_len);
+#define X(name) t.name = append(b, p.name);
+    EINET_TABLES(X)
+#undef X
     const size_t K = p.K, mb = spec->max_batch;
     size_t off = align256(b.size() * sizeof(int32_t));
     h->off_theta = off;
     off = align256(off + sizeof(float) * size_t(h->graph.num_vars) * p.C * h->graph.num_replica * p.TD * K);
     h->off_A = off;
     off = align256(off + sizeof(float) * size_t(p.num_nodes) * mb * K);
+    h->off_amax = off;
+    off = align256(off + sizeof(float) * 2 * p.ein_left.size() * mb);
     h->off_G = off;
     off = align256(off + sizeof(float) * size_t(p.num_nodes) * mb * K);
     h->off_Gp = off;
-    off = align256(off + sizeof(float) * 2 * p.ein_left.size() * mb * K);
+    off = align256(off + sizeof(float) * gp_blocks_per_item(p.K) * p.ein_left.size() * mb * K);
     h->ws_bytes = off;
     *out = h;
     return EINET_OK;
@@ -271,12 +253,9 @@ int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_
     h->ws = static_cast<char*>(workspace_dev);
     const int32_t* base = reinterpret_cast<const int32_t*>(h->ws);
     const auto& t = h->to;
-    h->dt = DevTables{base + t.ein_left,  base + t.ein_right,    base + t.ein_out,   base + t.ein_kout,
-                      base + t.ein_woff,  base + t.mix_node,     base + t.mix_kout,  base + t.mix_cptr,
-                      base + t.mix_child, base + t.mix_voff,     base + t.leaf_node, base + t.leaf_replica,
-                      base + t.leaf_sptr, base + t.leaf_var,     base + t.lv_leaf,   base + t.lv_var,
-                      base + t.rb_node,   base + t.rb_kout,      base + t.rb_mix,    base + t.rb_pptr,
-                      base + t.rb_pslot,  base + t.row_off,      base + t.row_len};
+#define X(name) h->dt.name = base + t.name;
+    EINET_TABLES(X)
+#undef X
     h->bound = true;
     return EINET_OK;
 }
@@ -313,27 +292,31 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
     float* G = reinterpret_cast<float*>(h->ws + h->off_G);
     float* Gp = reinterpret_cast<float*>(h->ws + h->off_Gp);
     if (logp_dev) launch_copy_root(A, logp_dev, d, s);
-    // top-down: regions of sum layer l (root first), then the einsum items that feed them
+    // top-down: posteriors of the regions of sum layer l (root first), then the einsum items below them
+    const float* amax = reinterpret_cast<const float*>(h->ws + h->off_amax);
     for (int l = p.num_layers - 1, step = 0; l >= 0; --l, ++step) {
         run(h, KC_REGION_BWD, s, [&] {
-            launch_region_backward(h->dt, p.rb_layer_ptr[step], p.rb_layer_ptr[step + 1] - p.rb_layer_ptr[step],
-                                   step == 0, h->params, h->stats, A, G, Gp, d, s);
+            launch_region_assemble(h->dt, p.rb_layer_ptr[step], p.rb_layer_ptr[step + 1] - p.rb_layer_ptr[step],
+                                   step == 0, G, Gp, d, s);
         });
         run(h, KC_EINSUM_BWD, s, [&] {
             launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params,
-                                   h->stats, A, G, Gp, d, s);
+                                   h->stats, A, amax, G, Gp, d, s);
         });
     }
     const int leaf_step = p.num_layers;
     run(h, KC_REGION_BWD, s, [&] {
-        launch_region_backward(h->dt, p.rb_layer_ptr[leaf_step],
-                               p.rb_layer_ptr[leaf_step + 1] - p.rb_layer_ptr[leaf_step], false, h->params, h->stats,
-                               A, G, Gp, d, s);
+        launch_region_assemble(h->dt, p.rb_layer_ptr[leaf_step],
+                               p.rb_layer_ptr[leaf_step + 1] - p.rb_layer_ptr[leaf_step], false, G, Gp, d, s);
     });
     run(h, KC_LEAF_BWD, s, [&] {
         launch_leaf_backward(h->dt, (int)p.lv_leaf.size(), x_dev, mask_dev, mask_mode, G, h->stats, p.phi_offset,
                              p.den_offset, p.tot_offset, d, s);
     });
+    if (!p.mix_node.empty())
+        run(h, KC_MIXING_BWD, s, [&] {
+            launch_mixing_stats(h->dt, (int)p.mix_node.size(), p.max_mix_children, h->params, h->stats, A, G, d, s);
+        });
     return check_hip(h, "einet_em_accumulate");
 }
 

@@ -16,7 +16,6 @@ namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int KMAX = 64;  // largest vector length K
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -77,85 +76,123 @@ __global__ void k_leaf_forward(const int32_t* __restrict__ leaf_node, const int3
 }
 
 // ------------------------------------------------------------------ einsum layer, forward
-// One workgroup per (einsum item, tile of 16 samples).  With eL = exp(L - a),
-// eR = exp(R - a') (a, a' the row maxima; Eq. 4) the layer needs
-//     S[b,k] = sum_i eL[b,i] * T[(k,i), b],   T[(k,i), b] = sum_j W[k,i,j] eR[b,j].
-// T is a dense GEMM (rows (k,i), columns b, contraction j) done with
-// v_mfma_f32_16x16x4_f32: a wave takes 4 outputs k (one per 16-lane group) and
-// 4 inputs i (one per accumulator register) at a time, so the i-reduction of
-// Eq. 4 is four in-lane FMAs per tile and the outer product of Sec. 3.2 is
-// never formed.  The contraction index is split in four contiguous chunks of
-// JC = ceil(K/4), one per lane group; the order of a sum's terms is free.
-template <int JC>
-__global__ __launch_bounds__(512) void k_einsum_forward(const int32_t* __restrict__ e_left,
+// With eL = exp(L - a), eR = exp(R - a') (a, a' the row maxima; Eq. 4) the layer needs
+//     S~[b,k] = sum_i eL[b,i] * T[(k,i), b],   T[(k,i), b] = sum_j W[k,i,j] eR[b,j].
+// T is a dense GEMM (rows (k,i), columns b, contraction j) on v_mfma_f32_16x16x4_f32;
+// one MFMA tile holds 4 outputs k (one per 16-lane group) x 4 inputs i (one per
+// accumulator register), so the i-reduction of Eq. 4 is four in-lane FMAs per tile
+// and the K x K outer product of Sec. 3.2 is never formed.
+//
+// One workgroup per (einsum item, tile of 4 outputs k).  Its slice W[4 k][K][K] is
+// contiguous in memory; it is staged once in LDS, zero-padded to multiples of 4,
+// with row strides chosen so that the A-operand reads of a half-wave hit 32
+// distinct banks (i-stride = 8 mod 16, k-stride = 2 mod 32, lane groups read
+// consecutive j).  Every wave then takes tiles of 16 samples: eR (the B operand)
+// lives in registers, eL in a wave-private LDS tile, and each tile costs KQ*KQ
+// MFMAs (KQ = ceil(K/4)).
+template <int KQ>
+struct FwdLayout {
+    static constexpr int KP = 4 * KQ;
+    static constexpr int SJ = ((KP + 7) / 16) * 16 + 8;   // smallest value >= KP that is 8 mod 16
+    static constexpr int SK = KP * SJ + 2;
+    static constexpr int LDS_W = ((4 * SK + 3) / 4) * 4;  // W slice, rounded so the eL tiles stay 16-byte aligned
+    static constexpr int SE = KP + 4;                     // row stride of a wave's eL tile
+    static constexpr int LDS_FLOATS = LDS_W + 8 * 16 * SE;
+};
+
+template <int KQ>
+__global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __restrict__ e_left,
                                                         const int32_t* __restrict__ e_right,
                                                         const int32_t* __restrict__ e_out,
                                                         const int32_t* __restrict__ e_kout,
                                                         const int32_t* __restrict__ e_woff,
                                                         const float* __restrict__ params, float* __restrict__ A,
-                                                        int B, int K, int n_btiles) {
-    constexpr int KP = 4 * JC;
-    __shared__ float sL[16 * KP];
-    __shared__ float sR[16 * KP];
-    __shared__ float sM[32];
+                                                        float* __restrict__ amax, int item0, int B, int K,
+                                                        int nkt) {
+    using LY = FwdLayout<KQ>;
+    constexpr int KP = LY::KP, SJ = LY::SJ, SK = LY::SK;
+    extern __shared__ float Wl[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
-    const int item = blockIdx.x / n_btiles, bt = blockIdx.x - item * n_btiles;
-    const int kout = e_kout[item];
-    const float* Lp = A + (size_t)e_left[item] * B * K;
-    const float* Rp = A + (size_t)e_right[item] * B * K;
-    const float* W = params + e_woff[item];
+    const int li = blockIdx.x / nkt, kt = blockIdx.x - li * nkt;
+    const int item = item0 + li;
+    const int kout = e_kout[li];
+    if (4 * kt >= kout) return;                        // root items have a single output entry
+    const float* Lp = A + (size_t)e_left[li] * B * K;
+    const float* Rp = A + (size_t)e_right[li] * B * K;
+    const float* W = params + e_woff[li];
 
-    for (int idx = tid; idx < 16 * KP; idx += blockDim.x) {
-        const int row = idx / KP, col = idx - row * KP, b = bt * 16 + row;
-        float vl = -INFINITY, vr = -INFINITY;
-        if (b < B && col < K) {
-            vl = Lp[(size_t)b * K + col];
-            vr = Rp[(size_t)b * K + col];
+    // stage W[4kt .. 4kt+3][.][.]
+    if ((K & 3) == 0) {
+        for (int q = tid; q < 4 * KP * KQ; q += blockDim.x) {
+            const int j4 = q % KQ, i = (q / KQ) % KP, kl = q / (KQ * KP);
+            const int k = 4 * kt + kl;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < kout && i < K) v = *reinterpret_cast<const float4*>(W + ((size_t)k * K + i) * K + 4 * j4);
+            float* dst = Wl + kl * SK + i * SJ + 4 * j4;
+            *reinterpret_cast<float2*>(dst) = make_float2(v.x, v.y);
+            *reinterpret_cast<float2*>(dst + 2) = make_float2(v.z, v.w);
         }
-        sL[idx] = vl;
-        sR[idx] = vr;
-    }
-    __syncthreads();
-    if (tid < 32) {
-        const float* src = (tid < 16) ? sL : sR;
-        const int row = tid & 15;
-        float m = -INFINITY;
-        for (int col = 0; col < K; ++col) m = fmaxf(m, src[row * KP + col]);
-        sM[tid] = (m == -INFINITY) ? 0.f : m;   // an all-zero input vector: keep exp(-inf) = 0, no NaN
-    }
-    __syncthreads();
-    for (int idx = tid; idx < 16 * KP; idx += blockDim.x) {
-        const int row = idx / KP;
-        sL[idx] = expf(sL[idx] - sM[row]);
-        sR[idx] = expf(sR[idx] - sM[16 + row]);
+    } else {
+        for (int q = tid; q < 4 * KP * KP; q += blockDim.x) {
+            const int j = q % KP, i = (q / KP) % KP, kl = q / (KP * KP);
+            const int k = 4 * kt + kl;
+            float v = 0.f;
+            if (k < kout && i < K && j < K) v = W[((size_t)k * K + i) * K + j];
+            Wl[kl * SK + i * SJ + j] = v;
+        }
     }
     __syncthreads();
 
-    const int c = lane & 15, g = lane >> 4;          // sample column, lane group
-    const int gm = c >> 2, rm = c & 3;               // as A-operand lane: row 4*gm+rm -> (k = 4kt+gm, i = 4it+rm)
-    float er[JC];
+    const int c = lane & 15, g = lane >> 4;          // sample column of the tile, lane group
+    const int gm = c >> 2, rm = c & 3;               // as A-operand lane: row 4*gm+rm = (k = 4kt+gm, i = 4it+rm)
+    const float* wl = Wl + gm * SK + rm * SJ + g;    // + it*4*SJ + 4*s : contraction index j = 4s + g
+    float* elw = Wl + LY::LDS_W + wave * (16 * LY::SE);   // this wave's eL tile [16][SE]
+    const int n_btiles = (B + 15) >> 4;
+    for (int bt0 = 0; bt0 < n_btiles; bt0 += nwaves) {
+        const int bt = bt0 + wave;
+        const int b = bt * 16 + c;
+        const bool ok = bt < n_btiles && b < B;
+        // lane (c, g) holds entries 4s+g of row b of both inputs
+        float er[KQ], el[KQ];
+        float mr = -INFINITY, ml = -INFINITY;
 #pragma unroll
-    for (int s = 0; s < JC; ++s) er[s] = sR[c * KP + g * JC + s];
-    const int b = bt * 16 + c;
-    const int nkt = (kout + 3) >> 2;
-    for (int kt = wave; kt < nkt; kt += nwaves) {
-        const int ka = 4 * kt + gm;
+        for (int s = 0; s < KQ; ++s) {
+            const int j = 4 * s + g;
+            const bool in = ok && j < K;
+            er[s] = in ? Rp[(size_t)b * K + j] : -INFINITY;
+            el[s] = in ? Lp[(size_t)b * K + j] : -INFINITY;
+            mr = fmaxf(mr, er[s]);
+            ml = fmaxf(ml, el[s]);
+        }
+        mr = fmaxf(mr, __shfl_xor(mr, 16, 64));
+        mr = fmaxf(mr, __shfl_xor(mr, 32, 64));
+        ml = fmaxf(ml, __shfl_xor(ml, 16, 64));
+        ml = fmaxf(ml, __shfl_xor(ml, 32, 64));
+        if (mr == -INFINITY) mr = 0.f;               // an all-zero input vector: exp(-inf) = 0, no NaN
+        if (ml == -INFINITY) ml = 0.f;
+        __syncthreads();                             // previous tile's eL reads are done
+#pragma unroll
+        for (int s = 0; s < KQ; ++s) {
+            er[s] = expf(er[s] - mr);                // stays in registers: the B operand
+            elw[c * LY::SE + 4 * s + g] = expf(el[s] - ml);
+        }
+        __syncthreads();
         float sacc = 0.f;
-        for (int it = 0; it < JC; ++it) {
-            const int ia = 4 * it + rm;
-            const bool row_ok = (ka < kout) && (ia < K);
-            const float* wrow = W + ((size_t)ka * K + ia) * K + g * JC;
+#pragma unroll
+        for (int it = 0; it < KQ; ++it) {
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < JC; ++s) {
-                const float w = (row_ok && (g * JC + s < K)) ? wrow[s] : 0.f;
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w, er[s], acc, 0, 0, 0);
-            }
-            const float* el = sL + c * KP + 4 * it;
-            sacc += acc[0] * el[0] + acc[1] * el[1] + acc[2] * el[2] + acc[3] * el[3];
+            for (int s = 0; s < KQ; ++s)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wl[it * 4 * SJ + 4 * s], er[s], acc, 0, 0, 0);
+            const float4 e4 = *reinterpret_cast<const float4*>(elw + c * LY::SE + 4 * it);
+            sacc += acc[0] * e4.x + acc[1] * e4.y + acc[2] * e4.z + acc[3] * e4.w;
         }
         const int k = 4 * kt + g;
-        if (b < B && k < kout) A[((size_t)e_out[item] * B + b) * K + k] = sM[c] + sM[16 + c] + logf(sacc);
+        if (ok && k < kout) A[((size_t)e_out[li] * B + b) * K + k] = ml + mr + logf(sacc);
+        if (ok && kt == 0 && g == 0) {                 // the shifts, kept for the top-down pass
+            amax[((size_t)item * 2) * B + b] = ml;
+            amax[((size_t)item * 2 + 1) * B + b] = mr;
+        }
     }
 }
 
@@ -185,206 +222,270 @@ __global__ void k_copy_root(const float* __restrict__ A, float* __restrict__ log
 }
 
 // ------------------------------------------------------------------ top-down pass, regions
-// One workgroup per region of the layer.  G[region] = sum of the slots its
-// parent partitions wrote (1 at the root).  A region with several partitions
-// also splits its posterior among its simple sums, rho = v * S^c / S (derivative
-// of the mixture of App. B), and adds sum_b G*rho to the mixing statistics.
-__global__ __launch_bounds__(256) void k_region_backward(
-    const int32_t* __restrict__ r_node, const int32_t* __restrict__ r_kout, const int32_t* __restrict__ r_mix,
-    const int32_t* __restrict__ r_pptr, const int32_t* __restrict__ r_pslot, const int32_t* __restrict__ m_cptr,
-    const int32_t* __restrict__ m_child, const int32_t* __restrict__ m_voff, int is_root,
-    const float* __restrict__ params, float* __restrict__ stats, const float* __restrict__ A, float* __restrict__ G,
-    const float* __restrict__ Gp, int B, int K) {
-    __shared__ float red[256];
-    const int item = blockIdx.x, tid = threadIdx.x;
-    const int node = r_node[item], kout = r_kout[item];
-    const int nbl = 256 / kout;                      // sample lanes per entry
-    const int k = tid % kout, bl = tid / kout;
-    const bool active = bl < nbl;
-    const int p0 = r_pptr[item], p1 = r_pptr[item + 1];
-    if (active)
+// G[region][b][k] = sum of the posterior blocks its parent partitions wrote (1 at
+// the root).  Element-wise, one thread per (region, b, k); summing here instead of
+// scattering from the producers keeps the pass free of atomics.
+__global__ void k_region_assemble(const int32_t* __restrict__ r_node, const int32_t* __restrict__ r_kout,
+                                  const int32_t* __restrict__ r_pptr, const int32_t* __restrict__ r_pstart,
+                                  const int32_t* __restrict__ r_pcnt, int is_root, float* __restrict__ G,
+                                  const float* __restrict__ Gp, int B, int K) {
+    const int item = blockIdx.x;
+    const int kout = r_kout[item];
+    const int e = blockIdx.y * blockDim.x + threadIdx.x;
+    if (e >= B * kout) return;
+    const int b = e / kout, k = e - b * kout;
+    const size_t blk = (size_t)B * K, o = (size_t)b * K + k;
+    float g = is_root ? 1.f : 0.f;
+    for (int p = r_pptr[item]; p < r_pptr[item + 1]; ++p) {
+        const float* src = Gp + (size_t)r_pstart[p] * blk + o;
+        const int n = r_pcnt[p];
+        for (int q = 0; q < n; ++q) g += src[q * blk];
+    }
+    G[(size_t)r_node[item] * blk + o] = g;
+}
+
+// Statistics of the mixing weights (App. B, Eq. 6): Nv[s,k,c] += v[s,k,c] * sum_b G[s][b,k] * S^c[b,k] / S[b,k].
+// One workgroup per (mixing item, child); a reduction over the batch through LDS.
+__global__ __launch_bounds__(1024) void k_mixing_stats(const int32_t* __restrict__ m_node,
+                                                       const int32_t* __restrict__ m_kout,
+                                                       const int32_t* __restrict__ m_cptr,
+                                                       const int32_t* __restrict__ m_child,
+                                                       const int32_t* __restrict__ m_voff,
+                                                       const float* __restrict__ params, float* __restrict__ stats,
+                                                       const float* __restrict__ A, const float* __restrict__ G, int B,
+                                                       int K) {
+    __shared__ float red[1024];
+    const int item = blockIdx.x, c = blockIdx.y, tid = threadIdx.x;
+    const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
+    if (c >= nc) return;
+    const int kout = m_kout[item];
+    const int nbl = 1024 / kout, k = tid % kout, bl = tid / kout;
+    const float* As = A + (size_t)m_node[item] * B * K;
+    const float* Ac = A + (size_t)m_child[c0 + c] * B * K;
+    const float* Gs = G + (size_t)m_node[item] * B * K;
+    float part = 0.f;
+    if (bl < nbl)
         for (int b = bl; b < B; b += nbl) {
-            float g = is_root ? 1.f : 0.f;
-            for (int p = p0; p < p1; ++p) g += Gp[((size_t)r_pslot[p] * B + b) * K + k];
-            G[((size_t)node * B + b) * K + k] = g;
+            const size_t o = (size_t)b * K + k;
+            const float g = Gs[o];
+            if (g != 0.f) part += g * expf(Ac[o] - As[o]);
         }
-    const int mix = r_mix[item];
-    if (mix < 0) return;
-    const int c0 = m_cptr[mix], nc = m_cptr[mix + 1] - c0;
-    for (int c = 0; c < nc; ++c) {
-        const int child = m_child[c0 + c];
-        float part = 0.f;
-        if (active) {
-            const float vkc = params[m_voff[mix] + (size_t)k * nc + c];
-            for (int b = bl; b < B; b += nbl) {
-                const size_t o = (size_t)b * K + k;
-                const float g = G[(size_t)node * B * K + o];     // written by this thread above
-                float gr = 0.f;
-                if (g != 0.f) gr = g * vkc * expf(A[(size_t)child * B * K + o] - A[(size_t)node * B * K + o]);
-                G[(size_t)child * B * K + o] = gr;
-                part += gr;
-            }
-        }
-        red[tid] = part;
-        __syncthreads();
-        if (active && bl == 0) {
-            float tot = 0.f;
-            for (int l = 0; l < nbl; ++l) tot += red[l * kout + k];
-            stats[m_voff[mix] + (size_t)k * nc + c] += tot;
-        }
-        __syncthreads();
+    red[tid] = part;
+    __syncthreads();
+    if (tid < kout) {
+        float tot = 0.f;
+        for (int l = 0; l < nbl; ++l) tot += red[l * kout + tid];
+        const size_t o = (size_t)m_voff[item] + (size_t)tid * nc + c;
+        stats[o] += params[o] * tot;
     }
 }
 
 // ------------------------------------------------------------------ top-down pass, einsum items
-// Weight statistics (Eq. 6): Nw[k,i,j] += W[k,i,j] * sum_b Q[b,k] eL[b,i] eR[b,j],
-// Q = G_out / S~ with S~ = exp(A_out - a - a') the shifted sum of Eq. 4.
-// One workgroup per (item, k); the batch is walked in chunks staged in LDS.
-constexpr int BW_CHUNK = 32;
-__global__ __launch_bounds__(256) void k_einsum_backward_w(
-    const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_out,
-    const int32_t* __restrict__ e_kout, const int32_t* __restrict__ e_woff, const float* __restrict__ params,
-    float* __restrict__ stats, const float* __restrict__ A, const float* __restrict__ G, int B, int K) {
-    __shared__ float sL[BW_CHUNK * KMAX];
-    __shared__ float sR[BW_CHUNK * KMAX];
-    __shared__ float sM[2 * BW_CHUNK];
-    __shared__ float sQ[BW_CHUNK];
-    const int item = blockIdx.x, k = blockIdx.y, tid = threadIdx.x;
-    if (k >= e_kout[item]) return;
-    const float* Lp = A + (size_t)e_left[item] * B * K;
-    const float* Rp = A + (size_t)e_right[item] * B * K;
-    const float* Op = A + (size_t)e_out[item] * B * K;
-    const float* Gout = G + (size_t)e_out[item] * B * K;
-    const int KK = K * K;
-    float acc[KMAX * KMAX / 256];
+// For one einsum item, with Q[b,k] = G_out[b,k] / S~[b,k] (S~ the shifted sum of Eq. 4):
+//   weight statistics (Eq. 6)   Nw[k,i,j] += W[k,i,j] * sum_b Q[b,k] eL[b,i] eR[b,j]        (GEMM-1)
+//   posterior of the children   U[b,i,j]   = sum_k Q[b,k] W[k,i,j]                           (GEMM-2)
+//                               Gp_left[b,i]  = eL[b,i] sum_j U[b,i,j] eR[b,j]
+//                               Gp_right[b,j] = eR[b,j] sum_i U[b,i,j] eL[b,i]
+// G_out is the posterior of the item's region times, for a region with several
+// partitions, the mixing weight and S^c/S; S^c cancels against S~, leaving
+//   Q = G[s] * v * exp(a + a' - A[s]).
+// One workgroup per (item, slice of four left entries i).  The slice W[:, 4 i, :]
+// is staged once in LDS and serves both GEMMs, so W is read once per pass.
+// GEMM-1 contracts over the batch: rows (k, i) in tiles of 4x4, columns j in tiles
+// of 16; the A operand Q*eL is formed on the fly, eR tiles sit in registers.
+// GEMM-2 contracts over k: rows (i, j) in tiles of 4x4, columns = 16 samples, one
+// sample tile per wave; the reductions over j (left) and over the slice's four i
+// (right) happen in registers.  Gp_left is complete for the slice's entries;
+// Gp_right is a partial sum, written to the slice's own block and added up by
+// k_region_assemble.
+template <int KQ>
+struct BwdLayout {
+    static constexpr int KP = 4 * KQ;
+    static constexpr int SI = ((KP + 7) / 16) * 16 + 8;   // stride between the slice's i rows: 8 mod 16
+    static constexpr int S = 4 * SI + 4;                  // stride between k rows: 4 mod 32
+    static constexpr int NJ = (KP + 15) / 16;             // column tiles of GEMM-1
+    static constexpr int SR = 16 * (NJ | 1);              // eR row stride: 16 mod 32
+    static constexpr int SQ = KP + 1;                     // Q row stride: odd
+    static constexpr int BC = 128;                        // samples per pass over the batch
+    static constexpr int OFF_R = KP * S;
+    static constexpr int OFF_Q = OFF_R + BC * SR;
+    static constexpr int OFF_L = ((OFF_Q + BC * SQ + 3) / 4) * 4;
+    static constexpr int LDS_FLOATS = OFF_L + BC * 4;
+    static constexpr int MAXU = (NJ * KQ + 7) / 8;        // GEMM-1 tiles per wave
+};
+
+template <int KQ>
+__global__ __launch_bounds__(512, 2) void k_einsum_backward(
+    const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_reg,
+    const int32_t* __restrict__ e_kout, const int32_t* __restrict__ e_woff, const int32_t* __restrict__ e_voff,
+    const int32_t* __restrict__ e_vstr, const float* __restrict__ params, float* __restrict__ stats,
+    const float* __restrict__ A, const float* __restrict__ amax, const float* __restrict__ G, float* __restrict__ Gp,
+    int item0, int B, int K) {
+    using LY = BwdLayout<KQ>;
+    constexpr int KP = LY::KP, SI = LY::SI, S = LY::S, SR = LY::SR, SQ = LY::SQ, BC = LY::BC;
+    extern __shared__ float lds[];
+    float* Wl = lds;
+    float* sR = lds + LY::OFF_R;
+    float* sQ = lds + LY::OFF_Q;
+    float* sL = lds + LY::OFF_L;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = blockIdx.x / KQ, it = blockIdx.x - li * KQ;
+    const int item = item0 + li;
+    const int kout = e_kout[li], nkt = (kout + 3) >> 2;
+    const size_t blk = (size_t)B * K;
+    const float* Lp = A + (size_t)e_left[li] * blk;
+    const float* Rp = A + (size_t)e_right[li] * blk;
+    const float* As = A + (size_t)e_reg[li] * blk;
+    const float* Gs = G + (size_t)e_reg[li] * blk;
+    const float* W = params + e_woff[li];
+    const int voff = e_voff[li], vstr = e_vstr[li];
+    const float* aL = amax + (size_t)item * 2 * B;
+    const float* aR = aL + B;
+
+    // stage W[:, 4it .. 4it+3, :], zero-padded
+    if ((K & 3) == 0) {
+        for (int q = tid; q < KP * 4 * KQ; q += 512) {
+            const int j4 = q % KQ, il = (q / KQ) & 3, k = q / (4 * KQ);
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < kout) v = *reinterpret_cast<const float4*>(W + ((size_t)k * K + 4 * it + il) * K + 4 * j4);
+            *reinterpret_cast<float4*>(Wl + k * S + il * SI + 4 * j4) = v;
+        }
+    } else {
+        for (int q = tid; q < KP * 4 * KP; q += 512) {
+            const int j = q % KP, il = (q / KP) & 3, k = q / (4 * KP);
+            const int i = 4 * it + il;
+            float v = 0.f;
+            if (k < kout && i < K && j < K) v = W[((size_t)k * K + i) * K + j];
+            Wl[k * S + il * SI + j] = v;
+        }
+    }
+
+    const int c = lane & 15, g = lane >> 4;
+    const int gm = c >> 2, rm = c & 3;
+    const int U = LY::NJ * nkt;
+    const int u0 = wave * U / 8, u1 = (wave + 1) * U / 8;
+    floatx4 acc1[LY::MAXU];
 #pragma unroll
-    for (int m = 0; m < KMAX * KMAX / 256; ++m) acc[m] = 0.f;
-    for (int b0 = 0; b0 < B; b0 += BW_CHUNK) {
-        const int nb = min(BW_CHUNK, B - b0);
-        for (int idx = tid; idx < nb * K; idx += 256) {
-            sL[idx] = Lp[(size_t)b0 * K + idx];
-            sR[idx] = Rp[(size_t)b0 * K + idx];
+    for (int q = 0; q < LY::MAXU; ++q) acc1[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int nblk = 1 + KQ;
+
+    for (int b0 = 0; b0 < B; b0 += BC) {
+        const int nb = min(BC, B - b0);
+        if (b0) __syncthreads();
+        for (int q = tid; q < BC * SR; q += 512) {
+            const int b = q / SR, j = q - b * SR;
+            float v = 0.f;
+            if (b < nb && j < K) v = expf(Rp[(size_t)(b0 + b) * K + j] - aR[b0 + b]);
+            sR[q] = v;
+        }
+        for (int q = tid; q < BC * KP; q += 512) {
+            const int b = q / KP, k = q - b * KP;
+            float v = 0.f;
+            if (b < nb && k < kout) {
+                const float gs = Gs[(size_t)(b0 + b) * K + k];
+                if (gs != 0.f) {
+                    const float vw = voff >= 0 ? params[voff + k * vstr] : 1.f;
+                    v = gs * vw * expf(aL[b0 + b] + aR[b0 + b] - As[(size_t)(b0 + b) * K + k]);
+                }
+            }
+            sQ[b * SQ + k] = v;
+        }
+        for (int q = tid; q < BC * 4; q += 512) {
+            const int b = q >> 2, i = 4 * it + (q & 3);
+            float v = 0.f;
+            if (b < nb && i < K) v = expf(Lp[(size_t)(b0 + b) * K + i] - aL[b0 + b]);
+            sL[q] = v;
         }
         __syncthreads();
-        if (tid < 2 * nb) {
-            const float* src = (tid < nb) ? sL : sR;
-            const int row = (tid < nb) ? tid : tid - nb;
-            float m = -INFINITY;
-            for (int col = 0; col < K; ++col) m = fmaxf(m, src[row * K + col]);
-            sM[tid] = (m == -INFINITY) ? 0.f : m;
-        }
-        __syncthreads();
-        for (int idx = tid; idx < nb * K; idx += 256) {
-            const int row = idx / K;
-            sL[idx] = expf(sL[idx] - sM[row]);
-            sR[idx] = expf(sR[idx] - sM[nb + row]);
-        }
-        if (tid < nb) {
-            const float g = Gout[(size_t)(b0 + tid) * K + k];
-            sQ[tid] = (g != 0.f) ? g * expf(sM[tid] + sM[nb + tid] - Op[(size_t)(b0 + tid) * K + k]) : 0.f;
-        }
-        __syncthreads();
+
+        // ---- GEMM-1: this wave's tiles (jt, kt), contraction over the nb samples in steps of 4
+        {
+            const int nsteps = (nb + 3) >> 2;
+            float el[32], er[32];
 #pragma unroll
-        for (int m = 0; m < KMAX * KMAX / 256; ++m) {
-            const int ij = tid + m * 256;
-            if (ij < KK) {
-                const int i = ij / K, j = ij - i * K;
-                float a = 0.f;
-                for (int b = 0; b < nb; ++b) a = fmaf(sQ[b] * sL[b * K + i], sR[b * K + j], a);
-                acc[m] += a;
+            for (int s = 0; s < 32; ++s) el[s] = sL[(4 * s + g) * 4 + rm];
+            int cur_jt = -1;
+#pragma unroll
+            for (int q = 0; q < LY::MAXU; ++q) {
+                const int u = u0 + q;
+                if (u < u1) {
+                    const int jt = u / nkt, kt = u - jt * nkt;
+                    if (jt != cur_jt) {
+#pragma unroll
+                        for (int s = 0; s < 32; ++s) er[s] = sR[(4 * s + g) * SR + 16 * jt + c];
+                        cur_jt = jt;
+                    }
+                    const float* qcol = sQ + g * SQ + 4 * kt + gm;
+#pragma unroll
+                    for (int s8 = 0; s8 < 4; ++s8) {
+                        if (8 * s8 < nsteps) {
+#pragma unroll
+                            for (int t = 0; t < 8; ++t) {
+                                const int s = 8 * s8 + t;
+                                acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qcol[4 * s * SQ] * el[s], er[s],
+                                                                               acc1[q], 0, 0, 0);
+                            }
+                        }
+                    }
+                }
             }
         }
-        __syncthreads();
-    }
-    const size_t base = (size_t)e_woff[item] + (size_t)k * KK;
-#pragma unroll
-    for (int m = 0; m < KMAX * KMAX / 256; ++m) {
-        const int ij = tid + m * 256;
-        if (ij < KK) stats[base + ij] += params[base + ij] * acc[m];
-    }
-}
 
-// Posterior sent to the children (chain rule through Eq. 4):
-//   U[b,i,j] = sum_k Q[b,k] W[k,i,j];  Gp_left[b,i] = eL[b,i] sum_j U eR[b,j];
-//   Gp_right[b,j] = eR[b,j] sum_i U eL[b,i].
-// One workgroup per (item, 16 samples); a wave takes 4 samples, lanes are j.
-constexpr int BG_SAMPLES = 4;
-__global__ __launch_bounds__(256) void k_einsum_backward_g(
-    const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_out,
-    const int32_t* __restrict__ e_kout, const int32_t* __restrict__ e_woff, const float* __restrict__ params,
-    const float* __restrict__ A, const float* __restrict__ G, float* __restrict__ Gp, int item0, int B, int K) {
-    constexpr int NB = 4 * BG_SAMPLES;
-    __shared__ float sL[NB * KMAX];
-    __shared__ float sR[NB * KMAX];
-    __shared__ float sQ[NB * KMAX];
-    __shared__ float sM[2 * NB];
-    const int item = item0 + blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int b0 = blockIdx.y * NB;
-    const int nb = min(NB, B - b0);
-    const int kout = e_kout[item];
-    const float* Lp = A + (size_t)e_left[item] * B * K;
-    const float* Rp = A + (size_t)e_right[item] * B * K;
-    const float* Op = A + (size_t)e_out[item] * B * K;
-    const float* Gout = G + (size_t)e_out[item] * B * K;
-    const float* W = params + e_woff[item];
-    for (int idx = tid; idx < NB * K; idx += 256) {
-        const bool ok = idx < nb * K;
-        sL[idx] = ok ? Lp[(size_t)b0 * K + idx] : -INFINITY;
-        sR[idx] = ok ? Rp[(size_t)b0 * K + idx] : -INFINITY;
-    }
-    __syncthreads();
-    if (tid < 2 * NB) {
-        const float* src = (tid < NB) ? sL : sR;
-        const int row = (tid < NB) ? tid : tid - NB;
-        float m = -INFINITY;
-        for (int col = 0; col < K; ++col) m = fmaxf(m, src[row * K + col]);
-        sM[tid] = (m == -INFINITY) ? 0.f : m;
-    }
-    __syncthreads();
-    for (int idx = tid; idx < NB * K; idx += 256) {
-        const int row = idx / K, col = idx - row * K;
-        sL[idx] = expf(sL[idx] - sM[row]);
-        sR[idx] = expf(sR[idx] - sM[NB + row]);
-        float q = 0.f;
-        if (row < nb && col < kout) {
-            const float g = Gout[(size_t)(b0 + row) * K + col];
-            if (g != 0.f) q = g * expf(sM[row] + sM[NB + row] - Op[(size_t)(b0 + row) * K + col]);
-        }
-        sQ[idx] = q;
-    }
-    __syncthreads();
-    const int j = lane;
-    const bool jok = j < K;
-    float accR[BG_SAMPLES], gl[BG_SAMPLES], erj[BG_SAMPLES];
+        // ---- GEMM-2: one tile of 16 samples per wave
+        if (wave * 16 < nb) {
+            const int bl = wave * 16 + c;
+            const bool ok = bl < nb;
+            float qv[KQ];
 #pragma unroll
-    for (int s = 0; s < BG_SAMPLES; ++s) {
-        accR[s] = 0.f;
-        gl[s] = 0.f;
-        erj[s] = jok ? sR[(wave * BG_SAMPLES + s) * K + j] : 0.f;
-    }
-    for (int i = 0; i < K; ++i) {
-        float U[BG_SAMPLES];
+            for (int s = 0; s < KQ; ++s) qv[s] = sQ[bl * SQ + 4 * s + g];
+            const float elv = sL[bl * 4 + g];
+            const float* wl = Wl + g * S + gm * SI + rm;
+            float gl = 0.f;
+            float* right = Gp + ((size_t)(item * nblk + 1 + it) * B + b0 + bl) * K;
 #pragma unroll
-        for (int s = 0; s < BG_SAMPLES; ++s) U[s] = 0.f;
-        for (int k = 0; k < kout; ++k) {
-            const float w = jok ? W[((size_t)k * K + i) * K + j] : 0.f;
+            for (int jt = 0; jt < KQ; ++jt) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < BG_SAMPLES; ++s) U[s] = fmaf(sQ[(wave * BG_SAMPLES + s) * K + k], w, U[s]);
-        }
+                for (int s = 0; s < KQ; ++s)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wl[4 * s * S + 4 * jt], qv[s], acc, 0, 0, 0);
+                const float4 e4 = *reinterpret_cast<const float4*>(sR + bl * SR + 4 * jt);
+                gl += acc[0] * e4.x + acc[1] * e4.y + acc[2] * e4.z + acc[3] * e4.w;
+                float t[4];
 #pragma unroll
-        for (int s = 0; s < BG_SAMPLES; ++s) {
-            accR[s] = fmaf(U[s], sL[(wave * BG_SAMPLES + s) * K + i], accR[s]);
-            const float t = wave_sum(U[s] * erj[s]);
-            if (lane == i) gl[s] = t;
+                for (int r = 0; r < 4; ++r) {
+                    t[r] = acc[r] * elv;                       // sum over the slice's four i = the four lane groups
+                    t[r] += __shfl_xor(t[r], 16, 64);
+                    t[r] += __shfl_xor(t[r], 32, 64);
+                }
+                if (ok && (jt & 3) == g) {
+                    if (4 * jt + 0 < K) right[4 * jt + 0] = t[0] * e4.x;
+                    if (4 * jt + 1 < K) right[4 * jt + 1] = t[1] * e4.y;
+                    if (4 * jt + 2 < K) right[4 * jt + 2] = t[2] * e4.z;
+                    if (4 * jt + 3 < K) right[4 * jt + 3] = t[3] * e4.w;
+                }
+            }
+            if (ok && 4 * it + g < K) Gp[((size_t)(item * nblk) * B + b0 + bl) * K + 4 * it + g] = elv * gl;
         }
     }
+
+    // ---- GEMM-1 epilogue: Nw += W * acc
+    const size_t wbase = (size_t)e_woff[li];
 #pragma unroll
-    for (int s = 0; s < BG_SAMPLES; ++s) {
-        const int row = wave * BG_SAMPLES + s;
-        if (row < nb && jok) {
-            const size_t o = (size_t)(b0 + row) * K + j;
-            Gp[(size_t)(2 * item) * B * K + o] = sL[row * K + j] * gl[s];
-            Gp[(size_t)(2 * item + 1) * B * K + o] = erj[s] * accR[s];
+    for (int q = 0; q < LY::MAXU; ++q) {
+        const int u = u0 + q;
+        if (u < u1) {
+            const int jt = u / nkt, kt = u - jt * nkt;
+            const int k = 4 * kt + g, j = 16 * jt + c;
+            if (k < kout && j < K) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int i = 4 * it + r;
+                    if (i < K) {
+                        const size_t idx = wbase + ((size_t)k * K + i) * K + j;
+                        stats[idx] += Wl[k * S + r * SI + j] * acc1[q][r];
+                    }
+                }
+            }
         }
     }
 }
@@ -488,13 +589,6 @@ __global__ void k_fill(float* __restrict__ p, float value, int64_t n) {
     for (; i < n; i += stride) p[i] = value;
 }
 
-int pick_waves(int nkt) {
-    // waves per workgroup: the largest count up to 8 that splits the k-tiles evenly, else 4
-    for (int w = 8; w >= 2; --w)
-        if (nkt % w == 0) return w;
-    return nkt < 4 ? nkt : 4;
-}
-
 }  // namespace
 
 // ====================================================================== launchers
@@ -511,21 +605,29 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, const float* x, const
                        mask, mask_mode, theta, A, d);
 }
 
-template <int JC>
-static void launch_einsum_forward_jc(const DevTables& t, int first, int count, const float* params, float* A,
-                                     const Dims& d, hipStream_t s) {
+template <int KQ>
+static void launch_einsum_forward_kq(const DevTables& t, int first, int count, const float* params, float* A,
+                                     float* amax, const Dims& d, hipStream_t s) {
+    const int nkt = (d.K + 3) / 4;
     const int n_btiles = (d.B + 15) / 16;
-    const int nw = pick_waves((d.K + 3) / 4);
-    hipLaunchKernelGGL(k_einsum_forward<JC>, dim3(count * n_btiles), dim3(64 * nw), 0, s, t.ein_left + first,
-                       t.ein_right + first, t.ein_out + first, t.ein_kout + first, t.ein_woff + first, params, A, d.B,
-                       d.K, n_btiles);
+    const int nw = n_btiles < 8 ? n_btiles : 8;
+    const size_t lds = sizeof(float) * FwdLayout<KQ>::LDS_FLOATS;
+    static bool attr_set = false;
+    if (lds > 64 * 1024 && !attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_forward<KQ>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_einsum_forward<KQ>, dim3(count * nkt), dim3(64 * nw), lds, s, t.ein_left + first,
+                       t.ein_right + first, t.ein_out + first, t.ein_kout + first, t.ein_woff + first, params, A, amax,
+                       first, d.B, d.K, nkt);
 }
 
-void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, const Dims& d,
-                           hipStream_t s) {
+void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, float* amax,
+                           const Dims& d, hipStream_t s) {
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
-    case J: launch_einsum_forward_jc<J>(t, first, count, params, A, d, s); break;
+    case J: launch_einsum_forward_kq<J>(t, first, count, params, A, amax, d, s); break;
         EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
         EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
         EINET_CASE(16)
@@ -545,21 +647,49 @@ void launch_copy_root(const float* A, float* logp, const Dims& d, hipStream_t s)
     hipLaunchKernelGGL(k_copy_root, dim3((d.B + 255) / 256), dim3(256), 0, s, A, logp, d.B, d.K);
 }
 
-void launch_region_backward(const DevTables& t, int first, int count, bool is_root_layer, const float* params,
-                            float* stats, const float* A, float* G, const float* Gp, const Dims& d, hipStream_t s) {
+void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
+                            const Dims& d, hipStream_t s) {
     if (count == 0) return;
-    hipLaunchKernelGGL(k_region_backward, dim3(count), dim3(256), 0, s, t.rb_node + first, t.rb_kout + first,
-                       t.rb_mix + first, t.rb_pptr + first, t.rb_pslot, t.mix_cptr, t.mix_child, t.mix_voff,
-                       is_root_layer ? 1 : 0, params, stats, A, G, Gp, d.B, d.K);
+    dim3 grid(count, (d.B * d.K + 255) / 256);
+    hipLaunchKernelGGL(k_region_assemble, grid, dim3(256), 0, s, t.rb_node + first, t.rb_kout + first,
+                       t.rb_pptr + first, t.rb_pstart, t.rb_pcnt, is_root_layer ? 1 : 0, G, Gp, d.B, d.K);
+}
+
+void launch_mixing_stats(const DevTables& t, int count, int max_children, const float* params, float* stats,
+                         const float* A, const float* G, const Dims& d, hipStream_t s) {
+    if (count == 0) return;
+    hipLaunchKernelGGL(k_mixing_stats, dim3(count, max_children), dim3(1024), 0, s, t.mix_node, t.mix_kout, t.mix_cptr,
+                       t.mix_child, t.mix_voff, params, stats, A, G, d.B, d.K);
+}
+
+template <int KQ>
+static void launch_einsum_backward_kq(const DevTables& t, int first, int count, const float* params, float* stats,
+                                      const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
+                                      hipStream_t s) {
+    const size_t lds = sizeof(float) * BwdLayout<KQ>::LDS_FLOATS;
+    static bool attr_set = false;
+    if (lds > 64 * 1024 && !attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_einsum_backward<KQ>, dim3(count * KQ), dim3(512), lds, s, t.ein_left + first,
+                       t.ein_right + first, t.ein_reg + first, t.ein_kout + first, t.ein_woff + first,
+                       t.ein_voff + first, t.ein_vstr + first, params, stats, A, amax, G, Gp, first, d.B, d.K);
 }
 
 void launch_einsum_backward(const DevTables& t, int first, int count, const float* params, float* stats,
-                            const float* A, const float* G, float* Gp, const Dims& d, hipStream_t s) {
+                            const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
+                            hipStream_t s) {
     if (count == 0) return;
-    hipLaunchKernelGGL(k_einsum_backward_w, dim3(count, d.K), dim3(256), 0, s, t.ein_left + first, t.ein_right + first,
-                       t.ein_out + first, t.ein_kout + first, t.ein_woff + first, params, stats, A, G, d.B, d.K);
-    hipLaunchKernelGGL(k_einsum_backward_g, dim3(count, (d.B + 15) / 16), dim3(256), 0, s, t.ein_left, t.ein_right,
-                       t.ein_out, t.ein_kout, t.ein_woff, params, A, G, Gp, first, d.B, d.K);
+    switch ((d.K + 3) / 4) {
+#define EINET_CASE(J) \
+    case J: launch_einsum_backward_kq<J>(t, first, count, params, stats, A, amax, G, Gp, d, s); break;
+        EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
+        EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
+        EINET_CASE(16)
+#undef EINET_CASE
+    }
 }
 
 void launch_leaf_backward(const DevTables& t, int n_lv, const float* x, const uint8_t* mask, int mask_mode,

@@ -8,13 +8,18 @@
 
 namespace einet_impl {
 
-// Device copies of the plan tables (pointers into the bound workspace).
+// Index tables of the plan: one int32 vector each on the host (Plan) and one
+// pointer each into the bound workspace on the device (DevTables).
+#define EINET_TABLES(X)                                                                                    \
+    X(ein_left) X(ein_right) X(ein_out) X(ein_reg) X(ein_kout) X(ein_woff) X(ein_voff) X(ein_vstr)         \
+    X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff)                                           \
+    X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
+    X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pstart) X(rb_pcnt) X(row_off) X(row_len)
+
 struct DevTables {
-    const int32_t *ein_left, *ein_right, *ein_out, *ein_kout, *ein_woff;
-    const int32_t *mix_node, *mix_kout, *mix_cptr, *mix_child, *mix_voff;
-    const int32_t *leaf_node, *leaf_replica, *leaf_sptr, *leaf_var, *lv_leaf, *lv_var;
-    const int32_t *rb_node, *rb_kout, *rb_mix, *rb_pptr, *rb_pslot;
-    const int32_t *row_off, *row_len;
+#define X(name) const int32_t* name;
+    EINET_TABLES(X)
+#undef X
 };
 
 struct Dims {
@@ -24,16 +29,22 @@ struct Dims {
 void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream_t s);
 void launch_leaf_forward(const DevTables& t, int n_leaves, const float* x, const uint8_t* mask, int mask_mode,
                          const float* theta, float* A, const Dims& d, hipStream_t s);
-void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, const Dims& d,
-                           hipStream_t s);
+void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, float* amax,
+                           const Dims& d, hipStream_t s);
 void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, const Dims& d,
                            hipStream_t s);
 void launch_copy_root(const float* A, float* logp, const Dims& d, hipStream_t s);
 
-void launch_region_backward(const DevTables& t, int first, int count, bool is_root_layer, const float* params,
-                            float* stats, const float* A, float* G, const float* Gp, const Dims& d, hipStream_t s);
+void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
+                            const Dims& d, hipStream_t s);
 void launch_einsum_backward(const DevTables& t, int first, int count, const float* params, float* stats,
-                            const float* A, const float* G, float* Gp, const Dims& d, hipStream_t s);
+                            const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
+                            hipStream_t s);
+void launch_mixing_stats(const DevTables& t, int count, int max_children, const float* params, float* stats,
+                         const float* A, const float* G, const Dims& d, hipStream_t s);
+// posterior blocks ([B][K] floats each) that one einsum item owns in Gp: one for its left child, then one
+// per slice of four left entries for its right child
+inline int gp_blocks_per_item(int K) { return 1 + (K + 3) / 4; }
 void launch_leaf_backward(const DevTables& t, int n_lv, const float* x, const uint8_t* mask, int mask_mode,
                           const float* G, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off,
                           const Dims& d, hipStream_t s);

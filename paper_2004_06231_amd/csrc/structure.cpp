@@ -230,8 +230,19 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& p, std::
             p.ein_left.push_back(g.partition[n][1]);
             p.ein_right.push_back(g.partition[n][2]);
             p.ein_out.push_back(simple_node[n] >= 0 ? simple_node[n] : parent);
+            p.ein_reg.push_back(parent);
             p.ein_kout.push_back(kout(parent));
             p.ein_woff.push_back((int32_t)p.w_offset[n]);
+            // mixing weight v[parent][k][c] of this partition sits at ein_voff + k * ein_vstr (App. B)
+            const auto& sib = g.parts_of[parent];
+            if (sib.size() > 1) {
+                int c = int(std::find(sib.begin(), sib.end(), n) - sib.begin());
+                p.ein_voff.push_back((int32_t)(p.v_offset[parent] + c));
+                p.ein_vstr.push_back((int32_t)sib.size());
+            } else {
+                p.ein_voff.push_back(-1);
+                p.ein_vstr.push_back(0);
+            }
             p.layer_partition.push_back(n);
         }
         p.ein_layer_ptr.push_back((int32_t)p.ein_left.size());
@@ -239,17 +250,16 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& p, std::
     }
 
     // ---- mixing items per layer
-    std::vector<int> mix_of(nr, -1);
     p.mix_layer_ptr.push_back(0);
     p.mix_cptr.push_back(0);
     for (auto& layer : sum_layers) {
         for (int s : layer) {
             if (g.parts_of[s].size() < 2) continue;
-            mix_of[s] = (int)p.mix_node.size();
             p.mix_node.push_back(s);
             p.mix_kout.push_back(kout(s));
             p.mix_voff.push_back((int32_t)p.v_offset[s]);
             for (int n : g.parts_of[s]) p.mix_child.push_back(simple_node[n]);
+            p.max_mix_children = std::max(p.max_mix_children, (int)g.parts_of[s].size());
             p.mix_cptr.push_back((int32_t)p.mix_child.size());
         }
         p.mix_layer_ptr.push_back((int32_t)p.mix_node.size());
@@ -270,21 +280,25 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& p, std::
         p.leaf_sptr.push_back((int32_t)p.leaf_var.size());
     }
 
-    // ---- top-down items: which posterior slots flow into each region
-    std::vector<std::vector<int>> slots(nr);
+    // ---- top-down items: which posterior blocks flow into each region.  Item e owns blocks
+    // e*nb .. e*nb+nb-1 of Gp: block 0 for its left child, blocks 1.. (one per slice) for its right child.
+    const int nb = gp_blocks_per_item(K);
+    std::vector<std::vector<std::pair<int, int>>> runs(nr);
     for (int n = 0; n < np; ++n) {
-        slots[g.partition[n][1]].push_back(2 * item_of[n]);
-        slots[g.partition[n][2]].push_back(2 * item_of[n] + 1);
+        runs[g.partition[n][1]].push_back({item_of[n] * nb, 1});
+        runs[g.partition[n][2]].push_back({item_of[n] * nb + 1, nb - 1});
     }
     p.rb_layer_ptr.push_back(0);
     p.rb_pptr.push_back(0);
     auto push_region = [&](int s) {
         p.rb_node.push_back(s);
         p.rb_kout.push_back(kout(s));
-        p.rb_mix.push_back(mix_of[s]);
-        std::sort(slots[s].begin(), slots[s].end());
-        for (int sl : slots[s]) p.rb_pslot.push_back(sl);
-        p.rb_pptr.push_back((int32_t)p.rb_pslot.size());
+        std::sort(runs[s].begin(), runs[s].end());
+        for (auto& r : runs[s]) {
+            p.rb_pstart.push_back(r.first);
+            p.rb_pcnt.push_back(r.second);
+        }
+        p.rb_pptr.push_back((int32_t)p.rb_pstart.size());
     };
     for (int l = p.num_layers - 1; l >= 0; --l) {
         for (int s : sum_layers[l]) push_region(s);

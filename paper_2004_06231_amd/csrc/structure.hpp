@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/einet.h"
+#include "kernels.hpp"
 
 namespace einet_impl {
 
@@ -34,21 +35,17 @@ struct Plan {
     int K = 0, C = 0, T = 0, TD = 0, family = 0;
     int num_nodes = 0;      // regions + simple sums
     int num_layers = 0;
+    int max_mix_children = 0;
 
-    // einsum items in execution order (bottom layer first); item e owns posterior slots 2e, 2e+1
-    std::vector<int32_t> ein_left, ein_right, ein_out, ein_kout, ein_woff;
+    // Index tables (see EINET_TABLES): einsum items in execution order (bottom layer first); mixing items
+    // grouped by the layer whose einsum they follow; leaves; top-down items (sum layers from the root
+    // down, then the leaves) with, per region, the runs of posterior blocks its parents write; M-step rows.
+#define X(name) std::vector<int32_t> name;
+    EINET_TABLES(X)
+#undef X
     std::vector<int32_t> ein_layer_ptr;             // [num_layers+1]
-    // mixing items, grouped by the layer whose einsum they follow
-    std::vector<int32_t> mix_node, mix_kout, mix_cptr, mix_child, mix_voff;
     std::vector<int32_t> mix_layer_ptr;             // [num_layers+1]
-    // leaves
-    std::vector<int32_t> leaf_node, leaf_replica, leaf_sptr, leaf_var;
-    std::vector<int32_t> lv_leaf, lv_var;           // one entry per (leaf, variable of its scope)
-    // top-down items: sum layers from the root down, then the leaves
-    std::vector<int32_t> rb_node, rb_kout, rb_mix, rb_pptr, rb_pslot;
     std::vector<int32_t> rb_layer_ptr;              // [num_layers+2]
-    // M-step rows (one per (n,k) and per (s,k))
-    std::vector<int32_t> row_off, row_len;
 
     // ABI view data
     std::vector<int32_t> scope_ptr, scope_var, layer_partition, layer_ptr, partition_flat;
