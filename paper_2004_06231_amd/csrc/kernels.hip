@@ -47,32 +47,49 @@ __global__ void k_leaf_derive(const float* __restrict__ phi, float* __restrict__
 
 // Leaf layer: A[leaf][b][k] = sum over the leaf's scope and the channels of the
 // log-density of x under entry k; a marginalised variable contributes 0.
-__global__ void k_leaf_forward(const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica,
-                               const int32_t* __restrict__ leaf_sptr, const int32_t* __restrict__ leaf_var,
-                               const float* __restrict__ x, const uint8_t* __restrict__ mask, int mask_mode,
-                               const float* __restrict__ theta, float* __restrict__ A, Dims d) {
-    const int leaf = blockIdx.x;
-    const int e = blockIdx.y * blockDim.x + threadIdx.x;
-    if (e >= d.B * d.K) return;
-    const int b = e / d.K, k = e - b * d.K;
+// A workgroup computes 256 consecutive outputs (b, k) of one leaf; its four
+// quarters each take every fourth variable of the scope and the partial sums
+// meet in LDS, so that a long scope does not become a long serial loop.
+__global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict__ leaf_node,
+                                                       const int32_t* __restrict__ leaf_replica,
+                                                       const int32_t* __restrict__ leaf_sptr,
+                                                       const int32_t* __restrict__ leaf_var,
+                                                       const float* __restrict__ x, const uint8_t* __restrict__ mask,
+                                                       int mask_mode, const float* __restrict__ theta,
+                                                       float* __restrict__ A, Dims d) {
+    __shared__ float red[3][256];
+    const int leaf = blockIdx.x, lo = threadIdx.x & 255, quarter = threadIdx.x >> 8;
+    const int f = blockIdx.y * 256 + lo;
+    const bool valid = f < d.B * d.K;
+    const int b = valid ? f / d.K : 0, k = valid ? f - b * d.K : 0;
     const int r = leaf_replica[leaf];
+    const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0;
+    const size_t tstride = (size_t)d.TD * d.K;
     float acc = 0.f;
-    for (int v = leaf_sptr[leaf]; v < leaf_sptr[leaf + 1]; ++v) {
-        const int var = leaf_var[v];
-        if (mask_mode == EINET_MASK_SHARED && !mask[var]) continue;
-        if (mask_mode == EINET_MASK_PER_SAMPLE && !mask[(size_t)b * d.D + var]) continue;
-        for (int c = 0; c < d.C; ++c) {
-            const float xv = x[((size_t)b * d.D + var) * d.C + c];
-            const float* th = theta + ((size_t)(var * d.C + c) * d.R + r) * d.TD * d.K + k;
+#pragma unroll 4
+    for (int v = quarter; v < nv; v += 4) {
+        const int var = leaf_var[s0 + v];
+        bool obs = true;
+        if (mask_mode == EINET_MASK_SHARED) obs = mask[var] != 0;
+        if (mask_mode == EINET_MASK_PER_SAMPLE) obs = mask[(size_t)b * d.D + var] != 0;
+        const float* xp = x + ((size_t)b * d.D + var) * d.C;
+        const float* th = theta + ((size_t)var * d.C * d.R + r) * tstride + k;
+        float part = 0.f;
+        for (int c = 0; c < d.C; ++c, th += (size_t)d.R * tstride) {
+            const float xv = xp[c];
             if (d.family == EINET_LEAF_GAUSSIAN) {
                 const float diff = xv - th[0];
-                acc += fmaf(th[d.K] * diff, diff, th[2 * d.K]);
+                part += fmaf(th[d.K] * diff, diff, th[2 * d.K]);
             } else {
-                acc += xv * th[0] + (1.f - xv) * th[d.K];
+                part += xv * th[0] + (1.f - xv) * th[d.K];
             }
         }
+        acc += obs ? part : 0.f;
     }
-    A[((size_t)leaf_node[leaf] * d.B + b) * d.K + k] = acc;
+    if (quarter) red[quarter - 1][lo] = acc;
+    __syncthreads();
+    if (quarter == 0 && valid)
+        A[((size_t)leaf_node[leaf] * d.B + b) * d.K + k] = acc + red[0][lo] + red[1][lo] + red[2][lo];
 }
 
 // ------------------------------------------------------------------ einsum layer, forward
@@ -226,9 +243,8 @@ __global__ void k_copy_root(const float* __restrict__ A, float* __restrict__ log
 // the root).  Element-wise, one thread per (region, b, k); summing here instead of
 // scattering from the producers keeps the pass free of atomics.
 __global__ void k_region_assemble(const int32_t* __restrict__ r_node, const int32_t* __restrict__ r_kout,
-                                  const int32_t* __restrict__ r_pptr, const int32_t* __restrict__ r_pstart,
-                                  const int32_t* __restrict__ r_pcnt, int is_root, float* __restrict__ G,
-                                  const float* __restrict__ Gp, int B, int K) {
+                                  const int32_t* __restrict__ r_pptr, const int32_t* __restrict__ r_pblk,
+                                  int is_root, float* __restrict__ G, const float* __restrict__ Gp, int B, int K) {
     const int item = blockIdx.x;
     const int kout = r_kout[item];
     const int e = blockIdx.y * blockDim.x + threadIdx.x;
@@ -236,11 +252,9 @@ __global__ void k_region_assemble(const int32_t* __restrict__ r_node, const int3
     const int b = e / kout, k = e - b * kout;
     const size_t blk = (size_t)B * K, o = (size_t)b * K + k;
     float g = is_root ? 1.f : 0.f;
-    for (int p = r_pptr[item]; p < r_pptr[item + 1]; ++p) {
-        const float* src = Gp + (size_t)r_pstart[p] * blk + o;
-        const int n = r_pcnt[p];
-        for (int q = 0; q < n; ++q) g += src[q * blk];
-    }
+    const int p1 = r_pptr[item + 1];
+#pragma unroll 8
+    for (int p = r_pptr[item]; p < p1; ++p) g += Gp[(size_t)r_pblk[p] * blk + o];
     G[(size_t)r_node[item] * blk + o] = g;
 }
 
@@ -292,7 +306,7 @@ __global__ __launch_bounds__(1024) void k_mixing_stats(const int32_t* __restrict
 // One workgroup per (item, slice of four left entries i).  The slice W[:, 4 i, :]
 // is staged once in LDS and serves both GEMMs, so W is read once per pass.
 // GEMM-1 contracts over the batch: rows (k, i) in tiles of 4x4, columns j in tiles
-// of 16; the A operand Q*eL is formed on the fly, eR tiles sit in registers.
+// of 16; the A operand Q*eL is formed on the fly from LDS (Q) and registers (eL).
 // GEMM-2 contracts over k: rows (i, j) in tiles of 4x4, columns = 16 samples, one
 // sample tile per wave; the reductions over j (left) and over the slice's four i
 // (right) happen in registers.  Gp_left is complete for the slice's entries;
@@ -315,7 +329,7 @@ struct BwdLayout {
 };
 
 template <int KQ>
-__global__ __launch_bounds__(512, 2) void k_einsum_backward(
+__global__ __launch_bounds__(512, 4) void k_einsum_backward(
     const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_reg,
     const int32_t* __restrict__ e_kout, const int32_t* __restrict__ e_woff, const int32_t* __restrict__ e_voff,
     const int32_t* __restrict__ e_vstr, const float* __restrict__ params, float* __restrict__ stats,
@@ -369,60 +383,62 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     for (int q = 0; q < LY::MAXU; ++q) acc1[q] = floatx4{0.f, 0.f, 0.f, 0.f};
     const int nblk = 1 + KQ;
 
+    // Staging of the per-sample operands: thread t owns row t/4 of the pass and a quarter
+    // (KQ consecutive entries) of its columns; all global loads are issued before any is used.
+    const int srow = tid >> 2, sq = tid & 3;
+    float vw[KQ];
+#pragma unroll
+    for (int u = 0; u < KQ; ++u) {
+        const int k = sq * KQ + u;
+        vw[u] = (voff >= 0 && k < kout) ? params[voff + k * vstr] : 1.f;
+    }
     for (int b0 = 0; b0 < B; b0 += BC) {
         const int nb = min(BC, B - b0);
         if (b0) __syncthreads();
-        for (int q = tid; q < BC * SR; q += 512) {
-            const int b = q / SR, j = q - b * SR;
-            float v = 0.f;
-            if (b < nb && j < K) v = expf(Rp[(size_t)(b0 + b) * K + j] - aR[b0 + b]);
-            sR[q] = v;
-        }
-        for (int q = tid; q < BC * KP; q += 512) {
-            const int b = q / KP, k = q - b * KP;
-            float v = 0.f;
-            if (b < nb && k < kout) {
-                const float gs = Gs[(size_t)(b0 + b) * K + k];
-                if (gs != 0.f) {
-                    const float vw = voff >= 0 ? params[voff + k * vstr] : 1.f;
-                    v = gs * vw * expf(aL[b0 + b] + aR[b0 + b] - As[(size_t)(b0 + b) * K + k]);
-                }
+        {
+            const bool rok = srow < nb;
+            const size_t ro = (size_t)(b0 + srow) * K;
+            float rv[KQ], gv[KQ], av[KQ];
+            const float al = rok ? aL[b0 + srow] : 0.f, ar = rok ? aR[b0 + srow] : 0.f;
+            const float lv = (rok && 4 * it + sq < K) ? Lp[ro + 4 * it + sq] : -INFINITY;
+#pragma unroll
+            for (int u = 0; u < KQ; ++u) {
+                const int k = sq * KQ + u;
+                rv[u] = (rok && k < K) ? Rp[ro + k] : -INFINITY;
+                gv[u] = (rok && k < kout) ? Gs[ro + k] : 0.f;
+                av[u] = (rok && k < kout) ? As[ro + k] : 0.f;
             }
-            sQ[b * SQ + k] = v;
-        }
-        for (int q = tid; q < BC * 4; q += 512) {
-            const int b = q >> 2, i = 4 * it + (q & 3);
-            float v = 0.f;
-            if (b < nb && i < K) v = expf(Lp[(size_t)(b0 + b) * K + i] - aL[b0 + b]);
-            sL[q] = v;
+#pragma unroll
+            for (int u = 0; u < KQ; ++u) {
+                const int k = sq * KQ + u;
+                sR[srow * SR + k] = expf(rv[u] - ar);
+                sQ[srow * SQ + k] = (gv[u] != 0.f) ? gv[u] * vw[u] * expf(al + ar - av[u]) : 0.f;
+            }
+            for (int j = KP + sq; j < SR; j += 4) sR[srow * SR + j] = 0.f;     // columns beyond the padded K
+            sL[srow * 4 + sq] = expf(lv - al);
         }
         __syncthreads();
 
         // ---- GEMM-1: this wave's tiles (jt, kt), contraction over the nb samples in steps of 4
         {
             const int nsteps = (nb + 3) >> 2;
-            float el[32], er[32];
+            float el[32];
 #pragma unroll
             for (int s = 0; s < 32; ++s) el[s] = sL[(4 * s + g) * 4 + rm];
-            int cur_jt = -1;
 #pragma unroll
             for (int q = 0; q < LY::MAXU; ++q) {
                 const int u = u0 + q;
                 if (u < u1) {
                     const int jt = u / nkt, kt = u - jt * nkt;
-                    if (jt != cur_jt) {
-#pragma unroll
-                        for (int s = 0; s < 32; ++s) er[s] = sR[(4 * s + g) * SR + 16 * jt + c];
-                        cur_jt = jt;
-                    }
                     const float* qcol = sQ + g * SQ + 4 * kt + gm;
+                    const float* rcol = sR + g * SR + 16 * jt + c;
 #pragma unroll
                     for (int s8 = 0; s8 < 4; ++s8) {
                         if (8 * s8 < nsteps) {
 #pragma unroll
                             for (int t = 0; t < 8; ++t) {
                                 const int s = 8 * s8 + t;
-                                acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qcol[4 * s * SQ] * el[s], er[s],
+                                acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qcol[4 * s * SQ] * el[s], rcol[4 * s * SR],
                                                                                acc1[q], 0, 0, 0);
                             }
                         }
@@ -491,30 +507,50 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
 }
 
 // ------------------------------------------------------------------ top-down pass, leaves
-// Posterior-weighted sufficient statistics (Eq. 6-7): one thread per
-// (leaf, variable of its scope, channel, entry k) walks the batch.
-__global__ void k_leaf_backward(const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var,
-                                const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica,
-                                int n_lv, const float* __restrict__ x, const uint8_t* __restrict__ mask,
-                                int mask_mode, const float* __restrict__ G, float* __restrict__ stats,
-                                int64_t phi_off, int64_t den_off, int64_t tot_off, Dims d) {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= n_lv * d.C * d.K) return;
-    const int k = idx % d.K, c = (idx / d.K) % d.C, e = idx / (d.K * d.C);
+// Posterior-weighted sufficient statistics (Eq. 6-7).  A workgroup owns 256
+// consecutive statistics entries (leaf variable, channel, k); its four quarters
+// each walk every fourth sample and the partial sums meet in LDS.
+__global__ __launch_bounds__(1024) void k_leaf_backward(
+    const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var, const int32_t* __restrict__ leaf_node,
+    const int32_t* __restrict__ leaf_replica, int n_lv, const float* __restrict__ x,
+    const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, float* __restrict__ stats,
+    int64_t phi_off, int64_t den_off, int64_t tot_off, Dims d) {
+    __shared__ float red[3][4][256];
+    const int lo = threadIdx.x & 255, quarter = threadIdx.x >> 8;
+    const int idx = blockIdx.x * 256 + lo;
+    const bool valid = idx < n_lv * d.C * d.K;
+    const int k = valid ? idx % d.K : 0, c = valid ? (idx / d.K) % d.C : 0, e = valid ? idx / (d.K * d.C) : 0;
     const int leaf = lv_leaf[e], var = lv_var[e], r = leaf_replica[leaf];
     const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K + k;
+    const float* xp = x + (size_t)var * d.C + c;
+    const bool shared_obs = mask_mode != EINET_MASK_SHARED || mask[var] != 0;
     float n1 = 0.f, n2 = 0.f, den = 0.f, tot = 0.f;
-    for (int b = 0; b < d.B; ++b) {
+#pragma unroll 4
+    for (int b = quarter; b < d.B; b += 4) {
         const float p = Gl[(size_t)b * d.K];
-        float m = 1.f;
-        if (mask_mode == EINET_MASK_SHARED) m = mask[var] ? 1.f : 0.f;
-        if (mask_mode == EINET_MASK_PER_SAMPLE) m = mask[(size_t)b * d.D + var] ? 1.f : 0.f;
-        const float xv = x[((size_t)b * d.D + var) * d.C + c];
-        const float pm = p * m;
+        bool obs = shared_obs;
+        if (mask_mode == EINET_MASK_PER_SAMPLE) obs = mask[(size_t)b * d.D + var] != 0;
+        const float xv = xp[(size_t)b * d.D * d.C];
+        const float pm = obs ? p : 0.f;
         tot += p;
         den += pm;
         n1 = fmaf(pm, xv, n1);
         n2 = fmaf(pm * xv, xv, n2);
+    }
+    if (quarter) {
+        red[quarter - 1][0][lo] = n1;
+        red[quarter - 1][1][lo] = n2;
+        red[quarter - 1][2][lo] = den;
+        red[quarter - 1][3][lo] = tot;
+    }
+    __syncthreads();
+    if (quarter || !valid) return;
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+        n1 += red[q][0][lo];
+        n2 += red[q][1][lo];
+        den += red[q][2][lo];
+        tot += red[q][3][lo];
     }
     const size_t ph = phi_off + ((size_t)(var * d.C + c) * d.R + r) * d.T * d.K + k;
     stats[ph] += n1;
@@ -601,7 +637,7 @@ void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream
 void launch_leaf_forward(const DevTables& t, int n_leaves, const float* x, const uint8_t* mask, int mask_mode,
                          const float* theta, float* A, const Dims& d, hipStream_t s) {
     dim3 grid(n_leaves, (d.B * d.K + 255) / 256);
-    hipLaunchKernelGGL(k_leaf_forward, grid, dim3(256), 0, s, t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, x,
+    hipLaunchKernelGGL(k_leaf_forward, grid, dim3(1024), 0, s, t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, x,
                        mask, mask_mode, theta, A, d);
 }
 
@@ -652,7 +688,7 @@ void launch_region_assemble(const DevTables& t, int first, int count, bool is_ro
     if (count == 0) return;
     dim3 grid(count, (d.B * d.K + 255) / 256);
     hipLaunchKernelGGL(k_region_assemble, grid, dim3(256), 0, s, t.rb_node + first, t.rb_kout + first,
-                       t.rb_pptr + first, t.rb_pstart, t.rb_pcnt, is_root_layer ? 1 : 0, G, Gp, d.B, d.K);
+                       t.rb_pptr + first, t.rb_pblk, is_root_layer ? 1 : 0, G, Gp, d.B, d.K);
 }
 
 void launch_mixing_stats(const DevTables& t, int count, int max_children, const float* params, float* stats,
@@ -696,7 +732,7 @@ void launch_leaf_backward(const DevTables& t, int n_lv, const float* x, const ui
                           const float* G, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off,
                           const Dims& d, hipStream_t s) {
     const int total = n_lv * d.C * d.K;
-    hipLaunchKernelGGL(k_leaf_backward, dim3((total + 255) / 256), dim3(256), 0, s, t.lv_leaf, t.lv_var, t.leaf_node,
+    hipLaunchKernelGGL(k_leaf_backward, dim3((total + 255) / 256), dim3(1024), 0, s, t.lv_leaf, t.lv_var, t.leaf_node,
                        t.leaf_replica, n_lv, x, mask, mask_mode, G, stats, phi_off, den_off, tot_off, d);
 }
 

@@ -14,7 +14,7 @@ namespace einet_impl {
     X(ein_left) X(ein_right) X(ein_out) X(ein_reg) X(ein_kout) X(ein_woff) X(ein_voff) X(ein_vstr)         \
     X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff)                                           \
     X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
-    X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pstart) X(rb_pcnt) X(row_off) X(row_len)
+    X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len)
 
 struct DevTables {
 #define X(name) const int32_t* name;

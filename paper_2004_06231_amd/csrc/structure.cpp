@@ -294,11 +294,9 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& p, std::
         p.rb_node.push_back(s);
         p.rb_kout.push_back(kout(s));
         std::sort(runs[s].begin(), runs[s].end());
-        for (auto& r : runs[s]) {
-            p.rb_pstart.push_back(r.first);
-            p.rb_pcnt.push_back(r.second);
-        }
-        p.rb_pptr.push_back((int32_t)p.rb_pstart.size());
+        for (auto& r : runs[s])
+            for (int q = 0; q < r.second; ++q) p.rb_pblk.push_back(r.first + q);
+        p.rb_pptr.push_back((int32_t)p.rb_pblk.size());
     };
     for (int l = p.num_layers - 1; l >= 0; --l) {
         for (int s : sum_layers[l]) push_region(s);
