@@ -118,7 +118,7 @@ void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, con
     const Plan& p = h->plan;
     float* A = reinterpret_cast<float*>(h->ws + h->off_A);
     const float* theta = reinterpret_cast<const float*>(h->ws + h->off_theta);
-    run(h, KC_LEAF_FWD, s, [&] { launch_leaf_forward(h->dt, (int)p.leaf_node.size(), x, mask, mask_mode, theta, A, d, s); });
+    run(h, KC_LEAF_FWD, s, [&] { launch_leaf_forward(h->dt, (int)p.leaf_node.size(), p.max_leaf_scope, x, mask, mask_mode, theta, A, d, s); });
     for (int l = 0; l < p.num_layers; ++l) {
         run(h, KC_EINSUM_FWD, s, [&] {
             launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params, A,

@@ -47,9 +47,10 @@ __global__ void k_leaf_derive(const float* __restrict__ phi, float* __restrict__
 
 // Leaf layer: A[leaf][b][k] = sum over the leaf's scope and the channels of the
 // log-density of x under entry k; a marginalised variable contributes 0.
-// A workgroup computes 256 consecutive outputs (b, k) of one leaf; its four
-// quarters each take every fourth variable of the scope and the partial sums
-// meet in LDS, so that a long scope does not become a long serial loop.
+// A workgroup of 1024 threads computes 1024/NCH consecutive outputs (b, k) of one
+// leaf; its NCH parts each take every NCH-th variable of the scope and the
+// partial sums meet in LDS, so that a long scope does not become a long serial loop.
+template <int NCH>
 __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict__ leaf_node,
                                                        const int32_t* __restrict__ leaf_replica,
                                                        const int32_t* __restrict__ leaf_sptr,
@@ -57,9 +58,10 @@ __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict
                                                        const float* __restrict__ x, const uint8_t* __restrict__ mask,
                                                        int mask_mode, const float* __restrict__ theta,
                                                        float* __restrict__ A, Dims d) {
-    __shared__ float red[3][256];
-    const int leaf = blockIdx.x, lo = threadIdx.x & 255, quarter = threadIdx.x >> 8;
-    const int f = blockIdx.y * 256 + lo;
+    constexpr int NO = 1024 / NCH;
+    __shared__ float red[NCH][NO];
+    const int leaf = blockIdx.x, lo = threadIdx.x % NO, part_id = threadIdx.x / NO;
+    const int f = blockIdx.y * NO + lo;
     const bool valid = f < d.B * d.K;
     const int b = valid ? f / d.K : 0, k = valid ? f - b * d.K : 0;
     const int r = leaf_replica[leaf];
@@ -67,7 +69,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict
     const size_t tstride = (size_t)d.TD * d.K;
     float acc = 0.f;
 #pragma unroll 4
-    for (int v = quarter; v < nv; v += 4) {
+    for (int v = part_id; v < nv; v += NCH) {
         const int var = leaf_var[s0 + v];
         bool obs = true;
         if (mask_mode == EINET_MASK_SHARED) obs = mask[var] != 0;
@@ -86,10 +88,13 @@ __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict
         }
         acc += obs ? part : 0.f;
     }
-    if (quarter) red[quarter - 1][lo] = acc;
+    red[part_id][lo] = acc;
     __syncthreads();
-    if (quarter == 0 && valid)
-        A[((size_t)leaf_node[leaf] * d.B + b) * d.K + k] = acc + red[0][lo] + red[1][lo] + red[2][lo];
+    if (part_id == 0 && valid) {
+#pragma unroll
+        for (int q = 1; q < NCH; ++q) acc += red[q][lo];
+        A[((size_t)leaf_node[leaf] * d.B + b) * d.K + k] = acc;
+    }
 }
 
 // ------------------------------------------------------------------ einsum layer, forward
@@ -507,17 +512,19 @@ __global__ __launch_bounds__(512, 4) void k_einsum_backward(
 }
 
 // ------------------------------------------------------------------ top-down pass, leaves
-// Posterior-weighted sufficient statistics (Eq. 6-7).  A workgroup owns 256
-// consecutive statistics entries (leaf variable, channel, k); its four quarters
-// each walk every fourth sample and the partial sums meet in LDS.
+// Posterior-weighted sufficient statistics (Eq. 6-7).  A workgroup of 1024 threads
+// owns 1024/NCH consecutive statistics entries (leaf variable, channel, k); its NCH
+// parts each walk every NCH-th sample and the partial sums meet in LDS.
+template <int NCH>
 __global__ __launch_bounds__(1024) void k_leaf_backward(
     const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var, const int32_t* __restrict__ leaf_node,
     const int32_t* __restrict__ leaf_replica, int n_lv, const float* __restrict__ x,
     const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, float* __restrict__ stats,
     int64_t phi_off, int64_t den_off, int64_t tot_off, Dims d) {
-    __shared__ float red[3][4][256];
-    const int lo = threadIdx.x & 255, quarter = threadIdx.x >> 8;
-    const int idx = blockIdx.x * 256 + lo;
+    constexpr int NO = 1024 / NCH;
+    __shared__ float red[NCH][4][NO];
+    const int lo = threadIdx.x % NO, part_id = threadIdx.x / NO;
+    const int idx = blockIdx.x * NO + lo;
     const bool valid = idx < n_lv * d.C * d.K;
     const int k = valid ? idx % d.K : 0, c = valid ? (idx / d.K) % d.C : 0, e = valid ? idx / (d.K * d.C) : 0;
     const int leaf = lv_leaf[e], var = lv_var[e], r = leaf_replica[leaf];
@@ -526,7 +533,7 @@ __global__ __launch_bounds__(1024) void k_leaf_backward(
     const bool shared_obs = mask_mode != EINET_MASK_SHARED || mask[var] != 0;
     float n1 = 0.f, n2 = 0.f, den = 0.f, tot = 0.f;
 #pragma unroll 4
-    for (int b = quarter; b < d.B; b += 4) {
+    for (int b = part_id; b < d.B; b += NCH) {
         const float p = Gl[(size_t)b * d.K];
         bool obs = shared_obs;
         if (mask_mode == EINET_MASK_PER_SAMPLE) obs = mask[(size_t)b * d.D + var] != 0;
@@ -537,16 +544,14 @@ __global__ __launch_bounds__(1024) void k_leaf_backward(
         n1 = fmaf(pm, xv, n1);
         n2 = fmaf(pm * xv, xv, n2);
     }
-    if (quarter) {
-        red[quarter - 1][0][lo] = n1;
-        red[quarter - 1][1][lo] = n2;
-        red[quarter - 1][2][lo] = den;
-        red[quarter - 1][3][lo] = tot;
-    }
+    red[part_id][0][lo] = n1;
+    red[part_id][1][lo] = n2;
+    red[part_id][2][lo] = den;
+    red[part_id][3][lo] = tot;
     __syncthreads();
-    if (quarter || !valid) return;
+    if (part_id || !valid) return;
 #pragma unroll
-    for (int q = 0; q < 3; ++q) {
+    for (int q = 1; q < NCH; ++q) {
         n1 += red[q][0][lo];
         n2 += red[q][1][lo];
         den += red[q][2][lo];
@@ -564,6 +569,9 @@ __global__ __launch_bounds__(1024) void k_leaf_backward(
 
 // ------------------------------------------------------------------ M-step (Eq. 7-9)
 // One wave per weight row (the K*K children of a sum entry, or its C mixing weights).
+// Rows of up to 64*NPL entries are held in registers, so statistics and parameters
+// are each read once and written once; longer rows fall back to several passes.
+template <int NPL>
 __global__ __launch_bounds__(256) void k_update_rows(const int32_t* __restrict__ row_off,
                                                      const int32_t* __restrict__ row_len, int n_rows,
                                                      float* __restrict__ params, float* __restrict__ stats,
@@ -571,6 +579,39 @@ __global__ __launch_bounds__(256) void k_update_rows(const int32_t* __restrict__
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (row >= n_rows) return;
     const int off = row_off[row], len = row_len[row];
+    if (len <= 64 * NPL) {
+        float n[NPL], w[NPL];
+        float s = 0.f;
+#pragma unroll
+        for (int t = 0; t < NPL; ++t) {
+            const int e = lane + 64 * t;
+            n[t] = e < len ? stats[off + e] : 0.f;
+            w[t] = e < len ? params[off + e] : 0.f;
+        }
+#pragma unroll
+        for (int t = 0; t < NPL; ++t) s += n[t];
+        const float tot = wave_sum(s);
+        const float inv = tot > 0.f ? 1.f / tot : 0.f;
+        float s2 = 0.f;
+#pragma unroll
+        for (int t = 0; t < NPL; ++t) {
+            n[t] = tot > 0.f ? n[t] * inv : w[t];
+            if (w_floor > 0.f && lane + 64 * t < len) {
+                n[t] = fmaxf(n[t], w_floor);
+                s2 += n[t];
+            }
+        }
+        const float norm = w_floor > 0.f ? 1.f / wave_sum(s2) : 1.f;
+#pragma unroll
+        for (int t = 0; t < NPL; ++t) {
+            const int e = lane + 64 * t;
+            if (e < len) {
+                params[off + e] = (1.f - step) * w[t] + step * (n[t] * norm);
+                stats[off + e] = 0.f;
+            }
+        }
+        return;
+    }
     float s = 0.f;
     for (int e = lane; e < len; e += 64) s += stats[off + e];
     const float tot = wave_sum(s);
@@ -634,11 +675,18 @@ void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream
     hipLaunchKernelGGL(k_leaf_derive, dim3((total + 255) / 256), dim3(256), 0, s, phi, theta, n, d.K, d.family);
 }
 
-void launch_leaf_forward(const DevTables& t, int n_leaves, const float* x, const uint8_t* mask, int mask_mode,
-                         const float* theta, float* A, const Dims& d, hipStream_t s) {
-    dim3 grid(n_leaves, (d.B * d.K + 255) / 256);
-    hipLaunchKernelGGL(k_leaf_forward, grid, dim3(1024), 0, s, t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, x,
-                       mask, mask_mode, theta, A, d);
+void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const float* x, const uint8_t* mask,
+                         int mask_mode, const float* theta, float* A, const Dims& d, hipStream_t s) {
+    // parts per workgroup: enough that each thread walks only a few variables of the scope
+    const int nch = max_scope >= 32 ? 16 : (max_scope >= 8 ? 4 : 1);
+    dim3 grid(n_leaves, (d.B * d.K + 1024 / nch - 1) / (1024 / nch));
+#define EINET_LAUNCH(N)                                                                                              \
+    hipLaunchKernelGGL(k_leaf_forward<N>, grid, dim3(1024), 0, s, t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, \
+                       x, mask, mask_mode, theta, A, d)
+    if (nch == 16) EINET_LAUNCH(16);
+    else if (nch == 4) EINET_LAUNCH(4);
+    else EINET_LAUNCH(1);
+#undef EINET_LAUNCH
 }
 
 template <int KQ>
@@ -732,14 +780,20 @@ void launch_leaf_backward(const DevTables& t, int n_lv, const float* x, const ui
                           const float* G, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off,
                           const Dims& d, hipStream_t s) {
     const int total = n_lv * d.C * d.K;
-    hipLaunchKernelGGL(k_leaf_backward, dim3((total + 255) / 256), dim3(1024), 0, s, t.lv_leaf, t.lv_var, t.leaf_node,
-                       t.leaf_replica, n_lv, x, mask, mask_mode, G, stats, phi_off, den_off, tot_off, d);
+    const int nch = d.B >= 16 ? 4 : 1;
+    const int no = 1024 / nch;
+#define EINET_LAUNCH(N)                                                                                            \
+    hipLaunchKernelGGL(k_leaf_backward<N>, dim3((total + no - 1) / no), dim3(1024), 0, s, t.lv_leaf, t.lv_var,        \
+                       t.leaf_node, t.leaf_replica, n_lv, x, mask, mask_mode, G, stats, phi_off, den_off, tot_off, d)
+    if (nch == 4) EINET_LAUNCH(4);
+    else EINET_LAUNCH(1);
+#undef EINET_LAUNCH
 }
 
 void launch_update_rows(const DevTables& t, int n_rows, float* params, float* stats, float step, float w_floor,
                         hipStream_t s) {
-    hipLaunchKernelGGL(k_update_rows, dim3((n_rows + 3) / 4), dim3(256), 0, s, t.row_off, t.row_len, n_rows, params,
-                       stats, step, w_floor);
+    hipLaunchKernelGGL(k_update_rows<32>, dim3((n_rows + 3) / 4), dim3(256), 0, s, t.row_off, t.row_len, n_rows,
+                       params, stats, step, w_floor);
 }
 
 void launch_update_leaves(float* params, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off, float step,

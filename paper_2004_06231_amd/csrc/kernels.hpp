@@ -27,8 +27,8 @@ struct Dims {
 };
 
 void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream_t s);
-void launch_leaf_forward(const DevTables& t, int n_leaves, const float* x, const uint8_t* mask, int mask_mode,
-                         const float* theta, float* A, const Dims& d, hipStream_t s);
+void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const float* x, const uint8_t* mask,
+                         int mask_mode, const float* theta, float* A, const Dims& d, hipStream_t s);
 void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, float* amax,
                            const Dims& d, hipStream_t s);
 void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, const Dims& d,

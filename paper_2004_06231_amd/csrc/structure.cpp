@@ -272,6 +272,7 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& p, std::
         int li = (int)p.leaf_node.size();
         p.leaf_node.push_back(s);
         p.leaf_replica.push_back(g.replica[s]);
+        p.max_leaf_scope = std::max(p.max_leaf_scope, (int)g.scope[s].size());
         for (int v : g.scope[s]) {
             p.leaf_var.push_back(v);
             p.lv_leaf.push_back(li);

@@ -36,6 +36,7 @@ struct Plan {
     int num_nodes = 0;      // regions + simple sums
     int num_layers = 0;
     int max_mix_children = 0;
+    int max_leaf_scope = 0;
 
     // Index tables (see EINET_TABLES): einsum items in execution order (bottom layer first); mixing items
     // grouped by the layer whose einsum they follow; leaves; top-down items (sum layers from the root
