@@ -308,15 +308,20 @@ __global__ __launch_bounds__(1024) void k_mixing_stats(const int32_t* __restrict
 // G_out is the posterior of the item's region times, for a region with several
 // partitions, the mixing weight and S^c/S; S^c cancels against S~, leaving
 //   Q = G[s] * v * exp(a + a' - A[s]).
-// One workgroup per (item, slice of four left entries i).  The slice W[:, 4 i, :]
-// is staged once in LDS and serves both GEMMs, so W is read once per pass.
+// A workgroup takes one item and a run of slices, a slice being four consecutive
+// left entries i.  eR and Q of up to 128 samples are staged once in LDS; the
+// slices W[:, 4 i, :] then stream through LDS one at a time (the next one is
+// already in flight in registers while the current one is used), and each serves
+// both GEMMs, so W is read once per pass.
 // GEMM-1 contracts over the batch: rows (k, i) in tiles of 4x4, columns j in tiles
-// of 16; the A operand Q*eL is formed on the fly from LDS (Q) and registers (eL).
-// GEMM-2 contracts over k: rows (i, j) in tiles of 4x4, columns = 16 samples, one
-// sample tile per wave; the reductions over j (left) and over the slice's four i
-// (right) happen in registers.  Gp_left is complete for the slice's entries;
-// Gp_right is a partial sum, written to the slice's own block and added up by
-// k_region_assemble.
+// of 16; the A operand Q*eL is formed on the fly; a wave owns up to MAXU tiles and
+// advances them together so that consecutive MFMAs are independent.
+// GEMM-2 contracts over k: rows (j, i) in tiles of 4x4, columns = 16 samples, one
+// sample tile per wave, all KQ row tiles advancing together.  The sum over the
+// slice's four i (right child) is in-lane; the sum over j (left child) is in-lane
+// across tiles plus one exchange between the four lane groups at the end.
+// Gp_left is complete for the slice's entries; Gp_right is a partial sum, written
+// to the slice's own block and added up by k_region_assemble.
 template <int KQ>
 struct BwdLayout {
     static constexpr int KP = 4 * KQ;
@@ -331,24 +336,42 @@ struct BwdLayout {
     static constexpr int OFF_L = ((OFF_Q + BC * SQ + 3) / 4) * 4;
     static constexpr int LDS_FLOATS = OFF_L + BC * 4;
     static constexpr int MAXU = (NJ * KQ + 7) / 8;        // GEMM-1 tiles per wave
+    static constexpr int NW4 = (KP * 4 * KQ + 511) / 512; // float4 per thread of one W slice
+    static constexpr int NW1 = (KP * 4 * KP + 511) / 512; // floats per thread when K is not a multiple of 4
 };
 
-template <int KQ>
-__global__ __launch_bounds__(512, 4) void k_einsum_backward(
+// GEMM-1 over one pass of the batch for NU tiles of this wave: step s contracts samples 4s..4s+3.
+template <int KQ, int NU>
+__device__ __forceinline__ void bwd_gemm1(floatx4* acc1, const float* const* qcol, const float* const* rcol,
+                                          const float* elcol, int nsteps) {
+    using LY = BwdLayout<KQ>;
+#pragma unroll 4
+    for (int s = 0; s < nsteps; ++s) {
+        const float e = elcol[16 * s];
+#pragma unroll
+        for (int q = 0; q < NU; ++q)
+            acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qcol[q][4 * s * LY::SQ] * e, rcol[q][4 * s * LY::SR],
+                                                           acc1[q], 0, 0, 0);
+    }
+}
+
+template <int KQ, bool VEC>
+__global__ __launch_bounds__(512, 2) void k_einsum_backward(
     const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_reg,
     const int32_t* __restrict__ e_kout, const int32_t* __restrict__ e_woff, const int32_t* __restrict__ e_voff,
     const int32_t* __restrict__ e_vstr, const float* __restrict__ params, float* __restrict__ stats,
     const float* __restrict__ A, const float* __restrict__ amax, const float* __restrict__ G, float* __restrict__ Gp,
-    int item0, int B, int K) {
+    int item0, int ngroups, int B, int K) {
     using LY = BwdLayout<KQ>;
-    constexpr int KP = LY::KP, SI = LY::SI, S = LY::S, SR = LY::SR, SQ = LY::SQ, BC = LY::BC;
+    constexpr int KP = LY::KP, SI = LY::SI, S = LY::S, SR = LY::SR, SQ = LY::SQ, BC = LY::BC, MAXU = LY::MAXU;
     extern __shared__ float lds[];
     float* Wl = lds;
     float* sR = lds + LY::OFF_R;
     float* sQ = lds + LY::OFF_Q;
     float* sL = lds + LY::OFF_L;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int li = blockIdx.x / KQ, it = blockIdx.x - li * KQ;
+    const int li = blockIdx.x / ngroups, grp = blockIdx.x - li * ngroups;
+    const int it0 = grp * KQ / ngroups, it1 = (grp + 1) * KQ / ngroups;     // this workgroup's slices
     const int item = item0 + li;
     const int kout = e_kout[li], nkt = (kout + 3) >> 2;
     const size_t blk = (size_t)B * K;
@@ -357,39 +380,71 @@ __global__ __launch_bounds__(512, 4) void k_einsum_backward(
     const float* As = A + (size_t)e_reg[li] * blk;
     const float* Gs = G + (size_t)e_reg[li] * blk;
     const float* W = params + e_woff[li];
+    const size_t wbase = (size_t)e_woff[li];
     const int voff = e_voff[li], vstr = e_vstr[li];
     const float* aL = amax + (size_t)item * 2 * B;
     const float* aR = aL + B;
+    const int nblk = 1 + KQ;
 
-    // stage W[:, 4it .. 4it+3, :], zero-padded
-    if ((K & 3) == 0) {
-        for (int q = tid; q < KP * 4 * KQ; q += 512) {
-            const int j4 = q % KQ, il = (q / KQ) & 3, k = q / (4 * KQ);
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k < kout) v = *reinterpret_cast<const float4*>(W + ((size_t)k * K + 4 * it + il) * K + 4 * j4);
-            *reinterpret_cast<float4*>(Wl + k * S + il * SI + 4 * j4) = v;
+    // registers that carry the next W slice
+    float4 w4[VEC ? LY::NW4 : 1];
+    float w1[VEC ? 1 : LY::NW1];
+    auto fetch_w = [&](int it) {
+        if constexpr (VEC) {
+#pragma unroll
+            for (int n = 0; n < LY::NW4; ++n) {
+                const int q = tid + 512 * n;
+                const int j4 = q % KQ, il = (q / KQ) & 3, k = q / (4 * KQ);
+                w4[n] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (k < kout) w4[n] = *reinterpret_cast<const float4*>(W + ((size_t)k * K + 4 * it + il) * K + 4 * j4);
+            }
+        } else {
+#pragma unroll
+            for (int n = 0; n < LY::NW1; ++n) {
+                const int q = tid + 512 * n;
+                const int j = q % KP, il = (q / KP) & 3, k = q / (4 * KP);
+                const int i = 4 * it + il;
+                w1[n] = (k < kout && i < K && j < K) ? W[((size_t)k * K + i) * K + j] : 0.f;
+            }
         }
-    } else {
-        for (int q = tid; q < KP * 4 * KP; q += 512) {
-            const int j = q % KP, il = (q / KP) & 3, k = q / (4 * KP);
-            const int i = 4 * it + il;
-            float v = 0.f;
-            if (k < kout && i < K && j < K) v = W[((size_t)k * K + i) * K + j];
-            Wl[k * S + il * SI + j] = v;
+    };
+    auto store_w = [&]() {
+        if constexpr (VEC) {
+#pragma unroll
+            for (int n = 0; n < LY::NW4; ++n) {
+                const int q = tid + 512 * n;
+                const int j4 = q % KQ, il = (q / KQ) & 3, k = q / (4 * KQ);
+                if (k < KP) *reinterpret_cast<float4*>(Wl + k * S + il * SI + 4 * j4) = w4[n];
+            }
+        } else {
+#pragma unroll
+            for (int n = 0; n < LY::NW1; ++n) {
+                const int q = tid + 512 * n;
+                const int j = q % KP, il = (q / KP) & 3, k = q / (4 * KP);
+                if (k < KP) Wl[k * S + il * SI + j] = w1[n];
+            }
         }
-    }
+    };
+    fetch_w(it0);
 
     const int c = lane & 15, g = lane >> 4;
     const int gm = c >> 2, rm = c & 3;
+    // GEMM-1 tiles of this wave: u = jt * nkt + kt
     const int U = LY::NJ * nkt;
-    const int u0 = wave * U / 8, u1 = (wave + 1) * U / 8;
-    floatx4 acc1[LY::MAXU];
+    const int u0 = wave * U / 8, nu = (wave + 1) * U / 8 - u0;
+    const float* qcol[MAXU];
+    const float* rcol[MAXU];
+    int ujt[MAXU], ukt[MAXU];
 #pragma unroll
-    for (int q = 0; q < LY::MAXU; ++q) acc1[q] = floatx4{0.f, 0.f, 0.f, 0.f};
-    const int nblk = 1 + KQ;
+    for (int q = 0; q < MAXU; ++q) {
+        const int u = min(u0 + q, U - 1);
+        ujt[q] = u / nkt;
+        ukt[q] = u - ujt[q] * nkt;
+        qcol[q] = sQ + g * SQ + 4 * ukt[q] + gm;
+        rcol[q] = sR + g * SR + 16 * ujt[q] + c;
+    }
 
-    // Staging of the per-sample operands: thread t owns row t/4 of the pass and a quarter
-    // (KQ consecutive entries) of its columns; all global loads are issued before any is used.
+    // staging of eR and Q: thread t owns row t/4 of the pass and a quarter of its columns
     const int srow = tid >> 2, sq = tid & 3;
     float vw[KQ];
 #pragma unroll
@@ -397,15 +452,16 @@ __global__ __launch_bounds__(512, 4) void k_einsum_backward(
         const int k = sq * KQ + u;
         vw[u] = (voff >= 0 && k < kout) ? params[voff + k * vstr] : 1.f;
     }
+
     for (int b0 = 0; b0 < B; b0 += BC) {
         const int nb = min(BC, B - b0);
-        if (b0) __syncthreads();
+        const int nsteps = (nb + 3) >> 2;
+        const bool rok = srow < nb;
+        const size_t ro = (size_t)(b0 + srow) * K;
+        const float al = rok ? aL[b0 + srow] : 0.f, ar = rok ? aR[b0 + srow] : 0.f;
+        __syncthreads();                                   // readers of the previous pass are done
         {
-            const bool rok = srow < nb;
-            const size_t ro = (size_t)(b0 + srow) * K;
             float rv[KQ], gv[KQ], av[KQ];
-            const float al = rok ? aL[b0 + srow] : 0.f, ar = rok ? aR[b0 + srow] : 0.f;
-            const float lv = (rok && 4 * it + sq < K) ? Lp[ro + 4 * it + sq] : -INFINITY;
 #pragma unroll
             for (int u = 0; u < KQ; ++u) {
                 const int k = sq * KQ + u;
@@ -420,90 +476,91 @@ __global__ __launch_bounds__(512, 4) void k_einsum_backward(
                 sQ[srow * SQ + k] = (gv[u] != 0.f) ? gv[u] * vw[u] * expf(al + ar - av[u]) : 0.f;
             }
             for (int j = KP + sq; j < SR; j += 4) sR[srow * SR + j] = 0.f;     // columns beyond the padded K
-            sL[srow * 4 + sq] = expf(lv - al);
-        }
-        __syncthreads();
-
-        // ---- GEMM-1: this wave's tiles (jt, kt), contraction over the nb samples in steps of 4
-        {
-            const int nsteps = (nb + 3) >> 2;
-            float el[32];
-#pragma unroll
-            for (int s = 0; s < 32; ++s) el[s] = sL[(4 * s + g) * 4 + rm];
-#pragma unroll
-            for (int q = 0; q < LY::MAXU; ++q) {
-                const int u = u0 + q;
-                if (u < u1) {
-                    const int jt = u / nkt, kt = u - jt * nkt;
-                    const float* qcol = sQ + g * SQ + 4 * kt + gm;
-                    const float* rcol = sR + g * SR + 16 * jt + c;
-#pragma unroll
-                    for (int s8 = 0; s8 < 4; ++s8) {
-                        if (8 * s8 < nsteps) {
-#pragma unroll
-                            for (int t = 0; t < 8; ++t) {
-                                const int s = 8 * s8 + t;
-                                acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qcol[4 * s * SQ] * el[s], rcol[4 * s * SR],
-                                                                               acc1[q], 0, 0, 0);
-                            }
-                        }
-                    }
-                }
-            }
         }
 
-        // ---- GEMM-2: one tile of 16 samples per wave
-        if (wave * 16 < nb) {
-            const int bl = wave * 16 + c;
-            const bool ok = bl < nb;
-            float qv[KQ];
-#pragma unroll
-            for (int s = 0; s < KQ; ++s) qv[s] = sQ[bl * SQ + 4 * s + g];
-            const float elv = sL[bl * 4 + g];
-            const float* wl = Wl + g * S + gm * SI + rm;
-            float gl = 0.f;
-            float* right = Gp + ((size_t)(item * nblk + 1 + it) * B + b0 + bl) * K;
-#pragma unroll
-            for (int jt = 0; jt < KQ; ++jt) {
-                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int s = 0; s < KQ; ++s)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wl[4 * s * S + 4 * jt], qv[s], acc, 0, 0, 0);
-                const float4 e4 = *reinterpret_cast<const float4*>(sR + bl * SR + 4 * jt);
-                gl += acc[0] * e4.x + acc[1] * e4.y + acc[2] * e4.z + acc[3] * e4.w;
-                float t[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    t[r] = acc[r] * elv;                       // sum over the slice's four i = the four lane groups
-                    t[r] += __shfl_xor(t[r], 16, 64);
-                    t[r] += __shfl_xor(t[r], 32, 64);
-                }
-                if (ok && (jt & 3) == g) {
-                    if (4 * jt + 0 < K) right[4 * jt + 0] = t[0] * e4.x;
-                    if (4 * jt + 1 < K) right[4 * jt + 1] = t[1] * e4.y;
-                    if (4 * jt + 2 < K) right[4 * jt + 2] = t[2] * e4.z;
-                    if (4 * jt + 3 < K) right[4 * jt + 3] = t[3] * e4.w;
-                }
-            }
-            if (ok && 4 * it + g < K) Gp[((size_t)(item * nblk) * B + b0 + bl) * K + 4 * it + g] = elv * gl;
-        }
-    }
+        for (int it = it0; it < it1; ++it) {
+            if (it != it0) __syncthreads();                // readers of the previous slice are done
+            store_w();
+            sL[srow * 4 + sq] = (rok && 4 * it + sq < K) ? expf(Lp[ro + 4 * it + sq] - al) : 0.f;
+            __syncthreads();
+            // next slice of this pass, or the first slice of the next pass, goes in flight now
+            if (it + 1 < it1) fetch_w(it + 1);
+            else if (b0 + BC < B) fetch_w(it0);
 
-    // ---- GEMM-1 epilogue: Nw += W * acc
-    const size_t wbase = (size_t)e_woff[li];
+            // statistics this wave will update, fetched early
+            float nw[MAXU][4];
 #pragma unroll
-    for (int q = 0; q < LY::MAXU; ++q) {
-        const int u = u0 + q;
-        if (u < u1) {
-            const int jt = u / nkt, kt = u - jt * nkt;
-            const int k = 4 * kt + g, j = 16 * jt + c;
-            if (k < kout && j < K) {
+            for (int q = 0; q < MAXU; ++q) {
+                const int k = 4 * ukt[q] + g, j = 16 * ujt[q] + c;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int i = 4 * it + r;
-                    if (i < K) {
-                        const size_t idx = wbase + ((size_t)k * K + i) * K + j;
-                        stats[idx] += Wl[k * S + r * SI + j] * acc1[q][r];
+                    nw[q][r] = (q < nu && k < kout && j < K && i < K) ? stats[wbase + ((size_t)k * K + i) * K + j] : 0.f;
+                }
+            }
+
+            // ---- GEMM-1
+            floatx4 acc1[MAXU];
+#pragma unroll
+            for (int q = 0; q < MAXU; ++q) acc1[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+            {
+                const float* elcol = sL + g * 4 + rm;
+                if (nu == MAXU) bwd_gemm1<KQ, MAXU>(acc1, qcol, rcol, elcol, nsteps);
+                else if (MAXU > 1 && nu == MAXU - 1)
+                    bwd_gemm1<KQ, (MAXU > 1 ? MAXU - 1 : 1)>(acc1, qcol, rcol, elcol, nsteps);
+                else
+                    for (int q = 0; q < nu; ++q) bwd_gemm1<KQ, 1>(acc1 + q, qcol + q, rcol + q, elcol, nsteps);
+            }
+
+            // ---- GEMM-2: one tile of 16 samples per wave
+            if (wave * 16 < nb) {
+                const int bl = wave * 16 + c;
+                const bool ok = bl < nb;
+                float erg[KQ];
+#pragma unroll
+                for (int s = 0; s < KQ; ++s) erg[s] = sR[bl * SR + 4 * s + g];
+                const float* qrow = sQ + bl * SQ + g;
+                const float4 e4 = *reinterpret_cast<const float4*>(sL + bl * 4);
+                const float* wl = Wl + g * S + rm * SI + gm;      // row 4*gm+rm of a tile = (j = 4jt+gm, i = 4it+rm)
+                floatx4 acc[KQ];
+#pragma unroll
+                for (int jt = 0; jt < KQ; ++jt) acc[jt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+                for (int s = 0; s < KQ; ++s) {
+                    const float qs = qrow[4 * s];
+#pragma unroll
+                    for (int jt = 0; jt < KQ; ++jt)
+                        acc[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl[4 * s * S + 4 * jt], qs, acc[jt], 0, 0, 0);
+                }
+                // acc[jt][r] = U[b][i = 4it+r][j = 4jt+g]
+                float gl0 = 0.f, gl1 = 0.f, gl2 = 0.f, gl3 = 0.f;
+                float* right = Gp + ((size_t)(item * nblk + 1 + it) * B + b0 + bl) * K;
+#pragma unroll
+                for (int jt = 0; jt < KQ; ++jt) {
+                    const float t = acc[jt][0] * e4.x + acc[jt][1] * e4.y + acc[jt][2] * e4.z + acc[jt][3] * e4.w;
+                    if (ok && 4 * jt + g < K) right[4 * jt + g] = erg[jt] * t;
+                    gl0 = fmaf(acc[jt][0], erg[jt], gl0);
+                    gl1 = fmaf(acc[jt][1], erg[jt], gl1);
+                    gl2 = fmaf(acc[jt][2], erg[jt], gl2);
+                    gl3 = fmaf(acc[jt][3], erg[jt], gl3);
+                }
+                gl0 += __shfl_xor(gl0, 16, 64); gl0 += __shfl_xor(gl0, 32, 64);
+                gl1 += __shfl_xor(gl1, 16, 64); gl1 += __shfl_xor(gl1, 32, 64);
+                gl2 += __shfl_xor(gl2, 16, 64); gl2 += __shfl_xor(gl2, 32, 64);
+                gl3 += __shfl_xor(gl3, 16, 64); gl3 += __shfl_xor(gl3, 32, 64);
+                const float glr = g == 0 ? gl0 * e4.x : (g == 1 ? gl1 * e4.y : (g == 2 ? gl2 * e4.z : gl3 * e4.w));
+                if (ok && 4 * it + g < K) Gp[((size_t)(item * nblk) * B + b0 + bl) * K + 4 * it + g] = glr;
+            }
+
+            // ---- GEMM-1 epilogue: Nw += W * acc
+#pragma unroll
+            for (int q = 0; q < MAXU; ++q) {
+                const int k = 4 * ukt[q] + g, j = 16 * ujt[q] + c;
+                if (q < nu && k < kout && j < K) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int i = 4 * it + r;
+                        if (i < K) stats[wbase + ((size_t)k * K + i) * K + j] = nw[q][r] + Wl[k * S + r * SI + j] * acc1[q][r];
                     }
                 }
             }
@@ -753,13 +810,23 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
     const size_t lds = sizeof(float) * BwdLayout<KQ>::LDS_FLOATS;
     static bool attr_set = false;
     if (lds > 64 * 1024 && !attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, false>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
-    hipLaunchKernelGGL(k_einsum_backward<KQ>, dim3(count * KQ), dim3(512), lds, s, t.ein_left + first,
-                       t.ein_right + first, t.ein_reg + first, t.ein_kout + first, t.ein_woff + first,
-                       t.ein_voff + first, t.ein_vstr + first, params, stats, A, amax, G, Gp, first, d.B, d.K);
+    // slices per item are spread over as many workgroups as keeps the launch within one round of the
+    // 256 compute units (one workgroup per unit)
+    int ngroups = 256 / count;
+    ngroups = ngroups < 1 ? 1 : (ngroups > KQ ? KQ : ngroups);
+#define EINET_LAUNCH(V)                                                                                           \
+    hipLaunchKernelGGL((k_einsum_backward<KQ, V>), dim3(count * ngroups), dim3(512), lds, s, t.ein_left + first,       \
+                       t.ein_right + first, t.ein_reg + first, t.ein_kout + first, t.ein_woff + first,                \
+                       t.ein_voff + first, t.ein_vstr + first, params, stats, A, amax, G, Gp, first, ngroups, d.B, d.K)
+    if ((d.K & 3) == 0) EINET_LAUNCH(true);
+    else EINET_LAUNCH(false);
+#undef EINET_LAUNCH
 }
 
 void launch_einsum_backward(const DevTables& t, int first, int count, const float* params, float* stats,
