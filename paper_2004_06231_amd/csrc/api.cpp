@@ -114,7 +114,8 @@ void run(einet_t* h, int cls, hipStream_t s, F&& launch) {
 }
 
 // Leaf layer, then einsum (+ mixing) layers bottom-up; fills the arena A.
-void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, const Dims& d, hipStream_t s) {
+void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, float* logp, const Dims& d,
+             hipStream_t s) {
     const Plan& p = h->plan;
     float* A = reinterpret_cast<float*>(h->ws + h->off_A);
     const float* theta = reinterpret_cast<const float*>(h->ws + h->off_theta);
@@ -122,12 +123,12 @@ void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, con
     for (int l = 0; l < p.num_layers; ++l) {
         run(h, KC_EINSUM_FWD, s, [&] {
             launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params, A,
-                                  reinterpret_cast<float*>(h->ws + h->off_amax), d, s);
+                                  reinterpret_cast<float*>(h->ws + h->off_amax), logp, d, s);
         });
         if (p.mix_layer_ptr[l + 1] > p.mix_layer_ptr[l])
             run(h, KC_MIXING_FWD, s, [&] {
                 launch_mixing_forward(h->dt, p.mix_layer_ptr[l], p.mix_layer_ptr[l + 1] - p.mix_layer_ptr[l],
-                                      h->params, A, d, s);
+                                      h->params, A, logp, d, s);
             });
     }
 }
@@ -275,8 +276,7 @@ int einet_logp(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask
     if (!logp_dev) return fail(h, EINET_ERR_INVALID_ARG, "logp_dev is NULL");
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Dims d = dims_of(h, B);
-    forward(h, x_dev, mask_dev, mask_mode, d, s);
-    launch_copy_root(reinterpret_cast<const float*>(h->ws + h->off_A), logp_dev, d, s);
+    forward(h, x_dev, mask_dev, mask_mode, logp_dev, d, s);
     return check_hip(h, "einet_logp");
 }
 
@@ -287,11 +287,10 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Dims d = dims_of(h, B);
     const Plan& p = h->plan;
-    forward(h, x_dev, mask_dev, mask_mode, d, s);
+    forward(h, x_dev, mask_dev, mask_mode, logp_dev, d, s);
     const float* A = reinterpret_cast<const float*>(h->ws + h->off_A);
     float* G = reinterpret_cast<float*>(h->ws + h->off_G);
     float* Gp = reinterpret_cast<float*>(h->ws + h->off_Gp);
-    if (logp_dev) launch_copy_root(A, logp_dev, d, s);
     // top-down: posteriors of the regions of sum layer l (root first), then the einsum items below them
     const float* amax = reinterpret_cast<const float*>(h->ws + h->off_amax);
     for (int l = p.num_layers - 1, step = 0; l >= 0; --l, ++step) {
@@ -331,10 +330,8 @@ int einet_em_update(einet_t* h, float step, float min_var, float max_var, float 
     const Plan& p = h->plan;
     run(h, KC_UPDATE, s, [&] {
         launch_update_rows(h->dt, (int)p.row_off.size(), h->params, h->stats, step, w_floor, s);
-        launch_update_leaves(h->params, h->stats, p.phi_offset, p.den_offset, p.tot_offset, step, min_var, max_var, d,
-                             s);
-        launch_fill(h->stats + p.den_offset, 0.f, p.n_stats - p.den_offset, s);
-        launch_leaf_derive(h->params + p.phi_offset, reinterpret_cast<float*>(h->ws + h->off_theta), d, s);
+        launch_update_leaves(h->params, h->stats, reinterpret_cast<float*>(h->ws + h->off_theta), p.phi_offset,
+                             p.den_offset, p.tot_offset, step, min_var, max_var, d, s);
     });
     return check_hip(h, "einet_em_update");
 }

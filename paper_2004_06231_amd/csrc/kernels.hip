@@ -129,8 +129,8 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
                                                         const int32_t* __restrict__ e_kout,
                                                         const int32_t* __restrict__ e_woff,
                                                         const float* __restrict__ params, float* __restrict__ A,
-                                                        float* __restrict__ amax, int item0, int B, int K,
-                                                        int nkt) {
+                                                        float* __restrict__ amax, float* __restrict__ logp,
+                                                        int item0, int B, int K, int nkt) {
     using LY = FwdLayout<KQ>;
     constexpr int KP = LY::KP, SJ = LY::SJ, SK = LY::SK;
     extern __shared__ float Wl[];
@@ -142,6 +142,25 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
     const float* Lp = A + (size_t)e_left[li] * B * K;
     const float* Rp = A + (size_t)e_right[li] * B * K;
     const float* W = params + e_woff[li];
+
+    const int c = lane & 15, g = lane >> 4;          // sample column of the tile, lane group
+    const int gm = c >> 2, rm = c & 3;               // as A-operand lane: row 4*gm+rm = (k = 4kt+gm, i = 4it+rm)
+    const int n_btiles = (B + 15) >> 4;
+    // lane (c, g) holds entries 4s+g of row b of both inputs; the first tile's rows are requested
+    // before W is staged so that the two memory round trips overlap
+    float er[KQ], el[KQ];
+    auto load_rows = [&](int bt) {
+        const int b = bt * 16 + c;
+        const bool ok = bt < n_btiles && b < B;
+#pragma unroll
+        for (int s = 0; s < KQ; ++s) {
+            const int j = 4 * s + g;
+            const bool in = ok && j < K;
+            er[s] = in ? Rp[(size_t)b * K + j] : -INFINITY;
+            el[s] = in ? Lp[(size_t)b * K + j] : -INFINITY;
+        }
+    };
+    load_rows(wave);
 
     // stage W[4kt .. 4kt+3][.][.]
     if ((K & 3) == 0) {
@@ -165,24 +184,16 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
     }
     __syncthreads();
 
-    const int c = lane & 15, g = lane >> 4;          // sample column of the tile, lane group
-    const int gm = c >> 2, rm = c & 3;               // as A-operand lane: row 4*gm+rm = (k = 4kt+gm, i = 4it+rm)
     const float* wl = Wl + gm * SK + rm * SJ + g;    // + it*4*SJ + 4*s : contraction index j = 4s + g
     float* elw = Wl + LY::LDS_W + wave * (16 * LY::SE);   // this wave's eL tile [16][SE]
-    const int n_btiles = (B + 15) >> 4;
     for (int bt0 = 0; bt0 < n_btiles; bt0 += nwaves) {
         const int bt = bt0 + wave;
         const int b = bt * 16 + c;
         const bool ok = bt < n_btiles && b < B;
-        // lane (c, g) holds entries 4s+g of row b of both inputs
-        float er[KQ], el[KQ];
+        if (bt0) load_rows(bt);
         float mr = -INFINITY, ml = -INFINITY;
 #pragma unroll
         for (int s = 0; s < KQ; ++s) {
-            const int j = 4 * s + g;
-            const bool in = ok && j < K;
-            er[s] = in ? Rp[(size_t)b * K + j] : -INFINITY;
-            el[s] = in ? Lp[(size_t)b * K + j] : -INFINITY;
             mr = fmaxf(mr, er[s]);
             ml = fmaxf(ml, el[s]);
         }
@@ -210,7 +221,11 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
             sacc += acc[0] * e4.x + acc[1] * e4.y + acc[2] * e4.z + acc[3] * e4.w;
         }
         const int k = 4 * kt + g;
-        if (ok && k < kout) A[((size_t)e_out[li] * B + b) * K + k] = ml + mr + logf(sacc);
+        if (ok && k < kout) {
+            const float val = ml + mr + logf(sacc);
+            A[((size_t)e_out[li] * B + b) * K + k] = val;
+            if (logp && e_out[li] == 0) logp[b] = val;       // node 0 is the root region (single entry)
+        }
         if (ok && kt == 0 && g == 0) {                 // the shifts, kept for the top-down pass
             amax[((size_t)item * 2) * B + b] = ml;
             amax[((size_t)item * 2 + 1) * B + b] = mr;
@@ -222,7 +237,7 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
 __global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32_t* __restrict__ m_kout,
                                  const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
                                  const int32_t* __restrict__ m_voff, const float* __restrict__ params,
-                                 float* __restrict__ A, int B, int K) {
+                                 float* __restrict__ A, float* __restrict__ logp, int B, int K) {
     const int item = blockIdx.x;
     const int kout = m_kout[item];
     const int e = blockIdx.y * blockDim.x + threadIdx.x;
@@ -236,11 +251,7 @@ __global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32
     float s = 0.f;
     for (int c = 0; c < nc; ++c) s += v[c] * expf(A[((size_t)m_child[c0 + c] * B + b) * K + k] - m);
     A[((size_t)m_node[item] * B + b) * K + k] = m + logf(s);
-}
-
-__global__ void k_copy_root(const float* __restrict__ A, float* __restrict__ logp, int B, int K) {
-    int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < B) logp[b] = A[(size_t)b * K];   // node 0 is the root region, entry 0
+    if (logp && m_node[item] == 0) logp[b] = m + logf(s);    // node 0 is the root region (single entry)
 }
 
 // ------------------------------------------------------------------ top-down pass, regions
@@ -689,31 +700,47 @@ __global__ __launch_bounds__(256) void k_update_rows(const int32_t* __restrict__
     }
 }
 
-__global__ void k_update_leaves(float* __restrict__ params, float* __restrict__ stats, int64_t phi_off,
-                                int64_t den_off, int64_t tot_off, float step, float min_var, float max_var, Dims d) {
+// Leaf M-step (Eq. 7-9, Sec. 4.2): one thread per (variable, replica, k) updates the
+// parameters of all channels, clears the statistics it owns and refreshes the
+// constants the leaf layer derives from the parameters.
+__global__ void k_update_leaves(float* __restrict__ params, float* __restrict__ stats, float* __restrict__ theta,
+                                int64_t phi_off, int64_t den_off, int64_t tot_off, float step, float min_var,
+                                float max_var, Dims d) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    const int n = d.D * d.C * d.R * d.K;
-    if (idx >= n) return;
-    const int k = idx % d.K, e = idx / d.K;          // e = (var*C + c)*R + r
-    const int r = e % d.R, var = e / (d.R * d.C);
+    if (idx >= d.D * d.R * d.K) return;
+    const int k = idx % d.K, r = (idx / d.K) % d.R, var = idx / (d.K * d.R);
     const size_t o = ((size_t)var * d.R + r) * d.K + k;
     const float tot = stats[tot_off + o], den = stats[den_off + o];
-    float nw[2];
-    for (int t = 0; t < d.T; ++t) {
-        const size_t ph = phi_off + ((size_t)e * d.T + t) * d.K + k;
-        const float old = params[ph];
-        const float hat = tot > 0.f ? (stats[ph] + (tot - den) * old) / tot : old;
-        nw[t] = (1.f - step) * old + step * hat;
-        stats[ph] = 0.f;
-    }
-    const size_t ph0 = phi_off + (size_t)e * d.T * d.K + k;
-    if (d.family == EINET_LEAF_GAUSSIAN) {
-        const float mu = nw[0];
-        const float var2 = fminf(fmaxf(fmaf(-mu, mu, nw[1]), min_var), max_var);
-        params[ph0] = mu;
-        params[ph0 + d.K] = fmaf(mu, mu, var2);
-    } else {
-        params[ph0] = fminf(fmaxf(nw[0], 1e-6f), 1.f - 1e-6f);
+    stats[tot_off + o] = 0.f;
+    stats[den_off + o] = 0.f;
+    for (int c = 0; c < d.C; ++c) {
+        const size_t e = (size_t)(var * d.C + c) * d.R + r;
+        float nw[2];
+        for (int t = 0; t < d.T; ++t) {
+            const size_t ph = phi_off + (e * d.T + t) * d.K + k;
+            const float old = params[ph];
+            const float hat = tot > 0.f ? (stats[ph] + (tot - den) * old) / tot : old;
+            nw[t] = (1.f - step) * old + step * hat;
+            stats[ph] = 0.f;
+        }
+        const size_t ph0 = phi_off + e * d.T * d.K + k;
+        float* th = theta + e * d.TD * d.K + k;
+        if (d.family == EINET_LEAF_GAUSSIAN) {
+            const float mu = nw[0];
+            const float var2 = fminf(fmaxf(fmaf(-mu, mu, nw[1]), min_var), max_var);
+            const float m2 = fmaf(mu, mu, var2);
+            params[ph0] = mu;
+            params[ph0 + d.K] = m2;
+            const float vd = fmaxf(fmaf(-mu, mu, m2), 1e-30f);   // as k_leaf_derive sees the stored pair
+            th[0] = mu;
+            th[d.K] = -0.5f / vd;
+            th[2 * d.K] = -0.5f * logf(6.283185307179586f * vd);
+        } else {
+            const float p = fminf(fmaxf(nw[0], 1e-6f), 1.f - 1e-6f);
+            params[ph0] = p;
+            th[0] = logf(p);
+            th[d.K] = log1pf(-p);
+        }
     }
 }
 
@@ -748,7 +775,7 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
 
 template <int KQ>
 static void launch_einsum_forward_kq(const DevTables& t, int first, int count, const float* params, float* A,
-                                     float* amax, const Dims& d, hipStream_t s) {
+                                     float* amax, float* logp, const Dims& d, hipStream_t s) {
     const int nkt = (d.K + 3) / 4;
     const int n_btiles = (d.B + 15) / 16;
     const int nw = n_btiles < 8 ? n_btiles : 8;
@@ -761,14 +788,14 @@ static void launch_einsum_forward_kq(const DevTables& t, int first, int count, c
     }
     hipLaunchKernelGGL(k_einsum_forward<KQ>, dim3(count * nkt), dim3(64 * nw), lds, s, t.ein_left + first,
                        t.ein_right + first, t.ein_out + first, t.ein_kout + first, t.ein_woff + first, params, A, amax,
-                       first, d.B, d.K, nkt);
+                       logp, first, d.B, d.K, nkt);
 }
 
 void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, float* amax,
-                           const Dims& d, hipStream_t s) {
+                           float* logp, const Dims& d, hipStream_t s) {
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
-    case J: launch_einsum_forward_kq<J>(t, first, count, params, A, amax, d, s); break;
+    case J: launch_einsum_forward_kq<J>(t, first, count, params, A, amax, logp, d, s); break;
         EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
         EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
         EINET_CASE(16)
@@ -776,16 +803,12 @@ void launch_einsum_forward(const DevTables& t, int first, int count, const float
     }
 }
 
-void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, const Dims& d,
-                           hipStream_t s) {
+void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, float* logp,
+                           const Dims& d, hipStream_t s) {
     if (count == 0) return;
     dim3 grid(count, (d.B * d.K + 255) / 256);
     hipLaunchKernelGGL(k_mixing_forward, grid, dim3(256), 0, s, t.mix_node + first, t.mix_kout + first,
-                       t.mix_cptr + first, t.mix_child, t.mix_voff + first, params, A, d.B, d.K);
-}
-
-void launch_copy_root(const float* A, float* logp, const Dims& d, hipStream_t s) {
-    hipLaunchKernelGGL(k_copy_root, dim3((d.B + 255) / 256), dim3(256), 0, s, A, logp, d.B, d.K);
+                       t.mix_cptr + first, t.mix_child, t.mix_voff + first, params, A, logp, d.B, d.K);
 }
 
 void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
@@ -863,11 +886,11 @@ void launch_update_rows(const DevTables& t, int n_rows, float* params, float* st
                        params, stats, step, w_floor);
 }
 
-void launch_update_leaves(float* params, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off, float step,
-                          float min_var, float max_var, const Dims& d, hipStream_t s) {
-    const int total = d.D * d.C * d.R * d.K;
-    hipLaunchKernelGGL(k_update_leaves, dim3((total + 255) / 256), dim3(256), 0, s, params, stats, phi_off, den_off,
-                       tot_off, step, min_var, max_var, d);
+void launch_update_leaves(float* params, float* stats, float* theta, int64_t phi_off, int64_t den_off,
+                          int64_t tot_off, float step, float min_var, float max_var, const Dims& d, hipStream_t s) {
+    const int total = d.D * d.R * d.K;
+    hipLaunchKernelGGL(k_update_leaves, dim3((total + 255) / 256), dim3(256), 0, s, params, stats, theta, phi_off,
+                       den_off, tot_off, step, min_var, max_var, d);
 }
 
 void launch_fill(float* p, float value, int64_t n, hipStream_t s) {

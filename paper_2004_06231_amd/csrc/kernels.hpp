@@ -29,11 +29,11 @@ struct Dims {
 void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream_t s);
 void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const float* x, const uint8_t* mask,
                          int mask_mode, const float* theta, float* A, const Dims& d, hipStream_t s);
+// logp (may be NULL): the launch that produces the root value also writes it there
 void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, float* amax,
+                           float* logp, const Dims& d, hipStream_t s);
+void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, float* logp,
                            const Dims& d, hipStream_t s);
-void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, const Dims& d,
-                           hipStream_t s);
-void launch_copy_root(const float* A, float* logp, const Dims& d, hipStream_t s);
 
 void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
                             const Dims& d, hipStream_t s);
@@ -51,8 +51,8 @@ void launch_leaf_backward(const DevTables& t, int n_lv, const float* x, const ui
 
 void launch_update_rows(const DevTables& t, int n_rows, float* params, float* stats, float step, float w_floor,
                         hipStream_t s);
-void launch_update_leaves(float* params, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off, float step,
-                          float min_var, float max_var, const Dims& d, hipStream_t s);
+void launch_update_leaves(float* params, float* stats, float* theta, int64_t phi_off, int64_t den_off,
+                          int64_t tot_off, float step, float min_var, float max_var, const Dims& d, hipStream_t s);
 void launch_fill(float* p, float value, int64_t n, hipStream_t s);
 
 }  // namespace einet_impl
