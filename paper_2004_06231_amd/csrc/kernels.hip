@@ -146,22 +146,6 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
     const int c = lane & 15, g = lane >> 4;          // sample column of the tile, lane group
     const int gm = c >> 2, rm = c & 3;               // as A-operand lane: row 4*gm+rm = (k = 4kt+gm, i = 4it+rm)
     const int n_btiles = (B + 15) >> 4;
-    // lane (c, g) holds entries 4s+g of row b of both inputs; the first tile's rows are requested
-    // before W is staged so that the two memory round trips overlap
-    float er[KQ], el[KQ];
-    auto load_rows = [&](int bt) {
-        const int b = bt * 16 + c;
-        const bool ok = bt < n_btiles && b < B;
-#pragma unroll
-        for (int s = 0; s < KQ; ++s) {
-            const int j = 4 * s + g;
-            const bool in = ok && j < K;
-            er[s] = in ? Rp[(size_t)b * K + j] : -INFINITY;
-            el[s] = in ? Lp[(size_t)b * K + j] : -INFINITY;
-        }
-    };
-    load_rows(wave);
-
     // stage W[4kt .. 4kt+3][.][.]
     if ((K & 3) == 0) {
         for (int q = tid; q < 4 * KP * KQ; q += blockDim.x) {
@@ -190,10 +174,15 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
         const int bt = bt0 + wave;
         const int b = bt * 16 + c;
         const bool ok = bt < n_btiles && b < B;
-        if (bt0) load_rows(bt);
+        // lane (c, g) holds entries 4s+g of row b of both inputs
+        float er[KQ], el[KQ];
         float mr = -INFINITY, ml = -INFINITY;
 #pragma unroll
         for (int s = 0; s < KQ; ++s) {
+            const int j = 4 * s + g;
+            const bool in = ok && j < K;
+            er[s] = in ? Rp[(size_t)b * K + j] : -INFINITY;
+            el[s] = in ? Lp[(size_t)b * K + j] : -INFINITY;
             mr = fmaxf(mr, er[s]);
             ml = fmaxf(ml, el[s]);
         }
