@@ -195,8 +195,8 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
         __syncthreads();                             // previous tile's eL reads are done
 #pragma unroll
         for (int s = 0; s < KQ; ++s) {
-            er[s] = expf(er[s] - mr);                // stays in registers: the B operand
-            elw[c * LY::SE + 4 * s + g] = expf(el[s] - ml);
+            er[s] = __expf(er[s] - mr);              // stays in registers: the B operand
+            elw[c * LY::SE + 4 * s + g] = __expf(el[s] - ml);
         }
         __syncthreads();
         float sacc = 0.f;
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
         }
         const int k = 4 * kt + g;
         if (ok && k < kout) {
-            const float val = ml + mr + logf(sacc);
+            const float val = ml + mr + __logf(sacc);
             A[((size_t)e_out[li] * B + b) * K + k] = val;
             if (logp && e_out[li] == 0) logp[b] = val;       // node 0 is the root region (single entry)
         }
@@ -434,15 +434,20 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     const int u0 = wave * U / 8, nu = (wave + 1) * U / 8 - u0;
     const float* qcol[MAXU];
     const float* rcol[MAXU];
-    int ujt[MAXU], ukt[MAXU];
+    int uoff[MAXU], uwl[MAXU];        // offset of (k, i = 0, j) in W / Nw, and in the LDS slice
+    bool uok[MAXU];
 #pragma unroll
     for (int q = 0; q < MAXU; ++q) {
         const int u = min(u0 + q, U - 1);
-        ujt[q] = u / nkt;
-        ukt[q] = u - ujt[q] * nkt;
-        qcol[q] = sQ + g * SQ + 4 * ukt[q] + gm;
-        rcol[q] = sR + g * SR + 16 * ujt[q] + c;
+        const int jt = u / nkt, ukt = u - jt * nkt;
+        qcol[q] = sQ + g * SQ + 4 * ukt + gm;
+        rcol[q] = sR + g * SR + 16 * jt + c;
+        const int k = 4 * ukt + g, j = 16 * jt + c;
+        uok[q] = q < nu && k < kout && j < K;
+        uoff[q] = uok[q] ? (k * K) * K + j : 0;
+        uwl[q] = uok[q] ? k * S + j : 0;
     }
+    float* Nw = stats + wbase;
 
     // staging of eR and Q: thread t owns row t/4 of the pass and a quarter of its columns
     const int srow = tid >> 2, sq = tid & 3;
@@ -457,23 +462,26 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
         const int nb = min(BC, B - b0);
         const int nsteps = (nb + 3) >> 2;
         const bool rok = srow < nb;
-        const size_t ro = (size_t)(b0 + srow) * K;
-        const float al = rok ? aL[b0 + srow] : 0.f, ar = rok ? aR[b0 + srow] : 0.f;
+        const int ro = (b0 + min(srow, nb - 1)) * K;       // a valid row even for the idle tail threads
+        const float al = aL[b0 + min(srow, nb - 1)], ar = aR[b0 + min(srow, nb - 1)];
         __syncthreads();                                   // readers of the previous pass are done
         {
             float rv[KQ], gv[KQ], av[KQ];
 #pragma unroll
             for (int u = 0; u < KQ; ++u) {
                 const int k = sq * KQ + u;
-                rv[u] = (rok && k < K) ? Rp[ro + k] : -INFINITY;
-                gv[u] = (rok && k < kout) ? Gs[ro + k] : 0.f;
-                av[u] = (rok && k < kout) ? As[ro + k] : 0.f;
+                const int kc = VEC ? k : min(k, K - 1);
+                rv[u] = Rp[ro + kc];
+                gv[u] = Gs[ro + min(kc, kout - 1)];
+                av[u] = As[ro + min(kc, kout - 1)];
             }
 #pragma unroll
             for (int u = 0; u < KQ; ++u) {
                 const int k = sq * KQ + u;
-                sR[srow * SR + k] = expf(rv[u] - ar);
-                sQ[srow * SQ + k] = (gv[u] != 0.f) ? gv[u] * vw[u] * expf(al + ar - av[u]) : 0.f;
+                const float e = __expf(rv[u] - ar);
+                const float q = gv[u] * vw[u] * __expf(al + ar - av[u]);
+                sR[srow * SR + k] = (rok && (VEC || k < K)) ? e : 0.f;
+                sQ[srow * SQ + k] = (rok && k < kout && gv[u] != 0.f) ? q : 0.f;
             }
             for (int j = KP + sq; j < SR; j += 4) sR[srow * SR + j] = 0.f;     // columns beyond the padded K
         }
@@ -481,7 +489,10 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
         for (int it = it0; it < it1; ++it) {
             if (it != it0) __syncthreads();                // readers of the previous slice are done
             store_w();
-            sL[srow * 4 + sq] = (rok && 4 * it + sq < K) ? expf(Lp[ro + 4 * it + sq] - al) : 0.f;
+            {
+                const float e = __expf(Lp[ro + min(4 * it + sq, K - 1)] - al);
+                sL[srow * 4 + sq] = (rok && 4 * it + sq < K) ? e : 0.f;
+            }
             __syncthreads();
             // next slice of this pass, or the first slice of the next pass, goes in flight now
             if (it + 1 < it1) fetch_w(it + 1);
@@ -490,14 +501,12 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
             // statistics this wave will update, fetched early
             float nw[MAXU][4];
 #pragma unroll
-            for (int q = 0; q < MAXU; ++q) {
-                const int k = 4 * ukt[q] + g, j = 16 * ujt[q] + c;
+            for (int q = 0; q < MAXU; ++q)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int i = 4 * it + r;
-                    nw[q][r] = (q < nu && k < kout && j < K && i < K) ? stats[wbase + ((size_t)k * K + i) * K + j] : 0.f;
+                    const int i = VEC ? 4 * it + r : min(4 * it + r, K - 1);
+                    nw[q][r] = Nw[uoff[q] + i * K];         // units that are not ours read a valid dummy
                 }
-            }
 
             // ---- GEMM-1
             floatx4 acc1[MAXU];
@@ -555,12 +564,11 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
             // ---- GEMM-1 epilogue: Nw += W * acc
 #pragma unroll
             for (int q = 0; q < MAXU; ++q) {
-                const int k = 4 * ukt[q] + g, j = 16 * ujt[q] + c;
-                if (q < nu && k < kout && j < K) {
+                if (uok[q]) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int i = 4 * it + r;
-                        if (i < K) stats[wbase + ((size_t)k * K + i) * K + j] = nw[q][r] + Wl[k * S + r * SI + j] * acc1[q][r];
+                        if (VEC || i < K) Nw[uoff[q] + i * K] = nw[q][r] + Wl[uwl[q] + r * SI] * acc1[q][r];
                     }
                 }
             }
