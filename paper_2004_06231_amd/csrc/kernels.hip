@@ -328,30 +328,40 @@ struct BwdLayout {
     static constexpr int SI = ((KP + 7) / 16) * 16 + 8;   // stride between the slice's i rows: 8 mod 16
     static constexpr int S = 4 * SI + 4;                  // stride between k rows: 4 mod 32
     static constexpr int NJ = (KP + 15) / 16;             // column tiles of GEMM-1
-    static constexpr int SR = 16 * (NJ | 1);              // eR row stride: 16 mod 32
-    static constexpr int SQ = KP + 1;                     // Q row stride: odd
     static constexpr int BC = 128;                        // samples per pass over the batch
-    static constexpr int OFF_R = KP * S;
-    static constexpr int OFF_Q = OFF_R + BC * SR;
-    static constexpr int OFF_L = ((OFF_Q + BC * SQ + 3) / 4) * 4;
-    static constexpr int LDS_FLOATS = OFF_L + BC * 4;
+    static constexpr int ST = BC + 4;                     // row stride of the sample-major operand copies: 4 mod 32
+    static constexpr int OFF_R = KP * S;                  // eR^T [16 NJ][ST]
+    static constexpr int OFF_Q = OFF_R + 16 * NJ * ST;    // Q^T  [KP][ST]
+    static constexpr int OFF_L = OFF_Q + KP * ST;         // eL^T [4][ST] of the current slice
+    static constexpr int LDS_FLOATS = OFF_L + 4 * ST;
     static constexpr int MAXU = (NJ * KQ + 7) / 8;        // GEMM-1 tiles per wave
     static constexpr int NW4 = (KP * 4 * KQ + 511) / 512; // float4 per thread of one W slice
     static constexpr int NW1 = (KP * 4 * KP + 511) / 512; // floats per thread when K is not a multiple of 4
 };
 
-// GEMM-1 over one pass of the batch for NU tiles of this wave: step s contracts samples 4s..4s+3.
+// GEMM-1 over one pass of the batch for NU tiles of this wave.  The operands are kept
+// sample-major in LDS (eR^T, Q^T, eL^T) and lane group g contracts samples g*RG .. g*RG+RG-1,
+// so that one 16-byte LDS read feeds four consecutive MFMA steps.
 template <int KQ, int NU>
 __device__ __forceinline__ void bwd_gemm1(floatx4* acc1, const float* const* qcol, const float* const* rcol,
-                                          const float* elcol, int nsteps) {
-    using LY = BwdLayout<KQ>;
-#pragma unroll 4
-    for (int s = 0; s < nsteps; ++s) {
-        const float e = elcol[16 * s];
+                                          const float* elcol, int rg) {
+#pragma unroll 2
+    for (int s = 0; s < rg; s += 4) {
+        const float4 e = *reinterpret_cast<const float4*>(elcol + s);
+        float4 qa[NU], rb[NU];
 #pragma unroll
-        for (int q = 0; q < NU; ++q)
-            acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qcol[q][4 * s * LY::SQ] * e, rcol[q][4 * s * LY::SR],
-                                                           acc1[q], 0, 0, 0);
+        for (int q = 0; q < NU; ++q) {
+            qa[q] = *reinterpret_cast<const float4*>(qcol[q] + s);
+            rb[q] = *reinterpret_cast<const float4*>(rcol[q] + s);
+        }
+#pragma unroll
+        for (int q = 0; q < NU; ++q) acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[q].x * e.x, rb[q].x, acc1[q], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < NU; ++q) acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[q].y * e.y, rb[q].y, acc1[q], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < NU; ++q) acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[q].z * e.z, rb[q].z, acc1[q], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < NU; ++q) acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[q].w * e.w, rb[q].w, acc1[q], 0, 0, 0);
     }
 }
 
@@ -363,7 +373,7 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     const float* __restrict__ A, const float* __restrict__ amax, const float* __restrict__ G, float* __restrict__ Gp,
     int item0, int ngroups, int B, int K) {
     using LY = BwdLayout<KQ>;
-    constexpr int KP = LY::KP, SI = LY::SI, S = LY::S, SR = LY::SR, SQ = LY::SQ, BC = LY::BC, MAXU = LY::MAXU;
+    constexpr int KP = LY::KP, SI = LY::SI, S = LY::S, ST = LY::ST, BC = LY::BC, MAXU = LY::MAXU;
     extern __shared__ float lds[];
     float* Wl = lds;
     float* sR = lds + LY::OFF_R;
@@ -440,8 +450,8 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     for (int q = 0; q < MAXU; ++q) {
         const int u = min(u0 + q, U - 1);
         const int jt = u / nkt, ukt = u - jt * nkt;
-        qcol[q] = sQ + g * SQ + 4 * ukt + gm;
-        rcol[q] = sR + g * SR + 16 * jt + c;
+        qcol[q] = sQ + (4 * ukt + gm) * ST;     // + g*RG + s
+        rcol[q] = sR + (16 * jt + c) * ST;
         const int k = 4 * ukt + g, j = 16 * jt + c;
         uok[q] = q < nu && k < kout && j < K;
         uoff[q] = uok[q] ? (k * K) * K + j : 0;
@@ -460,7 +470,7 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
 
     for (int b0 = 0; b0 < B; b0 += BC) {
         const int nb = min(BC, B - b0);
-        const int nsteps = (nb + 3) >> 2;
+        const int rg = (((nb + 3) >> 2) + 3) & ~3;         // samples per lane group in GEMM-1, multiple of 4
         const bool rok = srow < nb;
         const int ro = (b0 + min(srow, nb - 1)) * K;       // a valid row even for the idle tail threads
         const float al = aL[b0 + min(srow, nb - 1)], ar = aR[b0 + min(srow, nb - 1)];
@@ -480,10 +490,10 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
                 const int k = sq * KQ + u;
                 const float e = __expf(rv[u] - ar);
                 const float q = gv[u] * vw[u] * __expf(al + ar - av[u]);
-                sR[srow * SR + k] = (rok && (VEC || k < K)) ? e : 0.f;
-                sQ[srow * SQ + k] = (rok && k < kout && gv[u] != 0.f) ? q : 0.f;
+                sR[k * ST + srow] = (rok && (VEC || k < K)) ? e : 0.f;
+                sQ[k * ST + srow] = (rok && k < kout && gv[u] != 0.f) ? q : 0.f;
             }
-            for (int j = KP + sq; j < SR; j += 4) sR[srow * SR + j] = 0.f;     // columns beyond the padded K
+            for (int j = KP + sq; j < 16 * LY::NJ; j += 4) sR[j * ST + srow] = 0.f;   // rows beyond the padded K
         }
 
         for (int it = it0; it < it1; ++it) {
@@ -491,7 +501,7 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
             store_w();
             {
                 const float e = __expf(Lp[ro + min(4 * it + sq, K - 1)] - al);
-                sL[srow * 4 + sq] = (rok && 4 * it + sq < K) ? e : 0.f;
+                sL[sq * ST + srow] = (rok && 4 * it + sq < K) ? e : 0.f;
             }
             __syncthreads();
             // next slice of this pass, or the first slice of the next pass, goes in flight now
@@ -513,12 +523,19 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
 #pragma unroll
             for (int q = 0; q < MAXU; ++q) acc1[q] = floatx4{0.f, 0.f, 0.f, 0.f};
             {
-                const float* elcol = sL + g * 4 + rm;
-                if (nu == MAXU) bwd_gemm1<KQ, MAXU>(acc1, qcol, rcol, elcol, nsteps);
+                const float* elcol = sL + rm * ST + g * rg;
+                const float* qc[MAXU];
+                const float* rc[MAXU];
+#pragma unroll
+                for (int q = 0; q < MAXU; ++q) {
+                    qc[q] = qcol[q] + g * rg;
+                    rc[q] = rcol[q] + g * rg;
+                }
+                if (nu == MAXU) bwd_gemm1<KQ, MAXU>(acc1, qc, rc, elcol, rg);
                 else if (MAXU > 1 && nu == MAXU - 1)
-                    bwd_gemm1<KQ, (MAXU > 1 ? MAXU - 1 : 1)>(acc1, qcol, rcol, elcol, nsteps);
+                    bwd_gemm1<KQ, (MAXU > 1 ? MAXU - 1 : 1)>(acc1, qc, rc, elcol, rg);
                 else
-                    for (int q = 0; q < nu; ++q) bwd_gemm1<KQ, 1>(acc1 + q, qcol + q, rcol + q, elcol, nsteps);
+                    for (int q = 0; q < nu; ++q) bwd_gemm1<KQ, 1>(acc1 + q, qc + q, rc + q, elcol, rg);
             }
 
             // ---- GEMM-2: one tile of 16 samples per wave
@@ -527,16 +544,16 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
                 const bool ok = bl < nb;
                 float erg[KQ];
 #pragma unroll
-                for (int s = 0; s < KQ; ++s) erg[s] = sR[bl * SR + 4 * s + g];
-                const float* qrow = sQ + bl * SQ + g;
-                const float4 e4 = *reinterpret_cast<const float4*>(sL + bl * 4);
+                for (int s = 0; s < KQ; ++s) erg[s] = sR[(4 * s + g) * ST + bl];
+                const float* qrow = sQ + g * ST + bl;
+                const float4 e4 = make_float4(sL[bl], sL[ST + bl], sL[2 * ST + bl], sL[3 * ST + bl]);
                 const float* wl = Wl + g * S + rm * SI + gm;      // row 4*gm+rm of a tile = (j = 4jt+gm, i = 4it+rm)
                 floatx4 acc[KQ];
 #pragma unroll
                 for (int jt = 0; jt < KQ; ++jt) acc[jt] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 2
                 for (int s = 0; s < KQ; ++s) {
-                    const float qs = qrow[4 * s];
+                    const float qs = qrow[4 * s * ST];
 #pragma unroll
                     for (int jt = 0; jt < KQ; ++jt)
                         acc[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl[4 * s * S + 4 * jt], qs, acc[jt], 0, 0, 0);
