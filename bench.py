@@ -159,15 +159,14 @@ def main():
     if not args.no_cpu_baseline:
         # the float64 oracle, as it stands, on a bounded sample of the same batch
         from tests.common import make_config
-        n_cpu = 16
         _, oracle, _, xs, _ = make_config(WORKLOAD, batch=B)
         assert np.array_equal(xs, x_host)
         t0 = time.perf_counter()
-        stats, _ = oracle.em_accumulate(xs[:n_cpu], None, chunk=8)
+        stats, _ = oracle.em_accumulate(xs, None, chunk=8)
         oracle.em_update(stats, **em_kw)
         t_cpu = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 3), "unit": "samples/s", "cores": 1, "kind": "oracle",
-                               "sample": f"first {n_cpu} of the {B} samples of {cfg['name']}, one EM step "
+        out["cpu_baseline"] = {"value": round(B / t_cpu, 3), "unit": "samples/s", "cores": 1, "kind": "oracle",
+                               "sample": f"one EM step on the whole batch of {B} samples of {cfg['name']} "
                                          f"(float64 NumPy, single thread), {t_cpu:.1f} s"}
     print(json.dumps(out))
 
