@@ -185,10 +185,16 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
  *            num/den when nothing was masked), phi <- (1-step) phi + step hat;
  *            Bernoulli p clipped to [1e-6, 1-1e-6]; Gaussian variance
  *            E[x^2]-E[x]^2 projected to [min_var, max_var] (Sec. 4.2).
- * Zeroes the statistics and refreshes the derived leaf constants. */
+ * Afterwards the statistics are zero for every later call: the mixing and leaf
+ * statistics are cleared in memory; the einsum-weight statistics Nw are left
+ * as they are and the next einet_em_accumulate overwrites them instead of
+ * adding (saves one pass over the largest buffer), so the Nw part of the
+ * caller's buffer is unspecified between this call and that one; use
+ * einet_em_reset to have zeros in memory.  Also refreshes the derived leaf
+ * constants. */
 int einet_em_update(einet_t* h, float step, float min_var, float max_var, float w_floor, void* stream);
 
-/* Zeroes the statistics buffer. */
+/* Zeroes the whole statistics buffer in memory. */
 int einet_em_reset(einet_t* h, void* stream);
 
 /* Per-kernel timing for benchmarks (no passage of the paper: measurement aid).

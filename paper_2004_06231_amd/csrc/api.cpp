@@ -32,6 +32,10 @@ struct einet {
     struct Timed { int cls; hipEvent_t start, stop; };
     std::vector<Timed> timed;
 
+    // true while the einsum-weight statistics are logically zero: einet_em_update does not clear them,
+    // the next einet_em_accumulate overwrites them instead of adding
+    bool weight_stats_zero = false;
+
     bool bound = false;
     float* params = nullptr;
     float* stats = nullptr;
@@ -258,6 +262,7 @@ int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_
     EINET_TABLES(X)
 #undef X
     h->bound = true;
+    h->weight_stats_zero = false;   // the caller's buffer may hold statistics to be continued
     return EINET_OK;
 }
 
@@ -299,8 +304,8 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
                                    step == 0, G, Gp, d, s);
         });
         run(h, KC_EINSUM_BWD, s, [&] {
-            launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params,
-                                   h->stats, A, amax, G, Gp, d, s);
+            launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
+                                   !h->weight_stats_zero, h->params, h->stats, A, amax, G, Gp, d, s);
         });
     }
     const int leaf_step = p.num_layers;
@@ -316,6 +321,7 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
         run(h, KC_MIXING_BWD, s, [&] {
             launch_mixing_stats(h->dt, (int)p.mix_node.size(), p.max_mix_children, h->params, h->stats, A, G, d, s);
         });
+    h->weight_stats_zero = false;
     return check_hip(h, "einet_em_accumulate");
 }
 
@@ -329,10 +335,11 @@ int einet_em_update(einet_t* h, float step, float min_var, float max_var, float 
     const Dims d = dims_of(h, 0);
     const Plan& p = h->plan;
     run(h, KC_UPDATE, s, [&] {
-        launch_update_rows(h->dt, (int)p.row_off.size(), h->params, h->stats, step, w_floor, s);
+        launch_update_rows(h->dt, (int)p.row_off.size(), p.n_weight_rows, h->params, h->stats, step, w_floor, s);
         launch_update_leaves(h->params, h->stats, reinterpret_cast<float*>(h->ws + h->off_theta), p.phi_offset,
                              p.den_offset, p.tot_offset, step, min_var, max_var, d, s);
     });
+    h->weight_stats_zero = true;
     return check_hip(h, "einet_em_update");
 }
 
@@ -340,6 +347,7 @@ int einet_em_reset(einet_t* h, void* stream) {
     if (!h) return EINET_ERR_INVALID_ARG;
     if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
     launch_fill(h->stats, 0.f, h->plan.n_stats, static_cast<hipStream_t>(stream));
+    h->weight_stats_zero = true;
     return check_hip(h, "einet_em_reset");
 }
 

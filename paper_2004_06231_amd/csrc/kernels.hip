@@ -365,7 +365,7 @@ __device__ __forceinline__ void bwd_gemm1(floatx4* acc1, const float* const* qco
     }
 }
 
-template <int KQ, bool VEC>
+template <int KQ, bool VEC, bool ACCUM>
 __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_reg,
     const int32_t* __restrict__ e_kout, const int32_t* __restrict__ e_woff, const int32_t* __restrict__ e_voff,
@@ -508,14 +508,14 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
             if (it + 1 < it1) fetch_w(it + 1);
             else if (b0 + BC < B) fetch_w(it0);
 
-            // statistics this wave will update, fetched early
+            // statistics this wave will update, fetched early (not needed when they are known to be zero)
             float nw[MAXU][4];
 #pragma unroll
             for (int q = 0; q < MAXU; ++q)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int i = VEC ? 4 * it + r : min(4 * it + r, K - 1);
-                    nw[q][r] = Nw[uoff[q] + i * K];         // units that are not ours read a valid dummy
+                    nw[q][r] = ACCUM ? Nw[uoff[q] + i * K] : 0.f;   // units that are not ours read a valid dummy
                 }
 
             // ---- GEMM-1
@@ -656,10 +656,11 @@ __global__ __launch_bounds__(1024) void k_leaf_backward(
 template <int NPL>
 __global__ __launch_bounds__(256) void k_update_rows(const int32_t* __restrict__ row_off,
                                                      const int32_t* __restrict__ row_len, int n_rows,
-                                                     float* __restrict__ params, float* __restrict__ stats,
-                                                     float step, float w_floor) {
+                                                     int n_lazy_rows, float* __restrict__ params,
+                                                     float* __restrict__ stats, float step, float w_floor) {
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (row >= n_rows) return;
+    const bool clear = row >= n_lazy_rows;   // the first rows are overwritten, not added to, by the next E-step
     const int off = row_off[row], len = row_len[row];
     if (len <= 64 * NPL) {
         float n[NPL], w[NPL];
@@ -689,7 +690,7 @@ __global__ __launch_bounds__(256) void k_update_rows(const int32_t* __restrict__
             const int e = lane + 64 * t;
             if (e < len) {
                 params[off + e] = (1.f - step) * w[t] + step * (n[t] * norm);
-                stats[off + e] = 0.f;
+                if (clear) stats[off + e] = 0.f;
             }
         }
         return;
@@ -710,7 +711,7 @@ __global__ __launch_bounds__(256) void k_update_rows(const int32_t* __restrict__
         float hat = tot > 0.f ? stats[off + e] * inv : old;
         if (w_floor > 0.f) hat = fmaxf(hat, w_floor) * norm;
         params[off + e] = (1.f - step) * old + step * hat;
-        stats[off + e] = 0.f;
+        if (clear) stats[off + e] = 0.f;
     }
 }
 
@@ -841,15 +842,19 @@ void launch_mixing_stats(const DevTables& t, int count, int max_children, const 
 }
 
 template <int KQ>
-static void launch_einsum_backward_kq(const DevTables& t, int first, int count, const float* params, float* stats,
-                                      const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
-                                      hipStream_t s) {
+static void launch_einsum_backward_kq(const DevTables& t, int first, int count, bool accumulate,
+                                      const float* params, float* stats, const float* A, const float* amax,
+                                      const float* G, float* Gp, const Dims& d, hipStream_t s) {
     const size_t lds = sizeof(float) * BwdLayout<KQ>::LDS_FLOATS;
     static bool attr_set = false;
     if (lds > 64 * 1024 && !attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, true>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, true, true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, false>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, false, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, true, false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, false, false>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
@@ -857,22 +862,27 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
     // 256 compute units (one workgroup per unit)
     int ngroups = 256 / count;
     ngroups = ngroups < 1 ? 1 : (ngroups > KQ ? KQ : ngroups);
-#define EINET_LAUNCH(V)                                                                                           \
-    hipLaunchKernelGGL((k_einsum_backward<KQ, V>), dim3(count * ngroups), dim3(512), lds, s, t.ein_left + first,       \
+#define EINET_LAUNCH(V, ACC)                                                                                      \
+    hipLaunchKernelGGL((k_einsum_backward<KQ, V, ACC>), dim3(count * ngroups), dim3(512), lds, s, t.ein_left + first,  \
                        t.ein_right + first, t.ein_reg + first, t.ein_kout + first, t.ein_woff + first,                \
                        t.ein_voff + first, t.ein_vstr + first, params, stats, A, amax, G, Gp, first, ngroups, d.B, d.K)
-    if ((d.K & 3) == 0) EINET_LAUNCH(true);
-    else EINET_LAUNCH(false);
+    if ((d.K & 3) == 0) {
+        if (accumulate) EINET_LAUNCH(true, true);
+        else EINET_LAUNCH(true, false);
+    } else {
+        if (accumulate) EINET_LAUNCH(false, true);
+        else EINET_LAUNCH(false, false);
+    }
 #undef EINET_LAUNCH
 }
 
-void launch_einsum_backward(const DevTables& t, int first, int count, const float* params, float* stats,
-                            const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
+void launch_einsum_backward(const DevTables& t, int first, int count, bool accumulate, const float* params,
+                            float* stats, const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
                             hipStream_t s) {
     if (count == 0) return;
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
-    case J: launch_einsum_backward_kq<J>(t, first, count, params, stats, A, amax, G, Gp, d, s); break;
+    case J: launch_einsum_backward_kq<J>(t, first, count, accumulate, params, stats, A, amax, G, Gp, d, s); break;
         EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
         EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
         EINET_CASE(16)
@@ -894,10 +904,10 @@ void launch_leaf_backward(const DevTables& t, int n_lv, const float* x, const ui
 #undef EINET_LAUNCH
 }
 
-void launch_update_rows(const DevTables& t, int n_rows, float* params, float* stats, float step, float w_floor,
-                        hipStream_t s) {
+void launch_update_rows(const DevTables& t, int n_rows, int n_lazy_rows, float* params, float* stats, float step,
+                        float w_floor, hipStream_t s) {
     hipLaunchKernelGGL(k_update_rows<32>, dim3((n_rows + 3) / 4), dim3(256), 0, s, t.row_off, t.row_len, n_rows,
-                       params, stats, step, w_floor);
+                       n_lazy_rows, params, stats, step, w_floor);
 }
 
 void launch_update_leaves(float* params, float* stats, float* theta, int64_t phi_off, int64_t den_off,

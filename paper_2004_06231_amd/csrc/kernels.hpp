@@ -37,8 +37,9 @@ void launch_mixing_forward(const DevTables& t, int first, int count, const float
 
 void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
                             const Dims& d, hipStream_t s);
-void launch_einsum_backward(const DevTables& t, int first, int count, const float* params, float* stats,
-                            const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
+// accumulate = false: the weight statistics of these items are known to be zero and are overwritten
+void launch_einsum_backward(const DevTables& t, int first, int count, bool accumulate, const float* params,
+                            float* stats, const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
                             hipStream_t s);
 void launch_mixing_stats(const DevTables& t, int count, int max_children, const float* params, float* stats,
                          const float* A, const float* G, const Dims& d, hipStream_t s);
@@ -49,8 +50,9 @@ void launch_leaf_backward(const DevTables& t, int n_lv, const float* x, const ui
                           const float* G, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off,
                           const Dims& d, hipStream_t s);
 
-void launch_update_rows(const DevTables& t, int n_rows, float* params, float* stats, float step, float w_floor,
-                        hipStream_t s);
+// the statistics of the first n_lazy_rows rows are left as they are (the next E-step overwrites them)
+void launch_update_rows(const DevTables& t, int n_rows, int n_lazy_rows, float* params, float* stats, float step,
+                        float w_floor, hipStream_t s);
 void launch_update_leaves(float* params, float* stats, float* theta, int64_t phi_off, int64_t den_off,
                           int64_t tot_off, float step, float min_var, float max_var, const Dims& d, hipStream_t s);
 void launch_fill(float* p, float value, int64_t n, hipStream_t s);

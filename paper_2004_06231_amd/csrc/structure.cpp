@@ -312,6 +312,7 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& p, std::
             p.row_off.push_back((int32_t)(p.w_offset[n] + int64_t(k) * K * K));
             p.row_len.push_back(K * K);
         }
+    p.n_weight_rows = (int)p.row_off.size();
     for (int s = 0; s < nr; ++s)
         if (p.v_offset[s] >= 0) {
             int c = (int)g.parts_of[s].size();

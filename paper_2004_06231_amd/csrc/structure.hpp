@@ -37,6 +37,7 @@ struct Plan {
     int num_layers = 0;
     int max_mix_children = 0;
     int max_leaf_scope = 0;
+    int n_weight_rows = 0;  // rows of row_off/row_len that belong to einsum weights (the rest: mixing weights)
 
     // Index tables (see EINET_TABLES): einsum items in execution order (bottom layer first); mixing items
     // grouped by the layer whose einsum they follow; leaves; top-down items (sum layers from the root

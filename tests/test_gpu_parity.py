@@ -71,7 +71,14 @@ def test_em_update_matches_oracle(i):
     got = m.params.cpu().numpy().astype(np.float64)
     err = np.abs(got - ref)
     assert np.all(err <= 1e-3 * np.abs(ref) + 1e-7), f"worst {err.max():.3e}"
-    assert float(m.stats.abs().max()) == 0.0                     # the update zeroes the accumulators
+    # after the update the accumulators start from zero: one more E-step gives the statistics of one batch
+    m.set_params(c["flat"])
+    m.em_accumulate(dev(c["x"]))
+    assert_stats_close(m.stats, c["ref_stats"], c["oracle"].layout, m.n_params)
+    m.em_reset()
+    assert float(m.stats.abs().max()) == 0.0
+    m.em_accumulate(dev(c["x"]))
+    m.em_update(**kw)
     # the refreshed leaf constants are in use: logP under the new parameters
     assert_logp_close(m.logp(dev(c["x"][:8])), oracle.logp(c["x"][:8]))
     oracle.set_flat_params(c["flat"])
