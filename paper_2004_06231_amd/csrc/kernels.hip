@@ -515,7 +515,8 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int i = VEC ? 4 * it + r : min(4 * it + r, K - 1);
-                    nw[q][r] = ACCUM ? Nw[uoff[q] + i * K] : 0.f;   // units that are not ours read a valid dummy
+                    // (units that are not ours read a valid dummy; later passes over the batch always add)
+                    nw[q][r] = (ACCUM || b0 > 0) ? Nw[uoff[q] + i * K] : 0.f;
                 }
 
             // ---- GEMM-1
