@@ -44,12 +44,12 @@ def algorithmic_work(st, K, C, R, T, TD, B, D):
                             sum(12.0 * ko * K * K + 4.0 * B * (4 * K + 2 * ko) for ko in kout))
     w["mixing_forward"] = (0.0, sum(4.0 * (c + 1) * B * (1 if s == 0 else K) for s, c in mix.items()))
     w["leaf_forward"] = (0.0, 4.0 * B * D * C + 4.0 * D * C * R * TD * K + 4.0 * n_leaf * B * K)
-    w["leaf_backward"] = (0.0, 4.0 * B * D * C + 4.0 * n_leaf * B * K + 8.0 * (D * C * R * T * K + 2 * D * R * K))
+    w["leaf_mixing_backward"] = (0.0, 4.0 * B * D * C + 4.0 * n_leaf * B * K + 8.0 * (D * C * R * T * K + 2 * D * R * K)
+                                 + sum(4.0 * (c + 2) * B * (1 if s == 0 else K) for s, c in mix.items()))
     n_param = float(st["phi_offset"]) + D * C * R * T * K
     w["em_update"] = (0.0, 4.0 * 3 * n_param)       # read statistics and parameters, write parameters (+ zeroing)
     n_regions = st["num_regions"]
     w["region_backward"] = (0.0, 4.0 * B * K * (n_regions + 2 * len(part)))
-    w["mixing_backward"] = (0.0, sum(4.0 * (c + 2) * B * (1 if s == 0 else K) for s, c in mix.items()))
     return w
 
 

@@ -95,9 +95,9 @@ int check_batch_args(einet_t* h, const float* x, const uint8_t* mask, int mask_m
     return EINET_OK;
 }
 
-enum KernelClass { KC_LEAF_FWD, KC_EINSUM_FWD, KC_MIXING_FWD, KC_REGION_BWD, KC_EINSUM_BWD, KC_LEAF_BWD, KC_MIXING_BWD, KC_UPDATE, KC_COUNT };
+enum KernelClass { KC_LEAF_FWD, KC_EINSUM_FWD, KC_MIXING_FWD, KC_REGION_BWD, KC_EINSUM_BWD, KC_LEAF_BWD, KC_UPDATE, KC_COUNT };
 const char* const kKernelClassNames[KC_COUNT] = {"leaf_forward", "einsum_forward", "mixing_forward", "region_backward",
-                                                 "einsum_backward", "leaf_backward", "mixing_backward", "em_update"};
+                                                 "einsum_backward", "leaf_mixing_backward", "em_update"};
 
 // Runs `launch` (which enqueues kernels on s); when profiling, brackets it with two events.
 template <class F>
@@ -314,13 +314,9 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
                                p.rb_layer_ptr[leaf_step + 1] - p.rb_layer_ptr[leaf_step], false, G, Gp, d, s);
     });
     run(h, KC_LEAF_BWD, s, [&] {
-        launch_leaf_backward(h->dt, (int)p.lv_leaf.size(), x_dev, mask_dev, mask_mode, G, h->stats, p.phi_offset,
-                             p.den_offset, p.tot_offset, d, s);
+        launch_tail_backward(h->dt, (int)p.lv_leaf.size(), (int)p.mix_node.size(), p.max_mix_children, x_dev, mask_dev,
+                             mask_mode, h->params, A, G, h->stats, p.phi_offset, p.den_offset, p.tot_offset, d, s);
     });
-    if (!p.mix_node.empty())
-        run(h, KC_MIXING_BWD, s, [&] {
-            launch_mixing_stats(h->dt, (int)p.mix_node.size(), p.max_mix_children, h->params, h->stats, A, G, d, s);
-        });
     h->weight_stats_zero = false;
     return check_hip(h, "einet_em_accumulate");
 }
@@ -335,9 +331,9 @@ int einet_em_update(einet_t* h, float step, float min_var, float max_var, float 
     const Dims d = dims_of(h, 0);
     const Plan& p = h->plan;
     run(h, KC_UPDATE, s, [&] {
-        launch_update_rows(h->dt, (int)p.row_off.size(), p.n_weight_rows, h->params, h->stats, step, w_floor, s);
-        launch_update_leaves(h->params, h->stats, reinterpret_cast<float*>(h->ws + h->off_theta), p.phi_offset,
-                             p.den_offset, p.tot_offset, step, min_var, max_var, d, s);
+        launch_em_update(h->dt, (int)p.row_off.size(), p.n_weight_rows, h->params, h->stats,
+                         reinterpret_cast<float*>(h->ws + h->off_theta), p.phi_offset, p.den_offset, p.tot_offset,
+                         step, min_var, max_var, w_floor, d, s);
     });
     h->weight_stats_zero = true;
     return check_hip(h, "einet_em_update");

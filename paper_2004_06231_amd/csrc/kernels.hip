@@ -264,17 +264,17 @@ __global__ void k_region_assemble(const int32_t* __restrict__ r_node, const int3
 }
 
 // Statistics of the mixing weights (App. B, Eq. 6): Nv[s,k,c] += v[s,k,c] * sum_b G[s][b,k] * S^c[b,k] / S[b,k].
-// One workgroup per (mixing item, child); a reduction over the batch through LDS.
-__global__ __launch_bounds__(1024) void k_mixing_stats(const int32_t* __restrict__ m_node,
-                                                       const int32_t* __restrict__ m_kout,
-                                                       const int32_t* __restrict__ m_cptr,
-                                                       const int32_t* __restrict__ m_child,
-                                                       const int32_t* __restrict__ m_voff,
-                                                       const float* __restrict__ params, float* __restrict__ stats,
-                                                       const float* __restrict__ A, const float* __restrict__ G, int B,
-                                                       int K) {
+// One workgroup per (mixing item, child); a reduction over the batch through LDS.  Runs in the same
+// launch as the leaf statistics (k_tail_backward): the two are independent.
+__device__ __forceinline__ void mixing_stats_body(int item, int c, const int32_t* __restrict__ m_node,
+                                                  const int32_t* __restrict__ m_kout,
+                                                  const int32_t* __restrict__ m_cptr,
+                                                  const int32_t* __restrict__ m_child,
+                                                  const int32_t* __restrict__ m_voff, const float* __restrict__ params,
+                                                  float* __restrict__ stats, const float* __restrict__ A,
+                                                  const float* __restrict__ G, int B, int K) {
     __shared__ float red[1024];
-    const int item = blockIdx.x, c = blockIdx.y, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
     if (c >= nc) return;
     const int kout = m_kout[item];
@@ -599,15 +599,15 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
 // owns 1024/NCH consecutive statistics entries (leaf variable, channel, k); its NCH
 // parts each walk every NCH-th sample and the partial sums meet in LDS.
 template <int NCH>
-__global__ __launch_bounds__(1024) void k_leaf_backward(
-    const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var, const int32_t* __restrict__ leaf_node,
+__device__ __forceinline__ void leaf_backward_body(
+    int block, const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var, const int32_t* __restrict__ leaf_node,
     const int32_t* __restrict__ leaf_replica, int n_lv, const float* __restrict__ x,
     const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, float* __restrict__ stats,
     int64_t phi_off, int64_t den_off, int64_t tot_off, Dims d) {
     constexpr int NO = 1024 / NCH;
     __shared__ float red[NCH][4][NO];
     const int lo = threadIdx.x % NO, part_id = threadIdx.x / NO;
-    const int idx = blockIdx.x * NO + lo;
+    const int idx = block * NO + lo;
     const bool valid = idx < n_lv * d.C * d.K;
     const int k = valid ? idx % d.K : 0, c = valid ? (idx / d.K) % d.C : 0, e = valid ? idx / (d.K * d.C) : 0;
     const int leaf = lv_leaf[e], var = lv_var[e], r = leaf_replica[leaf];
@@ -650,16 +650,37 @@ __global__ __launch_bounds__(1024) void k_leaf_backward(
     }
 }
 
+// Last launch of the top-down pass: leaf statistics in the first n_leaf_blocks workgroups, mixing
+// statistics in the others (item = idx / max_children, child = idx % max_children).
+template <int NCH>
+__global__ __launch_bounds__(1024) void k_tail_backward(
+    int n_leaf_blocks, int max_children, const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var,
+    const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica, int n_lv,
+    const float* __restrict__ x, const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G,
+    float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const int32_t* __restrict__ m_node,
+    const int32_t* __restrict__ m_kout, const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
+    const int32_t* __restrict__ m_voff, const float* __restrict__ params, const float* __restrict__ A, Dims d) {
+    const int blk = blockIdx.x;
+    if (blk < n_leaf_blocks) {
+        leaf_backward_body<NCH>(blk, lv_leaf, lv_var, leaf_node, leaf_replica, n_lv, x, mask, mask_mode, G, stats,
+                                phi_off, den_off, tot_off, d);
+    } else {
+        const int idx = blk - n_leaf_blocks;
+        mixing_stats_body(idx / max_children, idx % max_children, m_node, m_kout, m_cptr, m_child, m_voff, params,
+                          stats, A, G, d.B, d.K);
+    }
+}
+
 // ------------------------------------------------------------------ M-step (Eq. 7-9)
 // One wave per weight row (the K*K children of a sum entry, or its C mixing weights).
 // Rows of up to 64*NPL entries are held in registers, so statistics and parameters
 // are each read once and written once; longer rows fall back to several passes.
 template <int NPL>
-__global__ __launch_bounds__(256) void k_update_rows(const int32_t* __restrict__ row_off,
-                                                     const int32_t* __restrict__ row_len, int n_rows,
-                                                     int n_lazy_rows, float* __restrict__ params,
-                                                     float* __restrict__ stats, float step, float w_floor) {
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+__device__ __forceinline__ void update_rows_body(int block, const int32_t* __restrict__ row_off,
+                                                 const int32_t* __restrict__ row_len, int n_rows, int n_lazy_rows,
+                                                 float* __restrict__ params, float* __restrict__ stats, float step,
+                                                 float w_floor) {
+    const int row = block * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (row >= n_rows) return;
     const bool clear = row >= n_lazy_rows;   // the first rows are overwritten, not added to, by the next E-step
     const int off = row_off[row], len = row_len[row];
@@ -719,10 +740,11 @@ __global__ __launch_bounds__(256) void k_update_rows(const int32_t* __restrict__
 // Leaf M-step (Eq. 7-9, Sec. 4.2): one thread per (variable, replica, k) updates the
 // parameters of all channels, clears the statistics it owns and refreshes the
 // constants the leaf layer derives from the parameters.
-__global__ void k_update_leaves(float* __restrict__ params, float* __restrict__ stats, float* __restrict__ theta,
-                                int64_t phi_off, int64_t den_off, int64_t tot_off, float step, float min_var,
-                                float max_var, Dims d) {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void update_leaves_body(int block, float* __restrict__ params, float* __restrict__ stats,
+                                                   float* __restrict__ theta, int64_t phi_off, int64_t den_off,
+                                                   int64_t tot_off, float step, float min_var, float max_var,
+                                                   Dims d) {
+    const int idx = block * blockDim.x + threadIdx.x;
     if (idx >= d.D * d.R * d.K) return;
     const int k = idx % d.K, r = (idx / d.K) % d.R, var = idx / (d.K * d.R);
     const size_t o = ((size_t)var * d.R + r) * d.K + k;
@@ -758,6 +780,21 @@ __global__ void k_update_leaves(float* __restrict__ params, float* __restrict__ 
             th[d.K] = log1pf(-p);
         }
     }
+}
+
+// The whole M-step in one launch: weight rows in the first n_row_blocks workgroups, leaves in the others.
+template <int NPL>
+__global__ __launch_bounds__(256) void k_em_update(int n_row_blocks, const int32_t* __restrict__ row_off,
+                                                   const int32_t* __restrict__ row_len, int n_rows, int n_lazy_rows,
+                                                   float* __restrict__ params, float* __restrict__ stats,
+                                                   float* __restrict__ theta, int64_t phi_off, int64_t den_off,
+                                                   int64_t tot_off, float step, float min_var, float max_var,
+                                                   float w_floor, Dims d) {
+    if ((int)blockIdx.x < n_row_blocks)
+        update_rows_body<NPL>(blockIdx.x, row_off, row_len, n_rows, n_lazy_rows, params, stats, step, w_floor);
+    else
+        update_leaves_body(blockIdx.x - n_row_blocks, params, stats, theta, phi_off, den_off, tot_off, step, min_var,
+                           max_var, d);
 }
 
 __global__ void k_fill(float* __restrict__ p, float value, int64_t n) {
@@ -835,13 +872,6 @@ void launch_region_assemble(const DevTables& t, int first, int count, bool is_ro
                        t.rb_pptr + first, t.rb_pblk, is_root_layer ? 1 : 0, G, Gp, d.B, d.K);
 }
 
-void launch_mixing_stats(const DevTables& t, int count, int max_children, const float* params, float* stats,
-                         const float* A, const float* G, const Dims& d, hipStream_t s) {
-    if (count == 0) return;
-    hipLaunchKernelGGL(k_mixing_stats, dim3(count, max_children), dim3(1024), 0, s, t.mix_node, t.mix_kout, t.mix_cptr,
-                       t.mix_child, t.mix_voff, params, stats, A, G, d.B, d.K);
-}
-
 template <int KQ>
 static void launch_einsum_backward_kq(const DevTables& t, int first, int count, bool accumulate,
                                       const float* params, float* stats, const float* A, const float* amax,
@@ -891,31 +921,32 @@ void launch_einsum_backward(const DevTables& t, int first, int count, bool accum
     }
 }
 
-void launch_leaf_backward(const DevTables& t, int n_lv, const float* x, const uint8_t* mask, int mask_mode,
-                          const float* G, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off,
-                          const Dims& d, hipStream_t s) {
+void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_children, const float* x,
+                          const uint8_t* mask, int mask_mode, const float* params, const float* A, const float* G,
+                          float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const Dims& d,
+                          hipStream_t s) {
     const int total = n_lv * d.C * d.K;
     const int nch = d.B >= 16 ? 4 : 1;
     const int no = 1024 / nch;
-#define EINET_LAUNCH(N)                                                                                            \
-    hipLaunchKernelGGL(k_leaf_backward<N>, dim3((total + no - 1) / no), dim3(1024), 0, s, t.lv_leaf, t.lv_var,        \
-                       t.leaf_node, t.leaf_replica, n_lv, x, mask, mask_mode, G, stats, phi_off, den_off, tot_off, d)
+    const int n_leaf_blocks = (total + no - 1) / no;
+    const int blocks = n_leaf_blocks + n_mix * max_children;
+#define EINET_LAUNCH(N)                                                                                              \
+    hipLaunchKernelGGL(k_tail_backward<N>, dim3(blocks), dim3(1024), 0, s, n_leaf_blocks, max_children > 0 ? max_children : 1, \
+                       t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, n_lv, x, mask, mask_mode, G, stats, phi_off, \
+                       den_off, tot_off, t.mix_node, t.mix_kout, t.mix_cptr, t.mix_child, t.mix_voff, params, A, d)
     if (nch == 4) EINET_LAUNCH(4);
     else EINET_LAUNCH(1);
 #undef EINET_LAUNCH
 }
 
-void launch_update_rows(const DevTables& t, int n_rows, int n_lazy_rows, float* params, float* stats, float step,
-                        float w_floor, hipStream_t s) {
-    hipLaunchKernelGGL(k_update_rows<32>, dim3((n_rows + 3) / 4), dim3(256), 0, s, t.row_off, t.row_len, n_rows,
-                       n_lazy_rows, params, stats, step, w_floor);
-}
-
-void launch_update_leaves(float* params, float* stats, float* theta, int64_t phi_off, int64_t den_off,
-                          int64_t tot_off, float step, float min_var, float max_var, const Dims& d, hipStream_t s) {
-    const int total = d.D * d.R * d.K;
-    hipLaunchKernelGGL(k_update_leaves, dim3((total + 255) / 256), dim3(256), 0, s, params, stats, theta, phi_off,
-                       den_off, tot_off, step, min_var, max_var, d);
+void launch_em_update(const DevTables& t, int n_rows, int n_lazy_rows, float* params, float* stats, float* theta,
+                      int64_t phi_off, int64_t den_off, int64_t tot_off, float step, float min_var, float max_var,
+                      float w_floor, const Dims& d, hipStream_t s) {
+    const int n_row_blocks = (n_rows + 3) / 4;
+    const int n_leaf_blocks = (d.D * d.R * d.K + 255) / 256;
+    hipLaunchKernelGGL(k_em_update<32>, dim3(n_row_blocks + n_leaf_blocks), dim3(256), 0, s, n_row_blocks, t.row_off,
+                       t.row_len, n_rows, n_lazy_rows, params, stats, theta, phi_off, den_off, tot_off, step, min_var,
+                       max_var, w_floor, d);
 }
 
 void launch_fill(float* p, float value, int64_t n, hipStream_t s) {

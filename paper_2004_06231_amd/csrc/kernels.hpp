@@ -41,20 +41,19 @@ void launch_region_assemble(const DevTables& t, int first, int count, bool is_ro
 void launch_einsum_backward(const DevTables& t, int first, int count, bool accumulate, const float* params,
                             float* stats, const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
                             hipStream_t s);
-void launch_mixing_stats(const DevTables& t, int count, int max_children, const float* params, float* stats,
-                         const float* A, const float* G, const Dims& d, hipStream_t s);
 // posterior blocks ([B][K] floats each) that one einsum item owns in Gp: one for its left child, then one
 // per slice of four left entries for its right child
 inline int gp_blocks_per_item(int K) { return 1 + (K + 3) / 4; }
-void launch_leaf_backward(const DevTables& t, int n_lv, const float* x, const uint8_t* mask, int mask_mode,
-                          const float* G, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off,
-                          const Dims& d, hipStream_t s);
-
-// the statistics of the first n_lazy_rows rows are left as they are (the next E-step overwrites them)
-void launch_update_rows(const DevTables& t, int n_rows, int n_lazy_rows, float* params, float* stats, float step,
-                        float w_floor, hipStream_t s);
-void launch_update_leaves(float* params, float* stats, float* theta, int64_t phi_off, int64_t den_off,
-                          int64_t tot_off, float step, float min_var, float max_var, const Dims& d, hipStream_t s);
+// leaf statistics and mixing statistics (independent of each other) in one launch
+void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_children, const float* x,
+                          const uint8_t* mask, int mask_mode, const float* params, const float* A, const float* G,
+                          float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const Dims& d,
+                          hipStream_t s);
+// the whole M-step in one launch; the statistics of the first n_lazy_rows weight rows are left as they
+// are (the next E-step overwrites them)
+void launch_em_update(const DevTables& t, int n_rows, int n_lazy_rows, float* params, float* stats, float* theta,
+                      int64_t phi_off, int64_t den_off, int64_t tot_off, float step, float min_var, float max_var,
+                      float w_floor, const Dims& d, hipStream_t s);
 void launch_fill(float* p, float value, int64_t n, hipStream_t s);
 
 }  // namespace einet_impl
