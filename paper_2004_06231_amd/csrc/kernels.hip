@@ -97,6 +97,77 @@ __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict
     }
 }
 
+// Leaf layer for leaves with long scopes (image cells): a workgroup of 1024 threads takes one leaf
+// and LEAF_BS samples.  The samples' values are staged in LDS with coalesced reads of x; thread
+// (k, part) loads the constants of a few (variable, channel) pairs once and applies them to all
+// staged samples from registers; the parts meet in LDS.
+constexpr int LEAF_BS = 8;
+__global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __restrict__ leaf_node,
+                                                            const int32_t* __restrict__ leaf_replica,
+                                                            const int32_t* __restrict__ leaf_sptr,
+                                                            const int32_t* __restrict__ leaf_var,
+                                                            const float* __restrict__ x,
+                                                            const uint8_t* __restrict__ mask, int mask_mode,
+                                                            const float* __restrict__ theta, float* __restrict__ A,
+                                                            Dims d) {
+    extern __shared__ float lds[];
+    const int leaf = blockIdx.x, b0 = blockIdx.y * LEAF_BS, tid = threadIdx.x;
+    const int nbs = min(LEAF_BS, d.B - b0);
+    const int r = leaf_replica[leaf];
+    const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0, np = nv * d.C;
+    float* xs = lds;                       // [LEAF_BS][np] values, NaN-free zeros where unused
+    float* ob = lds + LEAF_BS * np;        // [LEAF_BS][nv] 1 = observed
+    float* red = ob + LEAF_BS * nv;        // [nparts][LEAF_BS][K]
+    for (int idx = tid; idx < LEAF_BS * np; idx += 1024) {
+        const int b = idx / np, p = idx - b * np, v = p / d.C, c = p - v * d.C;
+        xs[idx] = b < nbs ? x[((size_t)(b0 + b) * d.D + leaf_var[s0 + v]) * d.C + c] : 0.f;
+    }
+    for (int idx = tid; idx < LEAF_BS * nv; idx += 1024) {
+        const int b = idx / nv, v = idx - b * nv;
+        float o = 1.f;
+        if (b < nbs && mask_mode == EINET_MASK_SHARED) o = mask[leaf_var[s0 + v]] ? 1.f : 0.f;
+        if (b < nbs && mask_mode == EINET_MASK_PER_SAMPLE) o = mask[(size_t)(b0 + b) * d.D + leaf_var[s0 + v]] ? 1.f : 0.f;
+        ob[idx] = o;
+    }
+    __syncthreads();
+    const int nparts = 1024 / d.K;
+    const int k = tid % d.K, part = tid / d.K;
+    const size_t tstride = (size_t)d.TD * d.K;
+    float acc[LEAF_BS];
+#pragma unroll
+    for (int b = 0; b < LEAF_BS; ++b) acc[b] = 0.f;
+    if (part < nparts) {
+        for (int p = part; p < np; p += nparts) {
+            const int v = p / d.C, c = p - v * d.C;
+            const float* th = theta + ((size_t)(leaf_var[s0 + v] * d.C + c) * d.R + r) * tstride + k;
+            if (d.family == EINET_LEAF_GAUSSIAN) {
+                const float mu = th[0], c1 = th[d.K], c0 = th[2 * d.K];
+#pragma unroll
+                for (int b = 0; b < LEAF_BS; ++b) {
+                    const float diff = xs[b * np + p] - mu;
+                    acc[b] += ob[b * nv + v] * fmaf(c1 * diff, diff, c0);
+                }
+            } else {
+                const float lp = th[0], l1p = th[d.K];
+#pragma unroll
+                for (int b = 0; b < LEAF_BS; ++b) {
+                    const float xv = xs[b * np + p];
+                    acc[b] += ob[b * nv + v] * (xv * lp + (1.f - xv) * l1p);
+                }
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < LEAF_BS; ++b) red[(part * LEAF_BS + b) * d.K + k] = acc[b];
+    }
+    __syncthreads();
+    if (tid < LEAF_BS * d.K) {
+        const int b = tid / d.K, kk = tid - b * d.K;
+        float sum = 0.f;
+        for (int q = 0; q < nparts; ++q) sum += red[(q * LEAF_BS + b) * d.K + kk];
+        if (b < nbs) A[((size_t)leaf_node[leaf] * d.B + b0 + b) * d.K + kk] = sum;
+    }
+}
+
 // ------------------------------------------------------------------ einsum layer, forward
 // With eL = exp(L - a), eR = exp(R - a') (a, a' the row maxima; Eq. 4) the layer needs
 //     S~[b,k] = sum_i eL[b,i] * T[(k,i), b],   T[(k,i), b] = sum_j W[k,i,j] eR[b,j].
@@ -814,6 +885,16 @@ void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream
 
 void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const float* x, const uint8_t* mask,
                          int mask_mode, const float* theta, float* A, const Dims& d, hipStream_t s) {
+    if (max_scope * d.C >= 32) {
+        // long scopes: one workgroup per (leaf, LEAF_BS samples), values staged in LDS
+        const size_t lds = sizeof(float) * ((size_t)LEAF_BS * max_scope * (d.C + 1) + (size_t)(1024 / d.K) * LEAF_BS * d.K);
+        if (lds <= 64 * 1024) {
+            dim3 grid(n_leaves, (d.B + LEAF_BS - 1) / LEAF_BS);
+            hipLaunchKernelGGL(k_leaf_forward_wide, grid, dim3(1024), lds, s, t.leaf_node, t.leaf_replica, t.leaf_sptr,
+                               t.leaf_var, x, mask, mask_mode, theta, A, d);
+            return;
+        }
+    }
     // parts per workgroup: enough that each thread walks only a few variables of the scope
     const int nch = max_scope >= 32 ? 16 : (max_scope >= 8 ? 4 : 1);
     dim3 grid(n_leaves, (d.B * d.K + 1024 / nch - 1) / (1024 / nch));
