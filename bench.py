@@ -53,12 +53,52 @@ def algorithmic_work(st, K, C, R, T, TD, B, D):
     return w
 
 
+def time_config(i, steps, warmup):
+    """EM-step and logP rates of configuration i (1-based) with its own seeded inputs."""
+    import numpy as np
+    import torch
+    import paper_2004_06231_amd as P
+    import workloads
+    cfg = workloads.get_config(i)
+    seed = workloads.config_seed(i)
+    K, C, fam, B = cfg["K"], cfg["channels"], cfg["family"], cfg["B"]
+    m = P.EiNet(cfg["structure"], K, C, fam, B, seed).bind("cuda:0")
+    st = m.structure()
+    D, R, T = st["num_vars"], st["num_replica"], st["T"]
+    rng = np.random.default_rng(seed)
+    flat = workloads.draw_params(rng, m.n_params, m.weight_blocks(), int(st["phi_offset"]), (D, C, R, T, K), fam,
+                                 cfg["leaf_range"])
+    x = torch.as_tensor(workloads.draw_data(rng, cfg["data"], B, D, C)).cuda()
+    mask = workloads.draw_mask(rng, cfg["mask"], B, D)
+    mask = None if mask is None else torch.as_tensor(mask).cuda()
+    m.set_params(flat)
+    logp = torch.empty(B, dtype=torch.float32, device="cuda")
+    kw = dict(step=0.5, min_var=1e-6, max_var=1e-2, w_floor=1e-9) if fam == P.GAUSSIAN else dict(step=0.5, w_floor=1e-9)
+    res = {"batch": B, "n_params": m.n_params}
+    for name, fn in (("em", lambda: (m.em_accumulate(x, None, logp), m.em_update(**kw))),
+                     ("logp", lambda: m.logp(x, mask, logp))):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        res[name + "_samples_per_s"] = round(B / dt, 1)
+        res[name + "_ms"] = round(1e3 * dt, 4)
+    m.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true")
+    ap.add_argument("--workload", type=int, default=WORKLOAD, help="configuration to time (1-5); the default is the headline")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; sharding over the batch with one all-reduce of the "
@@ -70,8 +110,9 @@ def main():
     import paper_2004_06231_amd as P
     import workloads
 
-    cfg = workloads.get_config(WORKLOAD)
-    seed = workloads.config_seed(WORKLOAD)
+    wl = args.workload
+    cfg = workloads.get_config(wl)
+    seed = workloads.config_seed(wl)
     K, C, fam, B = cfg["K"], cfg["channels"], cfg["family"], cfg["B"]
     m = P.EiNet(cfg["structure"], K, C, fam, B, seed).bind("cuda:0")
     st = m.structure()
@@ -149,17 +190,23 @@ def main():
         "metric": "EM samples/sec (fwd+bwd+M-step)", "value": round(B * args.steps / t_em, 1), "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg["name"], "structure": "Poon-Domingos 32x32x3, delta 8", "K": K, "batch": B,
-                   "leaves": "gaussian", "em": em_kw},
+        "config": {"workload": cfg["name"], "structure": cfg["structure"], "K": K, "batch": B,
+                   "leaves": "gaussian" if fam == P.GAUSSIAN else "bernoulli", "em": em_kw},
         "logp_samples_per_s": round(B * args.steps / t_lp, 1), "logp_ms_per_call": round(1e3 * t_lp / args.steps, 4),
         "kernels": kernels,
         "roofline": roof,
     }
 
+    if not args.no_other_configs:
+        # the other four configurations, for context (same protocol, fewer steps; not the headline value)
+        out["other_configs"] = {}
+        for i in [j for j in (1, 2, 3, 4, 5) if j != wl]:
+            out["other_configs"][workloads.get_config(i)["name"]] = time_config(i, max(5, args.steps // 3), args.warmup)
+
     if not args.no_cpu_baseline:
         # the float64 oracle, as it stands, on a bounded sample of the same batch
         from tests.common import make_config
-        _, oracle, _, xs, _ = make_config(WORKLOAD, batch=B)
+        _, oracle, _, xs, _ = make_config(wl, batch=B)
         assert np.array_equal(xs, x_host)
         t0 = time.perf_counter()
         stats, _ = oracle.em_accumulate(xs, None, chunk=8)
