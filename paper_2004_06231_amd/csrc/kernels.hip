@@ -1025,9 +1025,16 @@ void launch_em_update(const DevTables& t, int n_rows, int n_lazy_rows, float* pa
                       float w_floor, const Dims& d, hipStream_t s) {
     const int n_row_blocks = (n_rows + 3) / 4;
     const int n_leaf_blocks = (d.D * d.R * d.K + 255) / 256;
-    hipLaunchKernelGGL(k_em_update<32>, dim3(n_row_blocks + n_leaf_blocks), dim3(256), 0, s, n_row_blocks, t.row_off,
-                       t.row_len, n_rows, n_lazy_rows, params, stats, theta, phi_off, den_off, tot_off, step, min_var,
-                       max_var, w_floor, d);
+    // registers per lane for a weight row of K*K entries (mixing rows are shorter)
+    const int per_lane = (d.K * d.K + 63) / 64;
+#define EINET_LAUNCH(N)                                                                                             \
+    hipLaunchKernelGGL(k_em_update<N>, dim3(n_row_blocks + n_leaf_blocks), dim3(256), 0, s, n_row_blocks, t.row_off, \
+                       t.row_len, n_rows, n_lazy_rows, params, stats, theta, phi_off, den_off, tot_off, step, min_var, \
+                       max_var, w_floor, d)
+    if (per_lane <= 2) EINET_LAUNCH(2);
+    else if (per_lane <= 8) EINET_LAUNCH(8);
+    else EINET_LAUNCH(32);
+#undef EINET_LAUNCH
 }
 
 void launch_fill(float* p, float value, int64_t n, hipStream_t s) {
