@@ -391,8 +391,9 @@ __device__ __forceinline__ void mixing_stats_body(int item, int c, const int32_t
 // sample tile per wave, all KQ row tiles advancing together.  The sum over the
 // slice's four i (right child) is in-lane; the sum over j (left child) is in-lane
 // across tiles plus one exchange between the four lane groups at the end.
-// Gp_left is complete for the slice's entries; Gp_right is a partial sum, written
-// to the slice's own block and added up by k_region_assemble.
+// Gp_left is complete for the slice's entries; Gp_right is a partial sum over the
+// workgroup's slices (summed in LDS, each entry by the lane that owns it), written to
+// the workgroup's own block and added up by k_region_assemble.
 template <int KQ>
 struct BwdLayout {
     static constexpr int KP = 4 * KQ;
@@ -404,7 +405,9 @@ struct BwdLayout {
     static constexpr int OFF_R = KP * S;                  // eR^T [16 NJ][ST]
     static constexpr int OFF_Q = OFF_R + 16 * NJ * ST;    // Q^T  [KP][ST]
     static constexpr int OFF_L = OFF_Q + KP * ST;         // eL^T [4][ST] of the current slice
-    static constexpr int LDS_FLOATS = OFF_L + 4 * ST;
+    static constexpr int OFF_G = OFF_L + 4 * ST;          // Gp_right of the workgroup's slices [BC][KP] ...
+    static constexpr bool LDS_ACC = OFF_G + BC * KP <= 40960;   // ... if it fits in the 160 KB of LDS
+    static constexpr int LDS_FLOATS = OFF_G + (LDS_ACC ? BC * KP : 0);
     static constexpr int MAXU = (NJ * KQ + 7) / 8;        // GEMM-1 tiles per wave
     static constexpr int NW4 = (KP * 4 * KQ + 511) / 512; // float4 per thread of one W slice
     static constexpr int NW1 = (KP * 4 * KP + 511) / 512; // floats per thread when K is not a multiple of 4
@@ -450,9 +453,11 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     float* sR = lds + LY::OFF_R;
     float* sQ = lds + LY::OFF_Q;
     float* sL = lds + LY::OFF_L;
+    float* sG = lds + LY::OFF_G;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = blockIdx.x / ngroups, grp = blockIdx.x - li * ngroups;
     const int it0 = grp * KQ / ngroups, it1 = (grp + 1) * KQ / ngroups;     // this workgroup's slices
+    const bool multi = it1 - it0 > 1;   // several slices: their shares of Gp_right are summed in LDS first
     const int item = item0 + li;
     const int kout = e_kout[li], nkt = (kout + 3) >> 2;
     const size_t blk = (size_t)B * K;
@@ -565,6 +570,8 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
                 sQ[k * ST + srow] = (rok && k < kout && gv[u] != 0.f) ? q : 0.f;
             }
             for (int j = KP + sq; j < 16 * LY::NJ; j += 4) sR[j * ST + srow] = 0.f;   // rows beyond the padded K
+            if (multi && LY::LDS_ACC)
+                for (int u = 0; u < KQ; ++u) sG[srow * KP + sq * KQ + u] = 0.f;
         }
 
         for (int it = it0; it < it1; ++it) {
@@ -632,11 +639,15 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
                 }
                 // acc[jt][r] = U[b][i = 4it+r][j = 4jt+g]
                 float gl0 = 0.f, gl1 = 0.f, gl2 = 0.f, gl3 = 0.f;
-                float* right = Gp + ((size_t)(item * nblk + 1 + it) * B + b0 + bl) * K;
+                float* right = Gp + ((size_t)(item * nblk + 1 + grp) * B + b0 + bl) * K;
+                float* racc = sG + bl * KP;
 #pragma unroll
                 for (int jt = 0; jt < KQ; ++jt) {
                     const float t = acc[jt][0] * e4.x + acc[jt][1] * e4.y + acc[jt][2] * e4.z + acc[jt][3] * e4.w;
-                    if (ok && 4 * jt + g < K) right[4 * jt + g] = erg[jt] * t;
+                    // this lane owns the entry in every slice: no race, in LDS or (for the largest K, where the
+                    // accumulator does not fit) in the block itself
+                    if (multi && LY::LDS_ACC) racc[4 * jt + g] += erg[jt] * t;
+                    else if (ok && 4 * jt + g < K) right[4 * jt + g] = erg[jt] * t + (it > it0 ? right[4 * jt + g] : 0.f);
                     gl0 = fmaf(acc[jt][0], erg[jt], gl0);
                     gl1 = fmaf(acc[jt][1], erg[jt], gl1);
                     gl2 = fmaf(acc[jt][2], erg[jt], gl2);
@@ -660,6 +671,14 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
                         if (VEC || i < K) Nw[uoff[q] + i * K] = nw[q][r] + Wl[uwl[q] + r * SI] * acc1[q][r];
                     }
                 }
+            }
+        }
+        if (multi && LY::LDS_ACC) {                        // Gp_right of the workgroup's slices, row by row
+            __syncthreads();
+            float* right = Gp + ((size_t)(item * nblk + 1 + grp) * B + b0) * K;
+            for (int e = tid; e < nb * K; e += 512) {
+                const int b = e / K, j = e - b * K;
+                right[e] = sG[b * KP + j];
             }
         }
     }
@@ -970,10 +989,7 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
-    // slices per item are spread over as many workgroups as keeps the launch within one round of the
-    // 256 compute units (one workgroup per unit)
-    int ngroups = 256 / count;
-    ngroups = ngroups < 1 ? 1 : (ngroups > KQ ? KQ : ngroups);
+    const int ngroups = bwd_groups_per_item(count, d.K);
 #define EINET_LAUNCH(V, ACC)                                                                                      \
     hipLaunchKernelGGL((k_einsum_backward<KQ, V, ACC>), dim3(count * ngroups), dim3(512), lds, s, t.ein_left + first,  \
                        t.ein_right + first, t.ein_reg + first, t.ein_kout + first, t.ein_woff + first,                \

@@ -41,9 +41,18 @@ void launch_region_assemble(const DevTables& t, int first, int count, bool is_ro
 void launch_einsum_backward(const DevTables& t, int first, int count, bool accumulate, const float* params,
                             float* stats, const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
                             hipStream_t s);
-// posterior blocks ([B][K] floats each) that one einsum item owns in Gp: one for its left child, then one
-// per slice of four left entries for its right child
+// posterior blocks ([B][K] floats each) reserved per einsum item in Gp: one for its left child, then up to
+// one per slice of four left entries for its right child
 inline int gp_blocks_per_item(int K) { return 1 + (K + 3) / 4; }
+// Workgroups per item of the top-down einsum kernel for a layer of `count` items: the slices of an item are
+// spread over as many workgroups as keeps the launch within one round of the 256 compute units of the
+// MI355X (one workgroup per unit).  Workgroup grp takes slices grp*KQ/groups .. (grp+1)*KQ/groups - 1 and
+// writes right-child block 1+grp of the item.
+inline int bwd_groups_per_item(int count, int K) {
+    const int kq = (K + 3) / 4;
+    const int g = 256 / (count > 0 ? count : 1);
+    return g < 1 ? 1 : (g > kq ? kq : g);
+}
 // leaf statistics and mixing statistics (independent of each other) in one launch
 void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_children, const float* x,
                           const uint8_t* mask, int mask_mode, const float* params, const float* A, const float* G,

@@ -282,12 +282,18 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& p, std::
     }
 
     // ---- top-down items: which posterior blocks flow into each region.  Item e owns blocks
-    // e*nb .. e*nb+nb-1 of Gp: block 0 for its left child, blocks 1.. (one per slice) for its right child.
+    // e*nb .. e*nb+nb-1 of Gp: block 0 for its left child, blocks 1.. (one per workgroup of the top-down
+    // einsum kernel) for its right child.
     const int nb = gp_blocks_per_item(K);
     std::vector<std::vector<std::pair<int, int>>> runs(nr);
+    std::vector<int> layer_of_item(np, 0);
+    for (int l = 0; l < p.num_layers; ++l)
+        for (int e = p.ein_layer_ptr[l]; e < p.ein_layer_ptr[l + 1]; ++e) layer_of_item[e] = l;
     for (int n = 0; n < np; ++n) {
-        runs[g.partition[n][1]].push_back({item_of[n] * nb, 1});
-        runs[g.partition[n][2]].push_back({item_of[n] * nb + 1, nb - 1});
+        const int e = item_of[n], l = layer_of_item[e];
+        const int groups = bwd_groups_per_item(p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], K);
+        runs[g.partition[n][1]].push_back({e * nb, 1});
+        runs[g.partition[n][2]].push_back({e * nb + 1, groups});
     }
     p.rb_layer_ptr.push_back(0);
     p.rb_pptr.push_back(0);

@@ -107,6 +107,8 @@ SMALL = [
     (dict(kind="rat", D=12, depth=1, R=4), 7, 1, GAUSSIAN, 1),          # single sample
     (dict(kind="rat", D=40, depth=3, R=2), 13, 1, GAUSSIAN, 70),
     (dict(kind="rat", D=10, depth=2, R=1), 64, 1, BERNOULLI, 20),       # largest K
+    (dict(kind="rat", D=64, depth=5, R=2), 64, 1, GAUSSIAN, 20),        # largest K, several slices per workgroup
+    (dict(kind="rat", D=96, depth=5, R=3), 12, 1, BERNOULLI, 130),      # two passes over the batch, ragged second
     (dict(kind="pd", H=6, W=6, deltas=[2]), 6, 3, GAUSSIAN, 19),
     (dict(kind="pd", H=8, W=4, deltas=[4, 2]), 9, 1, BERNOULLI, 40),
     (dict(kind="pd", H=4, W=12, deltas=[4], axes=2), 17, 2, GAUSSIAN, 16),   # vertical cuts only
