@@ -162,8 +162,15 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
     __syncthreads();
     if (tid < LEAF_BS * d.K) {
         const int b = tid / d.K, kk = tid - b * d.K;
-        float sum = 0.f;
-        for (int q = 0; q < nparts; ++q) sum += red[(q * LEAF_BS + b) * d.K + kk];
+        // compensated sum: a scope of hundreds of variables gives partial sums of magnitude ~1e2..1e3, and the
+        // posteriors further up see the absolute error of this log-density
+        float sum = 0.f, comp = 0.f;
+        for (int q = 0; q < nparts; ++q) {
+            const float y = red[(q * LEAF_BS + b) * d.K + kk] - comp;
+            const float t = sum + y;
+            comp = (t - sum) - y;
+            sum = t;
+        }
         if (b < nbs) A[((size_t)leaf_node[leaf] * d.B + b0 + b) * d.K + kk] = sum;
     }
 }
@@ -786,11 +793,10 @@ __device__ __forceinline__ void update_rows_body(int block, const int32_t* __res
 #pragma unroll
         for (int t = 0; t < NPL; ++t) s += n[t];
         const float tot = wave_sum(s);
-        const float inv = tot > 0.f ? 1.f / tot : 0.f;
         float s2 = 0.f;
 #pragma unroll
         for (int t = 0; t < NPL; ++t) {
-            n[t] = tot > 0.f ? n[t] * inv : w[t];
+            n[t] = tot > 0.f ? n[t] / tot : w[t];      // a true division: 1/tot overflows for denormal totals
             if (w_floor > 0.f && lane + 64 * t < len) {
                 n[t] = fmaxf(n[t], w_floor);
                 s2 += n[t];
@@ -810,17 +816,16 @@ __device__ __forceinline__ void update_rows_body(int block, const int32_t* __res
     float s = 0.f;
     for (int e = lane; e < len; e += 64) s += stats[off + e];
     const float tot = wave_sum(s);
-    const float inv = tot > 0.f ? 1.f / tot : 0.f;
     float norm = 1.f;
     if (w_floor > 0.f) {
         float s2 = 0.f;
         for (int e = lane; e < len; e += 64)
-            s2 += fmaxf(tot > 0.f ? stats[off + e] * inv : params[off + e], w_floor);
+            s2 += fmaxf(tot > 0.f ? stats[off + e] / tot : params[off + e], w_floor);
         norm = 1.f / wave_sum(s2);
     }
     for (int e = lane; e < len; e += 64) {
         const float old = params[off + e];
-        float hat = tot > 0.f ? stats[off + e] * inv : old;
+        float hat = tot > 0.f ? stats[off + e] / tot : old;
         if (w_floor > 0.f) hat = fmaxf(hat, w_floor) * norm;
         params[off + e] = (1.f - step) * old + step * hat;
         if (clear) stats[off + e] = 0.f;

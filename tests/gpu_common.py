@@ -54,5 +54,6 @@ def assert_stats_close(got_flat, ref_flat, lay, n_params, rtol=STAT_RTOL, atol_r
         assert np.all(np.isfinite(g[name])), name
         i = int((err - tol).argmax())
         assert np.all(err <= tol), f"{name}: |d|={err[i]:.3e} ref={r[name][i]:.6e} tol={tol[i]:.3e} at {i}"
-        worst[name] = float((err / (np.abs(r[name]) + atol_rel * np.abs(r[name]).max() / rtol)).max())
+        scale = np.abs(r[name]) + atol_rel * np.abs(r[name]).max() / rtol
+        worst[name] = float((err[scale > 0] / scale[scale > 0]).max()) if np.any(scale > 0) else 0.0
     return worst

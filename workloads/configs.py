@@ -56,3 +56,17 @@ CONFIGS = [
 def get_config(i):
     """i is 1-based, as in the configuration list."""
     return CONFIGS[i - 1]
+
+
+def fig3_config(K=10, depth=4, R=10, B=100):
+    """One point of the efficiency sweeps of Sec. 4.1 (Fig. 3 and the inference-time figure of App. C):
+    random binary trees over D = 512 variables of Gaussian noise, one-dimensional Gaussian leaves,
+    defaults depth 4, R 10, K 10; inference is timed on batches of 100."""
+    return dict(
+        name=f"fig3_rat_d512_depth{depth}_r{R}_k{K}",
+        structure=dict(kind="rat", D=512, depth=depth, R=R),
+        K=K, channels=1, family=GAUSSIAN, B=B,
+        leaf_range=(-1.0, 1.0),
+        data=dict(kind="gaussian_noise"),
+        mask=None,
+    )
