@@ -793,10 +793,13 @@ __device__ __forceinline__ void update_rows_body(int block, const int32_t* __res
 #pragma unroll
         for (int t = 0; t < NPL; ++t) s += n[t];
         const float tot = wave_sum(s);
+        // 1/tot overflows for a denormal total: such rows are first scaled by an exact power of two
+        const float sc = tot < 0x1p-60f ? 0x1p+64f : 1.f;
+        const float inv = 1.f / (tot * sc);
         float s2 = 0.f;
 #pragma unroll
         for (int t = 0; t < NPL; ++t) {
-            n[t] = tot > 0.f ? n[t] / tot : w[t];      // a true division: 1/tot overflows for denormal totals
+            n[t] = tot > 0.f ? (n[t] * sc) * inv : w[t];
             if (w_floor > 0.f && lane + 64 * t < len) {
                 n[t] = fmaxf(n[t], w_floor);
                 s2 += n[t];
@@ -816,16 +819,18 @@ __device__ __forceinline__ void update_rows_body(int block, const int32_t* __res
     float s = 0.f;
     for (int e = lane; e < len; e += 64) s += stats[off + e];
     const float tot = wave_sum(s);
+    const float sc = tot < 0x1p-60f ? 0x1p+64f : 1.f;
+    const float inv = 1.f / (tot * sc);
     float norm = 1.f;
     if (w_floor > 0.f) {
         float s2 = 0.f;
         for (int e = lane; e < len; e += 64)
-            s2 += fmaxf(tot > 0.f ? stats[off + e] / tot : params[off + e], w_floor);
+            s2 += fmaxf(tot > 0.f ? (stats[off + e] * sc) * inv : params[off + e], w_floor);
         norm = 1.f / wave_sum(s2);
     }
     for (int e = lane; e < len; e += 64) {
         const float old = params[off + e];
-        float hat = tot > 0.f ? stats[off + e] / tot : old;
+        float hat = tot > 0.f ? (stats[off + e] * sc) * inv : old;
         if (w_floor > 0.f) hat = fmaxf(hat, w_floor) * norm;
         params[off + e] = (1.f - step) * old + step * hat;
         if (clear) stats[off + e] = 0.f;

@@ -196,3 +196,37 @@ def test_full_batch_em_is_monotone_on_gpu(family):
     oracle.set_flat_params(m.params.cpu().numpy())
     assert_logp_close(m.logp(xd), oracle.logp(x))
     m.close()
+
+
+@pytest.mark.parametrize("w_floor", [0.0, 1e-9])
+def test_update_of_a_sum_row_with_denormal_or_zero_posterior_mass(w_floor):
+    """A row of weight statistics whose total is a float32 denormal is still normalised (its reciprocal is not
+    representable), and a row without any mass keeps its weights (Eq. 7 leaves 0/0 open; the oracle does the same)."""
+    c = config_case(1)
+    oracle, m = c["oracle"], c["m"]
+    lay = oracle.layout
+    m.set_params(c["flat"])
+    m.em_reset()
+    m.em_accumulate(dev(c["x"]))
+    flat = m.stats.cpu().numpy().astype(np.float64)
+    shape = oracle.W[1].shape                                    # (K_out, K, K) of an inner partition
+    assert shape[0] >= 2
+    row = np.prod(shape[1:])
+    tiny = np.arange(row, dtype=np.float64) % 5 * 2.0 ** -140     # exact float32 denormals, total 2^-135 or so
+    flat[lay.w_off[1]: lay.w_off[1] + row] = tiny
+    flat[lay.w_off[1] + row: lay.w_off[1] + 2 * row] = 0.0
+    m.stats.copy_(torch.as_tensor(flat, dtype=torch.float32))
+    assert float(m.stats[lay.w_off[1]: lay.w_off[1] + row].sum()) > 0.0     # denormals are kept on the device
+    m.em_update(step=1.0, w_floor=w_floor)
+    oracle.set_flat_params(c["flat"])
+    oracle.em_update(oracle.stats_from_flat(flat), step=1.0, w_floor=w_floor)
+    ref = oracle.get_flat_params()
+    got = m.params.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    lo, hi = lay.w_off[1], lay.w_off[1] + 2 * row
+    assert np.all(np.abs(got[lo:hi] - ref[lo:hi]) <= 1e-5 * np.abs(ref[lo:hi]) + 1e-12)
+    assert np.all(np.abs(got - ref) <= 1e-3 * np.abs(ref) + 1e-7)
+    np.testing.assert_allclose(got[lo + row: hi], np.asarray(c["flat"], np.float64)[lo + row: hi], rtol=1e-6)
+    oracle.set_flat_params(c["flat"])
+    m.set_params(c["flat"])
+    m.em_reset()
