@@ -54,3 +54,11 @@ def all_binary(D):
     """[2^D, D, 1] array of every binary assignment."""
     idx = np.arange(2 ** D)
     return ((idx[:, None] >> np.arange(D)[None, :]) & 1).astype(np.float64)[:, :, None]
+
+
+def normalise_exactly(model):
+    """float32-rounded rows sum to 1 only to 1e-7; make them exact in float64."""
+    for n in range(len(model.W)):
+        model.W[n] /= model.W[n].sum(axis=(1, 2), keepdims=True)
+    for s in model.v:
+        model.v[s] /= model.v[s].sum(axis=1, keepdims=True)

@@ -9,15 +9,7 @@ import scipy.stats
 
 from oracle import structure as S
 from oracle.einet import OracleEiNet, BERNOULLI, GAUSSIAN, ef_log_density
-from tests.common import make_oracle, make_config, all_binary
-
-
-def normalise_exactly(model):
-    """float32-rounded rows sum to 1 only to 1e-7; make them exact in float64."""
-    for n in range(len(model.W)):
-        model.W[n] /= model.W[n].sum(axis=(1, 2), keepdims=True)
-    for s in model.v:
-        model.v[s] /= model.v[s].sum(axis=1, keepdims=True)
+from tests.common import normalise_exactly, make_oracle, make_config, all_binary
 
 
 RAT_TINY = dict(kind="rat", D=8, depth=3, R=2)
