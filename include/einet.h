@@ -189,13 +189,45 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
  * statistics are cleared in memory; the einsum-weight statistics Nw are left
  * as they are and the next einet_em_accumulate overwrites them instead of
  * adding (saves one pass over the largest buffer), so the Nw part of the
- * caller's buffer is unspecified between this call and that one; use
- * einet_em_reset to have zeros in memory.  Also refreshes the derived leaf
+ * caller's buffer is unspecified between this call and that one (a second
+ * einet_em_update in that interval keeps the einsum weights, as for zero
+ * statistics); use einet_em_reset to have zeros in memory.  Also refreshes the derived leaf
  * constants. */
 int einet_em_update(einet_t* h, float step, float min_var, float max_var, float w_floor, void* stream);
 
 /* Zeroes the whole statistics buffer in memory. */
 int einet_em_reset(einet_t* h, void* stream);
+
+/* Stochastic EM over one pass of the data (Eq. 8-9 with the schedule of
+ * Sec. 4.2): the N samples are visited in consecutive mini-batches of `batch`
+ * samples (the last one may be shorter); for each, einet_em_accumulate on that
+ * slice followed by einet_em_update(step, min_var, max_var, w_floor).  The
+ * result is exactly that of making those calls one by one; the loop runs in
+ * the library, enqueues everything on `stream` and never synchronises.
+ *   x_dev     device, [N][D][C] float32
+ *   mask_dev  device, as in einet_logp; EINET_MASK_PER_SAMPLE: [N][D]
+ *   batch     1 <= batch <= max_batch
+ *   logp_dev  device, [N] float32 or NULL: log-density of every sample under
+ *             the parameters in force when its mini-batch was visited
+ * Statistics present in the buffer at entry are consumed by the first update;
+ * the buffer is logically zero on return.  Errors as einet_em_accumulate and
+ * einet_em_update, plus EINET_ERR_INVALID_ARG for N < 1. */
+int einet_em_epoch(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int64_t N, int batch,
+                   float step, float min_var, float max_var, float w_floor, float* logp_dev, void* stream);
+
+/* Mixture of several EiNets (Sec. 4.2: one EiNet per cluster, the cluster
+ * proportions as coefficients):
+ *   out[b] = log sum_c exp(log_coef[c] + logp[c][b]),
+ * evaluated with a shift by the largest term; -inf when every term is -inf.
+ *   logp_dev      device, [n_components][B] float32: row c is the output of
+ *                 einet_logp of component c on the same batch
+ *   log_coef_dev  device, [n_components] float32
+ *   out_dev       device, [B] float32, written
+ * Needs no handle; asynchronous on `stream`.  Errors: EINET_ERR_INVALID_ARG
+ * (NULL pointers, n_components < 1, B < 1), EINET_ERR_HIP; the reason is read
+ * with einet_last_error(NULL). */
+int einet_mixture_logp(const float* logp_dev, const float* log_coef_dev, int n_components, int B, float* out_dev,
+                       void* stream);
 
 /* Per-kernel timing for benchmarks (no passage of the paper: measurement aid).
  * While enabled, every kernel launch of the compute calls above is bracketed

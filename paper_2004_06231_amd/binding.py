@@ -14,8 +14,8 @@ MAX_DELTAS = 8
 
 EXPORTED_SYMBOLS = [
     "einet_create", "einet_destroy", "einet_last_error", "einet_sizes", "einet_structure", "einet_bind",
-    "einet_refresh", "einet_logp", "einet_em_accumulate", "einet_em_update", "einet_em_reset",
-    "einet_profile_enable", "einet_profile_read",
+    "einet_refresh", "einet_logp", "einet_em_accumulate", "einet_em_update", "einet_em_reset", "einet_em_epoch",
+    "einet_mixture_logp", "einet_profile_enable", "einet_profile_read",
 ]
 
 
@@ -71,6 +71,8 @@ def load_library():
     lib.einet_em_accumulate.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.einet_em_update.argtypes = [vp, f32, f32, f32, f32, vp]
     lib.einet_em_reset.argtypes = [vp, vp]
+    lib.einet_em_epoch.argtypes = [vp, vp, vp, i32, C.c_int64, i32, f32, f32, f32, f32, vp, vp]
+    lib.einet_mixture_logp.argtypes = [vp, vp, i32, i32, vp, vp]
     lib.einet_profile_enable.argtypes = [vp, i32]
     lib.einet_profile_read.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                        C.POINTER(C.c_int64)]
@@ -228,6 +230,17 @@ class EiNet:
     def em_reset(self):
         self._check(self._lib.einet_em_reset(self._h, self._stream()))
 
+    def em_epoch(self, x, mask=None, batch=None, step=0.5, min_var=0.0, max_var=math.inf, w_floor=0.0, logp=None):
+        """x: cuda float32 [N, D, channels], visited in mini-batches of `batch` (default max_batch) samples."""
+        torch = self._torch
+        assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous() and x.dim() == 3
+        N = x.shape[0]
+        m, mode = self._mask_args(mask, N)
+        lp = None if logp is None else C.c_void_p(logp.data_ptr())
+        self._check(self._lib.einet_em_epoch(self._h, x.data_ptr(), m, mode, N, self.max_batch if batch is None else batch,
+                                             step, min_var, max_var, w_floor, lp, self._stream()))
+        return logp
+
     def profile_enable(self, enable=True):
         self._check(self._lib.einet_profile_enable(self._h, 1 if enable else 0))
 
@@ -283,6 +296,28 @@ def einet_em_update(m, step=1.0, min_var=0.0, max_var=math.inf, w_floor=0.0):
 
 def einet_em_reset(m):
     m.em_reset()
+
+
+def einet_em_epoch(m, x, mask=None, batch=None, step=0.5, min_var=0.0, max_var=math.inf, w_floor=0.0, logp=None):
+    return m.em_epoch(x, mask, batch, step, min_var, max_var, w_floor, logp)
+
+
+def einet_mixture_logp(component_logp, log_coef, out=None):
+    """component_logp: cuda float32 [n_components, B]; log_coef: cuda float32 [n_components]."""
+    import torch
+    lib = load_library()
+    for t in (component_logp, log_coef):
+        assert t.dtype == torch.float32 and t.is_cuda and t.is_contiguous()
+    n, B = component_logp.shape
+    assert log_coef.shape == (n,)
+    if out is None:
+        out = torch.empty(B, dtype=torch.float32, device=component_logp.device)
+    with torch.cuda.device(component_logp.device):
+        rc = lib.einet_mixture_logp(component_logp.data_ptr(), log_coef.data_ptr(), n, B, out.data_ptr(),
+                                    C.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if rc != 0:
+        raise EinetError(rc, lib.einet_last_error(None).decode())
+    return out
 
 
 def einet_profile_enable(m, enable=True):

@@ -96,6 +96,15 @@ int check_batch_args(einet_t* h, const float* x, const uint8_t* mask, int mask_m
 }
 
 enum KernelClass { KC_LEAF_FWD, KC_EINSUM_FWD, KC_MIXING_FWD, KC_REGION_BWD, KC_EINSUM_BWD, KC_LEAF_BWD, KC_UPDATE, KC_COUNT };
+int check_update_args(einet_t* h, float step, float min_var, float max_var, float w_floor) {
+    if (!h) return EINET_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
+    if (!(step > 0.f && step <= 1.f)) return fail(h, EINET_ERR_INVALID_ARG, "step must be in (0, 1]");
+    if (!(min_var >= 0.f) || !(max_var >= min_var) || !(w_floor >= 0.f))
+        return fail(h, EINET_ERR_INVALID_ARG, "need 0 <= min_var <= max_var and w_floor >= 0");
+    return EINET_OK;
+}
+
 const char* const kKernelClassNames[KC_COUNT] = {"leaf_forward", "einsum_forward", "mixing_forward", "region_backward",
                                                  "einsum_backward", "leaf_mixing_backward", "em_update"};
 
@@ -322,16 +331,13 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
 }
 
 int einet_em_update(einet_t* h, float step, float min_var, float max_var, float w_floor, void* stream) {
-    if (!h) return EINET_ERR_INVALID_ARG;
-    if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
-    if (!(step > 0.f && step <= 1.f)) return fail(h, EINET_ERR_INVALID_ARG, "step must be in (0, 1]");
-    if (!(min_var >= 0.f) || !(max_var >= min_var) || !(w_floor >= 0.f))
-        return fail(h, EINET_ERR_INVALID_ARG, "need 0 <= min_var <= max_var and w_floor >= 0");
+    int rc = check_update_args(h, step, min_var, max_var, w_floor);
+    if (rc != EINET_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Dims d = dims_of(h, 0);
     const Plan& p = h->plan;
     run(h, KC_UPDATE, s, [&] {
-        launch_em_update(h->dt, (int)p.row_off.size(), p.n_weight_rows, h->params, h->stats,
+        launch_em_update(h->dt, (int)p.row_off.size(), p.n_weight_rows, h->weight_stats_zero, h->params, h->stats,
                          reinterpret_cast<float*>(h->ws + h->off_theta), p.phi_offset, p.den_offset, p.tot_offset,
                          step, min_var, max_var, w_floor, d, s);
     });
@@ -345,6 +351,36 @@ int einet_em_reset(einet_t* h, void* stream) {
     launch_fill(h->stats, 0.f, h->plan.n_stats, static_cast<hipStream_t>(stream));
     h->weight_stats_zero = true;
     return check_hip(h, "einet_em_reset");
+}
+
+int einet_em_epoch(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int64_t N, int batch,
+                   float step, float min_var, float max_var, float w_floor, float* logp_dev, void* stream) {
+    int rc = check_batch_args(h, x_dev, mask_dev, mask_mode, batch);
+    if (rc != EINET_OK) return rc;
+    if (N < 1) return fail(h, EINET_ERR_INVALID_ARG, "N must be at least 1");
+    rc = check_update_args(h, step, min_var, max_var, w_floor);
+    if (rc != EINET_OK) return rc;
+    const size_t sample = (size_t)h->graph.num_vars * h->plan.C;
+    for (int64_t b0 = 0; b0 < N; b0 += batch) {
+        const int nb = (int)(N - b0 < batch ? N - b0 : batch);
+        const uint8_t* m = mask_mode == EINET_MASK_PER_SAMPLE ? mask_dev + (size_t)b0 * h->graph.num_vars : mask_dev;
+        rc = einet_em_accumulate(h, x_dev + (size_t)b0 * sample, m, mask_mode, nb, logp_dev ? logp_dev + b0 : nullptr,
+                                 stream);
+        if (rc != EINET_OK) return rc;
+        rc = einet_em_update(h, step, min_var, max_var, w_floor, stream);
+        if (rc != EINET_OK) return rc;
+    }
+    return EINET_OK;
+}
+
+int einet_mixture_logp(const float* logp_dev, const float* log_coef_dev, int n_components, int B, float* out_dev,
+                       void* stream) {
+    if (!logp_dev || !log_coef_dev || !out_dev)
+        return fail(nullptr, EINET_ERR_INVALID_ARG, "einet_mixture_logp: NULL pointer");
+    if (n_components < 1 || B < 1)
+        return fail(nullptr, EINET_ERR_INVALID_ARG, "einet_mixture_logp: n_components and B must be at least 1");
+    launch_mixture_logp(logp_dev, log_coef_dev, n_components, B, out_dev, static_cast<hipStream_t>(stream));
+    return check_hip(nullptr, "einet_mixture_logp");
 }
 
 int einet_profile_enable(einet_t* h, int enable) {

@@ -775,10 +775,11 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
 template <int NPL>
 __device__ __forceinline__ void update_rows_body(int block, const int32_t* __restrict__ row_off,
                                                  const int32_t* __restrict__ row_len, int n_rows, int n_lazy_rows,
-                                                 float* __restrict__ params, float* __restrict__ stats, float step,
-                                                 float w_floor) {
+                                                 int first_row, float* __restrict__ params,
+                                                 float* __restrict__ stats, float step, float w_floor) {
     const int row = block * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (row >= n_rows) return;
+    const bool have = row >= first_row;      // rows below first_row count as zero statistics (memory is stale)
     const bool clear = row >= n_lazy_rows;   // the first rows are overwritten, not added to, by the next E-step
     const int off = row_off[row], len = row_len[row];
     if (len <= 64 * NPL) {
@@ -787,7 +788,7 @@ __device__ __forceinline__ void update_rows_body(int block, const int32_t* __res
 #pragma unroll
         for (int t = 0; t < NPL; ++t) {
             const int e = lane + 64 * t;
-            n[t] = e < len ? stats[off + e] : 0.f;
+            n[t] = e < len && have ? stats[off + e] : 0.f;
             w[t] = e < len ? params[off + e] : 0.f;
         }
 #pragma unroll
@@ -817,7 +818,8 @@ __device__ __forceinline__ void update_rows_body(int block, const int32_t* __res
         return;
     }
     float s = 0.f;
-    for (int e = lane; e < len; e += 64) s += stats[off + e];
+    if (have)
+        for (int e = lane; e < len; e += 64) s += stats[off + e];
     const float tot = wave_sum(s);
     const float sc = tot < 0x1p-60f ? 0x1p+64f : 1.f;
     const float inv = 1.f / (tot * sc);
@@ -886,15 +888,33 @@ __device__ __forceinline__ void update_leaves_body(int block, float* __restrict_
 template <int NPL>
 __global__ __launch_bounds__(256) void k_em_update(int n_row_blocks, const int32_t* __restrict__ row_off,
                                                    const int32_t* __restrict__ row_len, int n_rows, int n_lazy_rows,
-                                                   float* __restrict__ params, float* __restrict__ stats,
-                                                   float* __restrict__ theta, int64_t phi_off, int64_t den_off,
+                                                   int first_row, float* __restrict__ params,
+                                                   float* __restrict__ stats, float* __restrict__ theta, int64_t phi_off, int64_t den_off,
                                                    int64_t tot_off, float step, float min_var, float max_var,
                                                    float w_floor, Dims d) {
     if ((int)blockIdx.x < n_row_blocks)
-        update_rows_body<NPL>(blockIdx.x, row_off, row_len, n_rows, n_lazy_rows, params, stats, step, w_floor);
+        update_rows_body<NPL>(blockIdx.x, row_off, row_len, n_rows, n_lazy_rows, first_row, params, stats, step,
+                              w_floor);
     else
         update_leaves_body(blockIdx.x - n_row_blocks, params, stats, theta, phi_off, den_off, tot_off, step, min_var,
                            max_var, d);
+}
+
+// Mixture of circuits (Sec. 4.2): out[b] = log sum_c exp(log_coef[c] + lp[c][b]); thread per sample, the
+// component rows are read coalesced across samples.
+__global__ void k_mixture_logp(const float* __restrict__ lp, const float* __restrict__ log_coef, int n_components,
+                               int B, float* __restrict__ out) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    float m = -INFINITY;
+    for (int c = 0; c < n_components; ++c) m = fmaxf(m, log_coef[c] + lp[(size_t)c * B + b]);
+    if (m == -INFINITY) {
+        out[b] = -INFINITY;
+        return;
+    }
+    float sum = 0.f;
+    for (int c = 0; c < n_components; ++c) sum += expf(log_coef[c] + lp[(size_t)c * B + b] - m);
+    out[b] = m + logf(sum);
 }
 
 __global__ void k_fill(float* __restrict__ p, float value, int64_t n) {
@@ -1046,7 +1066,8 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_child
 #undef EINET_LAUNCH
 }
 
-void launch_em_update(const DevTables& t, int n_rows, int n_lazy_rows, float* params, float* stats, float* theta,
+void launch_em_update(const DevTables& t, int n_rows, int n_lazy_rows, bool lazy_rows_are_zero, float* params,
+                      float* stats, float* theta,
                       int64_t phi_off, int64_t den_off, int64_t tot_off, float step, float min_var, float max_var,
                       float w_floor, const Dims& d, hipStream_t s) {
     const int n_row_blocks = (n_rows + 3) / 4;
@@ -1055,12 +1076,16 @@ void launch_em_update(const DevTables& t, int n_rows, int n_lazy_rows, float* pa
     const int per_lane = (d.K * d.K + 63) / 64;
 #define EINET_LAUNCH(N)                                                                                             \
     hipLaunchKernelGGL(k_em_update<N>, dim3(n_row_blocks + n_leaf_blocks), dim3(256), 0, s, n_row_blocks, t.row_off, \
-                       t.row_len, n_rows, n_lazy_rows, params, stats, theta, phi_off, den_off, tot_off, step, min_var, \
-                       max_var, w_floor, d)
+                       t.row_len, n_rows, n_lazy_rows, lazy_rows_are_zero ? n_lazy_rows : 0, params, stats, theta,    \
+                       phi_off, den_off, tot_off, step, min_var, max_var, w_floor, d)
     if (per_lane <= 2) EINET_LAUNCH(2);
     else if (per_lane <= 8) EINET_LAUNCH(8);
     else EINET_LAUNCH(32);
 #undef EINET_LAUNCH
+}
+
+void launch_mixture_logp(const float* lp, const float* log_coef, int n_components, int B, float* out, hipStream_t s) {
+    hipLaunchKernelGGL(k_mixture_logp, dim3((B + 255) / 256), dim3(256), 0, s, lp, log_coef, n_components, B, out);
 }
 
 void launch_fill(float* p, float value, int64_t n, hipStream_t s) {

@@ -59,10 +59,13 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_child
                           float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const Dims& d,
                           hipStream_t s);
 // the whole M-step in one launch; the statistics of the first n_lazy_rows weight rows are left as they
-// are (the next E-step overwrites them)
-void launch_em_update(const DevTables& t, int n_rows, int n_lazy_rows, float* params, float* stats, float* theta,
+// are (the next E-step overwrites them); when no E-step has run since they were last consumed
+// (lazy_rows_are_zero) those rows count as zero and their weights are kept
+void launch_em_update(const DevTables& t, int n_rows, int n_lazy_rows, bool lazy_rows_are_zero, float* params,
+                      float* stats, float* theta,
                       int64_t phi_off, int64_t den_off, int64_t tot_off, float step, float min_var, float max_var,
                       float w_floor, const Dims& d, hipStream_t s);
 void launch_fill(float* p, float value, int64_t n, hipStream_t s);
+void launch_mixture_logp(const float* lp, const float* log_coef, int n_components, int B, float* out, hipStream_t s);
 
 }  // namespace einet_impl

@@ -70,3 +70,20 @@ def fig3_config(K=10, depth=4, R=10, B=100):
         data=dict(kind="gaussian_noise"),
         mask=None,
     )
+
+
+def sec42_config(shape="svhn"):
+    """One mixture component of the image experiments of Sec. 4.2: Poon-Domingos structure with vertical
+    splits only, four strips (step 8 on 32x32, step 32 on 128x128), K = 40, Gaussian leaves factorised
+    over the three colour channels, mini-batches of 500.  Stand-in data: a seeded Gaussian mixture in
+    [0, 1], not the street-number or face images."""
+    H, delta = {"svhn": (32, 8), "celeba": (128, 32)}[shape]
+    return dict(
+        name=f"sec42_{shape}_pd_{H}x{H}x3_k40",
+        structure=dict(kind="pd", H=H, W=H, deltas=[delta], axes=2),
+        K=40, channels=3, family=GAUSSIAN, B=500,
+        leaf_range=(0.0, 1.0),
+        data=dict(kind="gaussian_mixture", components=5, std=0.1),
+        mask=None,
+        em=dict(step=0.5, min_var=1e-6, max_var=1e-2, w_floor=1e-9),
+    )
