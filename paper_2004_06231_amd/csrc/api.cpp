@@ -20,7 +20,7 @@ struct einet {
 
     // workspace layout (bytes from the start of the workspace)
     std::vector<int32_t> blob;      // all index tables, concatenated
-    size_t off_theta = 0, off_A = 0, off_amax = 0, off_G = 0, off_Gp = 0, ws_bytes = 0;
+    size_t off_theta = 0, off_A = 0, off_Off = 0, off_amax = 0, off_G = 0, off_Gp = 0, ws_bytes = 0;
     struct TableOffsets {
 #define X(name) size_t name;
         EINET_TABLES(X)
@@ -131,17 +131,20 @@ void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, flo
              hipStream_t s) {
     const Plan& p = h->plan;
     float* A = reinterpret_cast<float*>(h->ws + h->off_A);
+    double* Off = reinterpret_cast<double*>(h->ws + h->off_Off);
     const float* theta = reinterpret_cast<const float*>(h->ws + h->off_theta);
-    run(h, KC_LEAF_FWD, s, [&] { launch_leaf_forward(h->dt, (int)p.leaf_node.size(), p.max_leaf_scope, x, mask, mask_mode, theta, A, d, s); });
+    run(h, KC_LEAF_FWD, s, [&] {
+        launch_leaf_forward(h->dt, (int)p.leaf_node.size(), p.max_leaf_scope, x, mask, mask_mode, theta, A, Off, d, s);
+    });
     for (int l = 0; l < p.num_layers; ++l) {
         run(h, KC_EINSUM_FWD, s, [&] {
             launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params, A,
-                                  reinterpret_cast<float*>(h->ws + h->off_amax), logp, d, s);
+                                  Off, reinterpret_cast<float*>(h->ws + h->off_amax), logp, d, s);
         });
         if (p.mix_layer_ptr[l + 1] > p.mix_layer_ptr[l])
             run(h, KC_MIXING_FWD, s, [&] {
                 launch_mixing_forward(h->dt, p.mix_layer_ptr[l], p.mix_layer_ptr[l + 1] - p.mix_layer_ptr[l],
-                                      h->params, A, logp, d, s);
+                                      h->params, A, Off, logp, d, s);
             });
     }
 }
@@ -199,6 +202,8 @@ int einet_create(const einet_spec* spec, einet_t** out) {
     off = align256(off + sizeof(float) * size_t(h->graph.num_vars) * p.C * h->graph.num_replica * p.TD * K);
     h->off_A = off;
     off = align256(off + sizeof(float) * size_t(p.num_nodes) * mb * K);
+    h->off_Off = off;
+    off = align256(off + sizeof(double) * size_t(p.num_nodes) * mb);
     h->off_amax = off;
     off = align256(off + sizeof(float) * 2 * p.ein_left.size() * mb);
     h->off_G = off;
@@ -303,6 +308,7 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
     const Plan& p = h->plan;
     forward(h, x_dev, mask_dev, mask_mode, logp_dev, d, s);
     const float* A = reinterpret_cast<const float*>(h->ws + h->off_A);
+    const double* Off = reinterpret_cast<const double*>(h->ws + h->off_Off);
     float* G = reinterpret_cast<float*>(h->ws + h->off_G);
     float* Gp = reinterpret_cast<float*>(h->ws + h->off_Gp);
     // top-down: posteriors of the regions of sum layer l (root first), then the einsum items below them
@@ -314,7 +320,7 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
         });
         run(h, KC_EINSUM_BWD, s, [&] {
             launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
-                                   !h->weight_stats_zero, h->params, h->stats, A, amax, G, Gp, d, s);
+                                   !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp, d, s);
         });
     }
     const int leaf_step = p.num_layers;
@@ -324,7 +330,7 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
     });
     run(h, KC_LEAF_BWD, s, [&] {
         launch_tail_backward(h->dt, (int)p.lv_leaf.size(), (int)p.mix_node.size(), p.max_mix_children, x_dev, mask_dev,
-                             mask_mode, h->params, A, G, h->stats, p.phi_offset, p.den_offset, p.tot_offset, d, s);
+                             mask_mode, h->params, A, Off, G, h->stats, p.phi_offset, p.den_offset, p.tot_offset, d, s);
     });
     h->weight_stats_zero = false;
     return check_hip(h, "einet_em_accumulate");

@@ -2,7 +2,16 @@
 //
 // Activations live in a node-major arena A[node][b][k] (float32, log domain):
 // every region and every simple sum owns one dense [B][K] block, so a layer's
-// "gather" of left and right inputs (Sec. 3.3) is an index lookup.  The
+// "gather" of left and right inputs (Sec. 3.3) is an index lookup.  A block does
+// not hold the log-densities themselves but their residuals against one offset
+// per (node, sample), Off[node][b] (float64):
+//     log-density[node][b][k] = Off[node][b] + A[node][b][k].
+// Leaves take their largest entry as offset; an einsum output takes the offsets of
+// its children plus the two shifts of Eq. 4, so that its residual is log S~ in
+// [log of the smallest weight, 0]; a mixing output takes the largest offset of its
+// children.  Log-densities of large scopes have magnitudes of 1e3..1e5, where a
+// float32 resolves 1e-4..1e-2; the residuals stay small, and the posteriors of the
+// top-down pass (exponentials of differences) keep full float32 precision.  The
 // posterior arena G has the same shape; Gp[2e+side][b][k] holds what einsum
 // item e sends down to its left (side 0) or right (side 1) child, and a child
 // sums the slots of its parents when it is processed: no atomics anywhere.
@@ -45,11 +54,13 @@ __global__ void k_leaf_derive(const float* __restrict__ phi, float* __restrict__
     }
 }
 
-// Leaf layer: A[leaf][b][k] = sum over the leaf's scope and the channels of the
-// log-density of x under entry k; a marginalised variable contributes 0.
-// A workgroup of 1024 threads computes 1024/NCH consecutive outputs (b, k) of one
+// Leaf layer: value[b][k] = sum over the leaf's scope and the channels of the
+// log-density of x under entry k; a marginalised variable contributes 0.  Stored
+// as Off[leaf][b] = max_k value (0 if every entry is -inf) and A = value - Off.
+// A workgroup of 1024 threads computes the K entries of 1024/NCH/K samples of one
 // leaf; its NCH parts each take every NCH-th variable of the scope and the
-// partial sums meet in LDS, so that a long scope does not become a long serial loop.
+// partial sums (float64: a scope of thousands of variables sums to 1e4 and more)
+// meet in LDS, so that a long scope does not become a long serial loop.
 template <int NCH>
 __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict__ leaf_node,
                                                        const int32_t* __restrict__ leaf_replica,
@@ -57,17 +68,19 @@ __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict
                                                        const int32_t* __restrict__ leaf_var,
                                                        const float* __restrict__ x, const uint8_t* __restrict__ mask,
                                                        int mask_mode, const float* __restrict__ theta,
-                                                       float* __restrict__ A, Dims d) {
+                                                       float* __restrict__ A, double* __restrict__ Off, Dims d) {
     constexpr int NO = 1024 / NCH;
-    __shared__ float red[NCH][NO];
+    __shared__ double red[NCH][NO];
     const int leaf = blockIdx.x, lo = threadIdx.x % NO, part_id = threadIdx.x / NO;
-    const int f = blockIdx.y * NO + lo;
-    const bool valid = f < d.B * d.K;
-    const int b = valid ? f / d.K : 0, k = valid ? f - b * d.K : 0;
+    const int rows = NO / d.K;                       // whole samples per workgroup (K <= 64 <= NO)
+    const int bl = lo / d.K, k = lo - bl * d.K;
+    const int brow = blockIdx.y * rows + bl;
+    const bool valid = bl < rows && brow < d.B;
+    const int b = valid ? brow : 0;
     const int r = leaf_replica[leaf];
     const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0;
     const size_t tstride = (size_t)d.TD * d.K;
-    float acc = 0.f;
+    double acc = 0.0;
 #pragma unroll 4
     for (int v = part_id; v < nv; v += NCH) {
         const int var = leaf_var[s0 + v];
@@ -86,22 +99,38 @@ __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict
                 part += xv * th[0] + (1.f - xv) * th[d.K];
             }
         }
-        acc += obs ? part : 0.f;
+        acc += obs ? (double)part : 0.0;
     }
     red[part_id][lo] = acc;
     __syncthreads();
-    if (part_id == 0 && valid) {
+    if (part_id == 0) {
 #pragma unroll
         for (int q = 1; q < NCH; ++q) acc += red[q][lo];
-        A[((size_t)leaf_node[leaf] * d.B + b) * d.K + k] = acc;
+        red[0][lo] = acc;
+    }
+    __syncthreads();
+    if (part_id == 0 && valid) {
+        double m = -INFINITY;
+        for (int kk = 0; kk < d.K; ++kk) m = fmax(m, red[0][bl * d.K + kk]);
+        if (m == -INFINITY) m = 0.0;                 // every entry excludes the sample: residuals -inf
+        const size_t row = (size_t)leaf_node[leaf] * d.B + b;
+        A[row * d.K + k] = (float)(acc - m);
+        if (k == 0) Off[row] = m;
     }
 }
 
 // Leaf layer for leaves with long scopes (image cells): a workgroup of 1024 threads takes one leaf
 // and LEAF_BS samples.  The samples' values are staged in LDS with coalesced reads of x; thread
 // (k, part) loads the constants of a few (variable, channel) pairs once and applies them to all
-// staged samples from registers; the parts meet in LDS.
+// staged samples from registers; the parts (float64) meet in LDS, then offset and residuals as above.
 constexpr int LEAF_BS = 8;
+
+// bytes of LDS: float64 partial sums first, then the values, the observation flags and the finished entries
+__host__ __device__ inline size_t leaf_wide_lds_bytes(int max_scope, int C, int K) {
+    return sizeof(double) * ((size_t)(1024 / K) * LEAF_BS * K + (size_t)LEAF_BS * K) +
+           sizeof(float) * ((size_t)LEAF_BS * max_scope * (C + 1));
+}
+
 __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __restrict__ leaf_node,
                                                             const int32_t* __restrict__ leaf_replica,
                                                             const int32_t* __restrict__ leaf_sptr,
@@ -109,15 +138,17 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
                                                             const float* __restrict__ x,
                                                             const uint8_t* __restrict__ mask, int mask_mode,
                                                             const float* __restrict__ theta, float* __restrict__ A,
-                                                            Dims d) {
-    extern __shared__ float lds[];
+                                                            double* __restrict__ Off, int max_scope, Dims d) {
+    extern __shared__ double lds_d[];
     const int leaf = blockIdx.x, b0 = blockIdx.y * LEAF_BS, tid = threadIdx.x;
     const int nbs = min(LEAF_BS, d.B - b0);
     const int r = leaf_replica[leaf];
     const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0, np = nv * d.C;
-    float* xs = lds;                       // [LEAF_BS][np] values, NaN-free zeros where unused
-    float* ob = lds + LEAF_BS * np;        // [LEAF_BS][nv] 1 = observed
-    float* red = ob + LEAF_BS * nv;        // [nparts][LEAF_BS][K]
+    const int nparts = 1024 / d.K;
+    double* red = lds_d;                                  // [nparts][LEAF_BS][K]
+    double* val = red + (size_t)nparts * LEAF_BS * d.K;   // [LEAF_BS][K] finished entries
+    float* xs = reinterpret_cast<float*>(val + LEAF_BS * d.K);   // [LEAF_BS][np] values, zeros where unused
+    float* ob = xs + (size_t)LEAF_BS * max_scope * d.C;   // [LEAF_BS][nv] 1 = observed
     for (int idx = tid; idx < LEAF_BS * np; idx += 1024) {
         const int b = idx / np, p = idx - b * np, v = p / d.C, c = p - v * d.C;
         xs[idx] = b < nbs ? x[((size_t)(b0 + b) * d.D + leaf_var[s0 + v]) * d.C + c] : 0.f;
@@ -130,12 +161,11 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
         ob[idx] = o;
     }
     __syncthreads();
-    const int nparts = 1024 / d.K;
     const int k = tid % d.K, part = tid / d.K;
     const size_t tstride = (size_t)d.TD * d.K;
-    float acc[LEAF_BS];
+    double acc[LEAF_BS];
 #pragma unroll
-    for (int b = 0; b < LEAF_BS; ++b) acc[b] = 0.f;
+    for (int b = 0; b < LEAF_BS; ++b) acc[b] = 0.0;
     if (part < nparts) {
         for (int p = part; p < np; p += nparts) {
             const int v = p / d.C, c = p - v * d.C;
@@ -145,14 +175,14 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
 #pragma unroll
                 for (int b = 0; b < LEAF_BS; ++b) {
                     const float diff = xs[b * np + p] - mu;
-                    acc[b] += ob[b * nv + v] * fmaf(c1 * diff, diff, c0);
+                    acc[b] += (double)(ob[b * nv + v] * fmaf(c1 * diff, diff, c0));
                 }
             } else {
                 const float lp = th[0], l1p = th[d.K];
 #pragma unroll
                 for (int b = 0; b < LEAF_BS; ++b) {
                     const float xv = xs[b * np + p];
-                    acc[b] += ob[b * nv + v] * (xv * lp + (1.f - xv) * l1p);
+                    acc[b] += (double)(ob[b * nv + v] * (xv * lp + (1.f - xv) * l1p));
                 }
             }
         }
@@ -160,18 +190,21 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
         for (int b = 0; b < LEAF_BS; ++b) red[(part * LEAF_BS + b) * d.K + k] = acc[b];
     }
     __syncthreads();
-    if (tid < LEAF_BS * d.K) {
-        const int b = tid / d.K, kk = tid - b * d.K;
-        // compensated sum: a scope of hundreds of variables gives partial sums of magnitude ~1e2..1e3, and the
-        // posteriors further up see the absolute error of this log-density
-        float sum = 0.f, comp = 0.f;
-        for (int q = 0; q < nparts; ++q) {
-            const float y = red[(q * LEAF_BS + b) * d.K + kk] - comp;
-            const float t = sum + y;
-            comp = (t - sum) - y;
-            sum = t;
-        }
-        if (b < nbs) A[((size_t)leaf_node[leaf] * d.B + b0 + b) * d.K + kk] = sum;
+    const bool fin = tid < LEAF_BS * d.K;
+    const int fb = fin ? tid / d.K : 0, kk = tid - fb * d.K;
+    double sum = 0.0;
+    if (fin) {
+        for (int q = 0; q < nparts; ++q) sum += red[(q * LEAF_BS + fb) * d.K + kk];
+        val[fb * d.K + kk] = sum;
+    }
+    __syncthreads();
+    if (fin && fb < nbs) {
+        double m = -INFINITY;
+        for (int q = 0; q < d.K; ++q) m = fmax(m, val[fb * d.K + q]);
+        if (m == -INFINITY) m = 0.0;
+        const size_t row = (size_t)leaf_node[leaf] * d.B + b0 + fb;
+        A[row * d.K + kk] = (float)(sum - m);
+        if (kk == 0) Off[row] = m;
     }
 }
 
@@ -207,8 +240,8 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
                                                         const int32_t* __restrict__ e_kout,
                                                         const int32_t* __restrict__ e_woff,
                                                         const float* __restrict__ params, float* __restrict__ A,
-                                                        float* __restrict__ amax, float* __restrict__ logp,
-                                                        int item0, int B, int K, int nkt) {
+                                                        double* __restrict__ Off, float* __restrict__ amax,
+                                                        float* __restrict__ logp, int item0, int B, int K, int nkt) {
     using LY = FwdLayout<KQ>;
     constexpr int KP = LY::KP, SJ = LY::SJ, SK = LY::SK;
     extern __shared__ float Wl[];
@@ -288,23 +321,26 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
             sacc += acc[0] * e4.x + acc[1] * e4.y + acc[2] * e4.z + acc[3] * e4.w;
         }
         const int k = 4 * kt + g;
-        if (ok && k < kout) {
-            const float val = ml + mr + __logf(sacc);
-            A[((size_t)e_out[li] * B + b) * K + k] = val;
-            if (logp && e_out[li] == 0) logp[b] = val;       // node 0 is the root region (single entry)
-        }
-        if (ok && kt == 0 && g == 0) {                 // the shifts, kept for the top-down pass
-            amax[((size_t)item * 2) * B + b] = ml;
+        const float res = __logf(sacc);                // residual against Off[left] + Off[right] + ml + mr
+        if (ok && k < kout) A[((size_t)e_out[li] * B + b) * K + k] = res;
+        if (ok && kt == 0 && g == 0) {
+            const double off = Off[(size_t)e_left[li] * B + b] + Off[(size_t)e_right[li] * B + b] + (double)ml + (double)mr;
+            Off[(size_t)e_out[li] * B + b] = off;
+            if (logp && e_out[li] == 0) logp[b] = (float)(off + (double)res);   // node 0: the root region, one entry
+            amax[((size_t)item * 2) * B + b] = ml;     // the shifts, kept for the top-down pass
             amax[((size_t)item * 2 + 1) * B + b] = mr;
         }
     }
 }
 
 // ------------------------------------------------------------------ mixing layer, forward (App. B)
+// Offset of the output: the largest offset of the children (their residuals are at most 0, so no term
+// exceeds its weight); residual: log sum_c v[c] exp((Off[c] - Off[out]) + A[c]).
 __global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32_t* __restrict__ m_kout,
                                  const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
                                  const int32_t* __restrict__ m_voff, const float* __restrict__ params,
-                                 float* __restrict__ A, float* __restrict__ logp, int B, int K) {
+                                 float* __restrict__ A, double* __restrict__ Off, float* __restrict__ logp, int B,
+                                 int K) {
     const int item = blockIdx.x;
     const int kout = m_kout[item];
     const int e = blockIdx.y * blockDim.x + threadIdx.x;
@@ -312,13 +348,20 @@ __global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32
     const int b = e / kout, k = e - b * kout;
     const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
     const float* v = params + m_voff[item] + (size_t)k * nc;
-    float m = -INFINITY;
-    for (int c = 0; c < nc; ++c) m = fmaxf(m, A[((size_t)m_child[c0 + c] * B + b) * K + k]);
-    if (m == -INFINITY) m = 0.f;
+    double m = -INFINITY;
+    for (int c = 0; c < nc; ++c) m = fmax(m, Off[(size_t)m_child[c0 + c] * B + b]);
     float s = 0.f;
-    for (int c = 0; c < nc; ++c) s += v[c] * expf(A[((size_t)m_child[c0 + c] * B + b) * K + k] - m);
-    A[((size_t)m_node[item] * B + b) * K + k] = m + logf(s);
-    if (logp && m_node[item] == 0) logp[b] = m + logf(s);    // node 0 is the root region (single entry)
+    for (int c = 0; c < nc; ++c) {
+        const size_t row = (size_t)m_child[c0 + c] * B + b;
+        s += v[c] * expf((float)(Off[row] - m) + A[row * K + k]);
+    }
+    const float res = logf(s);
+    const size_t row = (size_t)m_node[item] * B + b;
+    A[row * K + k] = res;
+    if (k == 0) {
+        Off[row] = m;
+        if (logp && m_node[item] == 0) logp[b] = (float)(m + (double)res);   // node 0: the root region, one entry
+    }
 }
 
 // ------------------------------------------------------------------ top-down pass, regions
@@ -350,7 +393,8 @@ __device__ __forceinline__ void mixing_stats_body(int item, int c, const int32_t
                                                   const int32_t* __restrict__ m_child,
                                                   const int32_t* __restrict__ m_voff, const float* __restrict__ params,
                                                   float* __restrict__ stats, const float* __restrict__ A,
-                                                  const float* __restrict__ G, int B, int K) {
+                                                  const double* __restrict__ Off, const float* __restrict__ G, int B,
+                                                  int K) {
     __shared__ float red[1024];
     const int tid = threadIdx.x;
     const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
@@ -360,12 +404,14 @@ __device__ __forceinline__ void mixing_stats_body(int item, int c, const int32_t
     const float* As = A + (size_t)m_node[item] * B * K;
     const float* Ac = A + (size_t)m_child[c0 + c] * B * K;
     const float* Gs = G + (size_t)m_node[item] * B * K;
+    const double* Os = Off + (size_t)m_node[item] * B;
+    const double* Oc = Off + (size_t)m_child[c0 + c] * B;
     float part = 0.f;
     if (bl < nbl)
         for (int b = bl; b < B; b += nbl) {
             const size_t o = (size_t)b * K + k;
             const float g = Gs[o];
-            if (g != 0.f) part += g * expf(Ac[o] - As[o]);
+            if (g != 0.f) part += g * expf((float)(Oc[b] - Os[b]) + Ac[o] - As[o]);
         }
     red[tid] = part;
     __syncthreads();
@@ -383,9 +429,10 @@ __device__ __forceinline__ void mixing_stats_body(int item, int c, const int32_t
 //   posterior of the children   U[b,i,j]   = sum_k Q[b,k] W[k,i,j]                           (GEMM-2)
 //                               Gp_left[b,i]  = eL[b,i] sum_j U[b,i,j] eR[b,j]
 //                               Gp_right[b,j] = eR[b,j] sum_i U[b,i,j] eL[b,i]
-// G_out is the posterior of the item's region times, for a region with several
-// partitions, the mixing weight and S^c/S; S^c cancels against S~, leaving
-//   Q = G[s] * v * exp(a + a' - A[s]).
+// G_out is the posterior of the item's region s times, for a region with several
+// partitions, the mixing weight and S^c/S; S^c cancels against S~ (the residual of the
+// item's own output is log S~), leaving
+//   Q = G[s] * v * exp((Off[out] - Off[s]) - A[s])        (Off[out] = Off[s] for a single partition).
 // A workgroup takes one item and a run of slices, a slice being four consecutive
 // left entries i.  eR and Q of up to 128 samples are staged once in LDS; the
 // slices W[:, 4 i, :] then stream through LDS one at a time (the next one is
@@ -448,11 +495,12 @@ __device__ __forceinline__ void bwd_gemm1(floatx4* acc1, const float* const* qco
 
 template <int KQ, bool VEC, bool ACCUM>
 __global__ __launch_bounds__(512, 2) void k_einsum_backward(
-    const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_reg,
-    const int32_t* __restrict__ e_kout, const int32_t* __restrict__ e_woff, const int32_t* __restrict__ e_voff,
-    const int32_t* __restrict__ e_vstr, const float* __restrict__ params, float* __restrict__ stats,
-    const float* __restrict__ A, const float* __restrict__ amax, const float* __restrict__ G, float* __restrict__ Gp,
-    int item0, int ngroups, int B, int K) {
+    const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_out,
+    const int32_t* __restrict__ e_reg, const int32_t* __restrict__ e_kout, const int32_t* __restrict__ e_woff,
+    const int32_t* __restrict__ e_voff, const int32_t* __restrict__ e_vstr, const float* __restrict__ params,
+    float* __restrict__ stats, const float* __restrict__ A, const double* __restrict__ Off,
+    const float* __restrict__ amax, const float* __restrict__ G, float* __restrict__ Gp, int item0, int ngroups, int B,
+    int K) {
     using LY = BwdLayout<KQ>;
     constexpr int KP = LY::KP, SI = LY::SI, S = LY::S, ST = LY::ST, BC = LY::BC, MAXU = LY::MAXU;
     extern __shared__ float lds[];
@@ -477,6 +525,8 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     const int voff = e_voff[li], vstr = e_vstr[li];
     const float* aL = amax + (size_t)item * 2 * B;
     const float* aR = aL + B;
+    const double* Oo = Off + (size_t)e_out[li] * B;
+    const double* Os = Off + (size_t)e_reg[li] * B;
     const int nblk = 1 + KQ;
 
     // registers that carry the next W slice
@@ -557,6 +607,7 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
         const bool rok = srow < nb;
         const int ro = (b0 + min(srow, nb - 1)) * K;       // a valid row even for the idle tail threads
         const float al = aL[b0 + min(srow, nb - 1)], ar = aR[b0 + min(srow, nb - 1)];
+        const float dd = (float)(Oo[b0 + min(srow, nb - 1)] - Os[b0 + min(srow, nb - 1)]);
         __syncthreads();                                   // readers of the previous pass are done
         {
             float rv[KQ], gv[KQ], av[KQ];
@@ -572,7 +623,7 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
             for (int u = 0; u < KQ; ++u) {
                 const int k = sq * KQ + u;
                 const float e = __expf(rv[u] - ar);
-                const float q = gv[u] * vw[u] * __expf(al + ar - av[u]);
+                const float q = gv[u] * vw[u] * __expf(dd - av[u]);
                 sR[k * ST + srow] = (rok && (VEC || k < K)) ? e : 0.f;
                 sQ[k * ST + srow] = (rok && k < kout && gv[u] != 0.f) ? q : 0.f;
             }
@@ -756,7 +807,8 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
     const float* __restrict__ x, const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G,
     float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const int32_t* __restrict__ m_node,
     const int32_t* __restrict__ m_kout, const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
-    const int32_t* __restrict__ m_voff, const float* __restrict__ params, const float* __restrict__ A, Dims d) {
+    const int32_t* __restrict__ m_voff, const float* __restrict__ params, const float* __restrict__ A,
+    const double* __restrict__ Off, Dims d) {
     const int blk = blockIdx.x;
     if (blk < n_leaf_blocks) {
         leaf_backward_body<NCH>(blk, lv_leaf, lv_var, leaf_node, leaf_replica, n_lv, x, mask, mask_mode, G, stats,
@@ -764,7 +816,7 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
     } else {
         const int idx = blk - n_leaf_blocks;
         mixing_stats_body(idx / max_children, idx % max_children, m_node, m_kout, m_cptr, m_child, m_voff, params,
-                          stats, A, G, d.B, d.K);
+                          stats, A, Off, G, d.B, d.K);
     }
 }
 
@@ -933,23 +985,30 @@ void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream
 }
 
 void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const float* x, const uint8_t* mask,
-                         int mask_mode, const float* theta, float* A, const Dims& d, hipStream_t s) {
+                         int mask_mode, const float* theta, float* A, double* Off, const Dims& d, hipStream_t s) {
     if (max_scope * d.C >= 32) {
         // long scopes: one workgroup per (leaf, LEAF_BS samples), values staged in LDS
-        const size_t lds = sizeof(float) * ((size_t)LEAF_BS * max_scope * (d.C + 1) + (size_t)(1024 / d.K) * LEAF_BS * d.K);
-        if (lds <= 64 * 1024) {
+        const size_t lds = leaf_wide_lds_bytes(max_scope, d.C, d.K);
+        if (lds <= 80 * 1024) {                       // two workgroups per CU
+            static bool attr_set = false;
+            if (!attr_set) {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_leaf_forward_wide),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+                attr_set = true;
+            }
             dim3 grid(n_leaves, (d.B + LEAF_BS - 1) / LEAF_BS);
             hipLaunchKernelGGL(k_leaf_forward_wide, grid, dim3(1024), lds, s, t.leaf_node, t.leaf_replica, t.leaf_sptr,
-                               t.leaf_var, x, mask, mask_mode, theta, A, d);
+                               t.leaf_var, x, mask, mask_mode, theta, A, Off, max_scope, d);
             return;
         }
     }
     // parts per workgroup: enough that each thread walks only a few variables of the scope
     const int nch = max_scope >= 32 ? 16 : (max_scope >= 8 ? 4 : 1);
-    dim3 grid(n_leaves, (d.B * d.K + 1024 / nch - 1) / (1024 / nch));
+    const int rows = (1024 / nch) / d.K;              // whole samples per workgroup
+    dim3 grid(n_leaves, (d.B + rows - 1) / rows);
 #define EINET_LAUNCH(N)                                                                                              \
     hipLaunchKernelGGL(k_leaf_forward<N>, grid, dim3(1024), 0, s, t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, \
-                       x, mask, mask_mode, theta, A, d)
+                       x, mask, mask_mode, theta, A, Off, d)
     if (nch == 16) EINET_LAUNCH(16);
     else if (nch == 4) EINET_LAUNCH(4);
     else EINET_LAUNCH(1);
@@ -958,7 +1017,7 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
 
 template <int KQ>
 static void launch_einsum_forward_kq(const DevTables& t, int first, int count, const float* params, float* A,
-                                     float* amax, float* logp, const Dims& d, hipStream_t s) {
+                                     double* Off, float* amax, float* logp, const Dims& d, hipStream_t s) {
     const int nkt = (d.K + 3) / 4;
     const int n_btiles = (d.B + 15) / 16;
     const int nw = n_btiles < 8 ? n_btiles : 8;
@@ -970,15 +1029,15 @@ static void launch_einsum_forward_kq(const DevTables& t, int first, int count, c
         attr_set = true;
     }
     hipLaunchKernelGGL(k_einsum_forward<KQ>, dim3(count * nkt), dim3(64 * nw), lds, s, t.ein_left + first,
-                       t.ein_right + first, t.ein_out + first, t.ein_kout + first, t.ein_woff + first, params, A, amax,
-                       logp, first, d.B, d.K, nkt);
+                       t.ein_right + first, t.ein_out + first, t.ein_kout + first, t.ein_woff + first, params, A, Off,
+                       amax, logp, first, d.B, d.K, nkt);
 }
 
-void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, float* amax,
-                           float* logp, const Dims& d, hipStream_t s) {
+void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
+                           float* amax, float* logp, const Dims& d, hipStream_t s) {
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
-    case J: launch_einsum_forward_kq<J>(t, first, count, params, A, amax, logp, d, s); break;
+    case J: launch_einsum_forward_kq<J>(t, first, count, params, A, Off, amax, logp, d, s); break;
         EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
         EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
         EINET_CASE(16)
@@ -986,12 +1045,12 @@ void launch_einsum_forward(const DevTables& t, int first, int count, const float
     }
 }
 
-void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, float* logp,
-                           const Dims& d, hipStream_t s) {
+void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
+                           float* logp, const Dims& d, hipStream_t s) {
     if (count == 0) return;
     dim3 grid(count, (d.B * d.K + 255) / 256);
     hipLaunchKernelGGL(k_mixing_forward, grid, dim3(256), 0, s, t.mix_node + first, t.mix_kout + first,
-                       t.mix_cptr + first, t.mix_child, t.mix_voff + first, params, A, logp, d.B, d.K);
+                       t.mix_cptr + first, t.mix_child, t.mix_voff + first, params, A, Off, logp, d.B, d.K);
 }
 
 void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
@@ -1004,8 +1063,8 @@ void launch_region_assemble(const DevTables& t, int first, int count, bool is_ro
 
 template <int KQ>
 static void launch_einsum_backward_kq(const DevTables& t, int first, int count, bool accumulate,
-                                      const float* params, float* stats, const float* A, const float* amax,
-                                      const float* G, float* Gp, const Dims& d, hipStream_t s) {
+                                      const float* params, float* stats, const float* A, const double* Off,
+                                      const float* amax, const float* G, float* Gp, const Dims& d, hipStream_t s) {
     const size_t lds = sizeof(float) * BwdLayout<KQ>::LDS_FLOATS;
     static bool attr_set = false;
     if (lds > 64 * 1024 && !attr_set) {
@@ -1022,8 +1081,9 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
     const int ngroups = bwd_groups_per_item(count, d.K);
 #define EINET_LAUNCH(V, ACC)                                                                                      \
     hipLaunchKernelGGL((k_einsum_backward<KQ, V, ACC>), dim3(count * ngroups), dim3(512), lds, s, t.ein_left + first,  \
-                       t.ein_right + first, t.ein_reg + first, t.ein_kout + first, t.ein_woff + first,                \
-                       t.ein_voff + first, t.ein_vstr + first, params, stats, A, amax, G, Gp, first, ngroups, d.B, d.K)
+                       t.ein_right + first, t.ein_out + first, t.ein_reg + first, t.ein_kout + first,                 \
+                       t.ein_woff + first, t.ein_voff + first, t.ein_vstr + first, params, stats, A, Off, amax, G, Gp,  \
+                       first, ngroups, d.B, d.K)
     if ((d.K & 3) == 0) {
         if (accumulate) EINET_LAUNCH(true, true);
         else EINET_LAUNCH(true, false);
@@ -1035,12 +1095,12 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
 }
 
 void launch_einsum_backward(const DevTables& t, int first, int count, bool accumulate, const float* params,
-                            float* stats, const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
-                            hipStream_t s) {
+                            float* stats, const float* A, const double* Off, const float* amax, const float* G,
+                            float* Gp, const Dims& d, hipStream_t s) {
     if (count == 0) return;
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
-    case J: launch_einsum_backward_kq<J>(t, first, count, accumulate, params, stats, A, amax, G, Gp, d, s); break;
+    case J: launch_einsum_backward_kq<J>(t, first, count, accumulate, params, stats, A, Off, amax, G, Gp, d, s); break;
         EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
         EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
         EINET_CASE(16)
@@ -1049,8 +1109,8 @@ void launch_einsum_backward(const DevTables& t, int first, int count, bool accum
 }
 
 void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_children, const float* x,
-                          const uint8_t* mask, int mask_mode, const float* params, const float* A, const float* G,
-                          float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const Dims& d,
+                          const uint8_t* mask, int mask_mode, const float* params, const float* A, const double* Off,
+                          const float* G, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const Dims& d,
                           hipStream_t s) {
     const int total = n_lv * d.C * d.K;
     const int nch = d.B >= 16 ? 4 : 1;
@@ -1060,7 +1120,7 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_child
 #define EINET_LAUNCH(N)                                                                                              \
     hipLaunchKernelGGL(k_tail_backward<N>, dim3(blocks), dim3(1024), 0, s, n_leaf_blocks, max_children > 0 ? max_children : 1, \
                        t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, n_lv, x, mask, mask_mode, G, stats, phi_off, \
-                       den_off, tot_off, t.mix_node, t.mix_kout, t.mix_cptr, t.mix_child, t.mix_voff, params, A, d)
+                       den_off, tot_off, t.mix_node, t.mix_kout, t.mix_cptr, t.mix_child, t.mix_voff, params, A, Off, d)
     if (nch == 4) EINET_LAUNCH(4);
     else EINET_LAUNCH(1);
 #undef EINET_LAUNCH

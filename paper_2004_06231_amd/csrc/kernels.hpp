@@ -27,20 +27,21 @@ struct Dims {
 };
 
 void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream_t s);
+// A [node][B][K] float32 holds residuals, Off [node][B] float64 the offsets: log-density = Off + A
 void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const float* x, const uint8_t* mask,
-                         int mask_mode, const float* theta, float* A, const Dims& d, hipStream_t s);
+                         int mask_mode, const float* theta, float* A, double* Off, const Dims& d, hipStream_t s);
 // logp (may be NULL): the launch that produces the root value also writes it there
-void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, float* amax,
+void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
+                           float* amax, float* logp, const Dims& d, hipStream_t s);
+void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
                            float* logp, const Dims& d, hipStream_t s);
-void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, float* logp,
-                           const Dims& d, hipStream_t s);
 
 void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
                             const Dims& d, hipStream_t s);
 // accumulate = false: the weight statistics of these items are known to be zero and are overwritten
 void launch_einsum_backward(const DevTables& t, int first, int count, bool accumulate, const float* params,
-                            float* stats, const float* A, const float* amax, const float* G, float* Gp, const Dims& d,
-                            hipStream_t s);
+                            float* stats, const float* A, const double* Off, const float* amax, const float* G,
+                            float* Gp, const Dims& d, hipStream_t s);
 // posterior blocks ([B][K] floats each) reserved per einsum item in Gp: one for its left child, then up to
 // one per slice of four left entries for its right child
 inline int gp_blocks_per_item(int K) { return 1 + (K + 3) / 4; }
@@ -55,9 +56,9 @@ inline int bwd_groups_per_item(int count, int K) {
 }
 // leaf statistics and mixing statistics (independent of each other) in one launch
 void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_children, const float* x,
-                          const uint8_t* mask, int mask_mode, const float* params, const float* A, const float* G,
-                          float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const Dims& d,
-                          hipStream_t s);
+                          const uint8_t* mask, int mask_mode, const float* params, const float* A, const double* Off,
+                          const float* G, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off,
+                          const Dims& d, hipStream_t s);
 // the whole M-step in one launch; the statistics of the first n_lazy_rows weight rows are left as they
 // are (the next E-step overwrites them); when no E-step has run since they were last consumed
 // (lazy_rows_are_zero) those rows count as zero and their weights are kept

@@ -156,15 +156,16 @@ def test_sec42_component_shapes_match_oracle(shape, B):
     lp = torch.empty(B, device="cuda")
     m.em_accumulate(dev(x), None, lp)
     assert_logp_close(lp, ref_logp)
-    # the arena holds log-densities in float32: a posterior is exp of a difference of such values, so it carries
-    # a relative error of about one unit in the last place of the largest of them (6e-3 at |logP| = 5e4 for the
-    # 128x128x3 images, 4e-4 at 3e3 for 32x32x3); the tolerance of the statistics grows by that much
-    rtol = 1e-3 + 2.0 ** -23 * np.abs(ref_logp).max()
-    print("statistics rtol", rtol, flush=True)
+    # log-densities of 5e4 in magnitude (128x128x3): the arena keeps float32 residuals against float64 offsets
+    # per (node, sample), so the posteriors do not inherit the resolution of a float32 at that magnitude
+    # (6e-3); the statistics are asked to be ten times closer than the usual tolerance here
+    rtol = 1e-4
     assert_stats_close(m.stats, oracle.stats_to_flat(ref_stats), oracle.layout, m.n_params, rtol=rtol)
+    got_lp = lp.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got_lp - ref_logp) <= 2e-7 * np.abs(ref_logp))     # float32 rounding of the output
     m.em_update(**cfg["em"])
     oracle.em_update(ref_stats, **cfg["em"])
     ref = oracle.get_flat_params()
     got = m.params.cpu().numpy().astype(np.float64)
-    assert np.all(np.abs(got - ref) <= rtol * np.abs(ref) + 1e-7)
+    assert np.all(np.abs(got - ref) <= 1e-3 * np.abs(ref) + 1e-7)
     m.close()
