@@ -1,0 +1,107 @@
+"""Float64 oracle for top-down sampling from an EiNet: ancestral sampling and sampling from
+the conditional given evidence (inpainting), with leaf samples or leaf means (Sec. 2, the
+latent-variable reading of smooth and decomposable circuits; Sec. 4.2; App. D).
+
+TEST INFRASTRUCTURE ONLY (see the package docstring).  One sample at a time, plain loops.
+Every random number is an input: one uniform per (partition, sample) and per (region,
+sample) for the choices at the sums, one number per (sample, variable, channel) for the
+leaves.  Pinned by tests/test_oracle_sampling.py (hand-computed choices, empirical
+frequencies against the exact distribution and against Eq. 1, K = 1 closed forms).
+
+The procedure.  A forward pass with the evidence (unobserved variables integrated out)
+gives the value of every node.  Starting from the single entry of the root, a region with
+entry k chooses one of its partitions n with probability v[k,n] * S_n[k] / N[k] (a region
+with one partition has no choice), the partition chooses a pair (i, j) of entries of its
+children with probability W[k,i,j] * N_left[i] * N_right[j] / S_n[k], and the two children
+continue with i and j.  A leaf reached with entry k keeps its observed variables and fills
+the others from its k-th distribution.  Without evidence all node values are 1 and the
+choices follow the weights alone (ancestral sampling).
+
+Choosing from unnormalised weights w_0..w_{n-1} with a uniform u: the first index t whose
+running sum w_0 + ... + w_t exceeds u * (w_0 + ... + w_{n-1}); pairs (i, j) are numbered
+i * K + j.  `margin` reports how close u came to a boundary of its interval, relative to the
+total, so that a float32 implementation can be compared where the choice is not a toss-up.
+"""
+import numpy as np
+
+from .einet import BERNOULLI, GAUSSIAN
+
+
+def choose(w, u):
+    """(index, margin) of the inverse-CDF choice described in the module docstring."""
+    c = np.cumsum(w)
+    total = c[-1]
+    tau = u * total
+    t = int(np.searchsorted(c, tau, side="right"))        # first t with c[t] > tau
+    if t >= len(w):                                       # u so close to 1 that rounding ate the last interval
+        t = int(np.nonzero(w)[0][-1])
+    lo = c[t - 1] if t > 0 else 0.0
+    margin = min(tau - lo, c[t] - tau) / total
+    return t, margin
+
+
+def sample(model, B, u, noise=None, x=None, mask=None):
+    """Draws B samples.
+
+    u     : [num_partitions + num_regions, B] uniforms in [0, 1): row n decides the pair of
+            partition n, row num_partitions + s the partition of region s
+    noise : [B, D, C]; Gaussian leaves: standard normal numbers, x = mean + sd * noise;
+            Bernoulli leaves: uniforms, x = 1 if noise < p else 0; None: the leaf means
+            (E[x] of the chosen leaf entry, App. D)
+    x, mask : evidence [B, D, C] and mask ([D] or [B, D], 1 = observed); None: no evidence
+
+    Returns (samples [B, D, C] float64 with the observed entries copied from x,
+             margin [B]: the smallest margin over the choices made for each sample,
+             paths: per sample the list of (partition, i, j) chosen).
+    The evidence must have non-zero density."""
+    g, K, C = model.g, model.K, model.C
+    D, P = g.num_vars, g.num_partitions
+    u = np.asarray(u, dtype=np.float64)
+    assert u.shape == (P + g.num_regions, B)
+    if x is None:
+        x = np.zeros((B, D, C))
+        mask = np.zeros(D)
+    x = np.asarray(x, dtype=np.float64)
+    m = model._mask(mask, B, D)
+    _, N, S = model.forward(x, m)
+    out = x.copy()
+    margins = np.full(B, np.inf)
+    paths = []
+    for b in range(B):
+        path = []
+        todo = [(0, 0)]
+        while todo:
+            s, k = todo.pop()
+            if g.is_leaf(s):
+                r = g.replica[s]
+                for d in g.scopes[s]:
+                    if m[b, d]:
+                        continue
+                    for c in range(C):
+                        phi = model.phi[d, c, r, :, k]
+                        if noise is None:
+                            out[b, d, c] = phi[0]
+                        elif model.family == GAUSSIAN:
+                            out[b, d, c] = phi[0] + np.sqrt(phi[1] - phi[0] ** 2) * noise[b, d, c]
+                        else:
+                            assert model.family == BERNOULLI
+                            out[b, d, c] = 1.0 if noise[b, d, c] < phi[0] else 0.0
+                continue
+            parts = g.children[s]
+            if len(parts) == 1:
+                n = parts[0]
+            else:
+                w = np.array([model.v[s][k, ci] * np.exp(S[nn][b, k] - N[s][b, k]) for ci, nn in enumerate(parts)])
+                ci, mg = choose(w, u[P + s, b])
+                margins[b] = min(margins[b], mg)
+                n = parts[ci]
+            _, left, right = g.partitions[n]
+            w = model.W[n][k] * np.exp(N[left][b][:, None] + N[right][b][None, :] - S[n][b, k])
+            t, mg = choose(w.ravel(), u[n, b])
+            margins[b] = min(margins[b], mg)
+            i, j = divmod(t, K)
+            path.append((n, i, j))
+            todo.append((left, i))
+            todo.append((right, j))
+        paths.append(path)
+    return out, margins, paths
