@@ -215,6 +215,36 @@ int einet_em_reset(einet_t* h, void* stream);
 int einet_em_epoch(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int64_t N, int batch,
                    float step, float min_var, float max_var, float w_floor, float* logp_dev, void* stream);
 
+/* Top-down sampling (Sec. 2: the latent-variable reading of a smooth and
+ * decomposable circuit; Sec. 4.2: samples and inpainting; App. D: leaf means).
+ * Starting from the root entry, a region with several partitions chooses one
+ * with probability v[k][c] S^c[k] / S[k], a partition chooses the pair (i, j)
+ * of entries of its children with probability W[k][i][j] L[i] R[j] / S[k], and
+ * a leaf reached with entry k keeps its observed variables and fills the others
+ * from its k-th distribution.  With evidence a forward pass as in einet_logp
+ * (unobserved variables integrated out) provides the node values, so the draw
+ * is from the conditional of Eq. 1; without evidence the choices follow the
+ * weights alone (ancestral sampling) and no forward pass runs.
+ * A choice from weights w_0.. with a uniform u is the first index whose running
+ * sum exceeds u times the total; pairs are numbered i*K + j.  All random numbers
+ * are inputs:
+ *   u_dev      device, [num_partitions + num_regions][B] float32 uniforms in
+ *              [0,1): row n decides the pair of partition n, row
+ *              num_partitions + s the partition of region s (rows of decisions a
+ *              sample does not meet are not read)
+ *   noise_dev  device, [B][D][C] float32, or NULL for the leaf means (App. D).
+ *              Gaussian leaves: standard normal numbers, x = mean + sd * noise;
+ *              Bernoulli leaves: uniforms, x = 1 if noise < p else 0
+ *   x_dev, mask_dev, mask_mode   evidence as in einet_logp (1 = observed);
+ *              EINET_MASK_NONE means no evidence: both pointers must be NULL
+ *   out_dev    device, [B][D][C] float32, written completely: observed entries
+ *              are copied from x_dev
+ * The evidence must have non-zero density.  Uses the workspace (overwrites the
+ * activations and the posterior arena; the statistics buffer is not touched).
+ * Errors: as einet_logp; B above 65535: EINET_ERR_BATCH_TOO_LARGE. */
+int einet_sample(einet_t* h, int B, const float* x_dev, const uint8_t* mask_dev, int mask_mode, const float* u_dev,
+                 const float* noise_dev, float* out_dev, void* stream);
+
 /* Mixture of several EiNets (Sec. 4.2: one EiNet per cluster, the cluster
  * proportions as coefficients):
  *   out[b] = log sum_c exp(log_coef[c] + logp[c][b]),

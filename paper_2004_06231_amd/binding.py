@@ -15,7 +15,7 @@ MAX_DELTAS = 8
 EXPORTED_SYMBOLS = [
     "einet_create", "einet_destroy", "einet_last_error", "einet_sizes", "einet_structure", "einet_bind",
     "einet_refresh", "einet_logp", "einet_em_accumulate", "einet_em_update", "einet_em_reset", "einet_em_epoch",
-    "einet_mixture_logp", "einet_profile_enable", "einet_profile_read",
+    "einet_mixture_logp", "einet_sample", "einet_profile_enable", "einet_profile_read",
 ]
 
 
@@ -73,6 +73,7 @@ def load_library():
     lib.einet_em_reset.argtypes = [vp, vp]
     lib.einet_em_epoch.argtypes = [vp, vp, vp, i32, C.c_int64, i32, f32, f32, f32, f32, vp, vp]
     lib.einet_mixture_logp.argtypes = [vp, vp, i32, i32, vp, vp]
+    lib.einet_sample.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp]
     lib.einet_profile_enable.argtypes = [vp, i32]
     lib.einet_profile_read.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                        C.POINTER(C.c_int64)]
@@ -241,6 +242,31 @@ class EiNet:
                                              step, min_var, max_var, w_floor, lp, self._stream()))
         return logp
 
+    def sample(self, B, u, noise=None, x=None, mask=None, out=None):
+        """Top-down sampling.  u: cuda float32 [num_partitions + num_regions, B] uniforms; noise: cuda float32
+        [B, D, channels] (standard normal for Gaussian leaves, uniform for Bernoulli leaves) or None for the
+        leaf means; x, mask: evidence as in logp (mask 1 = observed), both None for unconditional samples."""
+        torch = self._torch
+        st = self.structure()
+        D = int(st["num_vars"])
+        assert u.dtype == torch.float32 and u.is_cuda and u.is_contiguous()
+        assert tuple(u.shape) == (int(st["num_partitions"]) + int(st["num_regions"]), B)
+        if noise is not None:
+            assert noise.dtype == torch.float32 and noise.is_cuda and noise.is_contiguous()
+            assert tuple(noise.shape) == (B, D, self.channels)
+        if out is None:
+            out = torch.empty(B, D, self.channels, dtype=torch.float32, device=self.device)
+        assert (x is None) == (mask is None)
+        xp = None
+        if x is not None:
+            assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous() and tuple(x.shape) == tuple(out.shape)
+            xp = C.c_void_p(x.data_ptr())
+        m, mode = self._mask_args(mask, B)
+        self._check(self._lib.einet_sample(self._h, B, xp, m, mode, u.data_ptr(),
+                                           None if noise is None else C.c_void_p(noise.data_ptr()), out.data_ptr(),
+                                           self._stream()))
+        return out
+
     def profile_enable(self, enable=True):
         self._check(self._lib.einet_profile_enable(self._h, 1 if enable else 0))
 
@@ -300,6 +326,10 @@ def einet_em_reset(m):
 
 def einet_em_epoch(m, x, mask=None, batch=None, step=0.5, min_var=0.0, max_var=math.inf, w_floor=0.0, logp=None):
     return m.em_epoch(x, mask, batch, step, min_var, max_var, w_floor, logp)
+
+
+def einet_sample(m, B, u, noise=None, x=None, mask=None, out=None):
+    return m.sample(B, u, noise, x, mask, out)
 
 
 def einet_mixture_logp(component_logp, log_coef, out=None):

@@ -95,7 +95,9 @@ int check_batch_args(einet_t* h, const float* x, const uint8_t* mask, int mask_m
     return EINET_OK;
 }
 
-enum KernelClass { KC_LEAF_FWD, KC_EINSUM_FWD, KC_MIXING_FWD, KC_REGION_BWD, KC_EINSUM_BWD, KC_LEAF_BWD, KC_UPDATE, KC_COUNT };
+enum KernelClass {
+    KC_LEAF_FWD, KC_EINSUM_FWD, KC_MIXING_FWD, KC_REGION_BWD, KC_EINSUM_BWD, KC_LEAF_BWD, KC_UPDATE, KC_SAMPLE, KC_COUNT
+};
 int check_update_args(einet_t* h, float step, float min_var, float max_var, float w_floor) {
     if (!h) return EINET_ERR_INVALID_ARG;
     if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
@@ -106,7 +108,8 @@ int check_update_args(einet_t* h, float step, float min_var, float max_var, floa
 }
 
 const char* const kKernelClassNames[KC_COUNT] = {"leaf_forward", "einsum_forward", "mixing_forward", "region_backward",
-                                                 "einsum_backward", "leaf_mixing_backward", "em_update"};
+                                                 "einsum_backward", "leaf_mixing_backward", "em_update",
+                                                 "sampling"};
 
 // Runs `launch` (which enqueues kernels on s); when profiling, brackets it with two events.
 template <class F>
@@ -377,6 +380,45 @@ int einet_em_epoch(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int 
         if (rc != EINET_OK) return rc;
     }
     return EINET_OK;
+}
+
+int einet_sample(einet_t* h, int B, const float* x_dev, const uint8_t* mask_dev, int mask_mode, const float* u_dev,
+                 const float* noise_dev, float* out_dev, void* stream) {
+    if (!h) return EINET_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
+    if (B < 1) return fail(h, EINET_ERR_INVALID_ARG, "B must be at least 1");
+    if (B > h->spec.max_batch) return fail(h, EINET_ERR_BATCH_TOO_LARGE, "B exceeds max_batch given to einet_create");
+    if (B > 65535) return fail(h, EINET_ERR_BATCH_TOO_LARGE, "einet_sample draws at most 65535 samples per call");
+    if (!u_dev || !out_dev) return fail(h, EINET_ERR_INVALID_ARG, "u_dev or out_dev is NULL");
+    const bool evidence = mask_mode != EINET_MASK_NONE;
+    if (evidence) {
+        int rc = check_batch_args(h, x_dev, mask_dev, mask_mode, B);
+        if (rc != EINET_OK) return rc;
+    } else if (x_dev || mask_dev) {
+        return fail(h, EINET_ERR_INVALID_ARG, "without evidence (EINET_MASK_NONE) x_dev and mask_dev must be NULL");
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dims d = dims_of(h, B);
+    const Plan& p = h->plan;
+    if (evidence) forward(h, x_dev, mask_dev, mask_mode, nullptr, d, s);
+    const float* A = reinterpret_cast<const float*>(h->ws + h->off_A);
+    const double* Off = reinterpret_cast<const double*>(h->ws + h->off_Off);
+    const float* amax = reinterpret_cast<const float*>(h->ws + h->off_amax);
+    // the chosen entries live where the posterior arena of the EM pass lives (one int32 per node and sample)
+    int32_t* sel = reinterpret_cast<int32_t*>(h->ws + h->off_G);
+    const int n_part = (int)h->graph.partition.size();
+    run(h, KC_SAMPLE, s, [&] {
+        launch_sample_init(sel, p.num_nodes, B, s);
+        for (int l = p.num_layers - 1; l >= 0; --l) {
+            launch_sample_mixing(h->dt, p.mix_layer_ptr[l], p.mix_layer_ptr[l + 1] - p.mix_layer_ptr[l], evidence,
+                                 h->params, A, Off, u_dev, n_part, sel, d, s);
+            launch_sample_einsum(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], evidence,
+                                 h->params, A, amax, u_dev, sel, d, s);
+        }
+        launch_sample_leaves(h->dt, (int)p.lv_leaf.size(), x_dev, mask_dev, mask_mode, h->params + p.phi_offset,
+                             noise_dev, sel, out_dev, d, s);
+    });
+    return check_hip(h, "einet_sample");
 }
 
 int einet_mixture_logp(const float* logp_dev, const float* log_coef_dev, int n_components, int B, float* out_dev,

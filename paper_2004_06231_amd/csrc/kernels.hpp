@@ -11,7 +11,7 @@ namespace einet_impl {
 // Index tables of the plan: one int32 vector each on the host (Plan) and one
 // pointer each into the bound workspace on the device (DevTables).
 #define EINET_TABLES(X)                                                                                    \
-    X(ein_left) X(ein_right) X(ein_out) X(ein_reg) X(ein_kout) X(ein_woff) X(ein_voff) X(ein_vstr)         \
+    X(ein_left) X(ein_right) X(ein_out) X(ein_reg) X(ein_kout) X(ein_woff) X(ein_voff) X(ein_vstr) X(ein_part) \
     X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff)                                           \
     X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
     X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len)
@@ -67,6 +67,20 @@ void launch_em_update(const DevTables& t, int n_rows, int n_lazy_rows, bool lazy
                       int64_t phi_off, int64_t den_off, int64_t tot_off, float step, float min_var, float max_var,
                       float w_floor, const Dims& d, hipStream_t s);
 void launch_fill(float* p, float value, int64_t n, hipStream_t s);
+
+// ---- top-down sampling.  sel[node][B] (int32) holds the entry each sample uses at a node, -1 where the
+// sample does not visit it.  u [num_partitions + num_regions][B]: the uniforms of the choices.
+// evidence = false: no forward pass has run, the choices follow the weights alone.
+void launch_sample_init(int32_t* sel, int num_nodes, int B, hipStream_t s);
+void launch_sample_mixing(const DevTables& t, int first, int count, bool evidence, const float* params,
+                          const float* A, const double* Off, const float* u, int num_partitions, int32_t* sel,
+                          const Dims& d, hipStream_t s);
+void launch_sample_einsum(const DevTables& t, int first, int count, bool evidence, const float* params,
+                          const float* A, const float* amax, const float* u, int32_t* sel, const Dims& d,
+                          hipStream_t s);
+void launch_sample_leaves(const DevTables& t, int n_lv, const float* x, const uint8_t* mask, int mask_mode,
+                          const float* phi, const float* noise, const int32_t* sel, float* out, const Dims& d,
+                          hipStream_t s);
 void launch_mixture_logp(const float* lp, const float* log_coef, int n_components, int B, float* out, hipStream_t s);
 
 }  // namespace einet_impl

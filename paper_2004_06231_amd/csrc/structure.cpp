@@ -244,6 +244,7 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& p, std::
                 p.ein_vstr.push_back(0);
             }
             p.layer_partition.push_back(n);
+            p.ein_part.push_back(n);
         }
         p.ein_layer_ptr.push_back((int32_t)p.ein_left.size());
         p.layer_ptr.push_back((int32_t)p.layer_partition.size());
