@@ -38,8 +38,17 @@ from .structure import RegionGraph, param_layout
 
 BERNOULLI = 0
 GAUSSIAN = 1
+BINOMIAL = 2      # leaf_param = number of trials N; x in {0..N}; phi = E[x] = N p
+CATEGORICAL = 3   # leaf_param = number of values V; x in {0..V-1}; phi = the V probabilities
 NUM_STATS = {BERNOULLI: 1, GAUSSIAN: 2}
-P_MIN = 1e-6  # Bernoulli p is kept in [P_MIN, 1 - P_MIN] by the M-step
+P_MIN = 1e-6  # probabilities are kept in [P_MIN, 1 - P_MIN] (categorical: >= P_MIN, renormalised) by the M-step
+
+
+def num_stats(family, leaf_param=0):
+    """|T|, the dimension of the sufficient statistic (Sec. 3.4)."""
+    if family == CATEGORICAL:
+        return int(leaf_param)
+    return 1 if family in (BERNOULLI, BINOMIAL) else 2
 
 
 def _logsumexp(a, axis):
@@ -50,12 +59,30 @@ def _logsumexp(a, axis):
     return np.squeeze(out, axis=axis)
 
 
-def ef_log_density(family, x, phi):
+def ef_log_density(family, x, phi, leaf_param=0):
     """log h(x) + T(x).theta(phi) - A(theta)  (Sec. 3.4).
 
     x   : [...]        values
     phi : [T, ...]     expectation parameters, broadcastable against x
+    leaf_param : trials N (binomial) or number of values V (categorical)
     """
+    if family == BINOMIAL:
+        from scipy.special import gammaln
+        N = float(leaf_param)
+        p = phi[0] / N                          # phi = E[x] = N p
+        theta = np.log(p) - np.log1p(-p)
+        A = -N * np.log1p(-p)
+        log_h = gammaln(N + 1.0) - gammaln(x + 1.0) - gammaln(N - x + 1.0)      # log of the binomial coefficient
+        return log_h + x * theta - A
+    if family == CATEGORICAL:
+        # T(x) = indicator vector of the value, theta_v = log phi_v, h = 1, A = 0 on the simplex
+        Tx = suff_stats(CATEGORICAL, x, leaf_param)
+        with np.errstate(divide="ignore"):
+            theta = np.log(phi)
+        out = 0.0
+        for v in range(int(leaf_param)):
+            out = out + np.where(Tx[v] != 0, theta[v], 0.0)
+        return out
     if family == BERNOULLI:
         p = phi[0]
         theta = np.log(p) - np.log1p(-p)        # natural parameter
@@ -72,20 +99,23 @@ def ef_log_density(family, x, phi):
     raise ValueError("unknown leaf family")
 
 
-def suff_stats(family, x):
+def suff_stats(family, x, leaf_param=0):
     """T(x) stacked on a new leading axis."""
-    if family == BERNOULLI:
+    if family in (BERNOULLI, BINOMIAL):
         return np.stack([x])
+    if family == CATEGORICAL:
+        return np.stack([(x == v).astype(np.float64) for v in range(int(leaf_param))])
     return np.stack([x, x * x])
 
 
 class OracleEiNet:
-    def __init__(self, graph: RegionGraph, K: int, channels: int, family: int):
+    def __init__(self, graph: RegionGraph, K: int, channels: int, family: int, leaf_param: int = 0):
         self.g = graph
         self.K = K
         self.C = channels
         self.family = family
-        self.T = NUM_STATS[family]
+        self.leaf_param = leaf_param
+        self.T = num_stats(family, leaf_param)
         self.layout = param_layout(graph, K, channels, self.T)
         self.W = [None] * graph.num_partitions        # [K_out, K, K]
         self.v = {}                                   # region -> [K_out, C_s]
@@ -162,7 +192,7 @@ class OracleEiNet:
                 for d in g.scopes[s]:
                     for c in range(self.C):
                         e = ef_log_density(self.family, x[:, d, c][:, None],
-                                           self.phi[d, c, r][:, None, :])      # [B, K]
+                                           self.phi[d, c, r][:, None, :], self.leaf_param)      # [B, K]
                         acc += m[:, d][:, None] * e
                 N[s] = acc
                 continue
@@ -244,7 +274,7 @@ class OracleEiNet:
                     stats["tot"][d, r] += Gs.sum(0)
                     stats["den"][d, r] += (m[:, d][:, None] * Gs).sum(0)
                     for c in range(self.C):
-                        Tx = suff_stats(self.family, x[:, d, c])            # [T, B]
+                        Tx = suff_stats(self.family, x[:, d, c], self.leaf_param)            # [T, B]
                         stats["num"][d, c, r] += np.einsum("tb,b,bk->tk", Tx, m[:, d], Gs)
                 continue
             ch = g.children[s]
@@ -300,6 +330,11 @@ class OracleEiNet:
         phi = (1.0 - lam) * self.phi + lam * hat
         if self.family == BERNOULLI:
             phi = np.clip(phi, P_MIN, 1.0 - P_MIN)
+        elif self.family == BINOMIAL:
+            phi = np.clip(phi, self.leaf_param * P_MIN, self.leaf_param * (1.0 - P_MIN))
+        elif self.family == CATEGORICAL:
+            phi = np.maximum(phi, P_MIN)
+            phi = phi / phi.sum(axis=3, keepdims=True)
         else:
             mu = phi[:, :, :, 0, :]
             var = np.clip(phi[:, :, :, 1, :] - mu ** 2, min_var, max_var)

@@ -24,7 +24,7 @@ total, so that a float32 implementation can be compared where the choice is not 
 """
 import numpy as np
 
-from .einet import BERNOULLI, GAUSSIAN
+from .einet import BERNOULLI, GAUSSIAN, BINOMIAL, CATEGORICAL, ef_log_density
 
 
 def choose(w, u):
@@ -46,8 +46,10 @@ def sample(model, B, u, noise=None, x=None, mask=None):
     u     : [num_partitions + num_regions, B] uniforms in [0, 1): row n decides the pair of
             partition n, row num_partitions + s the partition of region s
     noise : [B, D, C]; Gaussian leaves: standard normal numbers, x = mean + sd * noise;
-            Bernoulli leaves: uniforms, x = 1 if noise < p else 0; None: the leaf means
-            (E[x] of the chosen leaf entry, App. D)
+            Bernoulli leaves: uniforms, x = 1 if noise < p else 0; binomial and categorical
+            leaves: uniforms, x = the first value whose running probability sum exceeds
+            noise * (sum of all probabilities); None: the leaf means (E[x] of the chosen
+            leaf entry, App. D)
     x, mask : evidence [B, D, C] and mask ([D] or [B, D], 1 = observed); None: no evidence
 
     Returns (samples [B, D, C] float64 with the observed entries copied from x,
@@ -80,12 +82,20 @@ def sample(model, B, u, noise=None, x=None, mask=None):
                     for c in range(C):
                         phi = model.phi[d, c, r, :, k]
                         if noise is None:
-                            out[b, d, c] = phi[0]
+                            if model.family == CATEGORICAL:
+                                out[b, d, c] = float(np.dot(np.arange(model.leaf_param), phi))   # E[x]
+                            else:
+                                out[b, d, c] = phi[0]
                         elif model.family == GAUSSIAN:
                             out[b, d, c] = phi[0] + np.sqrt(phi[1] - phi[0] ** 2) * noise[b, d, c]
-                        else:
-                            assert model.family == BERNOULLI
+                        elif model.family == BERNOULLI:
                             out[b, d, c] = 1.0 if noise[b, d, c] < phi[0] else 0.0
+                        else:
+                            # discrete leaves: the first value whose cumulative probability exceeds the uniform
+                            n_val = model.leaf_param + 1 if model.family == BINOMIAL else model.leaf_param
+                            vals = np.arange(n_val, dtype=np.float64)
+                            pmf = np.exp(ef_log_density(model.family, vals, phi[:, None], model.leaf_param))
+                            out[b, d, c] = float(choose(pmf, noise[b, d, c])[0])
                 continue
             parts = g.children[s]
             if len(parts) == 1:

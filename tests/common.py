@@ -2,7 +2,7 @@
 import numpy as np
 
 from oracle import structure as ostruct
-from oracle.einet import OracleEiNet, NUM_STATS
+from oracle.einet import OracleEiNet, num_stats
 import workloads
 
 
@@ -21,18 +21,18 @@ def weight_blocks_of(graph, K, layout):
     return blocks
 
 
-def make_oracle(spec, K, channels, family, seed, leaf_range=(0.1, 0.9), rng=None):
+def make_oracle(spec, K, channels, family, seed, leaf_range=(0.1, 0.9), rng=None, leaf_param=0):
     """Oracle model with Dirichlet(1) weights and uniform leaf parameters.
     Returns (model, flat float32 parameters, rng)."""
     g = oracle_graph(spec, seed)
-    model = OracleEiNet(g, K, channels, family)
+    model = OracleEiNet(g, K, channels, family, leaf_param)
     lay = model.layout
     if rng is None:
         rng = np.random.default_rng(seed)
-    T = NUM_STATS[family]
+    T = num_stats(family, leaf_param)
     flat = workloads.draw_params(
         rng, lay.n_params, weight_blocks_of(g, K, lay), lay.phi_off,
-        (g.num_vars, channels, g.num_replica, T, K), family, leaf_range)
+        (g.num_vars, channels, g.num_replica, T, K), family, leaf_range, leaf_param)
     model.set_flat_params(flat)
     return model, flat, rng
 

@@ -8,6 +8,8 @@ mixture, see generate.py.
 """
 BERNOULLI = 0
 GAUSSIAN = 1
+BINOMIAL = 2
+CATEGORICAL = 3
 
 CONFIGS = [
     dict(
