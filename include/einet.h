@@ -49,7 +49,10 @@
  *   v   for each region with C_s > 1 partitions, in region order:
  *       [K_out][C_s] mixing weights, private per entry k (App. B)
  *   phi [D][channels][R][T][K] expectation parameters of the leaves
- *       (Sec. 3.4): Bernoulli T=1: p; Gaussian T=2: (E[x], E[x^2])
+ *       (Sec. 3.4): Bernoulli T=1: p; Gaussian T=2: (E[x], E[x^2]); binomial
+ *       with N = leaf_param trials T=1: E[x] = N p, x in {0..N}; categorical
+ *       over V = leaf_param values T=V: the probabilities, x in {0..V-1}
+ *       (discrete values are passed as float32 like all data)
  * Flat statistics buffer (float32, n_stats entries):
  *   Nw, Nv, num with the shapes of W, v, phi, then den [D][R][K] and
  *   tot [D][R][K]  (posterior mass of a leaf entry over observed samples /
@@ -77,7 +80,7 @@ enum {
 };
 
 enum { EINET_STRUCTURE_RAT = 0, EINET_STRUCTURE_PD = 1 };
-enum { EINET_LEAF_BERNOULLI = 0, EINET_LEAF_GAUSSIAN = 1 };
+enum { EINET_LEAF_BERNOULLI = 0, EINET_LEAF_GAUSSIAN = 1, EINET_LEAF_BINOMIAL = 2, EINET_LEAF_CATEGORICAL = 3 };
 enum { EINET_MASK_NONE = 0, EINET_MASK_SHARED = 1, EINET_MASK_PER_SAMPLE = 2 };
 enum { EINET_AXIS_Y = 1, EINET_AXIS_X = 2 };
 #define EINET_MAX_DELTAS 8
@@ -99,6 +102,8 @@ typedef struct einet_spec {
     int32_t num_deltas;    /* 1..EINET_MAX_DELTAS */
     int32_t deltas[EINET_MAX_DELTAS];
     int32_t axes;          /* EINET_AXIS_Y | EINET_AXIS_X; X alone = vertical cuts only */
+    /* leaves */
+    int32_t leaf_param;    /* binomial: trials N, 1..4095; categorical: values V, 2..256; else ignored */
 } einet_spec;
 
 /* Read-only view of the compiled structure; all pointers are host memory
@@ -183,8 +188,10 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
  *            w_floor and renormalised, w <- (1-step) w + step hat; v likewise;
  *   leaves : hat = (num + (tot-den) phi) / tot (kept if tot is 0; equals
  *            num/den when nothing was masked), phi <- (1-step) phi + step hat;
- *            Bernoulli p clipped to [1e-6, 1-1e-6]; Gaussian variance
- *            E[x^2]-E[x]^2 projected to [min_var, max_var] (Sec. 4.2).
+ *            Bernoulli p clipped to [1e-6, 1-1e-6] (binomial: E[x]/N);
+ *            categorical probabilities raised to at least 1e-6 and
+ *            renormalised; Gaussian variance E[x^2]-E[x]^2 projected to
+ *            [min_var, max_var] (Sec. 4.2).
  * Afterwards the statistics are zero for every later call: the mixing and leaf
  * statistics are cleared in memory; the einsum-weight statistics Nw are left
  * as they are and the next einet_em_accumulate overwrites them instead of
@@ -234,7 +241,9 @@ int einet_em_epoch(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int 
  *              sample does not meet are not read)
  *   noise_dev  device, [B][D][C] float32, or NULL for the leaf means (App. D).
  *              Gaussian leaves: standard normal numbers, x = mean + sd * noise;
- *              Bernoulli leaves: uniforms, x = 1 if noise < p else 0
+ *              Bernoulli leaves: uniforms, x = 1 if noise < p else 0; binomial
+ *              and categorical leaves: uniforms, x = the first value whose
+ *              running probability sum exceeds noise * (sum of all of them)
  *   x_dev, mask_dev, mask_mode   evidence as in einet_logp (1 = observed);
  *              EINET_MASK_NONE means no evidence: both pointers must be NULL
  *   out_dev    device, [B][D][C] float32, written completely: observed entries

@@ -7,7 +7,7 @@ import numpy as np
 
 from .build import LIB_PATH
 
-BERNOULLI, GAUSSIAN = 0, 1
+BERNOULLI, GAUSSIAN, BINOMIAL, CATEGORICAL = 0, 1, 2, 3
 STRUCTURE_RAT, STRUCTURE_PD = 0, 1
 MASK_NONE, MASK_SHARED, MASK_PER_SAMPLE = 0, 1, 2
 MAX_DELTAS = 8
@@ -29,7 +29,7 @@ class _Spec(C.Structure):
     _fields_ = [("structure", C.c_int32), ("K", C.c_int32), ("channels", C.c_int32), ("leaf_family", C.c_int32),
                 ("max_batch", C.c_int32), ("num_vars", C.c_int32), ("depth", C.c_int32), ("num_replica", C.c_int32),
                 ("seed", C.c_uint64), ("height", C.c_int32), ("width", C.c_int32), ("num_deltas", C.c_int32),
-                ("deltas", C.c_int32 * MAX_DELTAS), ("axes", C.c_int32)]
+                ("deltas", C.c_int32 * MAX_DELTAS), ("axes", C.c_int32), ("leaf_param", C.c_int32)]
 
 
 class _View(C.Structure):
@@ -81,9 +81,10 @@ def load_library():
     return lib
 
 
-def _make_spec(spec, K, channels, family, max_batch, seed):
+def _make_spec(spec, K, channels, family, max_batch, seed, leaf_param=0):
     s = _Spec()
     s.K, s.channels, s.leaf_family, s.max_batch = K, channels, family, max_batch
+    s.leaf_param = leaf_param
     if spec["kind"] == "rat":
         s.structure = STRUCTURE_RAT
         s.num_vars, s.depth, s.num_replica, s.seed = spec["D"], spec["depth"], spec["R"], seed
@@ -103,10 +104,10 @@ def _make_spec(spec, K, channels, family, max_batch, seed):
 class EiNet:
     """A model handle plus the torch tensors that back its device buffers."""
 
-    def __init__(self, structure, K, channels, family, max_batch, seed=0):
+    def __init__(self, structure, K, channels, family, max_batch, seed=0, leaf_param=0):
         self._lib = load_library()
         self._h = C.c_void_p()
-        spec = _make_spec(structure, K, channels, family, max_batch, seed)
+        spec = _make_spec(structure, K, channels, family, max_batch, seed, leaf_param)
         rc = self._lib.einet_create(C.byref(spec), C.byref(self._h))
         if rc != 0:
             raise EinetError(rc, self._lib.einet_last_error(None).decode())
@@ -280,8 +281,8 @@ class EiNet:
 
 
 # The C names, for callers who prefer the flat interface.
-def einet_create(structure, K, channels, family, max_batch, seed=0):
-    return EiNet(structure, K, channels, family, max_batch, seed)
+def einet_create(structure, K, channels, family, max_batch, seed=0, leaf_param=0):
+    return EiNet(structure, K, channels, family, max_batch, seed, leaf_param)
 
 
 def einet_destroy(m):

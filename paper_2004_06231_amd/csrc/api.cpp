@@ -79,6 +79,7 @@ Dims dims_of(const einet_t* h, int B) {
     d.T = h->plan.T;
     d.TD = h->plan.TD;
     d.family = h->plan.family;
+    d.P = h->plan.leaf_param;
     return d;
 }
 
@@ -162,8 +163,12 @@ int einet_create(const einet_spec* spec, einet_t** out) {
     if (spec->K < 1 || spec->K > 64) return fail(nullptr, EINET_ERR_INVALID_ARG, "K must be in 1..64");
     if (spec->channels < 1) return fail(nullptr, EINET_ERR_INVALID_ARG, "channels must be at least 1");
     if (spec->max_batch < 1) return fail(nullptr, EINET_ERR_INVALID_ARG, "max_batch must be at least 1");
-    if (spec->leaf_family != EINET_LEAF_BERNOULLI && spec->leaf_family != EINET_LEAF_GAUSSIAN)
+    if (spec->leaf_family < EINET_LEAF_BERNOULLI || spec->leaf_family > EINET_LEAF_CATEGORICAL)
         return fail(nullptr, EINET_ERR_INVALID_ARG, "unknown leaf_family");
+    if (spec->leaf_family == EINET_LEAF_BINOMIAL && (spec->leaf_param < 1 || spec->leaf_param > 4095))
+        return fail(nullptr, EINET_ERR_INVALID_ARG, "binomial leaves need leaf_param (trials) in 1..4095");
+    if (spec->leaf_family == EINET_LEAF_CATEGORICAL && (spec->leaf_param < 2 || spec->leaf_param > 256))
+        return fail(nullptr, EINET_ERR_INVALID_ARG, "categorical leaves need leaf_param (values) in 2..256");
     einet_t* h = new einet();
     h->spec = *spec;
     std::string err;
@@ -187,7 +192,7 @@ int einet_create(const einet_spec* spec, einet_t** out) {
         delete h;
         return fail(nullptr, EINET_ERR_INVALID_ARG, "unknown structure kind");
     }
-    if (ok) ok = compile_plan(h->graph, spec->K, spec->channels, spec->leaf_family, h->plan, err);
+    if (ok) ok = compile_plan(h->graph, spec->K, spec->channels, spec->leaf_family, spec->leaf_param, h->plan, err);
     if (!ok) {
         delete h;
         return fail(nullptr, EINET_ERR_BAD_STRUCTURE, err);

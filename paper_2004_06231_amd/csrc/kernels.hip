@@ -37,7 +37,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 //   Gaussian  phi = (E x, E x^2): mean, -1/(2 var), -log(2 pi var)/2
 //   Bernoulli phi = p           : log p, log(1-p)
 __global__ void k_leaf_derive(const float* __restrict__ phi, float* __restrict__ theta, int n_entries, int K,
-                              int family) {
+                              int family, int P) {
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= n_entries * K) return;
     int e = idx / K, k = idx - e * K;
@@ -47,11 +47,34 @@ __global__ void k_leaf_derive(const float* __restrict__ phi, float* __restrict__
         theta[(e * 3 + 0) * K + k] = m;
         theta[(e * 3 + 1) * K + k] = -0.5f / var;
         theta[(e * 3 + 2) * K + k] = -0.5f * logf(6.283185307179586f * var);
+    } else if (family == EINET_LEAF_CATEGORICAL) {
+        for (int v = 0; v < P; ++v) theta[((size_t)e * P + v) * K + k] = logf(phi[((size_t)e * P + v) * K + k]);
     } else {
-        float p = phi[e * K + k];
+        float p = phi[e * K + k] / (float)P;         // Bernoulli: P = 1; binomial: phi = P p
         theta[(e * 2 + 0) * K + k] = logf(p);
         theta[(e * 2 + 1) * K + k] = log1pf(-p);
     }
+}
+
+// Log-density of one value under one leaf entry, without the part that does not depend on the entry
+// (Sec. 3.4; th points at the entry's derived constants, which are K floats apart):
+//   Gaussian      -1/(2 var) (x - mean)^2 - log(2 pi var)/2
+//   Bernoulli, binomial with P trials   x log p + (P - x) log(1 - p); the binomial coefficient goes to the offset
+//   categorical   log p[x]
+template <int FAMILY>
+__device__ __forceinline__ float leaf_term(float xv, const float* __restrict__ th, int K, int P) {
+    if constexpr (FAMILY == EINET_LEAF_GAUSSIAN) {
+        const float diff = xv - th[0];
+        return fmaf(th[K] * diff, diff, th[2 * K]);
+    } else if constexpr (FAMILY == EINET_LEAF_CATEGORICAL) {
+        return th[(size_t)min(max((int)xv, 0), P - 1) * K];
+    } else {
+        return xv * th[0] + ((float)P - xv) * th[K];
+    }
+}
+
+__device__ __forceinline__ float leaf_base(const int32_t* __restrict__ logc, float xv, int P) {
+    return __int_as_float(logc[min(max((int)xv, 0), P)]);
 }
 
 // Leaf layer: value[b][k] = sum over the leaf's scope and the channels of the
@@ -60,15 +83,18 @@ __global__ void k_leaf_derive(const float* __restrict__ phi, float* __restrict__
 // A workgroup of 1024 threads computes the K entries of 1024/NCH/K samples of one
 // leaf; its NCH parts each take every NCH-th variable of the scope and the
 // partial sums (float64: a scope of thousands of variables sums to 1e4 and more)
-// meet in LDS, so that a long scope does not become a long serial loop.
-template <int NCH>
+// meet in LDS, so that a long scope does not become a long serial loop.  The family is a template
+// parameter: with a run-time switch inside the loop over the scope the loads of consecutive variables
+// are no longer issued together and the kernel takes twice as long.
+template <int NCH, int FAMILY>
 __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict__ leaf_node,
                                                        const int32_t* __restrict__ leaf_replica,
                                                        const int32_t* __restrict__ leaf_sptr,
                                                        const int32_t* __restrict__ leaf_var,
                                                        const float* __restrict__ x, const uint8_t* __restrict__ mask,
                                                        int mask_mode, const float* __restrict__ theta,
-                                                       float* __restrict__ A, double* __restrict__ Off, Dims d) {
+                                                       const int32_t* __restrict__ logc, float* __restrict__ A,
+                                                       double* __restrict__ Off, Dims d) {
     constexpr int NO = 1024 / NCH;
     __shared__ double red[NCH][NO];
     const int leaf = blockIdx.x, lo = threadIdx.x % NO, part_id = threadIdx.x / NO;
@@ -80,7 +106,8 @@ __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict
     const int r = leaf_replica[leaf];
     const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0;
     const size_t tstride = (size_t)d.TD * d.K;
-    double acc = 0.0;
+    const bool base = FAMILY == EINET_LEAF_BINOMIAL && k == 0;   // this thread also sums the binomial coefficients
+    double acc = 0.0, hacc = 0.0;
 #pragma unroll 4
     for (int v = part_id; v < nv; v += NCH) {
         const int var = leaf_var[s0 + v];
@@ -89,25 +116,30 @@ __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict
         if (mask_mode == EINET_MASK_PER_SAMPLE) obs = mask[(size_t)b * d.D + var] != 0;
         const float* xp = x + ((size_t)b * d.D + var) * d.C;
         const float* th = theta + ((size_t)var * d.C * d.R + r) * tstride + k;
-        float part = 0.f;
+        float part = 0.f, hpart = 0.f;
         for (int c = 0; c < d.C; ++c, th += (size_t)d.R * tstride) {
             const float xv = xp[c];
-            if (d.family == EINET_LEAF_GAUSSIAN) {
-                const float diff = xv - th[0];
-                part += fmaf(th[d.K] * diff, diff, th[2 * d.K]);
-            } else {
-                part += xv * th[0] + (1.f - xv) * th[d.K];
-            }
+            part += leaf_term<FAMILY>(xv, th, d.K, d.P);
+            if constexpr (FAMILY == EINET_LEAF_BINOMIAL)
+                if (base) hpart += leaf_base(logc, xv, d.P);
         }
         acc += obs ? (double)part : 0.0;
+        hacc += obs ? (double)hpart : 0.0;
     }
     red[part_id][lo] = acc;
     __syncthreads();
     if (part_id == 0) {
 #pragma unroll
         for (int q = 1; q < NCH; ++q) acc += red[q][lo];
-        red[0][lo] = acc;
     }
+    if constexpr (FAMILY == EINET_LEAF_BINOMIAL) {   // a second round for the base measure
+        __syncthreads();
+        red[part_id][lo] = hacc;
+        __syncthreads();
+        if (part_id == 0)
+            for (int q = 1; q < NCH; ++q) hacc += red[q][lo];
+    }
+    if (part_id == 0) red[0][lo] = acc;              // its own slot: nobody else has read or will write it
     __syncthreads();
     if (part_id == 0 && valid) {
         double m = -INFINITY;
@@ -115,7 +147,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict
         if (m == -INFINITY) m = 0.0;                 // every entry excludes the sample: residuals -inf
         const size_t row = (size_t)leaf_node[leaf] * d.B + b;
         A[row * d.K + k] = (float)(acc - m);
-        if (k == 0) Off[row] = m;
+        if (k == 0) Off[row] = m + hacc;
     }
 }
 
@@ -137,7 +169,8 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
                                                             const int32_t* __restrict__ leaf_var,
                                                             const float* __restrict__ x,
                                                             const uint8_t* __restrict__ mask, int mask_mode,
-                                                            const float* __restrict__ theta, float* __restrict__ A,
+                                                            const float* __restrict__ theta,
+                                                            const int32_t* __restrict__ logc, float* __restrict__ A,
                                                             double* __restrict__ Off, int max_scope, Dims d) {
     extern __shared__ double lds_d[];
     const int leaf = blockIdx.x, b0 = blockIdx.y * LEAF_BS, tid = threadIdx.x;
@@ -163,9 +196,10 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
     __syncthreads();
     const int k = tid % d.K, part = tid / d.K;
     const size_t tstride = (size_t)d.TD * d.K;
-    double acc[LEAF_BS];
+    const bool base = d.family == EINET_LEAF_BINOMIAL && k == 0;   // this thread also sums the binomial coefficients
+    double acc[LEAF_BS], hacc[LEAF_BS];
 #pragma unroll
-    for (int b = 0; b < LEAF_BS; ++b) acc[b] = 0.0;
+    for (int b = 0; b < LEAF_BS; ++b) acc[b] = hacc[b] = 0.0;
     if (part < nparts) {
         for (int p = part; p < np; p += nparts) {
             const int v = p / d.C, c = p - v * d.C;
@@ -177,12 +211,17 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
                     const float diff = xs[b * np + p] - mu;
                     acc[b] += (double)(ob[b * nv + v] * fmaf(c1 * diff, diff, c0));
                 }
+            } else if (d.family == EINET_LEAF_CATEGORICAL) {
+#pragma unroll
+                for (int b = 0; b < LEAF_BS; ++b)
+                    acc[b] += (double)(ob[b * nv + v] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + p], th, d.K, d.P));
             } else {
-                const float lp = th[0], l1p = th[d.K];
+                const float lp = th[0], l1p = th[d.K], nf = (float)d.P;
 #pragma unroll
                 for (int b = 0; b < LEAF_BS; ++b) {
                     const float xv = xs[b * np + p];
-                    acc[b] += (double)(ob[b * nv + v] * (xv * lp + (1.f - xv) * l1p));
+                    acc[b] += (double)(ob[b * nv + v] * (xv * lp + (nf - xv) * l1p));
+                    if (base) hacc[b] += (double)(ob[b * nv + v] * leaf_base(logc, xv, d.P));
                 }
             }
         }
@@ -198,13 +237,23 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
         val[fb * d.K + kk] = sum;
     }
     __syncthreads();
+    if (base && part < nparts) {                     // (after the barrier: the sums above have been read)
+#pragma unroll
+        for (int b = 0; b < LEAF_BS; ++b) red[(part * LEAF_BS + b) * d.K] = hacc[b];
+    }
+    if (d.family == EINET_LEAF_BINOMIAL) __syncthreads();
     if (fin && fb < nbs) {
         double m = -INFINITY;
         for (int q = 0; q < d.K; ++q) m = fmax(m, val[fb * d.K + q]);
         if (m == -INFINITY) m = 0.0;
         const size_t row = (size_t)leaf_node[leaf] * d.B + b0 + fb;
         A[row * d.K + kk] = (float)(sum - m);
-        if (kk == 0) Off[row] = m;
+        if (kk == 0) {
+            double h = 0.0;
+            if (d.family == EINET_LEAF_BINOMIAL)
+                for (int q = 0; q < nparts; ++q) h += red[(q * LEAF_BS + fb) * d.K];
+            Off[row] = m + h;
+        }
     }
 }
 
@@ -798,6 +847,45 @@ __device__ __forceinline__ void leaf_backward_body(
     }
 }
 
+// Categorical leaves: the sufficient statistic is the indicator of the value, so the posterior mass of a
+// sample goes to one of V rows.  One wave per (leaf variable, channel), lane k owns column k of a V x K
+// histogram in LDS and walks the samples; no two lanes touch the same cell.
+__global__ __launch_bounds__(64) void k_leaf_backward_categorical(
+    const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var, const int32_t* __restrict__ leaf_node,
+    const int32_t* __restrict__ leaf_replica, const float* __restrict__ x, const uint8_t* __restrict__ mask,
+    int mask_mode, const float* __restrict__ G, float* __restrict__ stats, int64_t phi_off, int64_t den_off,
+    int64_t tot_off, Dims d) {
+    extern __shared__ float hist[];                   // [V][K]
+    const int e = blockIdx.x / d.C, c = blockIdx.x - e * d.C, k = threadIdx.x;
+    const int leaf = lv_leaf[e], var = lv_var[e], r = leaf_replica[leaf];
+    const int V = d.P;
+    if (k < d.K)
+        for (int v = 0; v < V; ++v) hist[v * d.K + k] = 0.f;
+    const bool shared_obs = mask_mode != EINET_MASK_SHARED || mask[var] != 0;
+    float den = 0.f, tot = 0.f;
+    if (k < d.K) {
+        const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K + k;
+        for (int b = 0; b < d.B; ++b) {
+            const float p = Gl[(size_t)b * d.K];
+            bool obs = shared_obs;
+            if (mask_mode == EINET_MASK_PER_SAMPLE) obs = mask[(size_t)b * d.D + var] != 0;
+            const int v = min(max((int)x[((size_t)b * d.D + var) * d.C + c], 0), V - 1);
+            tot += p;
+            if (obs) {
+                den += p;
+                hist[v * d.K + k] += p;
+            }
+        }
+        const size_t ph = phi_off + ((size_t)(var * d.C + c) * d.R + r) * V * d.K + k;
+        for (int v = 0; v < V; ++v) stats[ph + (size_t)v * d.K] += hist[v * d.K + k];
+        if (c == 0) {
+            const size_t o = ((size_t)var * d.R + r) * d.K + k;
+            stats[den_off + o] += den;
+            stats[tot_off + o] += tot;
+        }
+    }
+}
+
 // Last launch of the top-down pass: leaf statistics in the first n_leaf_blocks workgroups, mixing
 // statistics in the others (item = idx / max_children, child = idx % max_children).
 template <int NCH>
@@ -905,6 +993,30 @@ __device__ __forceinline__ void update_leaves_body(int block, float* __restrict_
     const float tot = stats[tot_off + o], den = stats[den_off + o];
     stats[tot_off + o] = 0.f;
     stats[den_off + o] = 0.f;
+    if (d.family == EINET_LEAF_CATEGORICAL) {
+        // blend, raise to at least 1e-6, renormalise over the V values (two passes over the column)
+        for (int c = 0; c < d.C; ++c) {
+            const size_t e = (size_t)(var * d.C + c) * d.R + r;
+            float sum = 0.f;
+            for (int v = 0; v < d.P; ++v) {
+                const size_t ph = phi_off + (e * d.P + v) * d.K + k;
+                const float old = params[ph];
+                const float hat = tot > 0.f ? (stats[ph] + (tot - den) * old) / tot : old;
+                const float nw = fmaxf((1.f - step) * old + step * hat, 1e-6f);
+                stats[ph] = 0.f;
+                params[ph] = nw;
+                sum += nw;
+            }
+            const float inv = 1.f / sum;
+            for (int v = 0; v < d.P; ++v) {
+                const size_t ph = phi_off + (e * d.P + v) * d.K + k;
+                const float p = params[ph] * inv;
+                params[ph] = p;
+                theta[(e * d.P + v) * d.K + k] = logf(p);
+            }
+        }
+        return;
+    }
     for (int c = 0; c < d.C; ++c) {
         const size_t e = (size_t)(var * d.C + c) * d.R + r;
         float nw[2];
@@ -928,8 +1040,9 @@ __device__ __forceinline__ void update_leaves_body(int block, float* __restrict_
             th[d.K] = -0.5f / vd;
             th[2 * d.K] = -0.5f * logf(6.283185307179586f * vd);
         } else {
-            const float p = fminf(fmaxf(nw[0], 1e-6f), 1.f - 1e-6f);
-            params[ph0] = p;
+            const float nf = (float)d.P;               // Bernoulli: 1; binomial: phi = nf * p
+            const float p = fminf(fmaxf(nw[0] / nf, 1e-6f), 1.f - 1e-6f);
+            params[ph0] = nf * p;
             th[0] = logf(p);
             th[d.K] = log1pf(-p);
         }
@@ -1088,7 +1201,8 @@ __global__ void k_sample_leaves(const int32_t* __restrict__ lv_leaf, const int32
                                 const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica,
                                 int n_lv, const float* __restrict__ x, const uint8_t* __restrict__ mask, int mask_mode,
                                 const float* __restrict__ phi, const float* __restrict__ noise,
-                                const int32_t* __restrict__ sel, float* __restrict__ out, Dims d) {
+                                const int32_t* __restrict__ logc, const int32_t* __restrict__ sel,
+                                float* __restrict__ out, Dims d) {
     const int lv = blockIdx.x * blockDim.x + threadIdx.x, b = blockIdx.y;
     if (lv >= n_lv) return;
     const int leaf = lv_leaf[lv], var = lv_var[lv];
@@ -1107,7 +1221,44 @@ __global__ void k_sample_leaves(const int32_t* __restrict__ lv_leaf, const int32
         const float* ph = phi + (((size_t)var * d.C + c) * d.R + r) * d.T * d.K + k;
         const float mean = ph[0];
         float val = mean;
-        if (noise) {
+        if (d.family == EINET_LEAF_CATEGORICAL) {
+            float total = 0.f, ev = 0.f;
+            for (int v = 0; v < d.P; ++v) {
+                total += ph[(size_t)v * d.K];
+                ev = fmaf((float)v, ph[(size_t)v * d.K], ev);
+            }
+            val = ev;                                                    // E[x]
+            if (noise) {
+                const float tau = noise[o] * total;
+                float run = 0.f;
+                int pick = -1, last = 0;
+                for (int v = 0; v < d.P; ++v) {
+                    const float w = ph[(size_t)v * d.K];
+                    run += w;
+                    if (w > 0.f) last = v;
+                    if (pick < 0 && run > tau) pick = v;
+                }
+                val = (float)(pick < 0 ? last : pick);
+            }
+        } else if (d.family == EINET_LEAF_BINOMIAL) {
+            if (noise) {
+                const float p = mean / (float)d.P;
+                const float lp = logf(p), l1p = log1pf(-p);
+                float total = 0.f;
+                for (int v = 0; v <= d.P; ++v)
+                    total += expf(__int_as_float(logc[v]) + (float)v * lp + (float)(d.P - v) * l1p);
+                const float tau = noise[o] * total;
+                float run = 0.f;
+                int pick = -1, last = 0;
+                for (int v = 0; v <= d.P; ++v) {
+                    const float w = expf(__int_as_float(logc[v]) + (float)v * lp + (float)(d.P - v) * l1p);
+                    run += w;
+                    if (w > 0.f) last = v;
+                    if (pick < 0 && run > tau) pick = v;
+                }
+                val = (float)(pick < 0 ? last : pick);
+            }
+        } else if (noise) {
             if (d.family == EINET_LEAF_GAUSSIAN) val = mean + sqrtf(fmaxf(ph[d.K] - mean * mean, 0.f)) * noise[o];
             else val = noise[o] < mean ? 1.f : 0.f;
         }
@@ -1144,7 +1295,7 @@ __global__ void k_fill(float* __restrict__ p, float value, int64_t n) {
 void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream_t s) {
     const int n = d.D * d.C * d.R;
     const int total = n * d.K;
-    hipLaunchKernelGGL(k_leaf_derive, dim3((total + 255) / 256), dim3(256), 0, s, phi, theta, n, d.K, d.family);
+    hipLaunchKernelGGL(k_leaf_derive, dim3((total + 255) / 256), dim3(256), 0, s, phi, theta, n, d.K, d.family, d.P);
 }
 
 void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const float* x, const uint8_t* mask,
@@ -1161,7 +1312,7 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
             }
             dim3 grid(n_leaves, (d.B + LEAF_BS - 1) / LEAF_BS);
             hipLaunchKernelGGL(k_leaf_forward_wide, grid, dim3(1024), lds, s, t.leaf_node, t.leaf_replica, t.leaf_sptr,
-                               t.leaf_var, x, mask, mask_mode, theta, A, Off, max_scope, d);
+                               t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off, max_scope, d);
             return;
         }
     }
@@ -1169,12 +1320,20 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
     const int nch = max_scope >= 32 ? 16 : (max_scope >= 8 ? 4 : 1);
     const int rows = (1024 / nch) / d.K;              // whole samples per workgroup
     dim3 grid(n_leaves, (d.B + rows - 1) / rows);
-#define EINET_LAUNCH(N)                                                                                              \
-    hipLaunchKernelGGL(k_leaf_forward<N>, grid, dim3(1024), 0, s, t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, \
-                       x, mask, mask_mode, theta, A, Off, d)
-    if (nch == 16) EINET_LAUNCH(16);
-    else if (nch == 4) EINET_LAUNCH(4);
-    else EINET_LAUNCH(1);
+#define EINET_LAUNCH(N, F)                                                                                          \
+    hipLaunchKernelGGL((k_leaf_forward<N, F>), grid, dim3(1024), 0, s, t.leaf_node, t.leaf_replica, t.leaf_sptr,      \
+                       t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off, d)
+#define EINET_LAUNCH_FAMILY(N)                                                    \
+    switch (d.family) {                                                           \
+    case EINET_LEAF_GAUSSIAN: EINET_LAUNCH(N, EINET_LEAF_GAUSSIAN); break;        \
+    case EINET_LEAF_BINOMIAL: EINET_LAUNCH(N, EINET_LEAF_BINOMIAL); break;        \
+    case EINET_LEAF_CATEGORICAL: EINET_LAUNCH(N, EINET_LEAF_CATEGORICAL); break;  \
+    default: EINET_LAUNCH(N, EINET_LEAF_BERNOULLI); break;                        \
+    }
+    if (nch == 16) EINET_LAUNCH_FAMILY(16)
+    else if (nch == 4) EINET_LAUNCH_FAMILY(4)
+    else EINET_LAUNCH_FAMILY(1)
+#undef EINET_LAUNCH_FAMILY
 #undef EINET_LAUNCH
 }
 
@@ -1278,8 +1437,14 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_child
     const int total = n_lv * d.C * d.K;
     const int nch = d.B >= 16 ? 4 : 1;
     const int no = 1024 / nch;
-    const int n_leaf_blocks = (total + no - 1) / no;
+    const bool categorical = d.family == EINET_LEAF_CATEGORICAL;
+    if (categorical)     // indicator statistics: a histogram kernel of its own (at most 256 x 64 floats of LDS)
+        hipLaunchKernelGGL(k_leaf_backward_categorical, dim3(n_lv * d.C), dim3(64), sizeof(float) * d.P * d.K, s,
+                           t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, x, mask, mask_mode, G, stats, phi_off,
+                           den_off, tot_off, d);
+    const int n_leaf_blocks = categorical ? 0 : (total + no - 1) / no;
     const int blocks = n_leaf_blocks + n_mix * max_children;
+    if (blocks == 0) return;
 #define EINET_LAUNCH(N)                                                                                              \
     hipLaunchKernelGGL(k_tail_backward<N>, dim3(blocks), dim3(1024), 0, s, n_leaf_blocks, max_children > 0 ? max_children : 1, \
                        t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, n_lv, x, mask, mask_mode, G, stats, phi_off, \
@@ -1346,7 +1511,7 @@ void launch_sample_leaves(const DevTables& t, int n_lv, const float* x, const ui
                           const float* phi, const float* noise, const int32_t* sel, float* out, const Dims& d,
                           hipStream_t s) {
     hipLaunchKernelGGL(k_sample_leaves, dim3((n_lv + 255) / 256, d.B), dim3(256), 0, s, t.lv_leaf, t.lv_var,
-                       t.leaf_node, t.leaf_replica, n_lv, x, mask, mask_mode, phi, noise, sel, out, d);
+                       t.leaf_node, t.leaf_replica, n_lv, x, mask, mask_mode, phi, noise, t.leaf_logc, sel, out, d);
 }
 
 void launch_fill(float* p, float value, int64_t n, hipStream_t s) {

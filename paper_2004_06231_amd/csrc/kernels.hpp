@@ -9,12 +9,13 @@
 namespace einet_impl {
 
 // Index tables of the plan: one int32 vector each on the host (Plan) and one
-// pointer each into the bound workspace on the device (DevTables).
+// pointer each into the bound workspace on the device (DevTables).  leaf_logc holds
+// the float32 bit patterns of log C(N, v), v = 0..N, for binomial leaves.
 #define EINET_TABLES(X)                                                                                    \
     X(ein_left) X(ein_right) X(ein_out) X(ein_reg) X(ein_kout) X(ein_woff) X(ein_voff) X(ein_vstr) X(ein_part) \
     X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff)                                           \
     X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
-    X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len)
+    X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len) X(leaf_logc)
 
 struct DevTables {
 #define X(name) const int32_t* name;
@@ -24,6 +25,7 @@ struct DevTables {
 
 struct Dims {
     int B, D, C, R, K, T, TD, family;
+    int P;   // leaf parameter: trials of a binomial leaf (1 for Bernoulli), values of a categorical leaf
 };
 
 void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream_t s);

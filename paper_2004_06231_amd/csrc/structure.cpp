@@ -1,6 +1,9 @@
 // Structure generators and the layered plan (host only).
 #include "structure.hpp"
 
+#include <cmath>
+#include <cstring>
+
 #include <algorithm>
 #include <map>
 #include <numeric>
@@ -144,13 +147,24 @@ bool build_pd(int H, int W, const int32_t* deltas, int n_deltas, int axes, Regio
     return true;
 }
 
-bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& p, std::string& err) {
+bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param, Plan& p, std::string& err) {
     p = Plan();
     p.K = K;
     p.C = C;
     p.family = family;
-    p.T = family == EINET_LEAF_GAUSSIAN ? 2 : 1;
-    p.TD = family == EINET_LEAF_GAUSSIAN ? 3 : 2;
+    // sufficient statistics per leaf entry (Sec. 3.4) and constants the kernels derive from them
+    p.T = family == EINET_LEAF_GAUSSIAN ? 2 : (family == EINET_LEAF_CATEGORICAL ? leaf_param : 1);
+    p.TD = family == EINET_LEAF_GAUSSIAN ? 3 : (family == EINET_LEAF_CATEGORICAL ? leaf_param : 2);
+    p.leaf_param = family == EINET_LEAF_BINOMIAL || family == EINET_LEAF_CATEGORICAL ? leaf_param : 1;
+    if (family == EINET_LEAF_BINOMIAL)
+        for (int v = 0; v <= leaf_param; ++v) {
+            const float lc = (float)(std::lgamma(leaf_param + 1.0) - std::lgamma(v + 1.0) - std::lgamma(leaf_param - v + 1.0));
+            int32_t bits;
+            std::memcpy(&bits, &lc, sizeof bits);
+            p.leaf_logc.push_back(bits);
+        }
+    else
+        p.leaf_logc.push_back(0);                      // log C(1, v) = 0
     const int nr = (int)g.scope.size(), np = (int)g.partition.size();
     auto kout = [&](int s) { return s == 0 ? 1 : K; };
 

@@ -33,6 +33,7 @@ bool build_pd(int H, int W, const int32_t* deltas, int n_deltas, int axes, Regio
 // Everything the device needs, as host vectors (uploaded verbatim by einet_bind).
 struct Plan {
     int K = 0, C = 0, T = 0, TD = 0, family = 0;
+    int leaf_param = 1;     // trials of a binomial leaf (1 for Bernoulli), values of a categorical leaf
     int num_nodes = 0;      // regions + simple sums
     int num_layers = 0;
     int max_mix_children = 0;
@@ -56,6 +57,6 @@ struct Plan {
     int64_t n_params = 0, n_stats = 0;
 };
 
-bool compile_plan(const RegionGraph& g, int K, int C, int family, Plan& plan, std::string& err);
+bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param, Plan& plan, std::string& err);
 
 }  // namespace einet_impl

@@ -9,8 +9,8 @@ LOGP_RTOL, LOGP_ATOL = 1e-4, 1e-5       # |d| <= 1e-4 |ref| + 1e-5
 STAT_RTOL, STAT_ATOL_REL = 1e-3, 1e-6   # per tensor: |d| <= 1e-3 |ref| + 1e-6 max|ref|
 
 
-def gpu_model(spec, K, channels, family, max_batch, seed, flat):
-    m = P.EiNet(spec, K, channels, family, max_batch, seed).bind("cuda:0")
+def gpu_model(spec, K, channels, family, max_batch, seed, flat, leaf_param=0):
+    m = P.EiNet(spec, K, channels, family, max_batch, seed, leaf_param).bind("cuda:0")
     m.set_params(flat)
     return m
 
