@@ -15,6 +15,7 @@ einet     : forward pass (Sec. 3.2-3.4, Eq. 3, App. B), EM statistics (Eq. 6)
             and M-step (Eq. 7-9), all in float64.
 train     : the stochastic-EM loop over mini-batches (Eq. 8-9, Sec. 4.2) and the
             mixture of several EiNets (Sec. 4.2).
+init      : the counter-based random initialisation of the parameters.
 sampling  : top-down sampling, unconditional and given evidence, with leaf samples
             or leaf means (Sec. 2, Sec. 4.2, App. D).
 """
