@@ -161,6 +161,20 @@ int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_
  * caller has written the parameter buffer.  einet_em_update does it itself. */
 int einet_refresh(einet_t* h, void* stream);
 
+/* Random initial parameters, written into the bound parameter buffer (the
+ * paper prescribes no initialisation; this is the customary one): every weight
+ * row (the K*K weights of a sum entry, the C_s mixing weights of an entry) is a
+ * draw from the flat Dirichlet distribution, formed as normalised unit
+ * exponentials e = -log u; Bernoulli p, Gaussian mean and binomial E[x]/N are
+ * leaf_lo + (leaf_hi - leaf_lo) u, Gaussian variance 1; categorical tables as
+ * the weight rows.  u of the parameter at position p of the flat buffer is
+ * (top 23 bits of output p+1 of the SplitMix64 stream started at `seed`, plus
+ * 1/2) / 2^23, so an independent implementation reproduces the numbers.  Also
+ * refreshes the derived leaf constants.  Errors: EINET_ERR_NOT_BOUND,
+ * EINET_ERR_INVALID_ARG (leaf_lo > leaf_hi; probabilities outside (0,1)). */
+int einet_init_params(einet_t* h, uint64_t seed, float leaf_lo, float leaf_hi, void* stream);
+
+
 /* log P(x) per sample: leaf layer (Sec. 3.4), einsum layers with the
  * log-einsum-exp stabilisation (Eq. 4-5), mixing layers (App. B).
  *   x_dev     device, [B][D][channels] float32 (Bernoulli: 0.0 / 1.0)

@@ -14,7 +14,7 @@ MAX_DELTAS = 8
 
 EXPORTED_SYMBOLS = [
     "einet_create", "einet_destroy", "einet_last_error", "einet_sizes", "einet_structure", "einet_bind",
-    "einet_refresh", "einet_logp", "einet_em_accumulate", "einet_em_update", "einet_em_reset", "einet_em_epoch",
+    "einet_refresh", "einet_init_params", "einet_logp", "einet_em_accumulate", "einet_em_update", "einet_em_reset", "einet_em_epoch",
     "einet_mixture_logp", "einet_sample", "einet_profile_enable", "einet_profile_read",
 ]
 
@@ -67,6 +67,7 @@ def load_library():
     lib.einet_structure.argtypes = [vp, C.POINTER(_View)]
     lib.einet_bind.argtypes = [vp, vp, vp, vp, vp]
     lib.einet_refresh.argtypes = [vp, vp]
+    lib.einet_init_params.argtypes = [vp, C.c_uint64, f32, f32, vp]
     lib.einet_logp.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.einet_em_accumulate.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.einet_em_update.argtypes = [vp, f32, f32, f32, f32, vp]
@@ -194,6 +195,10 @@ class EiNet:
         self.params.copy_(t.to(self.device, non_blocking=False))
         self.refresh()
 
+    def init_params(self, seed=0, leaf_lo=0.1, leaf_hi=0.9):
+        """Random initial parameters (flat Dirichlet weight rows, uniform leaf parameters), on the device."""
+        self._check(self._lib.einet_init_params(self._h, seed, leaf_lo, leaf_hi, self._stream()))
+
     def refresh(self):
         self._check(self._lib.einet_refresh(self._h, self._stream()))
 
@@ -303,6 +308,10 @@ def einet_structure(m):
 
 def einet_bind(m, device="cuda:0"):
     return m.bind(device)
+
+
+def einet_init_params(m, seed=0, leaf_lo=0.1, leaf_hi=0.9):
+    m.init_params(seed, leaf_lo, leaf_hi)
 
 
 def einet_refresh(m):

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -147,7 +148,10 @@ void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, flo
         });
         if (p.mix_layer_ptr[l + 1] > p.mix_layer_ptr[l])
             run(h, KC_MIXING_FWD, s, [&] {
-                launch_mixing_forward(h->dt, p.mix_layer_ptr[l], p.mix_layer_ptr[l + 1] - p.mix_layer_ptr[l],
+                int most = 0;                         // partitions of the widest region of this layer
+                for (int i = p.mix_layer_ptr[l]; i < p.mix_layer_ptr[l + 1]; ++i)
+                    most = std::max(most, p.mix_cptr[i + 1] - p.mix_cptr[i]);
+                launch_mixing_forward(h->dt, p.mix_layer_ptr[l], p.mix_layer_ptr[l + 1] - p.mix_layer_ptr[l], most,
                                       h->params, A, Off, logp, d, s);
             });
     }
@@ -294,6 +298,20 @@ int einet_refresh(einet_t* h, void* stream) {
     launch_leaf_derive(h->params + h->plan.phi_offset, reinterpret_cast<float*>(h->ws + h->off_theta), dims_of(h, 0),
                        static_cast<hipStream_t>(stream));
     return check_hip(h, "einet_refresh");
+}
+
+int einet_init_params(einet_t* h, uint64_t seed, float leaf_lo, float leaf_hi, void* stream) {
+    if (!h) return EINET_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
+    if (!(leaf_lo <= leaf_hi)) return fail(h, EINET_ERR_INVALID_ARG, "need leaf_lo <= leaf_hi");
+    const bool prob = h->plan.family == EINET_LEAF_BERNOULLI || h->plan.family == EINET_LEAF_BINOMIAL;
+    if (prob && !(leaf_lo > 0.f && leaf_hi < 1.f))
+        return fail(h, EINET_ERR_INVALID_ARG, "Bernoulli and binomial leaves need 0 < leaf_lo <= leaf_hi < 1");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dims d = dims_of(h, 0);
+    launch_init_params(h->dt, (int)h->plan.row_off.size(), h->params, h->plan.phi_offset, seed, leaf_lo, leaf_hi, d, s);
+    launch_leaf_derive(h->params + h->plan.phi_offset, reinterpret_cast<float*>(h->ws + h->off_theta), d, s);
+    return check_hip(h, "einet_init_params");
 }
 
 int einet_logp(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int B, float* logp_dev,

@@ -80,74 +80,123 @@ __device__ __forceinline__ float leaf_base(const int32_t* __restrict__ logc, flo
 // Leaf layer: value[b][k] = sum over the leaf's scope and the channels of the
 // log-density of x under entry k; a marginalised variable contributes 0.  Stored
 // as Off[leaf][b] = max_k value (0 if every entry is -inf) and A = value - Off.
-// A workgroup of 1024 threads computes the K entries of 1024/NCH/K samples of one
-// leaf; its NCH parts each take every NCH-th variable of the scope and the
-// partial sums (float64: a scope of thousands of variables sums to 1e4 and more)
-// meet in LDS, so that a long scope does not become a long serial loop.  The family is a template
-// parameter: with a run-time switch inside the loop over the scope the loads of consecutive variables
-// are no longer issued together and the kernel takes twice as long.
-template <int NCH, int FAMILY>
-__global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict__ leaf_node,
-                                                       const int32_t* __restrict__ leaf_replica,
-                                                       const int32_t* __restrict__ leaf_sptr,
-                                                       const int32_t* __restrict__ leaf_var,
-                                                       const float* __restrict__ x, const uint8_t* __restrict__ mask,
-                                                       int mask_mode, const float* __restrict__ theta,
-                                                       const int32_t* __restrict__ logc, float* __restrict__ A,
-                                                       double* __restrict__ Off, Dims d) {
-    constexpr int NO = 1024 / NCH;
-    __shared__ double red[NCH][NO];
+// A workgroup of TPB threads serves one leaf: thread (part, sample slot, k) computes entry k of RB samples
+// (slot, slot + rows, ...), its part taking every NCH-th variable of the scope; the partial sums (float64:
+// a scope of thousands of variables sums to 1e4 and more) meet in LDS.  Several samples per thread because
+// the kernel is bound by the chain index -> value/constants of every thread, not by arithmetic: the
+// constants are loaded once for RB samples and there are RB times fewer threads to wait for.  The family
+// is a template parameter: with a run-time switch inside the loop over the scope the loads of consecutive
+// variables are no longer issued together and the kernel takes twice as long.
+template <int NCH, int FAMILY, int TPB, int RB>
+__global__ __launch_bounds__(TPB) void k_leaf_forward(const int32_t* __restrict__ leaf_node,
+                                                      const int32_t* __restrict__ leaf_replica,
+                                                      const int32_t* __restrict__ leaf_sptr,
+                                                      const int32_t* __restrict__ leaf_var,
+                                                      const float* __restrict__ x, const uint8_t* __restrict__ mask,
+                                                      int mask_mode, const float* __restrict__ theta,
+                                                      const int32_t* __restrict__ logc, float* __restrict__ A,
+                                                      double* __restrict__ Off, Dims d) {
+    constexpr int NO = TPB / NCH;
+    __shared__ double red[NCH][RB][NO];
     const int leaf = blockIdx.x, lo = threadIdx.x % NO, part_id = threadIdx.x / NO;
-    const int rows = NO / d.K;                       // whole samples per workgroup (K <= 64 <= NO)
+    const int rows = NO / d.K;                       // sample slots per workgroup (K <= 64 <= NO)
     const int bl = lo / d.K, k = lo - bl * d.K;
-    const int brow = blockIdx.y * rows + bl;
-    const bool valid = bl < rows && brow < d.B;
-    const int b = valid ? brow : 0;
+    int bs[RB];                                      // this thread's samples (clamped; `valid` says which exist)
+    bool valid[RB];
+#pragma unroll
+    for (int q = 0; q < RB; ++q) {
+        const int brow = (blockIdx.y * RB + q) * rows + bl;
+        valid[q] = bl < rows && brow < d.B;
+        bs[q] = valid[q] ? brow : 0;
+    }
     const int r = leaf_replica[leaf];
     const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0;
     const size_t tstride = (size_t)d.TD * d.K;
     const bool base = FAMILY == EINET_LEAF_BINOMIAL && k == 0;   // this thread also sums the binomial coefficients
-    double acc = 0.0, hacc = 0.0;
-#pragma unroll 4
-    for (int v = part_id; v < nv; v += NCH) {
-        const int var = leaf_var[s0 + v];
-        bool obs = true;
-        if (mask_mode == EINET_MASK_SHARED) obs = mask[var] != 0;
-        if (mask_mode == EINET_MASK_PER_SAMPLE) obs = mask[(size_t)b * d.D + var] != 0;
-        const float* xp = x + ((size_t)b * d.D + var) * d.C;
-        const float* th = theta + ((size_t)var * d.C * d.R + r) * tstride + k;
-        float part = 0.f, hpart = 0.f;
-        for (int c = 0; c < d.C; ++c, th += (size_t)d.R * tstride) {
-            const float xv = xp[c];
-            part += leaf_term<FAMILY>(xv, th, d.K, d.P);
-            if constexpr (FAMILY == EINET_LEAF_BINOMIAL)
-                if (base) hpart += leaf_base(logc, xv, d.P);
+    double acc[RB], hacc[RB];
+#pragma unroll
+    for (int q = 0; q < RB; ++q) acc[q] = hacc[q] = 0.0;
+    constexpr int U = RB > 1 ? 2 : 4;                // variables per round, their loads issued together
+    for (int v0 = part_id; v0 < nv; v0 += NCH * U) {
+        int var[U];
+        bool in[U];                                  // the variable exists (the last round may be short)
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * NCH;
+            in[u] = v < nv;
+            var[u] = in[u] ? leaf_var[s0 + v] : 0;
         }
-        acc += obs ? (double)part : 0.0;
-        hacc += obs ? (double)hpart : 0.0;
+        float obs[U][RB];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int q = 0; q < RB; ++q) {
+                bool o = in[u];
+                if (in[u] && mask_mode == EINET_MASK_SHARED) o = mask[var[u]] != 0;
+                if (in[u] && mask_mode == EINET_MASK_PER_SAMPLE) o = mask[(size_t)bs[q] * d.D + var[u]] != 0;
+                obs[u][q] = o ? 1.f : 0.f;
+            }
+        for (int c = 0; c < d.C; ++c) {
+            float t[U][RB], h[U][RB];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float* th = theta + ((size_t)(var[u] * d.C + c) * d.R + r) * tstride + k;
+#pragma unroll
+                for (int q = 0; q < RB; ++q) {
+                    t[u][q] = h[u][q] = 0.f;
+                    if (in[u]) {
+                        const float xv = x[((size_t)bs[q] * d.D + var[u]) * d.C + c];
+                        t[u][q] = leaf_term<FAMILY>(xv, th, d.K, d.P);
+                        if constexpr (FAMILY == EINET_LEAF_BINOMIAL)
+                            if (base) h[u][q] = leaf_base(logc, xv, d.P);
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int q = 0; q < RB; ++q) {
+                    acc[q] += obs[u][q] != 0.f ? (double)t[u][q] : 0.0;
+                    if constexpr (FAMILY == EINET_LEAF_BINOMIAL) hacc[q] += obs[u][q] != 0.f ? (double)h[u][q] : 0.0;
+                }
+        }
     }
-    red[part_id][lo] = acc;
+    if constexpr (NCH > 1) {
+#pragma unroll
+        for (int q = 0; q < RB; ++q) red[part_id][q][lo] = acc[q];
+        __syncthreads();
+        if (part_id == 0) {
+#pragma unroll
+            for (int q = 0; q < RB; ++q)
+#pragma unroll
+                for (int p = 1; p < NCH; ++p) acc[q] += red[p][q][lo];
+        }
+        if constexpr (FAMILY == EINET_LEAF_BINOMIAL) {   // a second round for the base measure
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < RB; ++q) red[part_id][q][lo] = hacc[q];
+            __syncthreads();
+            if (part_id == 0)
+                for (int q = 0; q < RB; ++q)
+                    for (int p = 1; p < NCH; ++p) hacc[q] += red[p][q][lo];
+        }
+    }
+    if (part_id == 0) {                              // its own slots: nobody else has read or will write them
+#pragma unroll
+        for (int q = 0; q < RB; ++q) red[0][q][lo] = acc[q];
+    }
     __syncthreads();
     if (part_id == 0) {
 #pragma unroll
-        for (int q = 1; q < NCH; ++q) acc += red[q][lo];
-    }
-    if constexpr (FAMILY == EINET_LEAF_BINOMIAL) {   // a second round for the base measure
-        __syncthreads();
-        red[part_id][lo] = hacc;
-        __syncthreads();
-        if (part_id == 0)
-            for (int q = 1; q < NCH; ++q) hacc += red[q][lo];
-    }
-    if (part_id == 0) red[0][lo] = acc;              // its own slot: nobody else has read or will write it
-    __syncthreads();
-    if (part_id == 0 && valid) {
-        double m = -INFINITY;
-        for (int kk = 0; kk < d.K; ++kk) m = fmax(m, red[0][bl * d.K + kk]);
-        if (m == -INFINITY) m = 0.0;                 // every entry excludes the sample: residuals -inf
-        const size_t row = (size_t)leaf_node[leaf] * d.B + b;
-        A[row * d.K + k] = (float)(acc - m);
-        if (k == 0) Off[row] = m + hacc;
+        for (int q = 0; q < RB; ++q) {
+            if (!valid[q]) continue;
+            double m = -INFINITY;
+            for (int kk = 0; kk < d.K; ++kk) m = fmax(m, red[0][q][bl * d.K + kk]);
+            if (m == -INFINITY) m = 0.0;             // every entry excludes the sample: residuals -inf
+            const size_t row = (size_t)leaf_node[leaf] * d.B + bs[q];
+            A[row * d.K + k] = (float)(acc[q] - m);
+            if (k == 0) Off[row] = m + hacc[q];
+        }
     }
 }
 
@@ -157,10 +206,12 @@ __global__ __launch_bounds__(1024) void k_leaf_forward(const int32_t* __restrict
 // staged samples from registers; the parts (float64) meet in LDS, then offset and residuals as above.
 constexpr int LEAF_BS = 8;
 
-// bytes of LDS: float64 partial sums first, then the values, the observation flags and the finished entries
+// bytes of LDS: the finished entries (float64) first, then the partial sums of the parts, the values and the
+// observation flags.  A part sums only a handful of terms, so float32 is enough for it; the sum over the
+// parts, of magnitude 1e2..1e4, is taken in float64.
 __host__ __device__ inline size_t leaf_wide_lds_bytes(int max_scope, int C, int K) {
-    return sizeof(double) * ((size_t)(1024 / K) * LEAF_BS * K + (size_t)LEAF_BS * K) +
-           sizeof(float) * ((size_t)LEAF_BS * max_scope * (C + 1));
+    return sizeof(double) * ((size_t)LEAF_BS * K) +
+           sizeof(float) * ((size_t)(1024 / K) * LEAF_BS * K + (size_t)LEAF_BS * max_scope * (C + 1));
 }
 
 __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __restrict__ leaf_node,
@@ -178,9 +229,9 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
     const int r = leaf_replica[leaf];
     const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0, np = nv * d.C;
     const int nparts = 1024 / d.K;
-    double* red = lds_d;                                  // [nparts][LEAF_BS][K]
-    double* val = red + (size_t)nparts * LEAF_BS * d.K;   // [LEAF_BS][K] finished entries
-    float* xs = reinterpret_cast<float*>(val + LEAF_BS * d.K);   // [LEAF_BS][np] values, zeros where unused
+    double* val = lds_d;                                  // [LEAF_BS][K] finished entries
+    float* red = reinterpret_cast<float*>(val + LEAF_BS * d.K);   // [nparts][LEAF_BS][K]
+    float* xs = red + (size_t)nparts * LEAF_BS * d.K;     // [LEAF_BS][np] values, zeros where unused
     float* ob = xs + (size_t)LEAF_BS * max_scope * d.C;   // [LEAF_BS][nv] 1 = observed
     for (int idx = tid; idx < LEAF_BS * np; idx += 1024) {
         const int b = idx / np, p = idx - b * np, v = p / d.C, c = p - v * d.C;
@@ -197,9 +248,9 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
     const int k = tid % d.K, part = tid / d.K;
     const size_t tstride = (size_t)d.TD * d.K;
     const bool base = d.family == EINET_LEAF_BINOMIAL && k == 0;   // this thread also sums the binomial coefficients
-    double acc[LEAF_BS], hacc[LEAF_BS];
+    float acc[LEAF_BS], hacc[LEAF_BS];
 #pragma unroll
-    for (int b = 0; b < LEAF_BS; ++b) acc[b] = hacc[b] = 0.0;
+    for (int b = 0; b < LEAF_BS; ++b) acc[b] = hacc[b] = 0.f;
     if (part < nparts) {
         for (int p = part; p < np; p += nparts) {
             const int v = p / d.C, c = p - v * d.C;
@@ -209,19 +260,19 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
 #pragma unroll
                 for (int b = 0; b < LEAF_BS; ++b) {
                     const float diff = xs[b * np + p] - mu;
-                    acc[b] += (double)(ob[b * nv + v] * fmaf(c1 * diff, diff, c0));
+                    acc[b] += ob[b * nv + v] * fmaf(c1 * diff, diff, c0);
                 }
             } else if (d.family == EINET_LEAF_CATEGORICAL) {
 #pragma unroll
                 for (int b = 0; b < LEAF_BS; ++b)
-                    acc[b] += (double)(ob[b * nv + v] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + p], th, d.K, d.P));
+                    acc[b] += ob[b * nv + v] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + p], th, d.K, d.P);
             } else {
                 const float lp = th[0], l1p = th[d.K], nf = (float)d.P;
 #pragma unroll
                 for (int b = 0; b < LEAF_BS; ++b) {
                     const float xv = xs[b * np + p];
-                    acc[b] += (double)(ob[b * nv + v] * (xv * lp + (nf - xv) * l1p));
-                    if (base) hacc[b] += (double)(ob[b * nv + v] * leaf_base(logc, xv, d.P));
+                    acc[b] += ob[b * nv + v] * (xv * lp + (nf - xv) * l1p);
+                    if (base) hacc[b] += ob[b * nv + v] * leaf_base(logc, xv, d.P);
                 }
             }
         }
@@ -231,9 +282,10 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
     __syncthreads();
     const bool fin = tid < LEAF_BS * d.K;
     const int fb = fin ? tid / d.K : 0, kk = tid - fb * d.K;
+    const int nact = min(nparts, np);                // parts beyond the number of pairs hold zeros
     double sum = 0.0;
     if (fin) {
-        for (int q = 0; q < nparts; ++q) sum += red[(q * LEAF_BS + fb) * d.K + kk];
+        for (int q = 0; q < nact; ++q) sum += (double)red[(q * LEAF_BS + fb) * d.K + kk];
         val[fb * d.K + kk] = sum;
     }
     __syncthreads();
@@ -251,7 +303,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
         if (kk == 0) {
             double h = 0.0;
             if (d.family == EINET_LEAF_BINOMIAL)
-                for (int q = 0; q < nparts; ++q) h += red[(q * LEAF_BS + fb) * d.K];
+                for (int q = 0; q < nact; ++q) h += (double)red[(q * LEAF_BS + fb) * d.K];
             Off[row] = m + h;
         }
     }
@@ -410,6 +462,41 @@ __global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32
     if (k == 0) {
         Off[row] = m;
         if (logp && m_node[item] == 0) logp[b] = (float)(m + (double)res);   // node 0: the root region, one entry
+    }
+}
+
+// The same for regions with many partitions (the root over R replicas of random binary trees): one wave per
+// output element, the children spread over the lanes, maximum and sum by wave reductions.
+__global__ __launch_bounds__(256) void k_mixing_forward_many(
+    const int32_t* __restrict__ m_node, const int32_t* __restrict__ m_kout, const int32_t* __restrict__ m_cptr,
+    const int32_t* __restrict__ m_child, const int32_t* __restrict__ m_voff, const float* __restrict__ params,
+    float* __restrict__ A, double* __restrict__ Off, float* __restrict__ logp, int B, int K) {
+    const int item = blockIdx.x;
+    const int kout = m_kout[item];
+    const int lane = threadIdx.x & 63;
+    const int e = blockIdx.y * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (e >= B * kout) return;                       // whole waves leave
+    const int b = e / kout, k = e - b * kout;
+    const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
+    const float* v = params + m_voff[item] + (size_t)k * nc;
+    double m = -INFINITY;
+    for (int c = lane; c < nc; c += 64) m = fmax(m, Off[(size_t)m_child[c0 + c] * B + b]);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = fmax(m, __shfl_xor(m, o, 64));
+    float s = 0.f;
+    for (int c = lane; c < nc; c += 64) {
+        const size_t row = (size_t)m_child[c0 + c] * B + b;
+        s += v[c] * expf((float)(Off[row] - m) + A[row * K + k]);
+    }
+    s = wave_sum(s);
+    if (lane == 0) {
+        const float res = logf(s);
+        const size_t row = (size_t)m_node[item] * B + b;
+        A[row * K + k] = res;
+        if (k == 0) {
+            Off[row] = m;
+            if (logp && m_node[item] == 0) logp[b] = (float)(m + (double)res);
+        }
     }
 }
 
@@ -1266,6 +1353,54 @@ __global__ void k_sample_leaves(const int32_t* __restrict__ lv_leaf, const int32
     }
 }
 
+// ------------------------------------------------------------------ random initial parameters
+// Counter-based: parameter number p of the flat buffer uses output p + 1 of the SplitMix64 stream started at
+// `seed`; its top 23 bits plus one half, over 2^23, are a uniform in (0, 1) that float32 holds exactly.
+__device__ __forceinline__ float init_uniform(uint64_t seed, uint64_t p) {
+    uint64_t z = seed + (p + 1) * 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return ((float)(z >> 41) + 0.5f) * 0x1p-23f;
+}
+
+// Weight rows (one wave each): normalised unit exponentials, i.e. a draw from the flat Dirichlet distribution.
+// Leaves (one thread per (variable, replica, entry) in the remaining workgroups): uniform in [lo, hi] for the
+// Bernoulli p, the Gaussian mean (variance 1) and the binomial E[x] / N; categorical tables as the weight rows.
+__global__ __launch_bounds__(256) void k_init_params(int n_row_blocks, const int32_t* __restrict__ row_off,
+                                                     const int32_t* __restrict__ row_len, int n_rows,
+                                                     float* __restrict__ params, int64_t phi_off, uint64_t seed,
+                                                     float lo, float hi, Dims d) {
+    if ((int)blockIdx.x < n_row_blocks) {
+        const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+        if (row >= n_rows) return;
+        const int off = row_off[row], len = row_len[row];
+        float s = 0.f;
+        for (int e = lane; e < len; e += 64) s += -logf(init_uniform(seed, (uint64_t)(off + e)));
+        const float inv = 1.f / wave_sum(s);
+        for (int e = lane; e < len; e += 64) params[off + e] = -logf(init_uniform(seed, (uint64_t)(off + e))) * inv;
+        return;
+    }
+    const int idx = (blockIdx.x - n_row_blocks) * blockDim.x + threadIdx.x;
+    if (idx >= d.D * d.R * d.K) return;
+    const int k = idx % d.K, r = (idx / d.K) % d.R, var = idx / (d.K * d.R);
+    for (int c = 0; c < d.C; ++c) {
+        const size_t e = (size_t)(var * d.C + c) * d.R + r;
+        const size_t ph = (size_t)phi_off + e * d.T * d.K + k;
+        if (d.family == EINET_LEAF_CATEGORICAL) {
+            float s = 0.f;
+            for (int v = 0; v < d.P; ++v) s += -logf(init_uniform(seed, ph + (size_t)v * d.K));
+            const float inv = 1.f / s;
+            for (int v = 0; v < d.P; ++v)
+                params[ph + (size_t)v * d.K] = -logf(init_uniform(seed, ph + (size_t)v * d.K)) * inv;
+        } else {
+            const float first = lo + (hi - lo) * init_uniform(seed, ph);
+            params[ph] = d.family == EINET_LEAF_BINOMIAL ? (float)d.P * first : first;
+            if (d.family == EINET_LEAF_GAUSSIAN) params[ph + d.K] = fmaf(first, first, 1.f);
+        }
+    }
+}
+
 // Mixture of circuits (Sec. 4.2): out[b] = log sum_c exp(log_coef[c] + lp[c][b]); thread per sample, the
 // component rows are read coalesced across samples.
 __global__ void k_mixture_logp(const float* __restrict__ lp, const float* __restrict__ log_coef, int n_components,
@@ -1300,16 +1435,12 @@ void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream
 
 void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const float* x, const uint8_t* mask,
                          int mask_mode, const float* theta, float* A, double* Off, const Dims& d, hipStream_t s) {
-    if (max_scope * d.C >= 32) {
-        // long scopes: one workgroup per (leaf, LEAF_BS samples), values staged in LDS
+    const int pairs = max_scope * d.C;
+    if (pairs >= 32 && pairs * d.K >= 768) {
+        // long scopes (at least three quarters of the 1024/K parts of a workgroup get a (variable, channel) pair): one
+        // workgroup per (leaf, LEAF_BS samples), values staged in LDS
         const size_t lds = leaf_wide_lds_bytes(max_scope, d.C, d.K);
-        if (lds <= 80 * 1024) {                       // two workgroups per CU
-            static bool attr_set = false;
-            if (!attr_set) {
-                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_leaf_forward_wide),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
-                attr_set = true;
-            }
+        if (lds <= 64 * 1024) {
             dim3 grid(n_leaves, (d.B + LEAF_BS - 1) / LEAF_BS);
             hipLaunchKernelGGL(k_leaf_forward_wide, grid, dim3(1024), lds, s, t.leaf_node, t.leaf_replica, t.leaf_sptr,
                                t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off, max_scope, d);
@@ -1317,23 +1448,30 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
         }
     }
     // parts per workgroup: enough that each thread walks only a few variables of the scope
-    const int nch = max_scope >= 32 ? 16 : (max_scope >= 8 ? 4 : 1);
-    const int rows = (1024 / nch) / d.K;              // whole samples per workgroup
-    dim3 grid(n_leaves, (d.B + rows - 1) / rows);
-#define EINET_LAUNCH(N, F)                                                                                          \
-    hipLaunchKernelGGL((k_leaf_forward<N, F>), grid, dim3(1024), 0, s, t.leaf_node, t.leaf_replica, t.leaf_sptr,      \
-                       t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off, d)
-#define EINET_LAUNCH_FAMILY(N)                                                    \
-    switch (d.family) {                                                           \
-    case EINET_LEAF_GAUSSIAN: EINET_LAUNCH(N, EINET_LEAF_GAUSSIAN); break;        \
-    case EINET_LEAF_BINOMIAL: EINET_LAUNCH(N, EINET_LEAF_BINOMIAL); break;        \
-    case EINET_LEAF_CATEGORICAL: EINET_LAUNCH(N, EINET_LEAF_CATEGORICAL); break;  \
-    default: EINET_LAUNCH(N, EINET_LEAF_BERNOULLI); break;                        \
+    const int nch = pairs >= 96 ? 16 : (pairs >= 24 ? 4 : 1);
+    // Many outputs (enough threads to fill the chip twice over): 256 threads with four samples each.
+    // Otherwise, and for long scopes with sixteen parts: 1024 threads, one sample each.
+    const bool many = nch != 16 && (int64_t)n_leaves * d.B * d.K * nch >= 1000000;
+    const int tpb = many ? 256 : 1024, rb = many ? 4 : 1;
+    const int rows = (tpb / nch) / d.K;               // sample slots per workgroup
+    dim3 grid(n_leaves, (d.B + rows * rb - 1) / (rows * rb));
+#define EINET_LAUNCH(N, F, TPB, RB)                                                                                 \
+    hipLaunchKernelGGL((k_leaf_forward<N, F, TPB, RB>), grid, dim3(TPB), 0, s, t.leaf_node, t.leaf_replica,           \
+                       t.leaf_sptr, t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off, d)
+#define EINET_LAUNCH_SHAPE(N, F) \
+    if (many) EINET_LAUNCH(N, F, 256, 4); else EINET_LAUNCH(N, F, 1024, 1)
+#define EINET_LAUNCH_FAMILY(N)                                                          \
+    switch (d.family) {                                                                 \
+    case EINET_LEAF_GAUSSIAN: EINET_LAUNCH_SHAPE(N, EINET_LEAF_GAUSSIAN); break;        \
+    case EINET_LEAF_BINOMIAL: EINET_LAUNCH_SHAPE(N, EINET_LEAF_BINOMIAL); break;        \
+    case EINET_LEAF_CATEGORICAL: EINET_LAUNCH_SHAPE(N, EINET_LEAF_CATEGORICAL); break;  \
+    default: EINET_LAUNCH_SHAPE(N, EINET_LEAF_BERNOULLI); break;                        \
     }
     if (nch == 16) EINET_LAUNCH_FAMILY(16)
     else if (nch == 4) EINET_LAUNCH_FAMILY(4)
     else EINET_LAUNCH_FAMILY(1)
 #undef EINET_LAUNCH_FAMILY
+#undef EINET_LAUNCH_SHAPE
 #undef EINET_LAUNCH
 }
 
@@ -1367,9 +1505,15 @@ void launch_einsum_forward(const DevTables& t, int first, int count, const float
     }
 }
 
-void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
-                           float* logp, const Dims& d, hipStream_t s) {
+void launch_mixing_forward(const DevTables& t, int first, int count, int max_children, const float* params, float* A,
+                           double* Off, float* logp, const Dims& d, hipStream_t s) {
     if (count == 0) return;
+    if (max_children >= 8) {                         // a wave per output element, children over the lanes
+        dim3 grid(count, (d.B * d.K + 3) / 4);
+        hipLaunchKernelGGL(k_mixing_forward_many, grid, dim3(256), 0, s, t.mix_node + first, t.mix_kout + first,
+                           t.mix_cptr + first, t.mix_child, t.mix_voff + first, params, A, Off, logp, d.B, d.K);
+        return;
+    }
     dim3 grid(count, (d.B * d.K + 255) / 256);
     hipLaunchKernelGGL(k_mixing_forward, grid, dim3(256), 0, s, t.mix_node + first, t.mix_kout + first,
                        t.mix_cptr + first, t.mix_child, t.mix_voff + first, params, A, Off, logp, d.B, d.K);
@@ -1512,6 +1656,14 @@ void launch_sample_leaves(const DevTables& t, int n_lv, const float* x, const ui
                           hipStream_t s) {
     hipLaunchKernelGGL(k_sample_leaves, dim3((n_lv + 255) / 256, d.B), dim3(256), 0, s, t.lv_leaf, t.lv_var,
                        t.leaf_node, t.leaf_replica, n_lv, x, mask, mask_mode, phi, noise, t.leaf_logc, sel, out, d);
+}
+
+void launch_init_params(const DevTables& t, int n_rows, float* params, int64_t phi_off, uint64_t seed, float lo,
+                        float hi, const Dims& d, hipStream_t s) {
+    const int n_row_blocks = (n_rows + 3) / 4;
+    const int n_leaf_blocks = (d.D * d.R * d.K + 255) / 256;
+    hipLaunchKernelGGL(k_init_params, dim3(n_row_blocks + n_leaf_blocks), dim3(256), 0, s, n_row_blocks, t.row_off,
+                       t.row_len, n_rows, params, phi_off, seed, lo, hi, d);
 }
 
 void launch_fill(float* p, float value, int64_t n, hipStream_t s) {

@@ -35,8 +35,9 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
 // logp (may be NULL): the launch that produces the root value also writes it there
 void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
                            float* amax, float* logp, const Dims& d, hipStream_t s);
-void launch_mixing_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
-                           float* logp, const Dims& d, hipStream_t s);
+// max_children: the largest number of partitions of a region of these items
+void launch_mixing_forward(const DevTables& t, int first, int count, int max_children, const float* params, float* A,
+                           double* Off, float* logp, const Dims& d, hipStream_t s);
 
 void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
                             const Dims& d, hipStream_t s);
@@ -69,6 +70,8 @@ void launch_em_update(const DevTables& t, int n_rows, int n_lazy_rows, bool lazy
                       int64_t phi_off, int64_t den_off, int64_t tot_off, float step, float min_var, float max_var,
                       float w_floor, const Dims& d, hipStream_t s);
 void launch_fill(float* p, float value, int64_t n, hipStream_t s);
+void launch_init_params(const DevTables& t, int n_rows, float* params, int64_t phi_off, uint64_t seed, float lo,
+                        float hi, const Dims& d, hipStream_t s);
 
 // ---- top-down sampling.  sel[node][B] (int32) holds the entry each sample uses at a node, -1 where the
 // sample does not visit it.  u [num_partitions + num_regions][B]: the uniforms of the choices.

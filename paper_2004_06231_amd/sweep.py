@@ -26,11 +26,8 @@ def run_point(point, epochs=3):
     cfg = workloads.fig3_config(**point, B=BATCH)
     seed = 512
     m = P.EiNet(cfg["structure"], cfg["K"], 1, cfg["family"], BATCH, seed).bind("cuda:0")
-    st = m.structure()
     rng = np.random.default_rng(seed)
-    flat = workloads.draw_params(rng, m.n_params, m.weight_blocks(), int(st["phi_offset"]),
-                                 (512, 1, st["num_replica"], 2, cfg["K"]), cfg["family"], cfg["leaf_range"])
-    m.set_params(flat)
+    m.init_params(seed, *cfg["leaf_range"])
     data = torch.as_tensor(workloads.draw_data(rng, cfg["data"], N_TRAIN, 512, 1)).cuda()
     batches = [data[i:i + BATCH].contiguous() for i in range(0, N_TRAIN, BATCH)]
     logp = torch.empty(BATCH, dtype=torch.float32, device="cuda")

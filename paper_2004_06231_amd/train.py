@@ -38,10 +38,8 @@ def main():
     sizes = np.maximum(sizes, B)
     for c in range(args.components):
         m = P.EiNet(cfg["structure"], K, C, fam, B, args.seed + c).bind("cuda:0")
-        st = m.structure()
-        D, R, T = st["num_vars"], st["num_replica"], st["T"]
-        m.set_params(workloads.draw_params(rng, m.n_params, m.weight_blocks(), int(st["phi_offset"]), (D, C, R, T, K),
-                                           fam, cfg["leaf_range"]))
+        D = int(m.structure()["num_vars"])
+        m.init_params(args.seed + c, *cfg["leaf_range"])
         data.append(torch.as_tensor(workloads.draw_data(rng, cfg["data"], int(sizes[c]), D, C)).cuda())
         lps.append(torch.empty(int(sizes[c]), dtype=torch.float32, device="cuda"))
         models.append(m)

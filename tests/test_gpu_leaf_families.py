@@ -23,6 +23,9 @@ CASES = [
     (CATEGORICAL, 5, dict(kind="rat", D=16, depth=3, R=2), 7, 2, 33, "per_sample"),
     (CATEGORICAL, 256, dict(kind="pd", H=8, W=8, deltas=[4]), 8, 3, 40, "shared"),       # 8-bit pixels, image cells
     (CATEGORICAL, 16, dict(kind="rat", D=96, depth=1, R=2), 64, 1, 130, None),           # largest K
+    # thousands of short leaves: the leaf kernel takes four samples per thread
+    (BINOMIAL, 9, dict(kind="rat", D=512, depth=7, R=20), 8, 1, 100, "per_sample"),
+    (CATEGORICAL, 4, dict(kind="rat", D=512, depth=7, R=20), 8, 1, 100, "shared"),
 ]
 
 

@@ -169,3 +169,24 @@ def test_sec42_component_shapes_match_oracle(shape, B):
     got = m.params.cpu().numpy().astype(np.float64)
     assert np.all(np.abs(got - ref) <= 1e-3 * np.abs(ref) + 1e-7)
     m.close()
+
+
+@pytest.mark.parametrize("family,param", [(BERNOULLI, 0), (GAUSSIAN, 0), (2, 9), (3, 6)])
+def test_init_params_matches_the_oracle_generator(family, param):
+    """The library's random initialisation is counter-based; the oracle reproduces the numbers from the seed."""
+    from oracle.init import init_params
+    spec = dict(kind="pd", H=4, W=6, deltas=[2])
+    oracle, flat, _ = make_oracle(spec, 7, 2, family, 3, leaf_param=param)
+    m = gpu_model(spec, 7, 2, family, 8, 3, flat, param)
+    m.init_params(seed=2 ** 63 + 12345, leaf_lo=0.25, leaf_hi=0.75)
+    ref = init_params(oracle, 2 ** 63 + 12345, 0.25, 0.75)
+    got = m.params.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 2e-6 * np.abs(ref) + 1e-12)
+    # the derived leaf constants were refreshed: logP under the new parameters
+    oracle.set_flat_params(got)
+    rng = np.random.default_rng(0)
+    x = rng.integers(0, 2 if family == BERNOULLI else max(param, 2), size=(8, 24, 2)).astype(np.float32)
+    assert_logp_close(m.logp(dev(x)), oracle.logp(x))
+    with pytest.raises(P.EinetError):
+        m.init_params(seed=1, leaf_lo=0.9, leaf_hi=0.1)
+    m.close()
