@@ -106,7 +106,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; sharding over the batch with one all-reduce of the "
-              "statistics per M-step is described in DESIGN.md, not built. Use --gpus 1.", file=sys.stderr)
+              "statistics per M-step is how it would scale out; that is not built. Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -355,7 +355,8 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
                                p.rb_layer_ptr[leaf_step + 1] - p.rb_layer_ptr[leaf_step], false, G, Gp, d, s);
     });
     run(h, KC_LEAF_BWD, s, [&] {
-        launch_tail_backward(h->dt, (int)p.lv_leaf.size(), (int)p.mix_node.size(), p.max_mix_children, x_dev, mask_dev,
+        launch_tail_backward(h->dt, (int)p.lv_leaf.size(), (int)p.leaf_node.size(), p.max_leaf_scope,
+                             (int)p.mix_node.size(), p.max_mix_children, x_dev, mask_dev,
                              mask_mode, h->params, A, Off, G, h->stats, p.phi_offset, p.den_offset, p.tot_offset, d, s);
     });
     h->weight_stats_zero = false;

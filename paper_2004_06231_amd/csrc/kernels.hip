@@ -973,8 +973,80 @@ __global__ __launch_bounds__(64) void k_leaf_backward_categorical(
     }
 }
 
+// The same statistics for leaves with long scopes (image cells).  A workgroup takes one leaf and a chunk of
+// its (variable, channel) pairs; per pass over 128 samples the leaf's posterior block G[leaf][b][.] (contiguous
+// in memory) and the pairs' values are copied to LDS, then thread (pair, k) walks the samples out of LDS.  The
+// walk of the kernel above waits a full memory latency for every few samples; here it waits for LDS.
+constexpr int CELL_BC = 128;                          // samples per pass
+__host__ __device__ inline int cell_pairs_per_group(int K) { return 1024 / K < 64 ? 1024 / K : 64; }
+__host__ __device__ inline size_t cell_lds_bytes(int K) {
+    return sizeof(float) * (size_t)CELL_BC * (K + cell_pairs_per_group(K)) + (size_t)CELL_BC * cell_pairs_per_group(K);
+}
+
+__device__ __forceinline__ void leaf_backward_cells_body(
+    int block, int chunks_per_leaf, const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica,
+    const int32_t* __restrict__ leaf_sptr, const int32_t* __restrict__ leaf_var, const float* __restrict__ x,
+    const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, float* __restrict__ stats,
+    int64_t phi_off, int64_t den_off, int64_t tot_off, Dims d) {
+    extern __shared__ float cell_lds[];
+    const int pc = cell_pairs_per_group(d.K);
+    float* Gs = cell_lds;                             // [CELL_BC][K]
+    float* xs = Gs + CELL_BC * d.K;                   // [CELL_BC][pc]
+    uint8_t* os = reinterpret_cast<uint8_t*>(xs + CELL_BC * pc);   // [CELL_BC][pc] 1 = observed
+    const int leaf = block / chunks_per_leaf, chunk = block - leaf * chunks_per_leaf;
+    const int s0 = leaf_sptr[leaf], npairs = (leaf_sptr[leaf + 1] - s0) * d.C;
+    const int p0 = chunk * pc;
+    if (p0 >= npairs) return;                         // (whole workgroup) this leaf has fewer chunks
+    const int np = min(pc, npairs - p0);
+    const int tid = threadIdx.x;
+    const int pl = tid / d.K, k = tid - pl * d.K;     // this thread's pair and entry
+    const bool mine = pl < np;
+    const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K;
+    float n1 = 0.f, n2 = 0.f, den = 0.f, tot = 0.f;
+    for (int b0 = 0; b0 < d.B; b0 += CELL_BC) {
+        const int nb = min(CELL_BC, d.B - b0);
+        if (b0 > 0) __syncthreads();                  // readers of the previous pass are done
+        for (int i = tid; i < nb * d.K; i += 1024) Gs[i] = Gl[(size_t)b0 * d.K + i];
+        for (int i = tid; i < nb * np; i += 1024) {
+            const int bb = i / np, p = i - bb * np;
+            const int pair = p0 + p, v = pair / d.C, c = pair - v * d.C;
+            const int var = leaf_var[s0 + v];
+            xs[bb * pc + p] = x[((size_t)(b0 + bb) * d.D + var) * d.C + c];
+            uint8_t o = 1;
+            if (mask_mode == EINET_MASK_SHARED) o = mask[var];
+            if (mask_mode == EINET_MASK_PER_SAMPLE) o = mask[(size_t)(b0 + bb) * d.D + var];
+            os[bb * pc + p] = o;
+        }
+        __syncthreads();
+        if (mine) {
+#pragma unroll 4
+            for (int bb = 0; bb < nb; ++bb) {
+                const float p = Gs[bb * d.K + k];
+                const float xv = xs[bb * pc + pl];
+                const float pm = os[bb * pc + pl] ? p : 0.f;
+                tot += p;
+                den += pm;
+                n1 = fmaf(pm, xv, n1);
+                n2 = fmaf(pm * xv, xv, n2);
+            }
+        }
+    }
+    if (!mine) return;
+    const int pair = p0 + pl, v = pair / d.C, c = pair - v * d.C;
+    const int var = leaf_var[s0 + v], r = leaf_replica[leaf];
+    const size_t ph = phi_off + ((size_t)(var * d.C + c) * d.R + r) * d.T * d.K + k;
+    stats[ph] += n1;
+    if (d.T == 2) stats[ph + d.K] += n2;
+    if (c == 0) {
+        const size_t o = ((size_t)var * d.R + r) * d.K + k;
+        stats[den_off + o] += den;
+        stats[tot_off + o] += tot;
+    }
+}
+
 // Last launch of the top-down pass: leaf statistics in the first n_leaf_blocks workgroups, mixing
-// statistics in the others (item = idx / max_children, child = idx % max_children).
+// statistics in the others (item = idx / max_children, child = idx % max_children).  NCH = 0 selects the
+// kernel body for long scopes (chunks_per_leaf workgroups per leaf).
 template <int NCH>
 __global__ __launch_bounds__(1024) void k_tail_backward(
     int n_leaf_blocks, int max_children, const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var,
@@ -983,11 +1055,16 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
     float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const int32_t* __restrict__ m_node,
     const int32_t* __restrict__ m_kout, const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
     const int32_t* __restrict__ m_voff, const float* __restrict__ params, const float* __restrict__ A,
-    const double* __restrict__ Off, Dims d) {
+    const double* __restrict__ Off, const int32_t* __restrict__ leaf_sptr, const int32_t* __restrict__ leaf_var,
+    int chunks_per_leaf, Dims d) {
     const int blk = blockIdx.x;
     if (blk < n_leaf_blocks) {
-        leaf_backward_body<NCH>(blk, lv_leaf, lv_var, leaf_node, leaf_replica, n_lv, x, mask, mask_mode, G, stats,
-                                phi_off, den_off, tot_off, d);
+        if constexpr (NCH == 0)
+            leaf_backward_cells_body(blk, chunks_per_leaf, leaf_node, leaf_replica, leaf_sptr, leaf_var, x, mask,
+                                     mask_mode, G, stats, phi_off, den_off, tot_off, d);
+        else
+            leaf_backward_body<NCH>(blk, lv_leaf, lv_var, leaf_node, leaf_replica, n_lv, x, mask, mask_mode, G, stats,
+                                    phi_off, den_off, tot_off, d);
     } else {
         const int idx = blk - n_leaf_blocks;
         mixing_stats_body(idx / max_children, idx % max_children, m_node, m_kout, m_cptr, m_child, m_voff, params,
@@ -1574,26 +1651,39 @@ void launch_einsum_backward(const DevTables& t, int first, int count, bool accum
     }
 }
 
-void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_children, const float* x,
-                          const uint8_t* mask, int mask_mode, const float* params, const float* A, const double* Off,
-                          const float* G, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const Dims& d,
-                          hipStream_t s) {
+void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_scope, int n_mix, int max_children,
+                          const float* x, const uint8_t* mask, int mask_mode, const float* params, const float* A,
+                          const double* Off, const float* G, float* stats, int64_t phi_off, int64_t den_off,
+                          int64_t tot_off, const Dims& d, hipStream_t s) {
     const int total = n_lv * d.C * d.K;
-    const int nch = d.B >= 16 ? 4 : 1;
-    const int no = 1024 / nch;
     const bool categorical = d.family == EINET_LEAF_CATEGORICAL;
     if (categorical)     // indicator statistics: a histogram kernel of its own (at most 256 x 64 floats of LDS)
         hipLaunchKernelGGL(k_leaf_backward_categorical, dim3(n_lv * d.C), dim3(64), sizeof(float) * d.P * d.K, s,
                            t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, x, mask, mask_mode, G, stats, phi_off,
                            den_off, tot_off, d);
-    const int n_leaf_blocks = categorical ? 0 : (total + no - 1) / no;
+    // long scopes: posterior block and values through LDS; short ones: straight from memory
+    const int cell_chunks = (max_scope * d.C + cell_pairs_per_group(d.K) - 1) / cell_pairs_per_group(d.K);
+    // (with fewer than 64 such workgroups the chip is better filled by the element-wise kernel)
+    const bool cells = !categorical && max_scope * d.C >= 32 && n_leaves * cell_chunks >= 64;
+    const int nch = cells ? 0 : (d.B >= 16 ? 4 : 1);
+    const int chunks_per_leaf = cells ? cell_chunks : 1;
+    const int n_leaf_blocks = categorical ? 0 : (cells ? n_leaves * chunks_per_leaf : (total + 1024 / nch - 1) / (1024 / nch));
     const int blocks = n_leaf_blocks + n_mix * max_children;
     if (blocks == 0) return;
+    const size_t lds = cells ? cell_lds_bytes(d.K) : 0;
+    static bool attr_set = false;
+    if (cells && !attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_backward<0>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+        attr_set = true;
+    }
 #define EINET_LAUNCH(N)                                                                                              \
-    hipLaunchKernelGGL(k_tail_backward<N>, dim3(blocks), dim3(1024), 0, s, n_leaf_blocks, max_children > 0 ? max_children : 1, \
-                       t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, n_lv, x, mask, mask_mode, G, stats, phi_off, \
-                       den_off, tot_off, t.mix_node, t.mix_kout, t.mix_cptr, t.mix_child, t.mix_voff, params, A, Off, d)
-    if (nch == 4) EINET_LAUNCH(4);
+    hipLaunchKernelGGL(k_tail_backward<N>, dim3(blocks), dim3(1024), lds, s, n_leaf_blocks,                           \
+                       max_children > 0 ? max_children : 1, t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, n_lv, x, \
+                       mask, mask_mode, G, stats, phi_off, den_off, tot_off, t.mix_node, t.mix_kout, t.mix_cptr,      \
+                       t.mix_child, t.mix_voff, params, A, Off, t.leaf_sptr, t.leaf_var, chunks_per_leaf, d)
+    if (nch == 0) EINET_LAUNCH(0);
+    else if (nch == 4) EINET_LAUNCH(4);
     else EINET_LAUNCH(1);
 #undef EINET_LAUNCH
 }

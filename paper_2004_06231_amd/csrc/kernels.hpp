@@ -58,10 +58,10 @@ inline int bwd_groups_per_item(int count, int K) {
     return g < 1 ? 1 : (g > kq ? kq : g);
 }
 // leaf statistics and mixing statistics (independent of each other) in one launch
-void launch_tail_backward(const DevTables& t, int n_lv, int n_mix, int max_children, const float* x,
-                          const uint8_t* mask, int mask_mode, const float* params, const float* A, const double* Off,
-                          const float* G, float* stats, int64_t phi_off, int64_t den_off, int64_t tot_off,
-                          const Dims& d, hipStream_t s);
+void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_scope, int n_mix, int max_children,
+                          const float* x, const uint8_t* mask, int mask_mode, const float* params, const float* A,
+                          const double* Off, const float* G, float* stats, int64_t phi_off, int64_t den_off,
+                          int64_t tot_off, const Dims& d, hipStream_t s);
 // the whole M-step in one launch; the statistics of the first n_lazy_rows weight rows are left as they
 // are (the next E-step overwrites them); when no E-step has run since they were last consumed
 // (lazy_rows_are_zero) those rows count as zero and their weights are kept
