@@ -1,0 +1,37 @@
+// Shared by the HIP translation units: the data layout of the arenas and small device helpers.
+//
+// Activations live in a node-major arena A[node][b][k] (float32, log domain):
+// every region and every simple sum owns one dense [B][K] block, so a layer's
+// "gather" of left and right inputs (Sec. 3.3) is an index lookup.  A block does
+// not hold the log-densities themselves but their residuals against one offset
+// per (node, sample), Off[node][b] (float64):
+//     log-density[node][b][k] = Off[node][b] + A[node][b][k].
+// Leaves take their largest entry as offset; an einsum output takes the offsets of
+// its children plus the two shifts of Eq. 4, so that its residual is log S~ in
+// [log of the smallest weight, 0]; a mixing output takes the largest offset of its
+// children.  Log-densities of large scopes have magnitudes of 1e3..1e5, where a
+// float32 resolves 1e-4..1e-2; the residuals stay small, and the posteriors of the
+// top-down pass (exponentials of differences) keep full float32 precision.  The
+// posterior arena G has the same shape; Gp[2e+side][b][k] holds what einsum
+// item e sends down to its left (side 0) or right (side 1) child, and a child
+// sums the slots of its parents when it is processed: no atomics anywhere.
+#ifndef EINET_DEVICE_COMMON_HPP
+#define EINET_DEVICE_COMMON_HPP
+
+#include "kernels.hpp"
+
+#include <cmath>
+
+namespace einet_impl {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+}  // namespace einet_impl
+
+#endif

@@ -1,0 +1,245 @@
+// Bottom-up pass: einsum layers (Eq. 3-5) and mixing layers (App. B).
+#include "device_common.hpp"
+
+namespace einet_impl {
+
+namespace {
+
+// ------------------------------------------------------------------ einsum layer, forward
+// With eL = exp(L - a), eR = exp(R - a') (a, a' the row maxima; Eq. 4) the layer needs
+//     S~[b,k] = sum_i eL[b,i] * T[(k,i), b],   T[(k,i), b] = sum_j W[k,i,j] eR[b,j].
+// T is a dense GEMM (rows (k,i), columns b, contraction j) on v_mfma_f32_16x16x4_f32;
+// one MFMA tile holds 4 outputs k (one per 16-lane group) x 4 inputs i (one per
+// accumulator register), so the i-reduction of Eq. 4 is four in-lane FMAs per tile
+// and the K x K outer product of Sec. 3.2 is never formed.
+//
+// One workgroup per (einsum item, tile of 4 outputs k).  Its slice W[4 k][K][K] is
+// contiguous in memory; it is staged once in LDS, zero-padded to multiples of 4,
+// with row strides chosen so that the A-operand reads of a half-wave hit 32
+// distinct banks (i-stride = 8 mod 16, k-stride = 2 mod 32, lane groups read
+// consecutive j).  Every wave then takes tiles of 16 samples: eR (the B operand)
+// lives in registers, eL in a wave-private LDS tile, and each tile costs KQ*KQ
+// MFMAs (KQ = ceil(K/4)).
+template <int KQ>
+struct FwdLayout {
+    static constexpr int KP = 4 * KQ;
+    static constexpr int SJ = ((KP + 7) / 16) * 16 + 8;   // smallest value >= KP that is 8 mod 16
+    static constexpr int SK = KP * SJ + 2;
+    static constexpr int LDS_W = ((4 * SK + 3) / 4) * 4;  // W slice, rounded so the eL tiles stay 16-byte aligned
+    static constexpr int SE = KP + 4;                     // row stride of a wave's eL tile
+    static constexpr int LDS_FLOATS = LDS_W + 8 * 16 * SE;
+};
+
+template <int KQ>
+__global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __restrict__ e_left,
+                                                        const int32_t* __restrict__ e_right,
+                                                        const int32_t* __restrict__ e_out,
+                                                        const int32_t* __restrict__ e_kout,
+                                                        const int32_t* __restrict__ e_woff,
+                                                        const float* __restrict__ params, float* __restrict__ A,
+                                                        double* __restrict__ Off, float* __restrict__ amax,
+                                                        float* __restrict__ logp, int item0, int B, int K, int nkt) {
+    using LY = FwdLayout<KQ>;
+    constexpr int KP = LY::KP, SJ = LY::SJ, SK = LY::SK;
+    extern __shared__ float Wl[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int li = blockIdx.x / nkt, kt = blockIdx.x - li * nkt;
+    const int item = item0 + li;
+    const int kout = e_kout[li];
+    if (4 * kt >= kout) return;                        // root items have a single output entry
+    const float* Lp = A + (size_t)e_left[li] * B * K;
+    const float* Rp = A + (size_t)e_right[li] * B * K;
+    const float* W = params + e_woff[li];
+
+    const int c = lane & 15, g = lane >> 4;          // sample column of the tile, lane group
+    const int gm = c >> 2, rm = c & 3;               // as A-operand lane: row 4*gm+rm = (k = 4kt+gm, i = 4it+rm)
+    const int n_btiles = (B + 15) >> 4;
+    // stage W[4kt .. 4kt+3][.][.]
+    if ((K & 3) == 0) {
+        for (int q = tid; q < 4 * KP * KQ; q += blockDim.x) {
+            const int j4 = q % KQ, i = (q / KQ) % KP, kl = q / (KQ * KP);
+            const int k = 4 * kt + kl;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < kout && i < K) v = *reinterpret_cast<const float4*>(W + ((size_t)k * K + i) * K + 4 * j4);
+            float* dst = Wl + kl * SK + i * SJ + 4 * j4;
+            *reinterpret_cast<float2*>(dst) = make_float2(v.x, v.y);
+            *reinterpret_cast<float2*>(dst + 2) = make_float2(v.z, v.w);
+        }
+    } else {
+        for (int q = tid; q < 4 * KP * KP; q += blockDim.x) {
+            const int j = q % KP, i = (q / KP) % KP, kl = q / (KP * KP);
+            const int k = 4 * kt + kl;
+            float v = 0.f;
+            if (k < kout && i < K && j < K) v = W[((size_t)k * K + i) * K + j];
+            Wl[kl * SK + i * SJ + j] = v;
+        }
+    }
+    __syncthreads();
+
+    const float* wl = Wl + gm * SK + rm * SJ + g;    // + it*4*SJ + 4*s : contraction index j = 4s + g
+    float* elw = Wl + LY::LDS_W + wave * (16 * LY::SE);   // this wave's eL tile [16][SE]
+    for (int bt0 = 0; bt0 < n_btiles; bt0 += nwaves) {
+        const int bt = bt0 + wave;
+        const int b = bt * 16 + c;
+        const bool ok = bt < n_btiles && b < B;
+        // lane (c, g) holds entries 4s+g of row b of both inputs
+        float er[KQ], el[KQ];
+        float mr = -INFINITY, ml = -INFINITY;
+#pragma unroll
+        for (int s = 0; s < KQ; ++s) {
+            const int j = 4 * s + g;
+            const bool in = ok && j < K;
+            er[s] = in ? Rp[(size_t)b * K + j] : -INFINITY;
+            el[s] = in ? Lp[(size_t)b * K + j] : -INFINITY;
+            mr = fmaxf(mr, er[s]);
+            ml = fmaxf(ml, el[s]);
+        }
+        mr = fmaxf(mr, __shfl_xor(mr, 16, 64));
+        mr = fmaxf(mr, __shfl_xor(mr, 32, 64));
+        ml = fmaxf(ml, __shfl_xor(ml, 16, 64));
+        ml = fmaxf(ml, __shfl_xor(ml, 32, 64));
+        if (mr == -INFINITY) mr = 0.f;               // an all-zero input vector: exp(-inf) = 0, no NaN
+        if (ml == -INFINITY) ml = 0.f;
+        __syncthreads();                             // previous tile's eL reads are done
+#pragma unroll
+        for (int s = 0; s < KQ; ++s) {
+            er[s] = __expf(er[s] - mr);              // stays in registers: the B operand
+            elw[c * LY::SE + 4 * s + g] = __expf(el[s] - ml);
+        }
+        __syncthreads();
+        float sacc = 0.f;
+#pragma unroll
+        for (int it = 0; it < KQ; ++it) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KQ; ++s)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wl[it * 4 * SJ + 4 * s], er[s], acc, 0, 0, 0);
+            const float4 e4 = *reinterpret_cast<const float4*>(elw + c * LY::SE + 4 * it);
+            sacc += acc[0] * e4.x + acc[1] * e4.y + acc[2] * e4.z + acc[3] * e4.w;
+        }
+        const int k = 4 * kt + g;
+        const float res = __logf(sacc);                // residual against Off[left] + Off[right] + ml + mr
+        if (ok && k < kout) A[((size_t)e_out[li] * B + b) * K + k] = res;
+        if (ok && kt == 0 && g == 0) {
+            const double off = Off[(size_t)e_left[li] * B + b] + Off[(size_t)e_right[li] * B + b] + (double)ml + (double)mr;
+            Off[(size_t)e_out[li] * B + b] = off;
+            if (logp && e_out[li] == 0) logp[b] = (float)(off + (double)res);   // node 0: the root region, one entry
+            amax[((size_t)item * 2) * B + b] = ml;     // the shifts, kept for the top-down pass
+            amax[((size_t)item * 2 + 1) * B + b] = mr;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ mixing layer, forward (App. B)
+// Offset of the output: the largest offset of the children (their residuals are at most 0, so no term
+// exceeds its weight); residual: log sum_c v[c] exp((Off[c] - Off[out]) + A[c]).
+__global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32_t* __restrict__ m_kout,
+                                 const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
+                                 const int32_t* __restrict__ m_voff, const float* __restrict__ params,
+                                 float* __restrict__ A, double* __restrict__ Off, float* __restrict__ logp, int B,
+                                 int K) {
+    const int item = blockIdx.x;
+    const int kout = m_kout[item];
+    const int e = blockIdx.y * blockDim.x + threadIdx.x;
+    if (e >= B * kout) return;
+    const int b = e / kout, k = e - b * kout;
+    const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
+    const float* v = params + m_voff[item] + (size_t)k * nc;
+    double m = -INFINITY;
+    for (int c = 0; c < nc; ++c) m = fmax(m, Off[(size_t)m_child[c0 + c] * B + b]);
+    float s = 0.f;
+    for (int c = 0; c < nc; ++c) {
+        const size_t row = (size_t)m_child[c0 + c] * B + b;
+        s += v[c] * expf((float)(Off[row] - m) + A[row * K + k]);
+    }
+    const float res = logf(s);
+    const size_t row = (size_t)m_node[item] * B + b;
+    A[row * K + k] = res;
+    if (k == 0) {
+        Off[row] = m;
+        if (logp && m_node[item] == 0) logp[b] = (float)(m + (double)res);   // node 0: the root region, one entry
+    }
+}
+
+// The same for regions with many partitions (the root over R replicas of random binary trees): one wave per
+// output element, the children spread over the lanes, maximum and sum by wave reductions.
+__global__ __launch_bounds__(256) void k_mixing_forward_many(
+    const int32_t* __restrict__ m_node, const int32_t* __restrict__ m_kout, const int32_t* __restrict__ m_cptr,
+    const int32_t* __restrict__ m_child, const int32_t* __restrict__ m_voff, const float* __restrict__ params,
+    float* __restrict__ A, double* __restrict__ Off, float* __restrict__ logp, int B, int K) {
+    const int item = blockIdx.x;
+    const int kout = m_kout[item];
+    const int lane = threadIdx.x & 63;
+    const int e = blockIdx.y * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (e >= B * kout) return;                       // whole waves leave
+    const int b = e / kout, k = e - b * kout;
+    const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
+    const float* v = params + m_voff[item] + (size_t)k * nc;
+    double m = -INFINITY;
+    for (int c = lane; c < nc; c += 64) m = fmax(m, Off[(size_t)m_child[c0 + c] * B + b]);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = fmax(m, __shfl_xor(m, o, 64));
+    float s = 0.f;
+    for (int c = lane; c < nc; c += 64) {
+        const size_t row = (size_t)m_child[c0 + c] * B + b;
+        s += v[c] * expf((float)(Off[row] - m) + A[row * K + k]);
+    }
+    s = wave_sum(s);
+    if (lane == 0) {
+        const float res = logf(s);
+        const size_t row = (size_t)m_node[item] * B + b;
+        A[row * K + k] = res;
+        if (k == 0) {
+            Off[row] = m;
+            if (logp && m_node[item] == 0) logp[b] = (float)(m + (double)res);
+        }
+    }
+}
+
+}  // namespace
+
+template <int KQ>
+static void launch_einsum_forward_kq(const DevTables& t, int first, int count, const float* params, float* A,
+                                     double* Off, float* amax, float* logp, const Dims& d, hipStream_t s) {
+    const int nkt = (d.K + 3) / 4;
+    const int n_btiles = (d.B + 15) / 16;
+    const int nw = n_btiles < 8 ? n_btiles : 8;
+    const size_t lds = sizeof(float) * FwdLayout<KQ>::LDS_FLOATS;
+    static bool attr_set = false;
+    if (lds > 64 * 1024 && !attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_forward<KQ>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_einsum_forward<KQ>, dim3(count * nkt), dim3(64 * nw), lds, s, t.ein_left + first,
+                       t.ein_right + first, t.ein_out + first, t.ein_kout + first, t.ein_woff + first, params, A, Off,
+                       amax, logp, first, d.B, d.K, nkt);
+}
+
+void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
+                           float* amax, float* logp, const Dims& d, hipStream_t s) {
+    switch ((d.K + 3) / 4) {
+#define EINET_CASE(J) \
+    case J: launch_einsum_forward_kq<J>(t, first, count, params, A, Off, amax, logp, d, s); break;
+        EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
+        EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
+        EINET_CASE(16)
+#undef EINET_CASE
+    }
+}
+
+void launch_mixing_forward(const DevTables& t, int first, int count, int max_children, const float* params, float* A,
+                           double* Off, float* logp, const Dims& d, hipStream_t s) {
+    if (count == 0) return;
+    if (max_children >= 8) {                         // a wave per output element, children over the lanes
+        dim3 grid(count, (d.B * d.K + 3) / 4);
+        hipLaunchKernelGGL(k_mixing_forward_many, grid, dim3(256), 0, s, t.mix_node + first, t.mix_kout + first,
+                           t.mix_cptr + first, t.mix_child, t.mix_voff + first, params, A, Off, logp, d.B, d.K);
+        return;
+    }
+    dim3 grid(count, (d.B * d.K + 255) / 256);
+    hipLaunchKernelGGL(k_mixing_forward, grid, dim3(256), 0, s, t.mix_node + first, t.mix_kout + first,
+                       t.mix_cptr + first, t.mix_child, t.mix_voff + first, params, A, Off, logp, d.B, d.K);
+}
+
+}  // namespace einet_impl

@@ -1,0 +1,280 @@
+// End of the top-down pass: statistics of the mixing weights and of the leaves (Eq. 6-7).
+#include "device_common.hpp"
+
+namespace einet_impl {
+
+namespace {
+
+// Statistics of the mixing weights (App. B, Eq. 6): Nv[s,k,c] += v[s,k,c] * sum_b G[s][b,k] * S^c[b,k] / S[b,k].
+// One workgroup per (mixing item, child); a reduction over the batch through LDS.  Runs in the same
+// launch as the leaf statistics (k_tail_backward): the two are independent.
+__device__ __forceinline__ void mixing_stats_body(int item, int c, const int32_t* __restrict__ m_node,
+                                                  const int32_t* __restrict__ m_kout,
+                                                  const int32_t* __restrict__ m_cptr,
+                                                  const int32_t* __restrict__ m_child,
+                                                  const int32_t* __restrict__ m_voff, const float* __restrict__ params,
+                                                  float* __restrict__ stats, const float* __restrict__ A,
+                                                  const double* __restrict__ Off, const float* __restrict__ G, int B,
+                                                  int K) {
+    __shared__ float red[1024];
+    const int tid = threadIdx.x;
+    const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
+    if (c >= nc) return;
+    const int kout = m_kout[item];
+    const int nbl = 1024 / kout, k = tid % kout, bl = tid / kout;
+    const float* As = A + (size_t)m_node[item] * B * K;
+    const float* Ac = A + (size_t)m_child[c0 + c] * B * K;
+    const float* Gs = G + (size_t)m_node[item] * B * K;
+    const double* Os = Off + (size_t)m_node[item] * B;
+    const double* Oc = Off + (size_t)m_child[c0 + c] * B;
+    float part = 0.f;
+    if (bl < nbl)
+        for (int b = bl; b < B; b += nbl) {
+            const size_t o = (size_t)b * K + k;
+            const float g = Gs[o];
+            if (g != 0.f) part += g * expf((float)(Oc[b] - Os[b]) + Ac[o] - As[o]);
+        }
+    red[tid] = part;
+    __syncthreads();
+    if (tid < kout) {
+        float tot = 0.f;
+        for (int l = 0; l < nbl; ++l) tot += red[l * kout + tid];
+        const size_t o = (size_t)m_voff[item] + (size_t)tid * nc + c;
+        stats[o] += params[o] * tot;
+    }
+}
+
+// ------------------------------------------------------------------ top-down pass, leaves
+// Posterior-weighted sufficient statistics (Eq. 6-7).  A workgroup of 1024 threads
+// owns 1024/NCH consecutive statistics entries (leaf variable, channel, k); its NCH
+// parts each walk every NCH-th sample and the partial sums meet in LDS.
+template <int NCH>
+__device__ __forceinline__ void leaf_backward_body(
+    int block, const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var, const int32_t* __restrict__ leaf_node,
+    const int32_t* __restrict__ leaf_replica, int n_lv, const float* __restrict__ x,
+    const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, float* __restrict__ stats,
+    int64_t phi_off, int64_t den_off, int64_t tot_off, Dims d) {
+    constexpr int NO = 1024 / NCH;
+    __shared__ float red[NCH][4][NO];
+    const int lo = threadIdx.x % NO, part_id = threadIdx.x / NO;
+    const int idx = block * NO + lo;
+    const bool valid = idx < n_lv * d.C * d.K;
+    const int k = valid ? idx % d.K : 0, c = valid ? (idx / d.K) % d.C : 0, e = valid ? idx / (d.K * d.C) : 0;
+    const int leaf = lv_leaf[e], var = lv_var[e], r = leaf_replica[leaf];
+    const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K + k;
+    const float* xp = x + (size_t)var * d.C + c;
+    const bool shared_obs = mask_mode != EINET_MASK_SHARED || mask[var] != 0;
+    float n1 = 0.f, n2 = 0.f, den = 0.f, tot = 0.f;
+#pragma unroll 4
+    for (int b = part_id; b < d.B; b += NCH) {
+        const float p = Gl[(size_t)b * d.K];
+        bool obs = shared_obs;
+        if (mask_mode == EINET_MASK_PER_SAMPLE) obs = mask[(size_t)b * d.D + var] != 0;
+        const float xv = xp[(size_t)b * d.D * d.C];
+        const float pm = obs ? p : 0.f;
+        tot += p;
+        den += pm;
+        n1 = fmaf(pm, xv, n1);
+        n2 = fmaf(pm * xv, xv, n2);
+    }
+    red[part_id][0][lo] = n1;
+    red[part_id][1][lo] = n2;
+    red[part_id][2][lo] = den;
+    red[part_id][3][lo] = tot;
+    __syncthreads();
+    if (part_id || !valid) return;
+#pragma unroll
+    for (int q = 1; q < NCH; ++q) {
+        n1 += red[q][0][lo];
+        n2 += red[q][1][lo];
+        den += red[q][2][lo];
+        tot += red[q][3][lo];
+    }
+    const size_t ph = phi_off + ((size_t)(var * d.C + c) * d.R + r) * d.T * d.K + k;
+    stats[ph] += n1;
+    if (d.T == 2) stats[ph + d.K] += n2;
+    if (c == 0) {
+        const size_t o = ((size_t)var * d.R + r) * d.K + k;
+        stats[den_off + o] += den;
+        stats[tot_off + o] += tot;
+    }
+}
+
+// Categorical leaves: the sufficient statistic is the indicator of the value, so the posterior mass of a
+// sample goes to one of V rows.  One wave per (leaf variable, channel), lane k owns column k of a V x K
+// histogram in LDS and walks the samples; no two lanes touch the same cell.
+__global__ __launch_bounds__(64) void k_leaf_backward_categorical(
+    const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var, const int32_t* __restrict__ leaf_node,
+    const int32_t* __restrict__ leaf_replica, const float* __restrict__ x, const uint8_t* __restrict__ mask,
+    int mask_mode, const float* __restrict__ G, float* __restrict__ stats, int64_t phi_off, int64_t den_off,
+    int64_t tot_off, Dims d) {
+    extern __shared__ float hist[];                   // [V][K]
+    const int e = blockIdx.x / d.C, c = blockIdx.x - e * d.C, k = threadIdx.x;
+    const int leaf = lv_leaf[e], var = lv_var[e], r = leaf_replica[leaf];
+    const int V = d.P;
+    if (k < d.K)
+        for (int v = 0; v < V; ++v) hist[v * d.K + k] = 0.f;
+    const bool shared_obs = mask_mode != EINET_MASK_SHARED || mask[var] != 0;
+    float den = 0.f, tot = 0.f;
+    if (k < d.K) {
+        const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K + k;
+        for (int b = 0; b < d.B; ++b) {
+            const float p = Gl[(size_t)b * d.K];
+            bool obs = shared_obs;
+            if (mask_mode == EINET_MASK_PER_SAMPLE) obs = mask[(size_t)b * d.D + var] != 0;
+            const int v = min(max((int)x[((size_t)b * d.D + var) * d.C + c], 0), V - 1);
+            tot += p;
+            if (obs) {
+                den += p;
+                hist[v * d.K + k] += p;
+            }
+        }
+        const size_t ph = phi_off + ((size_t)(var * d.C + c) * d.R + r) * V * d.K + k;
+        for (int v = 0; v < V; ++v) stats[ph + (size_t)v * d.K] += hist[v * d.K + k];
+        if (c == 0) {
+            const size_t o = ((size_t)var * d.R + r) * d.K + k;
+            stats[den_off + o] += den;
+            stats[tot_off + o] += tot;
+        }
+    }
+}
+
+// The same statistics for leaves with long scopes (image cells).  A workgroup takes one leaf and a chunk of
+// its (variable, channel) pairs; per pass over 128 samples the leaf's posterior block G[leaf][b][.] (contiguous
+// in memory) and the pairs' values are copied to LDS, then thread (pair, k) walks the samples out of LDS.  The
+// walk of the kernel above waits a full memory latency for every few samples; here it waits for LDS.
+constexpr int CELL_BC = 128;                          // samples per pass
+__host__ __device__ inline int cell_pairs_per_group(int K) { return 1024 / K < 64 ? 1024 / K : 64; }
+__host__ __device__ inline size_t cell_lds_bytes(int K) {
+    return sizeof(float) * (size_t)CELL_BC * (K + cell_pairs_per_group(K)) + (size_t)CELL_BC * cell_pairs_per_group(K);
+}
+
+__device__ __forceinline__ void leaf_backward_cells_body(
+    int block, int chunks_per_leaf, const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica,
+    const int32_t* __restrict__ leaf_sptr, const int32_t* __restrict__ leaf_var, const float* __restrict__ x,
+    const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, float* __restrict__ stats,
+    int64_t phi_off, int64_t den_off, int64_t tot_off, Dims d) {
+    extern __shared__ float cell_lds[];
+    const int pc = cell_pairs_per_group(d.K);
+    float* Gs = cell_lds;                             // [CELL_BC][K]
+    float* xs = Gs + CELL_BC * d.K;                   // [CELL_BC][pc]
+    uint8_t* os = reinterpret_cast<uint8_t*>(xs + CELL_BC * pc);   // [CELL_BC][pc] 1 = observed
+    const int leaf = block / chunks_per_leaf, chunk = block - leaf * chunks_per_leaf;
+    const int s0 = leaf_sptr[leaf], npairs = (leaf_sptr[leaf + 1] - s0) * d.C;
+    const int p0 = chunk * pc;
+    if (p0 >= npairs) return;                         // (whole workgroup) this leaf has fewer chunks
+    const int np = min(pc, npairs - p0);
+    const int tid = threadIdx.x;
+    const int pl = tid / d.K, k = tid - pl * d.K;     // this thread's pair and entry
+    const bool mine = pl < np;
+    const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K;
+    float n1 = 0.f, n2 = 0.f, den = 0.f, tot = 0.f;
+    for (int b0 = 0; b0 < d.B; b0 += CELL_BC) {
+        const int nb = min(CELL_BC, d.B - b0);
+        if (b0 > 0) __syncthreads();                  // readers of the previous pass are done
+        for (int i = tid; i < nb * d.K; i += 1024) Gs[i] = Gl[(size_t)b0 * d.K + i];
+        for (int i = tid; i < nb * np; i += 1024) {
+            const int bb = i / np, p = i - bb * np;
+            const int pair = p0 + p, v = pair / d.C, c = pair - v * d.C;
+            const int var = leaf_var[s0 + v];
+            xs[bb * pc + p] = x[((size_t)(b0 + bb) * d.D + var) * d.C + c];
+            uint8_t o = 1;
+            if (mask_mode == EINET_MASK_SHARED) o = mask[var];
+            if (mask_mode == EINET_MASK_PER_SAMPLE) o = mask[(size_t)(b0 + bb) * d.D + var];
+            os[bb * pc + p] = o;
+        }
+        __syncthreads();
+        if (mine) {
+#pragma unroll 4
+            for (int bb = 0; bb < nb; ++bb) {
+                const float p = Gs[bb * d.K + k];
+                const float xv = xs[bb * pc + pl];
+                const float pm = os[bb * pc + pl] ? p : 0.f;
+                tot += p;
+                den += pm;
+                n1 = fmaf(pm, xv, n1);
+                n2 = fmaf(pm * xv, xv, n2);
+            }
+        }
+    }
+    if (!mine) return;
+    const int pair = p0 + pl, v = pair / d.C, c = pair - v * d.C;
+    const int var = leaf_var[s0 + v], r = leaf_replica[leaf];
+    const size_t ph = phi_off + ((size_t)(var * d.C + c) * d.R + r) * d.T * d.K + k;
+    stats[ph] += n1;
+    if (d.T == 2) stats[ph + d.K] += n2;
+    if (c == 0) {
+        const size_t o = ((size_t)var * d.R + r) * d.K + k;
+        stats[den_off + o] += den;
+        stats[tot_off + o] += tot;
+    }
+}
+
+// Last launch of the top-down pass: leaf statistics in the first n_leaf_blocks workgroups, mixing
+// statistics in the others (item = idx / max_children, child = idx % max_children).  NCH = 0 selects the
+// kernel body for long scopes (chunks_per_leaf workgroups per leaf).
+template <int NCH>
+__global__ __launch_bounds__(1024) void k_tail_backward(
+    int n_leaf_blocks, int max_children, const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var,
+    const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica, int n_lv,
+    const float* __restrict__ x, const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G,
+    float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const int32_t* __restrict__ m_node,
+    const int32_t* __restrict__ m_kout, const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
+    const int32_t* __restrict__ m_voff, const float* __restrict__ params, const float* __restrict__ A,
+    const double* __restrict__ Off, const int32_t* __restrict__ leaf_sptr, const int32_t* __restrict__ leaf_var,
+    int chunks_per_leaf, Dims d) {
+    const int blk = blockIdx.x;
+    if (blk < n_leaf_blocks) {
+        if constexpr (NCH == 0)
+            leaf_backward_cells_body(blk, chunks_per_leaf, leaf_node, leaf_replica, leaf_sptr, leaf_var, x, mask,
+                                     mask_mode, G, stats, phi_off, den_off, tot_off, d);
+        else
+            leaf_backward_body<NCH>(blk, lv_leaf, lv_var, leaf_node, leaf_replica, n_lv, x, mask, mask_mode, G, stats,
+                                    phi_off, den_off, tot_off, d);
+    } else {
+        const int idx = blk - n_leaf_blocks;
+        mixing_stats_body(idx / max_children, idx % max_children, m_node, m_kout, m_cptr, m_child, m_voff, params,
+                          stats, A, Off, G, d.B, d.K);
+    }
+}
+
+}  // namespace
+
+void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_scope, int n_mix, int max_children,
+                          const float* x, const uint8_t* mask, int mask_mode, const float* params, const float* A,
+                          const double* Off, const float* G, float* stats, int64_t phi_off, int64_t den_off,
+                          int64_t tot_off, const Dims& d, hipStream_t s) {
+    const int total = n_lv * d.C * d.K;
+    const bool categorical = d.family == EINET_LEAF_CATEGORICAL;
+    if (categorical)     // indicator statistics: a histogram kernel of its own (at most 256 x 64 floats of LDS)
+        hipLaunchKernelGGL(k_leaf_backward_categorical, dim3(n_lv * d.C), dim3(64), sizeof(float) * d.P * d.K, s,
+                           t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, x, mask, mask_mode, G, stats, phi_off,
+                           den_off, tot_off, d);
+    // long scopes: posterior block and values through LDS; short ones: straight from memory
+    const int cell_chunks = (max_scope * d.C + cell_pairs_per_group(d.K) - 1) / cell_pairs_per_group(d.K);
+    // (with fewer than 64 such workgroups the chip is better filled by the element-wise kernel)
+    const bool cells = !categorical && max_scope * d.C >= 32 && n_leaves * cell_chunks >= 64;
+    const int nch = cells ? 0 : (d.B >= 16 ? 4 : 1);
+    const int chunks_per_leaf = cells ? cell_chunks : 1;
+    const int n_leaf_blocks = categorical ? 0 : (cells ? n_leaves * chunks_per_leaf : (total + 1024 / nch - 1) / (1024 / nch));
+    const int blocks = n_leaf_blocks + n_mix * max_children;
+    if (blocks == 0) return;
+    const size_t lds = cells ? cell_lds_bytes(d.K) : 0;
+    static bool attr_set = false;
+    if (cells && !attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_backward<0>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+        attr_set = true;
+    }
+#define EINET_LAUNCH(N)                                                                                              \
+    hipLaunchKernelGGL(k_tail_backward<N>, dim3(blocks), dim3(1024), lds, s, n_leaf_blocks,                           \
+                       max_children > 0 ? max_children : 1, t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, n_lv, x, \
+                       mask, mask_mode, G, stats, phi_off, den_off, tot_off, t.mix_node, t.mix_kout, t.mix_cptr,      \
+                       t.mix_child, t.mix_voff, params, A, Off, t.leaf_sptr, t.leaf_var, chunks_per_leaf, d)
+    if (nch == 0) EINET_LAUNCH(0);
+    else if (nch == 4) EINET_LAUNCH(4);
+    else EINET_LAUNCH(1);
+#undef EINET_LAUNCH
+}
+
+}  // namespace einet_impl
