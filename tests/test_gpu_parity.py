@@ -112,6 +112,8 @@ SMALL = [
     (dict(kind="pd", H=6, W=6, deltas=[2]), 6, 3, GAUSSIAN, 19),
     (dict(kind="pd", H=8, W=4, deltas=[4, 2]), 9, 1, BERNOULLI, 40),
     (dict(kind="pd", H=4, W=12, deltas=[4], axes=2), 17, 2, GAUSSIAN, 16),   # vertical cuts only
+    (dict(kind="pd", H=7, W=5, deltas=[3]), 5, 1, BERNOULLI, 23),            # cells of 9, 6, 3, 2 and 1 pixels
+    (dict(kind="pd", H=36, W=40, deltas=[8]), 8, 3, GAUSSIAN, 50),           # 25 image cells of 64 or 32 pixels
 ]
 
 
