@@ -142,7 +142,8 @@ const char* einet_last_error(const einet_t* h);
 
 /* Sizes the caller must allocate on the device: n_params and n_stats in
  * float32 elements, workspace in bytes (index tables, derived leaf constants,
- * activation and posterior arenas for max_batch samples).  All outputs: host. */
+ * activation arena with its per-sample offsets and posterior arenas for
+ * max_batch samples).  All outputs: host. */
 int einet_sizes(const einet_t* h, size_t* n_params, size_t* n_stats, size_t* workspace_bytes);
 
 /* Fills *view (host) with pointers into the handle's host tables. */
@@ -157,8 +158,9 @@ int einet_structure(const einet_t* h, einet_structure_view* view);
 int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_dev, void* stream);
 
 /* Recomputes what the kernels derive from the parameters (per leaf entry:
- * log p, log(1-p), or mean, -1/(2 var), -log(2 pi var)/2; Sec. 3.4) after the
- * caller has written the parameter buffer.  einet_em_update does it itself. */
+ * log p, log(1-p), or mean, -1/(2 var), -log(2 pi var)/2, or the logarithms
+ * of a categorical table; Sec. 3.4) after the caller has written the parameter
+ * buffer.  einet_em_update and einet_init_params do it themselves. */
 int einet_refresh(einet_t* h, void* stream);
 
 /* Random initial parameters, written into the bound parameter buffer (the
@@ -173,7 +175,6 @@ int einet_refresh(einet_t* h, void* stream);
  * refreshes the derived leaf constants.  Errors: EINET_ERR_NOT_BOUND,
  * EINET_ERR_INVALID_ARG (leaf_lo > leaf_hi; probabilities outside (0,1)). */
 int einet_init_params(einet_t* h, uint64_t seed, float leaf_lo, float leaf_hi, void* stream);
-
 
 /* log P(x) per sample: leaf layer (Sec. 3.4), einsum layers with the
  * log-einsum-exp stabilisation (Eq. 4-5), mixing layers (App. B).
@@ -212,8 +213,8 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
  * adding (saves one pass over the largest buffer), so the Nw part of the
  * caller's buffer is unspecified between this call and that one (a second
  * einet_em_update in that interval keeps the einsum weights, as for zero
- * statistics); use einet_em_reset to have zeros in memory.  Also refreshes the derived leaf
- * constants. */
+ * statistics); use einet_em_reset to have zeros in memory.  Also refreshes the
+ * derived leaf constants. */
 int einet_em_update(einet_t* h, float step, float min_var, float max_var, float w_floor, void* stream);
 
 /* Zeroes the whole statistics buffer in memory. */
