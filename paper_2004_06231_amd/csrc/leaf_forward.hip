@@ -1,6 +1,8 @@
 // Leaf layer (Sec. 3.4): constants derived from the expectation parameters, log-densities of the leaves.
 #include "device_common.hpp"
 
+#include <type_traits>
+
 namespace einet_impl {
 
 namespace {
@@ -173,20 +175,33 @@ __global__ __launch_bounds__(TPB) void k_leaf_forward(const int32_t* __restrict_
     }
 }
 
-// Leaf layer for leaves with long scopes (image cells): a workgroup of 1024 threads takes one leaf
-// and LEAF_BS samples.  The samples' values are staged in LDS with coalesced reads of x; thread
-// (k, part) loads the constants of a few (variable, channel) pairs once and applies them to all
-// staged samples from registers; the parts (float64) meet in LDS, then offset and residuals as above.
-constexpr int LEAF_BS = 8;
+// Leaf layer for leaves with scopes of more than LEAF_CHUNK (variable, channel) pairs (the strips of a
+// 128x128x3 image): a workgroup of 1024 threads takes one leaf and BS samples.  The scope is walked in chunks of at most LEAF_CHUNK (variable, channel) pairs: the
+// samples' values of a chunk are staged in LDS with coalesced reads of x; thread (k, part) loads the constants
+// of a few pairs once and applies them to all staged samples from registers.  A part sums only a handful of
+// terms per chunk, so float32 is enough there; across chunks and across parts the sums (magnitude 1e2..1e5)
+// are float64.  Then offset and residuals as above.
+constexpr int LEAF_RED = 8;   // the partial sums of the parts are [nparts][LEAF_RED][K] float32 in LDS
+constexpr int LEAF_CHUNK = 384;
+constexpr int LEAF_U = 4;      // pairs whose constants a thread requests together
 
-// bytes of LDS: the finished entries (float64) first, then the partial sums of the parts, the values and the
-// observation flags.  A part sums only a handful of terms, so float32 is enough for it; the sum over the
-// parts, of magnitude 1e2..1e4, is taken in float64.
-__host__ __device__ inline size_t leaf_wide_lds_bytes(int max_scope, int C, int K) {
-    return sizeof(double) * ((size_t)LEAF_BS * K) +
-           sizeof(float) * ((size_t)(1024 / K) * LEAF_BS * K + (size_t)LEAF_BS * max_scope * (C + 1));
+// variables per chunk (whole variables, so that a chunk holds all channels of each)
+__host__ __device__ inline int leaf_chunk_vars(int max_scope, int C) {
+    const int v = LEAF_CHUNK / C;
+    return max_scope < v ? max_scope : (v < 1 ? 1 : v);
+}
+// bytes of LDS for BS samples per workgroup: the finished entries (float64), the partial sums of the parts
+// ([nparts][LEAF_RED][K] float32, or the same bytes as [nparts][LEAF_RED/2][K] float64 for leaves of several
+// chunks, reduced four samples at a time), the values, the observation flags and the chunk's variable numbers
+__host__ __device__ inline size_t leaf_wide_lds_bytes(int max_scope, int C, int K, int BS) {
+    return sizeof(double) * ((size_t)BS * K) +
+           sizeof(float) * ((size_t)(1024 / K) * LEAF_RED * K + (size_t)(BS * (C + 1) + 1) * leaf_chunk_vars(max_scope, C));
 }
 
+// MASKED: some variables may be marginalised (else the flags are neither staged nor read).
+// BS: samples per workgroup (8: with 16 there are half as many workgroups, each twice as long, and the layer
+// of a 128x128x3 image, four leaves, took twice the time).
+template <bool MASKED, int BS>
 __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __restrict__ leaf_node,
                                                             const int32_t* __restrict__ leaf_replica,
                                                             const int32_t* __restrict__ leaf_sptr,
@@ -197,20 +212,198 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
                                                             const int32_t* __restrict__ logc, float* __restrict__ A,
                                                             double* __restrict__ Off, int max_scope, Dims d) {
     extern __shared__ double lds_d[];
-    const int leaf = blockIdx.x, b0 = blockIdx.y * LEAF_BS, tid = threadIdx.x;
-    const int nbs = min(LEAF_BS, d.B - b0);
+    const int leaf = blockIdx.x, b0 = blockIdx.y * BS, tid = threadIdx.x;
+    const int nbs = min(BS, d.B - b0);
+    const int r = leaf_replica[leaf];
+    const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0;
+    const int nparts = 1024 / d.K;
+    const int vch = leaf_chunk_vars(max_scope, d.C);      // variables per chunk
+    double* val = lds_d;                                  // [BS][K] finished entries
+    float* red = reinterpret_cast<float*>(val + BS * d.K);   // partial sums of the parts
+    double* redd = reinterpret_cast<double*>(red);        // the same memory as [nparts][LEAF_RED/2][K] float64
+    float* xs = red + (size_t)nparts * LEAF_RED * d.K;    // [BS][vch*C] values of the chunk
+    float* ob = xs + (size_t)BS * vch * d.C;         // [BS][vch] 1 = observed
+    int* vs = reinterpret_cast<int*>(ob + (size_t)BS * vch);   // [vch] variables of the chunk
+    const int k = tid % d.K, part = tid / d.K;
+    const size_t tstride = (size_t)d.TD * d.K;
+    const bool base = d.family == EINET_LEAF_BINOMIAL && k == 0;   // this thread also sums the binomial coefficients
+    typedef double acc_t;
+    acc_t acc[BS], hacc[BS];
+#pragma unroll
+    for (int b = 0; b < BS; ++b) acc[b] = hacc[b] = 0;
+    for (int v0 = 0; v0 < nv; v0 += vch) {
+        const int cv = min(vch, nv - v0), np = cv * d.C;  // variables and pairs of this chunk
+        if (v0 > 0) __syncthreads();                      // readers of the previous chunk are done
+        // the variable numbers of the chunk come from LDS below: one memory latency less in front of every load
+        // that depends on them, chunk after chunk
+        for (int v = tid; v < cv; v += 1024) vs[v] = leaf_var[s0 + v0 + v];
+        __syncthreads();
+        auto var_of = [&](int v) { return vs[v]; };
+        for (int idx = tid; idx < BS * np; idx += 1024) {
+            const int b = idx / np, p = idx - b * np, v = p / d.C, c = p - v * d.C;
+            xs[idx] = b < nbs ? x[((size_t)(b0 + b) * d.D + var_of(v)) * d.C + c] : 0.f;
+        }
+        for (int idx = tid; MASKED && idx < BS * cv; idx += 1024) {
+            const int b = idx / cv, v = idx - b * cv;
+            float o = 1.f;
+            if (b < nbs && mask_mode == EINET_MASK_SHARED) o = mask[var_of(v)] ? 1.f : 0.f;
+            if (b < nbs && mask_mode == EINET_MASK_PER_SAMPLE)
+                o = mask[(size_t)(b0 + b) * d.D + var_of(v)] ? 1.f : 0.f;
+            ob[idx] = o;
+        }
+        __syncthreads();
+        if (part < nparts) {
+            // LEAF_U pairs per round: their constants are requested together (one memory latency per round, not
+            // per pair), their terms are summed in float32 and the group goes to the float64 sums
+            for (int p0 = part; p0 < np; p0 += LEAF_U * nparts) {
+                const float* th[LEAF_U];
+                int pp[LEAF_U], vv[LEAF_U];
+                bool in[LEAF_U];
+#pragma unroll
+                for (int u = 0; u < LEAF_U; ++u) {
+                    const int p = p0 + u * nparts;
+                    in[u] = p < np;
+                    pp[u] = in[u] ? p : part;
+                    vv[u] = pp[u] / d.C;
+                    const int c = pp[u] - vv[u] * d.C;
+                    th[u] = theta + ((size_t)(var_of(vv[u]) * d.C + c) * d.R + r) * tstride + k;
+                }
+                float t[BS], ht[BS];
+#pragma unroll
+                for (int b = 0; b < BS; ++b) t[b] = ht[b] = 0.f;
+                if (d.family == EINET_LEAF_GAUSSIAN) {
+                    float mu[LEAF_U], c1[LEAF_U], c0[LEAF_U];
+#pragma unroll
+                    for (int u = 0; u < LEAF_U; ++u) {
+                        mu[u] = th[u][0];
+                        c1[u] = in[u] ? th[u][d.K] : 0.f;     // a pair that does not exist adds 0
+                        c0[u] = in[u] ? th[u][2 * d.K] : 0.f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < LEAF_U; ++u)
+                        if (in[u])
+#pragma unroll
+                        for (int b = 0; b < BS; ++b) {
+                            const float diff = xs[b * np + pp[u]] - mu[u];
+                            const float term = fmaf(c1[u] * diff, diff, c0[u]);
+                            t[b] += MASKED ? ob[b * cv + vv[u]] * term : term;
+                        }
+                } else if (d.family == EINET_LEAF_CATEGORICAL) {
+#pragma unroll
+                    for (int u = 0; u < LEAF_U; ++u)
+                        if (in[u])
+#pragma unroll
+                        for (int b = 0; b < BS; ++b) {
+                            const float term = leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + pp[u]], th[u], d.K, d.P);
+                            t[b] += MASKED ? ob[b * cv + vv[u]] * term : term;
+                        }
+                } else {
+                    float lp[LEAF_U], l1p[LEAF_U];
+                    const float nf = (float)d.P;
+#pragma unroll
+                    for (int u = 0; u < LEAF_U; ++u) {
+                        lp[u] = in[u] ? th[u][0] : 0.f;
+                        l1p[u] = in[u] ? th[u][d.K] : 0.f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < LEAF_U; ++u)
+                        if (in[u])
+#pragma unroll
+                        for (int b = 0; b < BS; ++b) {
+                            const float xv = xs[b * np + pp[u]];
+                            const float term = xv * lp[u] + (nf - xv) * l1p[u];
+                            t[b] += MASKED ? ob[b * cv + vv[u]] * term : term;
+                            if (base)
+                                ht[b] += MASKED ? ob[b * cv + vv[u]] * leaf_base(logc, xv, d.P) : leaf_base(logc, xv, d.P);
+                        }
+                }
+#pragma unroll
+                for (int b = 0; b < BS; ++b) {
+                    acc[b] += (acc_t)t[b];
+                    hacc[b] += (acc_t)ht[b];
+                }
+            }
+        }
+    }
+    const bool fin = tid < BS * d.K;
+    const int fb = fin ? tid / d.K : 0, kk = tid - fb * d.K;
+    const int nact = min(nparts, min(nv, vch) * d.C);     // parts beyond the pairs of a chunk hold zeros
+    double sum = 0.0, h = 0.0;
+    {
+        // float64 partial sums, half of the samples at a time (the same LDS bytes)
+        constexpr int HB = LEAF_RED / 2;
+#pragma unroll
+        for (int half = 0; half < BS / HB; ++half) {
+            __syncthreads();                              // the chunk loop, or the previous half, is done with LDS
+            if (part < nparts) {
+#pragma unroll
+                for (int b = 0; b < HB; ++b) redd[(part * HB + b) * d.K + k] = acc[half * HB + b];
+            }
+            __syncthreads();
+            if (fin && fb / HB == half)
+                for (int q = 0; q < nact; ++q) sum += redd[(q * HB + (fb - half * HB)) * d.K + kk];
+            if (d.family == EINET_LEAF_BINOMIAL) {
+                __syncthreads();
+                if (base && part < nparts) {
+#pragma unroll
+                    for (int b = 0; b < HB; ++b) redd[(part * HB + b) * d.K] = hacc[half * HB + b];
+                }
+                __syncthreads();
+                if (fin && kk == 0 && fb / HB == half)
+                    for (int q = 0; q < nact; ++q) h += redd[(q * HB + (fb - half * HB)) * d.K];
+            }
+        }
+    }
+    if (fin) val[fb * d.K + kk] = sum;
+    __syncthreads();
+    if (fin && fb < nbs) {
+        double m = -INFINITY;
+        for (int q = 0; q < d.K; ++q) m = fmax(m, val[fb * d.K + q]);
+        if (m == -INFINITY) m = 0.0;
+        const size_t row = (size_t)leaf_node[leaf] * d.B + b0 + fb;
+        A[row * d.K + kk] = (float)(sum - m);
+        if (kk == 0) Off[row] = m + h;
+    }
+}
+
+// The same for leaves whose scope fits one chunk (the image cells of the benchmark configurations): one
+// staging step, float32 sums per part (a part sums only a handful of terms), float64 across the parts.  A
+// workgroup of 1024 threads takes one leaf and LEAF_RED samples.  The samples' values are staged in LDS with coalesced reads of x; thread
+// (k, part) loads the constants of a few (variable, channel) pairs once and applies them to all
+// staged samples from registers; the parts (float64) meet in LDS, then offset and residuals as above.
+
+// bytes of LDS: the finished entries (float64) first, then the partial sums of the parts, the values and the
+// observation flags.  A part sums only a handful of terms, so float32 is enough for it; the sum over the
+// parts, of magnitude 1e2..1e4, is taken in float64.
+__host__ __device__ inline size_t leaf_wide1_lds_bytes(int max_scope, int C, int K) {
+    return sizeof(double) * ((size_t)LEAF_RED * K) +
+           sizeof(float) * ((size_t)(1024 / K) * LEAF_RED * K + (size_t)LEAF_RED * max_scope * (C + 1));
+}
+
+__global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __restrict__ leaf_node,
+                                                            const int32_t* __restrict__ leaf_replica,
+                                                            const int32_t* __restrict__ leaf_sptr,
+                                                            const int32_t* __restrict__ leaf_var,
+                                                            const float* __restrict__ x,
+                                                            const uint8_t* __restrict__ mask, int mask_mode,
+                                                            const float* __restrict__ theta,
+                                                            const int32_t* __restrict__ logc, float* __restrict__ A,
+                                                            double* __restrict__ Off, int max_scope, Dims d) {
+    extern __shared__ double lds_d[];
+    const int leaf = blockIdx.x, b0 = blockIdx.y * LEAF_RED, tid = threadIdx.x;
+    const int nbs = min(LEAF_RED, d.B - b0);
     const int r = leaf_replica[leaf];
     const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0, np = nv * d.C;
     const int nparts = 1024 / d.K;
-    double* val = lds_d;                                  // [LEAF_BS][K] finished entries
-    float* red = reinterpret_cast<float*>(val + LEAF_BS * d.K);   // [nparts][LEAF_BS][K]
-    float* xs = red + (size_t)nparts * LEAF_BS * d.K;     // [LEAF_BS][np] values, zeros where unused
-    float* ob = xs + (size_t)LEAF_BS * max_scope * d.C;   // [LEAF_BS][nv] 1 = observed
-    for (int idx = tid; idx < LEAF_BS * np; idx += 1024) {
+    double* val = lds_d;                                  // [LEAF_RED][K] finished entries
+    float* red = reinterpret_cast<float*>(val + LEAF_RED * d.K);   // [nparts][LEAF_RED][K]
+    float* xs = red + (size_t)nparts * LEAF_RED * d.K;     // [LEAF_RED][np] values, zeros where unused
+    float* ob = xs + (size_t)LEAF_RED * max_scope * d.C;   // [LEAF_RED][nv] 1 = observed
+    for (int idx = tid; idx < LEAF_RED * np; idx += 1024) {
         const int b = idx / np, p = idx - b * np, v = p / d.C, c = p - v * d.C;
         xs[idx] = b < nbs ? x[((size_t)(b0 + b) * d.D + leaf_var[s0 + v]) * d.C + c] : 0.f;
     }
-    for (int idx = tid; idx < LEAF_BS * nv; idx += 1024) {
+    for (int idx = tid; idx < LEAF_RED * nv; idx += 1024) {
         const int b = idx / nv, v = idx - b * nv;
         float o = 1.f;
         if (b < nbs && mask_mode == EINET_MASK_SHARED) o = mask[leaf_var[s0 + v]] ? 1.f : 0.f;
@@ -221,9 +414,9 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
     const int k = tid % d.K, part = tid / d.K;
     const size_t tstride = (size_t)d.TD * d.K;
     const bool base = d.family == EINET_LEAF_BINOMIAL && k == 0;   // this thread also sums the binomial coefficients
-    float acc[LEAF_BS], hacc[LEAF_BS];
+    float acc[LEAF_RED], hacc[LEAF_RED];
 #pragma unroll
-    for (int b = 0; b < LEAF_BS; ++b) acc[b] = hacc[b] = 0.f;
+    for (int b = 0; b < LEAF_RED; ++b) acc[b] = hacc[b] = 0.f;
     if (part < nparts) {
         for (int p = part; p < np; p += nparts) {
             const int v = p / d.C, c = p - v * d.C;
@@ -231,18 +424,18 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
             if (d.family == EINET_LEAF_GAUSSIAN) {
                 const float mu = th[0], c1 = th[d.K], c0 = th[2 * d.K];
 #pragma unroll
-                for (int b = 0; b < LEAF_BS; ++b) {
+                for (int b = 0; b < LEAF_RED; ++b) {
                     const float diff = xs[b * np + p] - mu;
                     acc[b] += ob[b * nv + v] * fmaf(c1 * diff, diff, c0);
                 }
             } else if (d.family == EINET_LEAF_CATEGORICAL) {
 #pragma unroll
-                for (int b = 0; b < LEAF_BS; ++b)
+                for (int b = 0; b < LEAF_RED; ++b)
                     acc[b] += ob[b * nv + v] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + p], th, d.K, d.P);
             } else {
                 const float lp = th[0], l1p = th[d.K], nf = (float)d.P;
 #pragma unroll
-                for (int b = 0; b < LEAF_BS; ++b) {
+                for (int b = 0; b < LEAF_RED; ++b) {
                     const float xv = xs[b * np + p];
                     acc[b] += ob[b * nv + v] * (xv * lp + (nf - xv) * l1p);
                     if (base) hacc[b] += ob[b * nv + v] * leaf_base(logc, xv, d.P);
@@ -250,21 +443,21 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
             }
         }
 #pragma unroll
-        for (int b = 0; b < LEAF_BS; ++b) red[(part * LEAF_BS + b) * d.K + k] = acc[b];
+        for (int b = 0; b < LEAF_RED; ++b) red[(part * LEAF_RED + b) * d.K + k] = acc[b];
     }
     __syncthreads();
-    const bool fin = tid < LEAF_BS * d.K;
+    const bool fin = tid < LEAF_RED * d.K;
     const int fb = fin ? tid / d.K : 0, kk = tid - fb * d.K;
     const int nact = min(nparts, np);                // parts beyond the number of pairs hold zeros
     double sum = 0.0;
     if (fin) {
-        for (int q = 0; q < nact; ++q) sum += (double)red[(q * LEAF_BS + fb) * d.K + kk];
+        for (int q = 0; q < nact; ++q) sum += (double)red[(q * LEAF_RED + fb) * d.K + kk];
         val[fb * d.K + kk] = sum;
     }
     __syncthreads();
     if (base && part < nparts) {                     // (after the barrier: the sums above have been read)
 #pragma unroll
-        for (int b = 0; b < LEAF_BS; ++b) red[(part * LEAF_BS + b) * d.K] = hacc[b];
+        for (int b = 0; b < LEAF_RED; ++b) red[(part * LEAF_RED + b) * d.K] = hacc[b];
     }
     if (d.family == EINET_LEAF_BINOMIAL) __syncthreads();
     if (fin && fb < nbs) {
@@ -276,7 +469,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
         if (kk == 0) {
             double h = 0.0;
             if (d.family == EINET_LEAF_BINOMIAL)
-                for (int q = 0; q < nact; ++q) h += (double)red[(q * LEAF_BS + fb) * d.K];
+                for (int q = 0; q < nact; ++q) h += (double)red[(q * LEAF_RED + fb) * d.K];
             Off[row] = m + h;
         }
     }
@@ -293,16 +486,27 @@ void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream
 void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const float* x, const uint8_t* mask,
                          int mask_mode, const float* theta, float* A, double* Off, const Dims& d, hipStream_t s) {
     const int pairs = max_scope * d.C;
-    if (pairs >= 32 && pairs * d.K >= 768) {
-        // long scopes (at least three quarters of the 1024/K parts of a workgroup get a (variable, channel) pair): one
-        // workgroup per (leaf, LEAF_BS samples), values staged in LDS
-        const size_t lds = leaf_wide_lds_bytes(max_scope, d.C, d.K);
-        if (lds <= 64 * 1024) {
-            dim3 grid(n_leaves, (d.B + LEAF_BS - 1) / LEAF_BS);
-            hipLaunchKernelGGL(k_leaf_forward_wide, grid, dim3(1024), lds, s, t.leaf_node, t.leaf_replica, t.leaf_sptr,
-                               t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off, max_scope, d);
+    if (pairs >= 32 && pairs * d.K >= 768 && leaf_wide_lds_bytes(max_scope, d.C, d.K, 8) <= 64 * 1024) {
+        // long scopes (at least three quarters of the 1024/K parts of a workgroup get a (variable, channel) pair):
+        // one workgroup per (leaf, 8 or 16 samples), values staged in LDS chunk by chunk
+        const bool multi = max_scope > leaf_chunk_vars(max_scope, d.C), masked = mask_mode != EINET_MASK_NONE;
+        dim3 grid(n_leaves, (d.B + LEAF_RED - 1) / LEAF_RED);
+        if (!multi) {
+            hipLaunchKernelGGL(k_leaf_forward_wide1, grid, dim3(1024), leaf_wide1_lds_bytes(max_scope, d.C, d.K), s,
+                               t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, x, mask, mask_mode, theta,
+                               t.leaf_logc, A, Off, max_scope, d);
             return;
         }
+        const size_t lds = leaf_wide_lds_bytes(max_scope, d.C, d.K, LEAF_RED);
+        if (masked)
+            hipLaunchKernelGGL((k_leaf_forward_wide<true, LEAF_RED>), grid, dim3(1024), lds, s, t.leaf_node,
+                               t.leaf_replica, t.leaf_sptr, t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off,
+                               max_scope, d);
+        else
+            hipLaunchKernelGGL((k_leaf_forward_wide<false, LEAF_RED>), grid, dim3(1024), lds, s, t.leaf_node,
+                               t.leaf_replica, t.leaf_sptr, t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off,
+                               max_scope, d);
+        return;
     }
     // parts per workgroup: enough that each thread walks only a few variables of the scope
     const int nch = pairs >= 96 ? 16 : (pairs >= 24 ? 4 : 1);

@@ -145,38 +145,49 @@ __global__ __launch_bounds__(64) void k_leaf_backward_categorical(
 // walk of the kernel above waits a full memory latency for every few samples; here it waits for LDS.
 constexpr int CELL_BC = 128;                          // samples per pass
 __host__ __device__ inline int cell_pairs_per_group(int K) { return 1024 / K < 64 ? 1024 / K : 64; }
-__host__ __device__ inline size_t cell_lds_bytes(int K) {
-    return sizeof(float) * (size_t)CELL_BC * (K + cell_pairs_per_group(K)) + (size_t)CELL_BC * cell_pairs_per_group(K);
+// PPT: pairs per thread.  With four, a workgroup covers four times the pairs (for image rows of three channels
+// 400 contiguous bytes of x per sample instead of 100) and the posterior block is copied a quarter as often.
+__host__ __device__ inline size_t cell_lds_bytes(int K, int PPT) {
+    return sizeof(float) * ((size_t)CELL_BC * (K + cell_pairs_per_group(K) * PPT) + cell_pairs_per_group(K) * PPT + 2) +
+           (size_t)CELL_BC * cell_pairs_per_group(K) * PPT;
 }
 
+template <int PPT>
 __device__ __forceinline__ void leaf_backward_cells_body(
     int block, int chunks_per_leaf, const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica,
     const int32_t* __restrict__ leaf_sptr, const int32_t* __restrict__ leaf_var, const float* __restrict__ x,
     const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, float* __restrict__ stats,
     int64_t phi_off, int64_t den_off, int64_t tot_off, Dims d) {
     extern __shared__ float cell_lds[];
-    const int pc = cell_pairs_per_group(d.K);
+    const int pc = cell_pairs_per_group(d.K) * PPT;   // pairs per workgroup
     float* Gs = cell_lds;                             // [CELL_BC][K]
     float* xs = Gs + CELL_BC * d.K;                   // [CELL_BC][pc]
-    uint8_t* os = reinterpret_cast<uint8_t*>(xs + CELL_BC * pc);   // [CELL_BC][pc] 1 = observed
+    int* vsl = reinterpret_cast<int*>(xs + CELL_BC * pc);          // [pc + 2] variables the chunk's pairs belong to
+    uint8_t* os = reinterpret_cast<uint8_t*>(vsl + pc + 2);        // [CELL_BC][pc] 1 = observed
     const int leaf = block / chunks_per_leaf, chunk = block - leaf * chunks_per_leaf;
     const int s0 = leaf_sptr[leaf], npairs = (leaf_sptr[leaf + 1] - s0) * d.C;
     const int p0 = chunk * pc;
     if (p0 >= npairs) return;                         // (whole workgroup) this leaf has fewer chunks
     const int np = min(pc, npairs - p0);
     const int tid = threadIdx.x;
-    const int pl = tid / d.K, k = tid - pl * d.K;     // this thread's pair and entry
-    const bool mine = pl < np;
+    const int pl = (tid / d.K) * PPT, k = tid % d.K;  // this thread's first pair and its entry
     const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K;
-    float n1 = 0.f, n2 = 0.f, den = 0.f, tot = 0.f;
+    // the variable numbers go to LDS once, so that the loads of the values do not each wait for one
+    const int vfirst = p0 / d.C, vcount = (p0 + np - 1) / d.C - vfirst + 1;
+    for (int j = tid; j < vcount; j += 1024) vsl[j] = leaf_var[s0 + vfirst + j];
+    __syncthreads();
+    float n1[PPT], n2[PPT], den[PPT], tot = 0.f;
+#pragma unroll
+    for (int q = 0; q < PPT; ++q) n1[q] = n2[q] = den[q] = 0.f;
     for (int b0 = 0; b0 < d.B; b0 += CELL_BC) {
         const int nb = min(CELL_BC, d.B - b0);
         if (b0 > 0) __syncthreads();                  // readers of the previous pass are done
         for (int i = tid; i < nb * d.K; i += 1024) Gs[i] = Gl[(size_t)b0 * d.K + i];
+#pragma unroll 4
         for (int i = tid; i < nb * np; i += 1024) {
             const int bb = i / np, p = i - bb * np;
             const int pair = p0 + p, v = pair / d.C, c = pair - v * d.C;
-            const int var = leaf_var[s0 + v];
+            const int var = vsl[v - vfirst];
             xs[bb * pc + p] = x[((size_t)(b0 + bb) * d.D + var) * d.C + c];
             uint8_t o = 1;
             if (mask_mode == EINET_MASK_SHARED) o = mask[var];
@@ -184,36 +195,44 @@ __device__ __forceinline__ void leaf_backward_cells_body(
             os[bb * pc + p] = o;
         }
         __syncthreads();
-        if (mine) {
+        if (pl < np) {
 #pragma unroll 4
             for (int bb = 0; bb < nb; ++bb) {
                 const float p = Gs[bb * d.K + k];
-                const float xv = xs[bb * pc + pl];
-                const float pm = os[bb * pc + pl] ? p : 0.f;
                 tot += p;
-                den += pm;
-                n1 = fmaf(pm, xv, n1);
-                n2 = fmaf(pm * xv, xv, n2);
+#pragma unroll
+                for (int q = 0; q < PPT; ++q) {
+                    // (pairs beyond np read stale LDS values; their sums are never written)
+                    const float xv = xs[bb * pc + pl + q];
+                    const float pm = os[bb * pc + pl + q] ? p : 0.f;
+                    den[q] += pm;
+                    n1[q] = fmaf(pm, xv, n1[q]);
+                    n2[q] = fmaf(pm * xv, xv, n2[q]);
+                }
             }
         }
     }
-    if (!mine) return;
-    const int pair = p0 + pl, v = pair / d.C, c = pair - v * d.C;
-    const int var = leaf_var[s0 + v], r = leaf_replica[leaf];
-    const size_t ph = phi_off + ((size_t)(var * d.C + c) * d.R + r) * d.T * d.K + k;
-    stats[ph] += n1;
-    if (d.T == 2) stats[ph + d.K] += n2;
-    if (c == 0) {
-        const size_t o = ((size_t)var * d.R + r) * d.K + k;
-        stats[den_off + o] += den;
-        stats[tot_off + o] += tot;
+    const int r = leaf_replica[leaf];
+#pragma unroll
+    for (int q = 0; q < PPT; ++q) {
+        if (pl + q >= np) continue;
+        const int pair = p0 + pl + q, v = pair / d.C, c = pair - v * d.C;
+        const int var = vsl[v - vfirst];
+        const size_t ph = phi_off + ((size_t)(var * d.C + c) * d.R + r) * d.T * d.K + k;
+        stats[ph] += n1[q];
+        if (d.T == 2) stats[ph + d.K] += n2[q];
+        if (c == 0) {
+            const size_t o = ((size_t)var * d.R + r) * d.K + k;
+            stats[den_off + o] += den[q];
+            stats[tot_off + o] += tot;
+        }
     }
 }
 
 // Last launch of the top-down pass: leaf statistics in the first n_leaf_blocks workgroups, mixing
 // statistics in the others (item = idx / max_children, child = idx % max_children).  NCH = 0 selects the
-// kernel body for long scopes (chunks_per_leaf workgroups per leaf).
-template <int NCH>
+// kernel body for long scopes (chunks_per_leaf workgroups per leaf, PPT pairs per thread).
+template <int NCH, int PPT>
 __global__ __launch_bounds__(1024) void k_tail_backward(
     int n_leaf_blocks, int max_children, const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var,
     const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica, int n_lv,
@@ -226,8 +245,8 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
     const int blk = blockIdx.x;
     if (blk < n_leaf_blocks) {
         if constexpr (NCH == 0)
-            leaf_backward_cells_body(blk, chunks_per_leaf, leaf_node, leaf_replica, leaf_sptr, leaf_var, x, mask,
-                                     mask_mode, G, stats, phi_off, den_off, tot_off, d);
+            leaf_backward_cells_body<PPT>(blk, chunks_per_leaf, leaf_node, leaf_replica, leaf_sptr, leaf_var, x, mask,
+                                          mask_mode, G, stats, phi_off, den_off, tot_off, d);
         else
             leaf_backward_body<NCH>(blk, lv_leaf, lv_var, leaf_node, leaf_replica, n_lv, x, mask, mask_mode, G, stats,
                                     phi_off, den_off, tot_off, d);
@@ -251,29 +270,35 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
                            t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, x, mask, mask_mode, G, stats, phi_off,
                            den_off, tot_off, d);
     // long scopes: posterior block and values through LDS; short ones: straight from memory
-    const int cell_chunks = (max_scope * d.C + cell_pairs_per_group(d.K) - 1) / cell_pairs_per_group(d.K);
+    const int pc1 = cell_pairs_per_group(d.K);
+    const int chunks1 = (max_scope * d.C + pc1 - 1) / pc1;
     // (with fewer than 64 such workgroups the chip is better filled by the element-wise kernel)
-    const bool cells = !categorical && max_scope * d.C >= 32 && n_leaves * cell_chunks >= 64;
+    const bool cells = !categorical && max_scope * d.C >= 32 && n_leaves * chunks1 >= 64;
+    // four pairs per thread when there would be more than a thousand workgroups (and the values still fit LDS)
+    const int ppt = cells && n_leaves * chunks1 >= 1024 && pc1 * 4 <= 128 ? 4 : 1;
     const int nch = cells ? 0 : (d.B >= 16 ? 4 : 1);
-    const int chunks_per_leaf = cells ? cell_chunks : 1;
+    const int chunks_per_leaf = cells ? (max_scope * d.C + pc1 * ppt - 1) / (pc1 * ppt) : 1;
     const int n_leaf_blocks = categorical ? 0 : (cells ? n_leaves * chunks_per_leaf : (total + 1024 / nch - 1) / (1024 / nch));
     const int blocks = n_leaf_blocks + n_mix * max_children;
     if (blocks == 0) return;
-    const size_t lds = cells ? cell_lds_bytes(d.K) : 0;
+    const size_t lds = cells ? cell_lds_bytes(d.K, ppt) : 0;
     static bool attr_set = false;
     if (cells && !attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_backward<0>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_backward<0, 1>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_backward<0, 4>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
         attr_set = true;
     }
-#define EINET_LAUNCH(N)                                                                                              \
-    hipLaunchKernelGGL(k_tail_backward<N>, dim3(blocks), dim3(1024), lds, s, n_leaf_blocks,                           \
+#define EINET_LAUNCH(N, P)                                                                                           \
+    hipLaunchKernelGGL((k_tail_backward<N, P>), dim3(blocks), dim3(1024), lds, s, n_leaf_blocks,                      \
                        max_children > 0 ? max_children : 1, t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, n_lv, x, \
                        mask, mask_mode, G, stats, phi_off, den_off, tot_off, t.mix_node, t.mix_kout, t.mix_cptr,      \
                        t.mix_child, t.mix_voff, params, A, Off, t.leaf_sptr, t.leaf_var, chunks_per_leaf, d)
-    if (nch == 0) EINET_LAUNCH(0);
-    else if (nch == 4) EINET_LAUNCH(4);
-    else EINET_LAUNCH(1);
+    if (nch == 0 && ppt == 4) EINET_LAUNCH(0, 4);
+    else if (nch == 0) EINET_LAUNCH(0, 1);
+    else if (nch == 4) EINET_LAUNCH(4, 1);
+    else EINET_LAUNCH(1, 1);
 #undef EINET_LAUNCH
 }
 
