@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--workload", type=int, default=WORKLOAD, help="configuration to time (1-5); the default is the headline")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="batch size instead of the configuration's own (for batch-scaling tables; not the headline)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; sharding over the batch with one all-reduce of the "
@@ -117,7 +119,7 @@ def main():
     wl = args.workload
     cfg = workloads.get_config(wl)
     seed = workloads.config_seed(wl)
-    K, C, fam, B = cfg["K"], cfg["channels"], cfg["family"], cfg["B"]
+    K, C, fam, B = cfg["K"], cfg["channels"], cfg["family"], args.batch or cfg["B"]
     m = P.EiNet(cfg["structure"], K, C, fam, B, seed).bind("cuda:0")
     st = m.structure()
     D, R, T = st["num_vars"], st["num_replica"], st["T"]
@@ -215,7 +217,7 @@ def main():
                     frac=round(achieved / PEAK_HBM_GBS, 4))
     roof.update(kernel=dom, avg_launch_us=round(avg_launch_s * 1e6, 2), launches_per_step=n_launch,
                 algorithmic_flop_per_step=flop, algorithmic_bytes_per_step=byts,
-                traffic=MEASURED_TRAFFIC.get((wl, dom)),
+                traffic=MEASURED_TRAFFIC.get((wl, dom)) if B == cfg["B"] else None,
                 timing="hip events around each launch, separate pass of the same steps")
 
     out = {

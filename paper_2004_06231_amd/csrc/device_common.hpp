@@ -26,6 +26,14 @@ namespace einet_impl {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// Workgroups of a launch are handed to the 8 XCDs round-robin by blockIdx.x, and every XCD has an L2 of its own.
+// This renumbering gives each XCD a contiguous range of work items, so that neighbouring items (the workgroups
+// of one partition, which read the same child rows) meet in one L2.  It is a bijection on [0, gridDim.x).
+__device__ __forceinline__ int xcd_contiguous_block() {
+    const int n = gridDim.x, x = blockIdx.x & 7, q = n >> 3, r = n & 7;
+    return x * q + min(x, r) + (blockIdx.x >> 3);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -76,14 +76,22 @@ struct BwdLayout {
 template <int KQ, int NU>
 __device__ __forceinline__ void bwd_gemm1(floatx4* acc1, const float* const* qcol, const float* const* rcol,
                                           const float* elcol, int rg) {
-#pragma unroll 2
+    // operands of the next four samples are requested before the MFMAs of the current four are issued
+    float4 e = *reinterpret_cast<const float4*>(elcol);
+    float4 qa[NU], rb[NU];
+#pragma unroll
+    for (int q = 0; q < NU; ++q) {
+        qa[q] = *reinterpret_cast<const float4*>(qcol[q]);
+        rb[q] = *reinterpret_cast<const float4*>(rcol[q]);
+    }
     for (int s = 0; s < rg; s += 4) {
-        const float4 e = *reinterpret_cast<const float4*>(elcol + s);
-        float4 qa[NU], rb[NU];
+        const int sn = min(s + 4, rg - 4);           // the last round reads its own operands again
+        const float4 en = *reinterpret_cast<const float4*>(elcol + sn);
+        float4 qn[NU], rn[NU];
 #pragma unroll
         for (int q = 0; q < NU; ++q) {
-            qa[q] = *reinterpret_cast<const float4*>(qcol[q] + s);
-            rb[q] = *reinterpret_cast<const float4*>(rcol[q] + s);
+            qn[q] = *reinterpret_cast<const float4*>(qcol[q] + sn);
+            rn[q] = *reinterpret_cast<const float4*>(rcol[q] + sn);
         }
 #pragma unroll
         for (int q = 0; q < NU; ++q) acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[q].x * e.x, rb[q].x, acc1[q], 0, 0, 0);
@@ -93,6 +101,12 @@ __device__ __forceinline__ void bwd_gemm1(floatx4* acc1, const float* const* qco
         for (int q = 0; q < NU; ++q) acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[q].z * e.z, rb[q].z, acc1[q], 0, 0, 0);
 #pragma unroll
         for (int q = 0; q < NU; ++q) acc1[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[q].w * e.w, rb[q].w, acc1[q], 0, 0, 0);
+        e = en;
+#pragma unroll
+        for (int q = 0; q < NU; ++q) {
+            qa[q] = qn[q];
+            rb[q] = rn[q];
+        }
     }
 }
 
@@ -113,7 +127,8 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     float* sL = lds + LY::OFF_L;
     float* sG = lds + LY::OFF_G;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int li = blockIdx.x / ngroups, grp = blockIdx.x - li * ngroups;
+    const int vb = xcd_contiguous_block();
+    const int li = vb / ngroups, grp = vb - li * ngroups;
     const int it0 = grp * KQ / ngroups, it1 = (grp + 1) * KQ / ngroups;     // this workgroup's slices
     const bool multi = it1 - it0 > 1;   // several slices: their shares of Gp_right are summed in LDS first
     const int item = item0 + li;
@@ -195,29 +210,69 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     }
     float* Nw = stats + wbase;
 
-    // staging of eR and Q: thread t owns row t/4 of the pass and a quarter of its columns
+    // staging of eR and Q
     const int srow = tid >> 2, sq = tid & 3;
-    float vw[KQ];
-#pragma unroll
-    for (int u = 0; u < KQ; ++u) {
-        const int k = sq * KQ + u;
-        vw[u] = (voff >= 0 && k < kout) ? params[voff + k * vstr] : 1.f;
-    }
+    constexpr int NF = (BC * KQ + 511) / 512;      // float4 of a [BC][K] block per thread
 
     for (int b0 = 0; b0 < B; b0 += BC) {
         const int nb = min(BC, B - b0);
         const int rg = (((nb + 3) >> 2) + 3) & ~3;         // samples per lane group in GEMM-1, multiple of 4
         const bool rok = srow < nb;
         const int ro = (b0 + min(srow, nb - 1)) * K;       // a valid row even for the idle tail threads
-        const float al = aL[b0 + min(srow, nb - 1)], ar = aR[b0 + min(srow, nb - 1)];
-        const float dd = (float)(Oo[b0 + min(srow, nb - 1)] - Os[b0 + min(srow, nb - 1)]);
+        const float al = aL[b0 + min(srow, nb - 1)];
         __syncthreads();                                   // readers of the previous pass are done
-        {
+        if constexpr (VEC) {
+            // the [nb][K] blocks are contiguous: 16-byte loads, consecutive threads consecutive addresses
+            float4 r4[NF], g4[NF], a4[NF], v4[NF];
+            float arn[NF], ddn[NF];
+#pragma unroll
+            for (int n = 0; n < NF; ++n) {
+                const int f = min(tid + 512 * n, nb * KQ - 1);
+                const int row = f / KQ, k4 = f - row * KQ;
+                r4[n] = *reinterpret_cast<const float4*>(Rp + (size_t)(b0 + row) * K + 4 * k4);
+                g4[n] = *reinterpret_cast<const float4*>(Gs + (size_t)(b0 + row) * K + 4 * k4);
+                a4[n] = *reinterpret_cast<const float4*>(As + (size_t)(b0 + row) * K + 4 * k4);
+                arn[n] = aR[b0 + row];
+                ddn[n] = (float)(Oo[b0 + row] - Os[b0 + row]);
+                v4[n] = make_float4(1.f, 1.f, 1.f, 1.f);
+                if (voff >= 0) {
+                    v4[n].x = params[voff + min(4 * k4 + 0, kout - 1) * vstr];
+                    v4[n].y = params[voff + min(4 * k4 + 1, kout - 1) * vstr];
+                    v4[n].z = params[voff + min(4 * k4 + 2, kout - 1) * vstr];
+                    v4[n].w = params[voff + min(4 * k4 + 3, kout - 1) * vstr];
+                }
+            }
+#pragma unroll
+            for (int n = 0; n < NF; ++n) {
+                const int f = tid + 512 * n;
+                if (f < BC * KQ) {
+                    const int row = f / KQ, k4 = f - row * KQ;
+                    const bool in = row < nb;
+                    const float rr[4] = {r4[n].x, r4[n].y, r4[n].z, r4[n].w};
+                    const float gg[4] = {g4[n].x, g4[n].y, g4[n].z, g4[n].w};
+                    const float aa[4] = {a4[n].x, a4[n].y, a4[n].z, a4[n].w};
+                    const float vv[4] = {v4[n].x, v4[n].y, v4[n].z, v4[n].w};
+#pragma unroll
+                    for (int c4 = 0; c4 < 4; ++c4) {
+                        const int k = 4 * k4 + c4;
+                        const float e = __expf(rr[c4] - arn[n]);
+                        const float q = gg[c4] * vv[c4] * __expf(ddn[n] - aa[c4]);
+                        sR[k * ST + row] = in ? e : 0.f;
+                        sQ[k * ST + row] = (in && k < kout && gg[c4] != 0.f) ? q : 0.f;
+                    }
+                }
+            }
+            for (int j = KP + sq; j < 16 * LY::NJ; j += 4) sR[j * ST + srow] = 0.f;   // rows beyond the padded K
+            if (multi && LY::LDS_ACC)
+                for (int u = 0; u < KQ; ++u) sG[srow * KP + sq * KQ + u] = 0.f;
+        } else {
+            const float ar = aR[b0 + min(srow, nb - 1)];
+            const float dd = (float)(Oo[b0 + min(srow, nb - 1)] - Os[b0 + min(srow, nb - 1)]);
             float rv[KQ], gv[KQ], av[KQ];
 #pragma unroll
             for (int u = 0; u < KQ; ++u) {
                 const int k = sq * KQ + u;
-                const int kc = VEC ? k : min(k, K - 1);
+                const int kc = min(k, K - 1);
                 rv[u] = Rp[ro + kc];
                 gv[u] = Gs[ro + min(kc, kout - 1)];
                 av[u] = As[ro + min(kc, kout - 1)];
@@ -225,9 +280,10 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
 #pragma unroll
             for (int u = 0; u < KQ; ++u) {
                 const int k = sq * KQ + u;
+                const float vw = (voff >= 0 && k < kout) ? params[voff + k * vstr] : 1.f;
                 const float e = __expf(rv[u] - ar);
-                const float q = gv[u] * vw[u] * __expf(dd - av[u]);
-                sR[k * ST + srow] = (rok && (VEC || k < K)) ? e : 0.f;
+                const float q = gv[u] * vw * __expf(dd - av[u]);
+                sR[k * ST + srow] = (rok && k < K) ? e : 0.f;
                 sQ[k * ST + srow] = (rok && k < kout && gv[u] != 0.f) ? q : 0.f;
             }
             for (int j = KP + sq; j < 16 * LY::NJ; j += 4) sR[j * ST + srow] = 0.f;   // rows beyond the padded K

@@ -43,7 +43,8 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
     constexpr int KP = LY::KP, SJ = LY::SJ, SK = LY::SK;
     extern __shared__ float Wl[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
-    const int li = blockIdx.x / nkt, kt = blockIdx.x - li * nkt;
+    const int vb = xcd_contiguous_block();
+    const int li = vb / nkt, kt = vb - li * nkt;
     const int item = item0 + li;
     const int kout = e_kout[li];
     if (4 * kt >= kout) return;                        // root items have a single output entry
