@@ -30,6 +30,14 @@ struct FwdLayout {
     static constexpr int LDS_FLOATS = LDS_W + 8 * 16 * SE;
 };
 
+// Orders the LDS traffic of one wave: what its lanes wrote before is visible to all its lanes after (the LDS
+// serves the requests of a wave in order; this keeps the compiler from moving accesses across).
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int KQ>
 __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __restrict__ e_left,
                                                         const int32_t* __restrict__ e_right,
@@ -86,12 +94,51 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
         // lane (c, g) holds entries 4s+g of row b of both inputs
         float er[KQ], el[KQ];
         float mr = -INFINITY, ml = -INFINITY;
+        if ((K & 3) == 0) {
+            // The 16 rows of the tile are contiguous in memory: they are fetched with 16-byte loads, consecutive
+            // lanes consecutive addresses, and reach the operand layout through the wave's LDS tile.
+            constexpr int NFW = (16 * KQ + 63) / 64;
+            const int rows = bt < n_btiles ? min(16, B - 16 * bt) : 0;
+            float4 rawR[NFW], rawL[NFW];
+#pragma unroll
+            for (int n = 0; n < NFW; ++n) {
+                const int f = min(lane + 64 * n, max(rows, 1) * KQ - 1);
+                rawR[n] = rawL[n] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (rows > 0) {
+                    rawR[n] = *reinterpret_cast<const float4*>(Rp + (size_t)16 * bt * K + 4 * f);
+                    rawL[n] = *reinterpret_cast<const float4*>(Lp + (size_t)16 * bt * K + 4 * f);
+                }
+            }
+            wave_lds_sync();                         // the previous tile's reads of eL are done
+#pragma unroll
+            for (int n = 0; n < NFW; ++n) {
+                const int f = lane + 64 * n;
+                if (f < 16 * KQ) *reinterpret_cast<float4*>(elw + (f / KQ) * LY::SE + 4 * (f % KQ)) = rawR[n];
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (int s = 0; s < KQ; ++s) er[s] = ok ? elw[c * LY::SE + 4 * s + g] : -INFINITY;
+            wave_lds_sync();
+#pragma unroll
+            for (int n = 0; n < NFW; ++n) {
+                const int f = lane + 64 * n;
+                if (f < 16 * KQ) *reinterpret_cast<float4*>(elw + (f / KQ) * LY::SE + 4 * (f % KQ)) = rawL[n];
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (int s = 0; s < KQ; ++s) el[s] = ok ? elw[c * LY::SE + 4 * s + g] : -INFINITY;
+        } else {
+#pragma unroll
+            for (int s = 0; s < KQ; ++s) {
+                const int j = 4 * s + g;
+                const bool in = ok && j < K;
+                er[s] = in ? Rp[(size_t)b * K + j] : -INFINITY;
+                el[s] = in ? Lp[(size_t)b * K + j] : -INFINITY;
+            }
+            wave_lds_sync();                         // the previous tile's reads of eL are done
+        }
 #pragma unroll
         for (int s = 0; s < KQ; ++s) {
-            const int j = 4 * s + g;
-            const bool in = ok && j < K;
-            er[s] = in ? Rp[(size_t)b * K + j] : -INFINITY;
-            el[s] = in ? Lp[(size_t)b * K + j] : -INFINITY;
             mr = fmaxf(mr, er[s]);
             ml = fmaxf(ml, el[s]);
         }
@@ -101,13 +148,13 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
         ml = fmaxf(ml, __shfl_xor(ml, 32, 64));
         if (mr == -INFINITY) mr = 0.f;               // an all-zero input vector: exp(-inf) = 0, no NaN
         if (ml == -INFINITY) ml = 0.f;
-        __syncthreads();                             // previous tile's eL reads are done
+        // (the tile is private to the wave, and every lane overwrites the entries it has read itself)
 #pragma unroll
         for (int s = 0; s < KQ; ++s) {
             er[s] = __expf(er[s] - mr);              // stays in registers: the B operand
             elw[c * LY::SE + 4 * s + g] = __expf(el[s] - ml);
         }
-        __syncthreads();
+        wave_lds_sync();
         float sacc = 0.f;
 #pragma unroll
         for (int it = 0; it < KQ; ++it) {
