@@ -37,6 +37,12 @@ struct einet {
     // the next einet_em_accumulate overwrites them instead of adding
     bool weight_stats_zero = false;
 
+    // The posterior of the root is 1 for every sample.  Its entries (b, 0), b < root_ones_batch, of the posterior
+    // arena hold that value from an earlier E-step (the arena is laid out for the batch size of the call, the
+    // root first, so a call with B samples leaves exactly the first B of them alone); 0 after einet_bind and
+    // after einet_sample, which uses the arena for the choices.
+    int root_ones_batch = 0;
+
     bool bound = false;
     float* params = nullptr;
     float* stats = nullptr;
@@ -288,6 +294,7 @@ int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_
     EINET_TABLES(X)
 #undef X
     h->bound = true;
+    h->root_ones_batch = 0;
     h->weight_stats_zero = false;   // the caller's buffer may hold statistics to be continued
     return EINET_OK;
 }
@@ -340,10 +347,12 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
     // top-down: posteriors of the regions of sum layer l (root first), then the einsum items below them
     const float* amax = reinterpret_cast<const float*>(h->ws + h->off_amax);
     for (int l = p.num_layers - 1, step = 0; l >= 0; --l, ++step) {
-        run(h, KC_REGION_BWD, s, [&] {
-            launch_region_assemble(h->dt, p.rb_layer_ptr[step], p.rb_layer_ptr[step + 1] - p.rb_layer_ptr[step],
-                                   step == 0, G, Gp, d, s);
-        });
+        // (the top sum layer is the root alone: nothing to launch when its ones are still in place)
+        if (step > 0 || B > h->root_ones_batch)
+            run(h, KC_REGION_BWD, s, [&] {
+                launch_region_assemble(h->dt, p.rb_layer_ptr[step], p.rb_layer_ptr[step + 1] - p.rb_layer_ptr[step],
+                                       step == 0, G, Gp, d, s);
+            });
         run(h, KC_EINSUM_BWD, s, [&] {
             launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
                                    !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp, d, s);
@@ -360,6 +369,7 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
                              mask_mode, h->params, A, Off, G, h->stats, p.phi_offset, p.den_offset, p.tot_offset, d, s);
     });
     h->weight_stats_zero = false;
+    h->root_ones_batch = B;
     return check_hip(h, "einet_em_accumulate");
 }
 
@@ -430,6 +440,7 @@ int einet_sample(einet_t* h, int B, const float* x_dev, const uint8_t* mask_dev,
     const float* amax = reinterpret_cast<const float*>(h->ws + h->off_amax);
     // the chosen entries live where the posterior arena of the EM pass lives (one int32 per node and sample)
     int32_t* sel = reinterpret_cast<int32_t*>(h->ws + h->off_G);
+    h->root_ones_batch = 0;
     const int n_part = (int)h->graph.partition.size();
     run(h, KC_SAMPLE, s, [&] {
         launch_sample_init(sel, p.num_nodes, B, s);

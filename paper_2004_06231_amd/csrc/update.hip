@@ -19,6 +19,54 @@ __device__ __forceinline__ void update_rows_body(int block, const int32_t* __res
     const bool have = row >= first_row;      // rows below first_row count as zero statistics (memory is stale)
     const bool clear = row >= n_lazy_rows;   // the first rows are overwritten, not added to, by the next E-step
     const int off = row_off[row], len = row_len[row];
+    if constexpr (NPL >= 4) {
+        // rows of whole 16-byte groups (K even): the same with four entries per load
+        if (len <= 64 * NPL && ((off | len) & 3) == 0) {
+            constexpr int NV = NPL / 4;
+            const int len4 = len >> 2;
+            const float4* st4 = reinterpret_cast<const float4*>(stats + off);
+            float4* pa4 = reinterpret_cast<float4*>(params + off);
+            float n[NV][4], w[NV][4];
+            float s = 0.f;
+#pragma unroll
+            for (int t = 0; t < NV; ++t) {
+                const int e = lane + 64 * t;
+                const float4 nv = e < len4 && have ? st4[e] : make_float4(0.f, 0.f, 0.f, 0.f);
+                const float4 wv = e < len4 ? pa4[e] : make_float4(0.f, 0.f, 0.f, 0.f);
+                n[t][0] = nv.x, n[t][1] = nv.y, n[t][2] = nv.z, n[t][3] = nv.w;
+                w[t][0] = wv.x, w[t][1] = wv.y, w[t][2] = wv.z, w[t][3] = wv.w;
+            }
+#pragma unroll
+            for (int t = 0; t < NV; ++t) s += (n[t][0] + n[t][1]) + (n[t][2] + n[t][3]);
+            const float tot = wave_sum(s);
+            const float sc = tot < 0x1p-60f ? 0x1p+64f : 1.f;
+            const float inv = 1.f / (tot * sc);
+            float s2 = 0.f;
+#pragma unroll
+            for (int t = 0; t < NV; ++t)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    n[t][c] = tot > 0.f ? (n[t][c] * sc) * inv : w[t][c];
+                    if (w_floor > 0.f && lane + 64 * t < len4) {
+                        n[t][c] = fmaxf(n[t][c], w_floor);
+                        s2 += n[t][c];
+                    }
+                }
+            const float norm = w_floor > 0.f ? 1.f / wave_sum(s2) : 1.f;
+#pragma unroll
+            for (int t = 0; t < NV; ++t) {
+                const int e = lane + 64 * t;
+                if (e < len4) {
+                    pa4[e] = make_float4((1.f - step) * w[t][0] + step * (n[t][0] * norm),
+                                         (1.f - step) * w[t][1] + step * (n[t][1] * norm),
+                                         (1.f - step) * w[t][2] + step * (n[t][2] * norm),
+                                         (1.f - step) * w[t][3] + step * (n[t][3] * norm));
+                    if (clear) reinterpret_cast<float4*>(stats + off)[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+            return;
+        }
+    }
     if (len <= 64 * NPL) {
         float n[NPL], w[NPL];
         float s = 0.f;

@@ -190,3 +190,31 @@ def test_init_params_matches_the_oracle_generator(family, param):
     with pytest.raises(P.EinetError):
         m.init_params(seed=1, leaf_lo=0.9, leaf_hi=0.1)
     m.close()
+
+
+def test_statistics_do_not_depend_on_earlier_calls_of_the_handle():
+    """The top-down pass keeps the posterior of the root (all ones) in its arena between calls when it can; batch
+    sizes going up and down and a sampling call in between (it uses the same arena) must not show in the result."""
+    spec = dict(kind="pd", H=4, W=4, deltas=[2, 1])
+    K, C, family, seed = 6, 1, GAUSSIAN, 9
+    oracle, flat, rng = make_oracle(spec, K, C, family, seed, leaf_range=(0.2, 0.8))
+    D = oracle.g.num_vars
+    m = gpu_model(spec, K, C, family, 64, seed, flat)
+    n_choices = m.structure()["num_partitions"] + m.structure()["num_regions"]
+    for step, B in enumerate([40, 17, 40, 64, 3, 64]):
+        x = _data(rng, family, B, D, C)
+        if step == 3:
+            m.sample(8, torch.rand(n_choices, 8, device="cuda"), None)
+        fresh = gpu_model(spec, K, C, family, 64, seed, flat)
+        m.em_reset()
+        fresh.em_reset()
+        lp, lp2 = torch.empty(B, device="cuda"), torch.empty(B, device="cuda")
+        m.em_accumulate(dev(x), None, lp)
+        fresh.em_accumulate(dev(x), None, lp2)
+        assert torch.equal(lp, lp2)
+        assert torch.equal(m.stats, fresh.stats), f"call {step} with {B} samples"
+        ref_stats, _ = oracle.em_accumulate(x, None)
+        from tests.gpu_common import assert_stats_close
+        assert_stats_close(m.stats, oracle.stats_to_flat(ref_stats), oracle.layout, m.n_params)
+        fresh.close()
+    m.close()
