@@ -25,8 +25,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_FP32_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
 WORKLOAD = 4
 # HBM bytes per launch of the dominant kernel on the default workload, from two rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE; see profiles/hbm_traffic_cfg4.md): (54389 + 81433) KiB over six launches
-MEASURED_TRAFFIC = {(4, "einsum_backward"): 23.18e6}
+# (FETCH_SIZE, WRITE_SIZE; see profiles/hbm_traffic_cfg4.md): (31721 + 77890) KiB over six launches
+MEASURED_TRAFFIC = {(4, "einsum_backward"): 18.71e6}
 
 
 def algorithmic_work(st, K, C, R, T, TD, B, D):
