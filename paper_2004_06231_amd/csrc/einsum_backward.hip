@@ -347,12 +347,22 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
                 floatx4 acc[KQ];
 #pragma unroll
                 for (int jt = 0; jt < KQ; ++jt) acc[jt] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (nkt == KQ) {
 #pragma unroll 2
-                for (int s = 0; s < KQ; ++s) {
-                    const float qs = qrow[4 * s * ST];
+                    for (int s = 0; s < KQ; ++s) {
+                        const float qs = qrow[4 * s * ST];
 #pragma unroll
-                    for (int jt = 0; jt < KQ; ++jt)
-                        acc[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl[4 * s * S + 4 * jt], qs, acc[jt], 0, 0, 0);
+                        for (int jt = 0; jt < KQ; ++jt)
+                            acc[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl[4 * s * S + 4 * jt], qs, acc[jt], 0, 0, 0);
+                    }
+                } else {
+                    // an item of the root has one output entry: the other contraction steps would add zeros
+                    for (int s = 0; s < nkt; ++s) {
+                        const float qs = qrow[4 * s * ST];
+#pragma unroll
+                        for (int jt = 0; jt < KQ; ++jt)
+                            acc[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl[4 * s * S + 4 * jt], qs, acc[jt], 0, 0, 0);
+                    }
                 }
                 // acc[jt][r] = U[b][i = 4it+r][j = 4jt+g]
                 float gl0 = 0.f, gl1 = 0.f, gl2 = 0.f, gl3 = 0.f;
