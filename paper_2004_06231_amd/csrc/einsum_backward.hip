@@ -21,8 +21,16 @@ __global__ void k_region_assemble(const int32_t* __restrict__ r_node, const int3
     const size_t blk = (size_t)B * K, o = (size_t)b * K + k;
     float g = is_root ? 1.f : 0.f;
     const int p1 = r_pptr[item + 1];
-#pragma unroll 8
-    for (int p = r_pptr[item]; p < p1; ++p) g += Gp[(size_t)r_pblk[p] * blk + o];
+    // sixteen blocks per round, all requested before the first is added: a region of a Poon-Domingos structure
+    // has a few dozen parent blocks, and one memory latency per block would be the whole kernel
+    for (int p0 = r_pptr[item]; p0 < p1; p0 += 16) {
+        float v[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) v[q] = Gp[(size_t)r_pblk[min(p0 + q, p1 - 1)] * blk + o];
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            if (p0 + q < p1) g += v[q];
+    }
     G[(size_t)r_node[item] * blk + o] = g;
 }
 

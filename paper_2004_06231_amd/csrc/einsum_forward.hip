@@ -91,6 +91,10 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
         const int bt = bt0 + wave;
         const int b = bt * 16 + c;
         const bool ok = bt < n_btiles && b < B;
+        // offsets of the children, needed only when the result is stored: requested now, used at the end
+        double off_children = 0.0;
+        if (ok && kt == 0 && g == 0)
+            off_children = Off[(size_t)e_left[li] * B + b] + Off[(size_t)e_right[li] * B + b];
         // lane (c, g) holds entries 4s+g of row b of both inputs
         float er[KQ], el[KQ];
         float mr = -INFINITY, ml = -INFINITY;
@@ -169,7 +173,7 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
         const float res = __logf(sacc);                // residual against Off[left] + Off[right] + ml + mr
         if (ok && k < kout) A[((size_t)e_out[li] * B + b) * K + k] = res;
         if (ok && kt == 0 && g == 0) {
-            const double off = Off[(size_t)e_left[li] * B + b] + Off[(size_t)e_right[li] * B + b] + (double)ml + (double)mr;
+            const double off = off_children + (double)ml + (double)mr;
             Off[(size_t)e_out[li] * B + b] = off;
             if (logp && e_out[li] == 0) logp[b] = (float)(off + (double)res);   // node 0: the root region, one entry
             amax[((size_t)item * 2) * B + b] = ml;     // the shifts, kept for the top-down pass
@@ -181,6 +185,7 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
 // ------------------------------------------------------------------ mixing layer, forward (App. B)
 // Offset of the output: the largest offset of the children (their residuals are at most 0, so no term
 // exceeds its weight); residual: log sum_c v[c] exp((Off[c] - Off[out]) + A[c]).
+constexpr int MIX_UNROLL = 8;
 __global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32_t* __restrict__ m_kout,
                                  const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
                                  const int32_t* __restrict__ m_voff, const float* __restrict__ params,
@@ -194,11 +199,30 @@ __global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32
     const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
     const float* v = params + m_voff[item] + (size_t)k * nc;
     double m = -INFINITY;
-    for (int c = 0; c < nc; ++c) m = fmax(m, Off[(size_t)m_child[c0 + c] * B + b]);
     float s = 0.f;
-    for (int c = 0; c < nc; ++c) {
-        const size_t row = (size_t)m_child[c0 + c] * B + b;
-        s += v[c] * expf((float)(Off[row] - m) + A[row * K + k]);
+    if (nc <= MIX_UNROLL) {
+        // offsets, residuals and weights of all children are requested together: one memory latency, not two
+        double off[MIX_UNROLL];
+        float a[MIX_UNROLL], w[MIX_UNROLL];
+#pragma unroll
+        for (int c = 0; c < MIX_UNROLL; ++c) {
+            const size_t row = (size_t)m_child[c0 + min(c, nc - 1)] * B + b;
+            off[c] = Off[row];
+            a[c] = A[row * K + k];
+            w[c] = v[min(c, nc - 1)];
+        }
+#pragma unroll
+        for (int c = 0; c < MIX_UNROLL; ++c)
+            if (c < nc) m = fmax(m, off[c]);
+#pragma unroll
+        for (int c = 0; c < MIX_UNROLL; ++c)
+            if (c < nc) s += w[c] * expf((float)(off[c] - m) + a[c]);
+    } else {
+        for (int c = 0; c < nc; ++c) m = fmax(m, Off[(size_t)m_child[c0 + c] * B + b]);
+        for (int c = 0; c < nc; ++c) {
+            const size_t row = (size_t)m_child[c0 + c] * B + b;
+            s += v[c] * expf((float)(Off[row] - m) + A[row * K + k]);
+        }
     }
     const float res = logf(s);
     const size_t row = (size_t)m_node[item] * B + b;
