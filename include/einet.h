@@ -150,7 +150,9 @@ int einet_sizes(const einet_t* h, size_t* n_params, size_t* n_stats, size_t* wor
 int einet_structure(const einet_t* h, einet_structure_view* view);
 
 /* Registers the caller's device buffers (params: n_params floats, stats:
- * n_stats floats, workspace: workspace_bytes, 256-byte aligned) and uploads
+ * n_stats floats, both 16-byte aligned: the kernels read whole groups of four
+ * weights; workspace: workspace_bytes, 256-byte aligned; a misaligned buffer is
+ * EINET_ERR_INVALID_ARG) and uploads
  * the index tables into the workspace on `stream`, synchronising once.  The
  * buffers stay owned by the caller and must outlive every later call.  The
  * parameter buffer may be uninitialised at this point; call einet_refresh

@@ -281,6 +281,8 @@ int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_
     if (!h) return EINET_ERR_INVALID_ARG;
     if (!params_dev || !stats_dev || !workspace_dev) return fail(h, EINET_ERR_INVALID_ARG, "NULL device buffer");
     if (reinterpret_cast<uintptr_t>(workspace_dev) % 256) return fail(h, EINET_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    if (reinterpret_cast<uintptr_t>(params_dev) % 16 || reinterpret_cast<uintptr_t>(stats_dev) % 16)
+        return fail(h, EINET_ERR_INVALID_ARG, "params and stats must be 16-byte aligned");
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipMemcpyAsync(workspace_dev, h->blob.data(), h->blob.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);

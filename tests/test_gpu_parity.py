@@ -232,3 +232,23 @@ def test_update_of_a_sum_row_with_denormal_or_zero_posterior_mass(w_floor):
     oracle.set_flat_params(c["flat"])
     m.set_params(c["flat"])
     m.em_reset()
+
+
+def test_bind_rejects_misaligned_buffers():
+    """The kernels read parameters and statistics in groups of four floats: einet_bind turns a parameter or
+    statistics buffer that is not 16-byte aligned, or a workspace that is not 256-byte aligned, into an error."""
+    import ctypes as C
+    m = P.EiNet(dict(kind="rat", D=8, depth=2, R=2), 4, 1, BERNOULLI, 16, 3)
+    lib = P.load_library()
+    params = torch.zeros(m.n_params + 8, dtype=torch.float32, device="cuda")
+    stats = torch.zeros(m.n_stats + 8, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(m.workspace_bytes + 512, dtype=torch.uint8, device="cuda")
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ok = (params.data_ptr(), stats.data_ptr(), ws.data_ptr())
+    assert all(p % 256 == 0 for p in ok)
+    for shift in ((4, 0, 0), (0, 8, 0), (0, 0, 16)):
+        rc = lib.einet_bind(m._h, *(C.c_void_p(p + s) for p, s in zip(ok, shift)), stream)
+        assert rc != 0, shift
+        assert b"aligned" in lib.einet_last_error(m._h)
+    assert lib.einet_bind(m._h, *(C.c_void_p(p) for p in ok), stream) == 0
+    m.close()
