@@ -12,9 +12,11 @@
 // children.  Log-densities of large scopes have magnitudes of 1e3..1e5, where a
 // float32 resolves 1e-4..1e-2; the residuals stay small, and the posteriors of the
 // top-down pass (exponentials of differences) keep full float32 precision.  The
-// posterior arena G has the same shape; Gp[2e+side][b][k] holds what einsum
-// item e sends down to its left (side 0) or right (side 1) child, and a child
-// sums the slots of its parents when it is processed: no atomics anywhere.
+// posterior arena G has the same shape; Gp holds what einsum item e sends down:
+// blocks e*nb .. e*nb+nb-1 ([b][k] each, nb = 1 + ceil(K/4)), the first for its
+// left child, the others, one per workgroup of the item's top-down launch, shares
+// for its right child.  A child sums the blocks of its parents when it is
+// processed: no atomics anywhere.
 #ifndef EINET_DEVICE_COMMON_HPP
 #define EINET_DEVICE_COMMON_HPP
 

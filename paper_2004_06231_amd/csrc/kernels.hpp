@@ -1,4 +1,5 @@
-// Launchers of the HIP kernels (device code lives in kernels.hip).  All pointers
+// Launchers of the HIP kernels (device code: leaf_forward, einsum_forward, einsum_backward, statistics, update and
+// sampling .hip).  All pointers
 // are device pointers; every launcher only enqueues work on `stream`.
 #pragma once
 #include <hip/hip_runtime.h>
