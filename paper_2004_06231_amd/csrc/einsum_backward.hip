@@ -26,7 +26,7 @@ __global__ void k_region_assemble(const int32_t* __restrict__ r_node, const int3
     for (int p0 = r_pptr[item]; p0 < p1; p0 += 16) {
         float v[16];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) v[q] = Gp[(size_t)r_pblk[min(p0 + q, p1 - 1)] * blk + o];
+        for (int q = 0; q < 16; ++q) v[q] = p0 + q < p1 ? Gp[(size_t)r_pblk[p0 + q] * blk + o] : 0.f;
 #pragma unroll
         for (int q = 0; q < 16; ++q)
             if (p0 + q < p1) g += v[q];

@@ -206,10 +206,14 @@ __global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32
         float a[MIX_UNROLL], w[MIX_UNROLL];
 #pragma unroll
         for (int c = 0; c < MIX_UNROLL; ++c) {
-            const size_t row = (size_t)m_child[c0 + min(c, nc - 1)] * B + b;
-            off[c] = Off[row];
-            a[c] = A[row * K + k];
-            w[c] = v[min(c, nc - 1)];
+            off[c] = 0.0;
+            a[c] = w[c] = 0.f;
+            if (c < nc) {
+                const size_t row = (size_t)m_child[c0 + c] * B + b;
+                off[c] = Off[row];
+                a[c] = A[row * K + k];
+                w[c] = v[c];
+            }
         }
 #pragma unroll
         for (int c = 0; c < MIX_UNROLL; ++c)

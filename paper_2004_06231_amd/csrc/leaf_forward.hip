@@ -418,27 +418,53 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
 #pragma unroll
     for (int b = 0; b < LEAF_RED; ++b) acc[b] = hacc[b] = 0.f;
     if (part < nparts) {
-        for (int p = part; p < np; p += nparts) {
-            const int v = p / d.C, c = p - v * d.C;
-            const float* th = theta + ((size_t)(leaf_var[s0 + v] * d.C + c) * d.R + r) * tstride + k;
-            if (d.family == EINET_LEAF_GAUSSIAN) {
-                const float mu = th[0], c1 = th[d.K], c0 = th[2 * d.K];
-#pragma unroll
-                for (int b = 0; b < LEAF_RED; ++b) {
-                    const float diff = xs[b * np + p] - mu;
-                    acc[b] += ob[b * nv + v] * fmaf(c1 * diff, diff, c0);
-                }
-            } else if (d.family == EINET_LEAF_CATEGORICAL) {
+        if (d.family == EINET_LEAF_CATEGORICAL) {
+            for (int p = part; p < np; p += nparts) {
+                const int v = p / d.C, c = p - v * d.C;
+                const float* th = theta + ((size_t)(leaf_var[s0 + v] * d.C + c) * d.R + r) * tstride + k;
 #pragma unroll
                 for (int b = 0; b < LEAF_RED; ++b)
                     acc[b] += ob[b * nv + v] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + p], th, d.K, d.P);
-            } else {
-                const float lp = th[0], l1p = th[d.K], nf = (float)d.P;
+            }
+        } else {
+            // Four pairs per round: their variable numbers are requested together, then their constants, so that
+            // a round waits for two memory latencies instead of eight.  The terms are added in the order of the
+            // pairs, as a pair-by-pair loop would.
+            const bool gauss = d.family == EINET_LEAF_GAUSSIAN;
+            const float nf = (float)d.P;
+            for (int p = part; p < np; p += 4 * nparts) {
+                int vq[4], pq[4], var[4];
+                float t0[4], t1[4], t2[4];
 #pragma unroll
-                for (int b = 0; b < LEAF_RED; ++b) {
-                    const float xv = xs[b * np + p];
-                    acc[b] += ob[b * nv + v] * (xv * lp + (nf - xv) * l1p);
-                    if (base) hacc[b] += ob[b * nv + v] * leaf_base(logc, xv, d.P);
+                for (int q = 0; q < 4; ++q) {
+                    pq[q] = min(p + q * nparts, np - 1);
+                    vq[q] = pq[q] / d.C;
+                    var[q] = leaf_var[s0 + vq[q]];
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float* th = theta + ((size_t)(var[q] * d.C + (pq[q] - vq[q] * d.C)) * d.R + r) * tstride + k;
+                    t0[q] = th[0];
+                    t1[q] = th[d.K];
+                    t2[q] = gauss ? th[2 * d.K] : 0.f;
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (p + q * nparts >= np) break;
+                    if (gauss) {
+#pragma unroll
+                        for (int b = 0; b < LEAF_RED; ++b) {
+                            const float diff = xs[b * np + pq[q]] - t0[q];
+                            acc[b] += ob[b * nv + vq[q]] * fmaf(t1[q] * diff, diff, t2[q]);
+                        }
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < LEAF_RED; ++b) {
+                            const float xv = xs[b * np + pq[q]];
+                            acc[b] += ob[b * nv + vq[q]] * (xv * t0[q] + (nf - xv) * t1[q]);
+                            if (base) hacc[b] += ob[b * nv + vq[q]] * leaf_base(logc, xv, d.P);
+                        }
+                    }
                 }
             }
         }
