@@ -189,20 +189,18 @@ __device__ __forceinline__ void leaf_backward_cells_body(
             const int pair = p0 + p, v = pair / d.C, c = pair - v * d.C;
             const int var = vsl[v - vfirst];
             xs[bb * pc + p] = x[((size_t)(b0 + bb) * d.D + var) * d.C + c];
-            uint8_t o = 1;
-            if (mask_mode == EINET_MASK_SHARED) o = mask[var];
-            if (mask_mode == EINET_MASK_PER_SAMPLE) o = mask[(size_t)(b0 + bb) * d.D + var];
-            os[bb * pc + p] = o;
+            if (mask_mode == EINET_MASK_SHARED) os[bb * pc + p] = mask[var];
+            if (mask_mode == EINET_MASK_PER_SAMPLE) os[bb * pc + p] = mask[(size_t)(b0 + bb) * d.D + var];
         }
         __syncthreads();
-        if (pl < np) {
+        // (pairs beyond np read stale LDS values; their sums are never written)
+        if (pl < np && mask_mode != EINET_MASK_NONE) {
 #pragma unroll 4
             for (int bb = 0; bb < nb; ++bb) {
                 const float p = Gs[bb * d.K + k];
                 tot += p;
 #pragma unroll
                 for (int q = 0; q < PPT; ++q) {
-                    // (pairs beyond np read stale LDS values; their sums are never written)
                     const float xv = xs[bb * pc + pl + q];
                     const float pm = os[bb * pc + pl + q] ? p : 0.f;
                     den[q] += pm;
@@ -210,7 +208,23 @@ __device__ __forceinline__ void leaf_backward_cells_body(
                     n2[q] = fmaf(pm * xv, xv, n2[q]);
                 }
             }
+        } else if (pl < np) {                         // everything observed: no flags to read, den = tot
+#pragma unroll 4
+            for (int bb = 0; bb < nb; ++bb) {
+                const float p = Gs[bb * d.K + k];
+                tot += p;
+#pragma unroll
+                for (int q = 0; q < PPT; ++q) {
+                    const float xv = xs[bb * pc + pl + q];
+                    n1[q] = fmaf(p, xv, n1[q]);
+                    n2[q] = fmaf(p * xv, xv, n2[q]);
+                }
+            }
         }
+    }
+    if (mask_mode == EINET_MASK_NONE) {
+#pragma unroll
+        for (int q = 0; q < PPT; ++q) den[q] = tot;
     }
     const int r = leaf_replica[leaf];
 #pragma unroll
