@@ -446,12 +446,9 @@ int einet_sample(einet_t* h, int B, const float* x_dev, const uint8_t* mask_dev,
     const int n_part = (int)h->graph.partition.size();
     run(h, KC_SAMPLE, s, [&] {
         launch_sample_init(sel, p.num_nodes, B, s);
-        for (int l = p.num_layers - 1; l >= 0; --l) {
-            launch_sample_mixing(h->dt, p.mix_layer_ptr[l], p.mix_layer_ptr[l + 1] - p.mix_layer_ptr[l], evidence,
-                                 h->params, A, Off, u_dev, n_part, sel, d, s);
-            launch_sample_einsum(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], evidence,
-                                 h->params, A, amax, u_dev, sel, d, s);
-        }
+        for (int l = p.num_layers - 1; l >= 0; --l)
+            launch_sample_regions(h->dt, p.sr_layer_ptr[l], p.sr_layer_ptr[l + 1] - p.sr_layer_ptr[l], evidence,
+                                  h->params, A, Off, amax, u_dev, n_part, sel, d, s);
         launch_sample_leaves(h->dt, (int)p.lv_leaf.size(), x_dev, mask_dev, mask_mode, h->params + p.phi_offset,
                              noise_dev, sel, out_dev, d, s);
     });

@@ -16,7 +16,8 @@ namespace einet_impl {
     X(ein_left) X(ein_right) X(ein_out) X(ein_reg) X(ein_kout) X(ein_woff) X(ein_voff) X(ein_vstr) X(ein_part) \
     X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff)                                           \
     X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
-    X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len) X(leaf_logc)
+    X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len) X(leaf_logc)                         \
+    X(sr_node) X(sr_pptr) X(sr_item) X(sr_mix)
 
 struct DevTables {
 #define X(name) const int32_t* name;
@@ -78,12 +79,11 @@ void launch_init_params(const DevTables& t, int n_rows, float* params, int64_t p
 // sample does not visit it.  u [num_partitions + num_regions][B]: the uniforms of the choices.
 // evidence = false: no forward pass has run, the choices follow the weights alone.
 void launch_sample_init(int32_t* sel, int num_nodes, int B, hipStream_t s);
-void launch_sample_mixing(const DevTables& t, int first, int count, bool evidence, const float* params,
-                          const float* A, const double* Off, const float* u, int num_partitions, int32_t* sel,
-                          const Dims& d, hipStream_t s);
-void launch_sample_einsum(const DevTables& t, int first, int count, bool evidence, const float* params,
-                          const float* A, const float* amax, const float* u, int32_t* sel, const Dims& d,
-                          hipStream_t s);
+// One launch per sum layer: for every region of the layer that a sample reaches, the choice of a partition
+// (regions with several) and then of a pair of child entries.  Items first .. first+count-1 of the sr_* tables.
+void launch_sample_regions(const DevTables& t, int first, int count, bool evidence, const float* params,
+                           const float* A, const double* Off, const float* amax, const float* u, int num_partitions,
+                           int32_t* sel, const Dims& d, hipStream_t s);
 void launch_sample_leaves(const DevTables& t, int n_lv, const float* x, const uint8_t* mask, int mask_mode,
                           const float* phi, const float* noise, const int32_t* sel, float* out, const Dims& d,
                           hipStream_t s);

@@ -18,19 +18,15 @@ __global__ void k_sample_init(int32_t* __restrict__ sel, int64_t n, int B) {
 // exceeds u times the total.
 //
 // Region with several partitions: partition c has weight v[k][c] * S^c[k] / S[k] given the evidence
-// (App. B), v[k][c] without.  One thread per (region, sample).
-__global__ void k_sample_mixing(const int32_t* __restrict__ m_node, const int32_t* __restrict__ m_cptr,
-                                const int32_t* __restrict__ m_child, const int32_t* __restrict__ m_voff,
-                                int evidence, const float* __restrict__ params, const float* __restrict__ A,
-                                const double* __restrict__ Off, const float* __restrict__ u, int num_partitions,
-                                int32_t* __restrict__ sel, int B, int K) {
-    const int item = blockIdx.x, b = blockIdx.y * blockDim.x + threadIdx.x;
-    if (b >= B) return;
-    const int s = m_node[item];
-    const int k = sel[(size_t)s * B + b];
-    if (k < 0) return;
-    const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
-    const float* v = params + m_voff[item] + (size_t)k * nc;
+// (App. B), v[k][c] without.  Every lane of the wave walks the few partitions; all get the same answer.
+__device__ __forceinline__ int sample_partition(int mi, int s, int k, int b, const int32_t* __restrict__ m_cptr,
+                                                const int32_t* __restrict__ m_child,
+                                                const int32_t* __restrict__ m_voff, int evidence,
+                                                const float* __restrict__ params, const float* __restrict__ A,
+                                                const double* __restrict__ Off, const float* __restrict__ u,
+                                                int num_partitions, int B, int K) {
+    const int c0 = m_cptr[mi], nc = m_cptr[mi + 1] - c0;
+    const float* v = params + m_voff[mi] + (size_t)k * nc;
     const size_t srow = (size_t)s * B + b;
     float total = 0.f;
     for (int c = 0; c < nc; ++c) {
@@ -47,40 +43,50 @@ __global__ void k_sample_mixing(const int32_t* __restrict__ m_node, const int32_
         if (w > 0.f) last = c;
         if (pick < 0 && run > tau) pick = c;
     }
-    if (pick < 0) pick = last;                       // u so close to 1 that rounding ate the last interval
-    sel[(size_t)m_child[c0 + pick] * B + b] = k;
+    return pick < 0 ? last : pick;                   // u so close to 1 that rounding ate the last interval
 }
 
 // Partition: the pair (i, j) has weight W[k][i][j] * eL[i] * eR[j] given the evidence (the posterior of
 // Eq. 6 for the chosen output entry k), W[k][i][j] without; pairs are numbered i * K + j.  One wave per
-// (item, sample): the K*K weights go to LDS, every lane sums a run of consecutive pairs, a wave scan of
-// the run sums finds the run that holds the threshold and its lane walks it.
+// (region, sample): it first chooses the partition (above), then the K*K weights of that partition go to LDS,
+// every lane sums a run of consecutive pairs, a wave scan of the run sums finds the run that holds the
+// threshold and its lane walks it.
 constexpr int SAMPLE_WAVES = 4;
 __device__ __forceinline__ int sample_pos(int t) { return t + (t >> 5); }   // padded: runs start in different banks
 
-__global__ __launch_bounds__(64 * SAMPLE_WAVES) void k_sample_einsum(
-    const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_out,
+__global__ __launch_bounds__(64 * SAMPLE_WAVES) void k_sample_regions(
+    const int32_t* __restrict__ sr_node, const int32_t* __restrict__ sr_pptr, const int32_t* __restrict__ sr_item,
+    const int32_t* __restrict__ sr_mix, const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
+    const int32_t* __restrict__ m_voff, const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right,
     const int32_t* __restrict__ e_woff, const int32_t* __restrict__ e_part, int evidence,
-    const float* __restrict__ params, const float* __restrict__ A, const float* __restrict__ amax,
-    const float* __restrict__ u, int32_t* __restrict__ sel, int item0, int B, int K) {
+    const float* __restrict__ params, const float* __restrict__ A, const double* __restrict__ Off,
+    const float* __restrict__ amax, const float* __restrict__ u, int num_partitions, int32_t* __restrict__ sel, int B,
+    int K) {
     extern __shared__ float lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int li = blockIdx.x, b = blockIdx.y * SAMPLE_WAVES + wave;
+    const int ri = blockIdx.x, b = blockIdx.y * SAMPLE_WAVES + wave;
     if (b >= B) return;                              // whole waves leave: no barrier below
-    const int k = sel[(size_t)e_out[li] * B + b];
+    const int s = sr_node[ri];
+    const int k = sel[(size_t)s * B + b];
     if (k < 0) return;
+    const int mi = sr_mix[ri];
+    int c = 0;
+    if (mi >= 0) {
+        c = sample_partition(mi, s, k, b, m_cptr, m_child, m_voff, evidence, params, A, Off, u, num_partitions, B, K);
+        if (lane == 0) sel[(size_t)m_child[m_cptr[mi] + c] * B + b] = k;
+    }
+    const int item = sr_item[sr_pptr[ri] + c];       // einsum item of the chosen partition
     const int KK = K * K;
     float* wl = lds + wave * (sample_pos(KK) + 1 + 128);
     float* el = wl + sample_pos(KK) + 1;
     float* er = el + 64;
-    const int item = item0 + li;
     if (evidence) {
         const float al = amax[(size_t)item * 2 * B + b], ar = amax[((size_t)item * 2 + 1) * B + b];
-        el[lane] = lane < K ? __expf(A[((size_t)e_left[li] * B + b) * K + lane] - al) : 0.f;
-        er[lane] = lane < K ? __expf(A[((size_t)e_right[li] * B + b) * K + lane] - ar) : 0.f;
+        el[lane] = lane < K ? __expf(A[((size_t)e_left[item] * B + b) * K + lane] - al) : 0.f;
+        er[lane] = lane < K ? __expf(A[((size_t)e_right[item] * B + b) * K + lane] - ar) : 0.f;
         __builtin_amdgcn_wave_barrier();
     }
-    const float* row = params + e_woff[li] + (size_t)k * KK;
+    const float* row = params + e_woff[item] + (size_t)k * KK;
     for (int t = lane; t < KK; t += 64) {
         float w = row[t];
         if (evidence) {
@@ -101,7 +107,7 @@ __global__ __launch_bounds__(64 * SAMPLE_WAVES) void k_sample_einsum(
         if (lane >= o) incl += up;
     }
     const float total = __shfl(incl, 63, 64);
-    const float tau = u[(size_t)e_part[li] * B + b] * total;
+    const float tau = u[(size_t)e_part[item] * B + b] * total;
     const unsigned long long hit = __ballot(incl > tau && t1 > t0);
     int pick = -1;
     if (hit != 0ull) {
@@ -129,8 +135,8 @@ __global__ __launch_bounds__(64 * SAMPLE_WAVES) void k_sample_einsum(
     }
     if (lane == 0) {
         const int i = pick / K;
-        sel[(size_t)e_left[li] * B + b] = i;
-        sel[(size_t)e_right[li] * B + b] = pick - i * K;
+        sel[(size_t)e_left[item] * B + b] = i;
+        sel[(size_t)e_right[item] * B + b] = pick - i * K;
     }
 }
 
@@ -213,30 +219,22 @@ void launch_sample_init(int32_t* sel, int num_nodes, int B, hipStream_t s) {
     hipLaunchKernelGGL(k_sample_init, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, sel, n, B);
 }
 
-void launch_sample_mixing(const DevTables& t, int first, int count, bool evidence, const float* params,
-                          const float* A, const double* Off, const float* u, int num_partitions, int32_t* sel,
-                          const Dims& d, hipStream_t s) {
-    if (count == 0) return;
-    hipLaunchKernelGGL(k_sample_mixing, dim3(count, (d.B + 63) / 64), dim3(64), 0, s, t.mix_node + first,
-                       t.mix_cptr + first, t.mix_child, t.mix_voff + first, evidence ? 1 : 0, params, A, Off, u,
-                       num_partitions, sel, d.B, d.K);
-}
-
-void launch_sample_einsum(const DevTables& t, int first, int count, bool evidence, const float* params,
-                          const float* A, const float* amax, const float* u, int32_t* sel, const Dims& d,
-                          hipStream_t s) {
+void launch_sample_regions(const DevTables& t, int first, int count, bool evidence, const float* params,
+                           const float* A, const double* Off, const float* amax, const float* u, int num_partitions,
+                           int32_t* sel, const Dims& d, hipStream_t s) {
     if (count == 0) return;
     const int KK = d.K * d.K;
     const size_t lds = sizeof(float) * SAMPLE_WAVES * (size_t)(KK + (KK >> 5) + 1 + 128);   // at most 68 KB (K = 64)
     static bool attr_set = false;
     if (lds > 64 * 1024 && !attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sample_einsum),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sample_regions),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024);
         attr_set = true;
     }
-    hipLaunchKernelGGL(k_sample_einsum, dim3(count, (d.B + SAMPLE_WAVES - 1) / SAMPLE_WAVES), dim3(64 * SAMPLE_WAVES),
-                       lds, s, t.ein_left + first, t.ein_right + first, t.ein_out + first, t.ein_woff + first,
-                       t.ein_part + first, evidence ? 1 : 0, params, A, amax, u, sel, first, d.B, d.K);
+    hipLaunchKernelGGL(k_sample_regions, dim3(count, (d.B + SAMPLE_WAVES - 1) / SAMPLE_WAVES), dim3(64 * SAMPLE_WAVES),
+                       lds, s, t.sr_node + first, t.sr_pptr + first, t.sr_item, t.sr_mix + first, t.mix_cptr,
+                       t.mix_child, t.mix_voff, t.ein_left, t.ein_right, t.ein_woff, t.ein_part, evidence ? 1 : 0,
+                       params, A, Off, amax, u, num_partitions, sel, d.B, d.K);
 }
 
 void launch_sample_leaves(const DevTables& t, int n_lv, const float* x, const uint8_t* mask, int mask_mode,

@@ -280,6 +280,23 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param
         p.mix_layer_ptr.push_back((int32_t)p.mix_node.size());
     }
 
+    // ---- sampling items: the sum regions layer by layer, each with the einsum items of its partitions
+    {
+        std::vector<int> mix_of(nr, -1);
+        for (size_t i = 0; i < p.mix_node.size(); ++i) mix_of[p.mix_node[i]] = (int)i;
+        p.sr_layer_ptr.push_back(0);
+        p.sr_pptr.push_back(0);
+        for (auto& layer : sum_layers) {
+            for (int s : layer) {
+                p.sr_node.push_back(s);
+                p.sr_mix.push_back(mix_of[s]);
+                for (int n : g.parts_of[s]) p.sr_item.push_back(item_of[n]);
+                p.sr_pptr.push_back((int32_t)p.sr_item.size());
+            }
+            p.sr_layer_ptr.push_back((int32_t)p.sr_node.size());
+        }
+    }
+
     // ---- leaves
     p.leaf_sptr.push_back(0);
     for (int s = 0; s < nr; ++s) {

@@ -42,13 +42,16 @@ struct Plan {
 
     // Index tables (see EINET_TABLES): einsum items in execution order (bottom layer first); mixing items
     // grouped by the layer whose einsum they follow; leaves; top-down items (sum layers from the root
-    // down, then the leaves) with, per region, the runs of posterior blocks its parents write; M-step rows.
+    // down, then the leaves) with, per region, the runs of posterior blocks its parents write; M-step rows;
+    // sampling items: every sum region with the einsum items of its partitions (sr_item[sr_pptr[r] ..], in the
+    // order of the region's mixing weights) and its mixing item (sr_mix, -1 for a single partition).
 #define X(name) std::vector<int32_t> name;
     EINET_TABLES(X)
 #undef X
     std::vector<int32_t> ein_layer_ptr;             // [num_layers+1]
     std::vector<int32_t> mix_layer_ptr;             // [num_layers+1]
     std::vector<int32_t> rb_layer_ptr;              // [num_layers+2]
+    std::vector<int32_t> sr_layer_ptr;              // [num_layers+1]: sampling items (sum regions) per layer, bottom-up
 
     // ABI view data
     std::vector<int32_t> scope_ptr, scope_var, layer_partition, layer_ptr, partition_flat;
