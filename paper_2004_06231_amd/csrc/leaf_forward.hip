@@ -443,28 +443,31 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
+                    // a pair beyond the scope repeats the last one with all constants zero: its terms are zero
+                    const bool in = p + q * nparts < np;
                     const float* th = theta + ((size_t)(var[q] * d.C + (pq[q] - vq[q] * d.C)) * d.R + r) * tstride + k;
-                    t0[q] = th[0];
-                    t1[q] = th[d.K];
-                    t2[q] = gauss ? th[2 * d.K] : 0.f;
+                    t0[q] = in ? th[0] : 0.f;
+                    t1[q] = in ? th[d.K] : 0.f;
+                    t2[q] = (in && gauss) ? th[2 * d.K] : 0.f;
                 }
+                if (gauss) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (p + q * nparts >= np) break;
-                    if (gauss) {
+                    for (int q = 0; q < 4; ++q)
 #pragma unroll
                         for (int b = 0; b < LEAF_RED; ++b) {
                             const float diff = xs[b * np + pq[q]] - t0[q];
                             acc[b] += ob[b * nv + vq[q]] * fmaf(t1[q] * diff, diff, t2[q]);
                         }
-                    } else {
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
 #pragma unroll
                         for (int b = 0; b < LEAF_RED; ++b) {
                             const float xv = xs[b * np + pq[q]];
+                            // (nf * t1 is zero for a pair beyond the scope: both logarithms were set to zero)
                             acc[b] += ob[b * nv + vq[q]] * (xv * t0[q] + (nf - xv) * t1[q]);
-                            if (base) hacc[b] += ob[b * nv + vq[q]] * leaf_base(logc, xv, d.P);
+                            if (base && p + q * nparts < np) hacc[b] += ob[b * nv + vq[q]] * leaf_base(logc, xv, d.P);
                         }
-                    }
                 }
             }
         }
