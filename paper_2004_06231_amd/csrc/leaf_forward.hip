@@ -397,18 +397,19 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
     const int nparts = 1024 / d.K;
     double* val = lds_d;                                  // [LEAF_RED][K] finished entries
     float* red = reinterpret_cast<float*>(val + LEAF_RED * d.K);   // [nparts][LEAF_RED][K]
-    float* xs = red + (size_t)nparts * LEAF_RED * d.K;     // [LEAF_RED][np] values, zeros where unused
-    float* ob = xs + (size_t)LEAF_RED * max_scope * d.C;   // [LEAF_RED][nv] 1 = observed
+    // pair-major: the LEAF_RED samples of a pair (a variable) are contiguous and are read with 16-byte loads
+    float* xs = red + (size_t)nparts * LEAF_RED * d.K;     // [np][LEAF_RED] values, zeros where unused
+    float* ob = xs + (size_t)LEAF_RED * max_scope * d.C;   // [nv][LEAF_RED] 1 = observed
     for (int idx = tid; idx < LEAF_RED * np; idx += 1024) {
         const int b = idx / np, p = idx - b * np, v = p / d.C, c = p - v * d.C;
-        xs[idx] = b < nbs ? x[((size_t)(b0 + b) * d.D + leaf_var[s0 + v]) * d.C + c] : 0.f;
+        xs[p * LEAF_RED + b] = b < nbs ? x[((size_t)(b0 + b) * d.D + leaf_var[s0 + v]) * d.C + c] : 0.f;
     }
     for (int idx = tid; idx < LEAF_RED * nv; idx += 1024) {
         const int b = idx / nv, v = idx - b * nv;
         float o = 1.f;
         if (b < nbs && mask_mode == EINET_MASK_SHARED) o = mask[leaf_var[s0 + v]] ? 1.f : 0.f;
         if (b < nbs && mask_mode == EINET_MASK_PER_SAMPLE) o = mask[(size_t)(b0 + b) * d.D + leaf_var[s0 + v]] ? 1.f : 0.f;
-        ob[idx] = o;
+        ob[v * LEAF_RED + b] = o;
     }
     __syncthreads();
     const int k = tid % d.K, part = tid / d.K;
@@ -424,7 +425,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
                 const float* th = theta + ((size_t)(leaf_var[s0 + v] * d.C + c) * d.R + r) * tstride + k;
 #pragma unroll
                 for (int b = 0; b < LEAF_RED; ++b)
-                    acc[b] += ob[b * nv + v] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + p], th, d.K, d.P);
+                    acc[b] += ob[v * LEAF_RED + b] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[p * LEAF_RED + b], th, d.K, d.P);
             }
         } else {
             // Four pairs per round: their variable numbers are requested together, then their constants, so that
@@ -450,24 +451,38 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
                     t1[q] = in ? th[d.K] : 0.f;
                     t2[q] = (in && gauss) ? th[2 * d.K] : 0.f;
                 }
+                static_assert(LEAF_RED == 8, "two 16-byte reads per pair");
                 if (gauss) {
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 xa = *reinterpret_cast<const float4*>(xs + pq[q] * LEAF_RED);
+                        const float4 xb = *reinterpret_cast<const float4*>(xs + pq[q] * LEAF_RED + 4);
+                        const float4 oa = *reinterpret_cast<const float4*>(ob + vq[q] * LEAF_RED);
+                        const float4 oc = *reinterpret_cast<const float4*>(ob + vq[q] * LEAF_RED + 4);
+                        const float xv[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+                        const float ov[8] = {oa.x, oa.y, oa.z, oa.w, oc.x, oc.y, oc.z, oc.w};
 #pragma unroll
                         for (int b = 0; b < LEAF_RED; ++b) {
-                            const float diff = xs[b * np + pq[q]] - t0[q];
-                            acc[b] += ob[b * nv + vq[q]] * fmaf(t1[q] * diff, diff, t2[q]);
+                            const float diff = xv[b] - t0[q];
+                            acc[b] += ov[b] * fmaf(t1[q] * diff, diff, t2[q]);
                         }
+                    }
                 } else {
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 xa = *reinterpret_cast<const float4*>(xs + pq[q] * LEAF_RED);
+                        const float4 xb = *reinterpret_cast<const float4*>(xs + pq[q] * LEAF_RED + 4);
+                        const float4 oa = *reinterpret_cast<const float4*>(ob + vq[q] * LEAF_RED);
+                        const float4 oc = *reinterpret_cast<const float4*>(ob + vq[q] * LEAF_RED + 4);
+                        const float xv[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+                        const float ov[8] = {oa.x, oa.y, oa.z, oa.w, oc.x, oc.y, oc.z, oc.w};
 #pragma unroll
                         for (int b = 0; b < LEAF_RED; ++b) {
-                            const float xv = xs[b * np + pq[q]];
                             // (nf * t1 is zero for a pair beyond the scope: both logarithms were set to zero)
-                            acc[b] += ob[b * nv + vq[q]] * (xv * t0[q] + (nf - xv) * t1[q]);
-                            if (base && p + q * nparts < np) hacc[b] += ob[b * nv + vq[q]] * leaf_base(logc, xv, d.P);
+                            acc[b] += ov[b] * (xv[b] * t0[q] + (nf - xv[b]) * t1[q]);
+                            if (base && p + q * nparts < np) hacc[b] += ov[b] * leaf_base(logc, xv[b], d.P);
                         }
+                    }
                 }
             }
         }
