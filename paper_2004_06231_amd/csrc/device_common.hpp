@@ -28,6 +28,15 @@ namespace einet_impl {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// Raises the dynamic-LDS limit of a kernel.  A refusal is not kept as the thread's last error: the launch
+// that needs the memory then fails and reports it, instead of a later, unrelated call.
+template <class Kernel>
+inline void allow_dynamic_lds(Kernel kernel, size_t bytes) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)bytes) != hipSuccess)
+        (void)hipGetLastError();
+}
+
 // Workgroups of a launch are handed to the 8 XCDs round-robin by blockIdx.x, and every XCD has an L2 of its own.
 // This renumbering gives each XCD a contiguous range of work items, so that neighbouring items (the workgroups
 // of one partition, which read the same child rows) meet in one L2.  It is a bijection on [0, gridDim.x).

@@ -436,14 +436,10 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
     const size_t lds = sizeof(float) * BwdLayout<KQ>::LDS_FLOATS;
     static bool attr_set = false;
     if (lds > 64 * 1024 && !attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, true, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, false, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, true, false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_backward<KQ, false, false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        allow_dynamic_lds(&k_einsum_backward<KQ, true, true>, lds);
+        allow_dynamic_lds(&k_einsum_backward<KQ, false, true>, lds);
+        allow_dynamic_lds(&k_einsum_backward<KQ, true, false>, lds);
+        allow_dynamic_lds(&k_einsum_backward<KQ, false, false>, lds);
         attr_set = true;
     }
     const int ngroups = bwd_groups_per_item(count, d.K);

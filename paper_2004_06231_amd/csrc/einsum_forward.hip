@@ -283,8 +283,7 @@ static void launch_einsum_forward_kq(const DevTables& t, int first, int count, c
     const size_t lds = sizeof(float) * FwdLayout<KQ>::LDS_FLOATS;
     static bool attr_set = false;
     if (lds > 64 * 1024 && !attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_einsum_forward<KQ>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        allow_dynamic_lds(&k_einsum_forward<KQ>, lds);
         attr_set = true;
     }
     hipLaunchKernelGGL(k_einsum_forward<KQ>, dim3(count * nkt), dim3(64 * nw), lds, s, t.ein_left + first,

@@ -227,8 +227,7 @@ void launch_sample_regions(const DevTables& t, int first, int count, bool eviden
     const size_t lds = sizeof(float) * SAMPLE_WAVES * (size_t)(KK + (KK >> 5) + 1 + 128);   // at most 68 KB (K = 64)
     static bool attr_set = false;
     if (lds > 64 * 1024 && !attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sample_regions),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024);
+        allow_dynamic_lds(&k_sample_regions, 72 * 1024);
         attr_set = true;
     }
     hipLaunchKernelGGL(k_sample_regions, dim3(count, (d.B + SAMPLE_WAVES - 1) / SAMPLE_WAVES), dim3(64 * SAMPLE_WAVES),

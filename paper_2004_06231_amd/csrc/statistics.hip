@@ -298,10 +298,8 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
     const size_t lds = cells ? cell_lds_bytes(d.K, ppt) : 0;
     static bool attr_set = false;
     if (cells && !attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_backward<0, 1>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_backward<0, 4>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        allow_dynamic_lds(&k_tail_backward<0, 1>, 64 * 1024);
+        allow_dynamic_lds(&k_tail_backward<0, 4>, 128 * 1024);
         attr_set = true;
     }
 #define EINET_LAUNCH(N, P)                                                                                           \

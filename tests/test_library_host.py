@@ -95,3 +95,15 @@ def test_calls_before_bind_fail_cleanly():
         if torch.cuda.is_available():
             raise RuntimeError("GPU present: bind would succeed")
         m.bind()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU; bench.py says so and exits before it touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert r.stdout.strip() == ""
