@@ -185,22 +185,23 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
 // ------------------------------------------------------------------ mixing layer, forward (App. B)
 // Offset of the output: the largest offset of the children (their residuals are at most 0, so no term
 // exceeds its weight); residual: log sum_c v[c] exp((Off[c] - Off[out]) + A[c]).
-constexpr int MIX_UNROLL = 8;
-__global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32_t* __restrict__ m_kout,
-                                 const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
-                                 const int32_t* __restrict__ m_voff, const float* __restrict__ params,
+constexpr int MIX_UNROLL = MIX_REC_CHILDREN;
+__global__ void k_mixing_forward(const int32_t* __restrict__ m_rec, const float* __restrict__ params,
                                  float* __restrict__ A, double* __restrict__ Off, float* __restrict__ logp, int B,
                                  int K) {
-    const int item = blockIdx.x;
-    const int kout = m_kout[item];
+    // the item's record: node, entries, weight offset, number of partitions, partition nodes
+    const int32_t* rec = m_rec + (size_t)blockIdx.x * MIX_REC_INTS;
+    const int node = rec[0], kout = rec[1], nc = rec[3];
+    int child[MIX_UNROLL];
+#pragma unroll
+    for (int c = 0; c < MIX_UNROLL; ++c) child[c] = rec[4 + c];
     const int e = blockIdx.y * blockDim.x + threadIdx.x;
     if (e >= B * kout) return;
     const int b = e / kout, k = e - b * kout;
-    const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
-    const float* v = params + m_voff[item] + (size_t)k * nc;
+    const float* v = params + rec[2] + (size_t)k * nc;
     double m = -INFINITY;
     float s = 0.f;
-    if (nc <= MIX_UNROLL) {
+    {
         // offsets, residuals and weights of all children are requested together: one memory latency, not two
         double off[MIX_UNROLL];
         float a[MIX_UNROLL], w[MIX_UNROLL];
@@ -209,7 +210,7 @@ __global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32
             off[c] = 0.0;
             a[c] = w[c] = 0.f;
             if (c < nc) {
-                const size_t row = (size_t)m_child[c0 + c] * B + b;
+                const size_t row = (size_t)child[c] * B + b;
                 off[c] = Off[row];
                 a[c] = A[row * K + k];
                 w[c] = v[c];
@@ -221,19 +222,13 @@ __global__ void k_mixing_forward(const int32_t* __restrict__ m_node, const int32
 #pragma unroll
         for (int c = 0; c < MIX_UNROLL; ++c)
             if (c < nc) s += w[c] * expf((float)(off[c] - m) + a[c]);
-    } else {
-        for (int c = 0; c < nc; ++c) m = fmax(m, Off[(size_t)m_child[c0 + c] * B + b]);
-        for (int c = 0; c < nc; ++c) {
-            const size_t row = (size_t)m_child[c0 + c] * B + b;
-            s += v[c] * expf((float)(Off[row] - m) + A[row * K + k]);
-        }
     }
     const float res = logf(s);
-    const size_t row = (size_t)m_node[item] * B + b;
+    const size_t row = (size_t)node * B + b;
     A[row * K + k] = res;
     if (k == 0) {
         Off[row] = m;
-        if (logp && m_node[item] == 0) logp[b] = (float)(m + (double)res);   // node 0: the root region, one entry
+        if (logp && node == 0) logp[b] = (float)(m + (double)res);   // node 0: the root region, one entry
     }
 }
 
@@ -313,8 +308,8 @@ void launch_mixing_forward(const DevTables& t, int first, int count, int max_chi
         return;
     }
     dim3 grid(count, (d.B * d.K + 255) / 256);
-    hipLaunchKernelGGL(k_mixing_forward, grid, dim3(256), 0, s, t.mix_node + first, t.mix_kout + first,
-                       t.mix_cptr + first, t.mix_child, t.mix_voff + first, params, A, Off, logp, d.B, d.K);
+    hipLaunchKernelGGL(k_mixing_forward, grid, dim3(256), 0, s, t.mix_rec + (size_t)first * MIX_REC_INTS, params, A,
+                       Off, logp, d.B, d.K);
 }
 
 }  // namespace einet_impl

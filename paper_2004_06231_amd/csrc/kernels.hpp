@@ -14,7 +14,7 @@ namespace einet_impl {
 // the float32 bit patterns of log C(N, v), v = 0..N, for binomial leaves.
 #define EINET_TABLES(X)                                                                                    \
     X(ein_left) X(ein_right) X(ein_out) X(ein_reg) X(ein_kout) X(ein_woff) X(ein_voff) X(ein_vstr) X(ein_part) \
-    X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff)                                           \
+    X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff) X(mix_rec)                                \
     X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
     X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len) X(leaf_logc)                         \
     X(sr_node) X(sr_pptr) X(sr_item) X(sr_mix)
@@ -37,6 +37,10 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
 // logp (may be NULL): the launch that produces the root value also writes it there
 void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
                            float* amax, float* logp, const Dims& d, hipStream_t s);
+// A mixing item with at most MIX_REC_CHILDREN partitions also has a record of MIX_REC_INTS ints in mix_rec:
+// node, entries, offset of its weights, number of partitions, then the nodes of the partitions.  The kernel gets
+// all of it with one request instead of walking three tables one after the other.
+constexpr int MIX_REC_CHILDREN = 8, MIX_REC_INTS = 16;
 // max_children: the largest number of partitions of a region of these items
 void launch_mixing_forward(const DevTables& t, int first, int count, int max_children, const float* params, float* A,
                            double* Off, float* logp, const Dims& d, hipStream_t s);

@@ -280,6 +280,18 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param
         p.mix_layer_ptr.push_back((int32_t)p.mix_node.size());
     }
 
+    // ---- one record per mixing item (see MIX_REC_INTS)
+    p.mix_rec.assign(p.mix_node.size() * MIX_REC_INTS, -1);
+    for (size_t i = 0; i < p.mix_node.size(); ++i) {
+        int32_t* rec = p.mix_rec.data() + i * MIX_REC_INTS;
+        const int nc = p.mix_cptr[i + 1] - p.mix_cptr[i];
+        rec[0] = p.mix_node[i];
+        rec[1] = p.mix_kout[i];
+        rec[2] = p.mix_voff[i];
+        rec[3] = nc;
+        for (int c = 0; c < nc && c < MIX_REC_CHILDREN; ++c) rec[4 + c] = p.mix_child[p.mix_cptr[i] + c];
+    }
+
     // ---- sampling items: the sum regions layer by layer, each with the einsum items of its partitions
     {
         std::vector<int> mix_of(nr, -1);
