@@ -10,28 +10,41 @@ namespace {
 // G[region][b][k] = sum of the posterior blocks its parent partitions wrote (1 at
 // the root).  Element-wise, one thread per (region, b, k); summing here instead of
 // scattering from the producers keeps the pass free of atomics.
-__global__ void k_region_assemble(const int32_t* __restrict__ r_node, const int32_t* __restrict__ r_kout,
-                                  const int32_t* __restrict__ r_pptr, const int32_t* __restrict__ r_pblk,
-                                  int is_root, float* __restrict__ G, const float* __restrict__ Gp, int B, int K) {
-    const int item = blockIdx.x;
-    const int kout = r_kout[item];
+__global__ void k_region_assemble(const int32_t* __restrict__ r_rec, const int32_t* __restrict__ r_pblk, int is_root,
+                                  float* __restrict__ G, const float* __restrict__ Gp, int B, int K) {
+    // the region's record: node, entries, number of parent blocks, start of its block list, first block numbers
+    const int32_t* rec = r_rec + (size_t)blockIdx.x * RB_REC_INTS;
+    const int node = rec[0], kout = rec[1], cnt = rec[2];
     const int e = blockIdx.y * blockDim.x + threadIdx.x;
     if (e >= B * kout) return;
     const int b = e / kout, k = e - b * kout;
     const size_t blk = (size_t)B * K, o = (size_t)b * K + k;
     float g = is_root ? 1.f : 0.f;
-    const int p1 = r_pptr[item + 1];
-    // sixteen blocks per round, all requested before the first is added: a region of a Poon-Domingos structure
-    // has a few dozen parent blocks, and one memory latency per block would be the whole kernel
-    for (int p0 = r_pptr[item]; p0 < p1; p0 += 16) {
+    // Fourteen blocks per round, all requested before the first is added: a region of a Poon-Domingos structure
+    // has a few dozen parent blocks, and one memory latency per block would be the whole kernel.  The numbers of
+    // the first 28 blocks come with the record, so that the blocks are the second request, not the third.
+    constexpr int RND = RB_REC_BLOCKS / 2;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        if (r * RND < cnt) {
+            float v[RND];
+#pragma unroll
+            for (int q = 0; q < RND; ++q) v[q] = r * RND + q < cnt ? Gp[(size_t)rec[4 + r * RND + q] * blk + o] : 0.f;
+#pragma unroll
+            for (int q = 0; q < RND; ++q)
+                if (r * RND + q < cnt) g += v[q];
+        }
+    }
+    for (int p0 = RB_REC_BLOCKS; p0 < cnt; p0 += 16) {   // the rest of a very long list
+        const int32_t* list = r_pblk + rec[3];
         float v[16];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) v[q] = p0 + q < p1 ? Gp[(size_t)r_pblk[p0 + q] * blk + o] : 0.f;
+        for (int q = 0; q < 16; ++q) v[q] = p0 + q < cnt ? Gp[(size_t)list[p0 + q] * blk + o] : 0.f;
 #pragma unroll
         for (int q = 0; q < 16; ++q)
-            if (p0 + q < p1) g += v[q];
+            if (p0 + q < cnt) g += v[q];
     }
-    G[(size_t)r_node[item] * blk + o] = g;
+    G[(size_t)node * blk + o] = g;
 }
 
 // ------------------------------------------------------------------ top-down pass, einsum items
@@ -425,8 +438,8 @@ void launch_region_assemble(const DevTables& t, int first, int count, bool is_ro
                             const Dims& d, hipStream_t s) {
     if (count == 0) return;
     dim3 grid(count, (d.B * d.K + 255) / 256);
-    hipLaunchKernelGGL(k_region_assemble, grid, dim3(256), 0, s, t.rb_node + first, t.rb_kout + first,
-                       t.rb_pptr + first, t.rb_pblk, is_root_layer ? 1 : 0, G, Gp, d.B, d.K);
+    hipLaunchKernelGGL(k_region_assemble, grid, dim3(256), 0, s, t.rb_rec + (size_t)first * RB_REC_INTS, t.rb_pblk,
+                       is_root_layer ? 1 : 0, G, Gp, d.B, d.K);
 }
 
 template <int KQ>

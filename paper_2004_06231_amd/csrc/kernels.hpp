@@ -17,7 +17,7 @@ namespace einet_impl {
     X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff) X(mix_rec)                                \
     X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
     X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len) X(leaf_logc)                         \
-    X(sr_node) X(sr_pptr) X(sr_item) X(sr_mix)
+    X(sr_node) X(sr_pptr) X(sr_item) X(sr_mix) X(rb_rec)
 
 struct DevTables {
 #define X(name) const int32_t* name;
@@ -45,6 +45,9 @@ constexpr int MIX_REC_CHILDREN = 8, MIX_REC_INTS = 16;
 void launch_mixing_forward(const DevTables& t, int first, int count, int max_children, const float* params, float* A,
                            double* Off, float* logp, const Dims& d, hipStream_t s);
 
+// Every top-down region also has a record of RB_REC_INTS ints in rb_rec: node, entries, number of parent blocks,
+// position of its list in rb_pblk, then the first RB_REC_BLOCKS block numbers (the rest, if any, only in the list).
+constexpr int RB_REC_INTS = 32, RB_REC_BLOCKS = 28;
 void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
                             const Dims& d, hipStream_t s);
 // accumulate = false: the weight statistics of these items are known to be zero and are overwritten

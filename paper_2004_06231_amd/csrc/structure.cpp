@@ -356,6 +356,18 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param
     for (int s : p.leaf_node) push_region(s);
     p.rb_layer_ptr.push_back((int32_t)p.rb_node.size());
 
+    // ---- one record per top-down region (see RB_REC_INTS)
+    p.rb_rec.assign(p.rb_node.size() * RB_REC_INTS, 0);
+    for (size_t i = 0; i < p.rb_node.size(); ++i) {
+        int32_t* rec = p.rb_rec.data() + i * RB_REC_INTS;
+        const int cnt = p.rb_pptr[i + 1] - p.rb_pptr[i];
+        rec[0] = p.rb_node[i];
+        rec[1] = p.rb_kout[i];
+        rec[2] = cnt;
+        rec[3] = p.rb_pptr[i];
+        for (int q = 0; q < cnt && q < RB_REC_BLOCKS; ++q) rec[4 + q] = p.rb_pblk[p.rb_pptr[i] + q];
+    }
+
     // ---- M-step rows
     for (int n = 0; n < np; ++n)
         for (int k = 0; k < kout(g.partition[n][0]); ++k) {
