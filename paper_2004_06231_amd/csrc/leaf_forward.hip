@@ -377,7 +377,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
 // parts, of magnitude 1e2..1e4, is taken in float64.
 __host__ __device__ inline size_t leaf_wide1_lds_bytes(int max_scope, int C, int K) {
     return sizeof(double) * ((size_t)LEAF_RED * K) +
-           sizeof(float) * ((size_t)(1024 / K) * LEAF_RED * K + (size_t)LEAF_RED * max_scope * (C + 1));
+           sizeof(float) * ((size_t)(1024 / K) * LEAF_RED * K + (size_t)LEAF_RED * max_scope * (C + 1) + max_scope);
 }
 
 __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __restrict__ leaf_node,
@@ -400,6 +400,8 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
     // pair-major: the LEAF_RED samples of a pair (a variable) are contiguous and are read with 16-byte loads
     float* xs = red + (size_t)nparts * LEAF_RED * d.K;     // [np][LEAF_RED] values, zeros where unused
     float* ob = xs + (size_t)LEAF_RED * max_scope * d.C;   // [nv][LEAF_RED] 1 = observed
+    int* vs = reinterpret_cast<int*>(ob + (size_t)LEAF_RED * max_scope);   // [nv] the leaf's variables
+    for (int v = tid; v < nv; v += 1024) vs[v] = leaf_var[s0 + v];
     for (int idx = tid; idx < LEAF_RED * np; idx += 1024) {
         const int b = idx / np, p = idx - b * np, v = p / d.C, c = p - v * d.C;
         xs[p * LEAF_RED + b] = b < nbs ? x[((size_t)(b0 + b) * d.D + leaf_var[s0 + v]) * d.C + c] : 0.f;
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
         if (d.family == EINET_LEAF_CATEGORICAL) {
             for (int p = part; p < np; p += nparts) {
                 const int v = p / d.C, c = p - v * d.C;
-                const float* th = theta + ((size_t)(leaf_var[s0 + v] * d.C + c) * d.R + r) * tstride + k;
+                const float* th = theta + ((size_t)(vs[v] * d.C + c) * d.R + r) * tstride + k;
 #pragma unroll
                 for (int b = 0; b < LEAF_RED; ++b)
                     acc[b] += ob[v * LEAF_RED + b] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[p * LEAF_RED + b], th, d.K, d.P);
@@ -440,7 +442,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
                 for (int q = 0; q < 4; ++q) {
                     pq[q] = min(p + q * nparts, np - 1);
                     vq[q] = pq[q] / d.C;
-                    var[q] = leaf_var[s0 + vq[q]];
+                    var[q] = vs[vq[q]];
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
