@@ -17,7 +17,7 @@ namespace einet_impl {
     X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff) X(mix_rec)                                \
     X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
     X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len) X(leaf_logc)                         \
-    X(sr_node) X(sr_pptr) X(sr_item) X(sr_mix) X(rb_rec)
+    X(sr_node) X(sr_pptr) X(sr_item) X(sr_mix) X(rb_rec) X(sr_rec)
 
 struct DevTables {
 #define X(name) const int32_t* name;
@@ -86,6 +86,12 @@ void launch_init_params(const DevTables& t, int n_rows, float* params, int64_t p
 // sample does not visit it.  u [num_partitions + num_regions][B]: the uniforms of the choices.
 // evidence = false: no forward pass has run, the choices follow the weights alone.
 void launch_sample_init(int32_t* sel, int num_nodes, int B, hipStream_t s);
+// A sampling item (sum region) with at most SR_REC_PARTS partitions also has a record of SR_REC_INTS ints in
+// sr_rec: node, number of partitions, offset of its mixing weights (-1: one partition), unused, then per partition
+// SR_REC_STRIDE ints: einsum item, left node, right node, offset of W, partition number, node of the partition's
+// own output (-1: the region itself), unused.  Regions with more partitions have nparts only (the kernel then walks
+// the tables).
+constexpr int SR_REC_INTS = 64, SR_REC_PARTS = 8, SR_REC_STRIDE = 7;
 // One launch per sum layer: for every region of the layer that a sample reaches, the choice of a partition
 // (regions with several) and then of a pair of child entries.  Items first .. first+count-1 of the sr_* tables.
 void launch_sample_regions(const DevTables& t, int first, int count, bool evidence, const float* params,

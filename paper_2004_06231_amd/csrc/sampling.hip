@@ -55,7 +55,7 @@ constexpr int SAMPLE_WAVES = 4;
 __device__ __forceinline__ int sample_pos(int t) { return t + (t >> 5); }   // padded: runs start in different banks
 
 __global__ __launch_bounds__(64 * SAMPLE_WAVES) void k_sample_regions(
-    const int32_t* __restrict__ sr_node, const int32_t* __restrict__ sr_pptr, const int32_t* __restrict__ sr_item,
+    const int32_t* __restrict__ sr_rec, const int32_t* __restrict__ sr_pptr, const int32_t* __restrict__ sr_item,
     const int32_t* __restrict__ sr_mix, const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
     const int32_t* __restrict__ m_voff, const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right,
     const int32_t* __restrict__ e_woff, const int32_t* __restrict__ e_part, int evidence,
@@ -66,27 +66,69 @@ __global__ __launch_bounds__(64 * SAMPLE_WAVES) void k_sample_regions(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ri = blockIdx.x, b = blockIdx.y * SAMPLE_WAVES + wave;
     if (b >= B) return;                              // whole waves leave: no barrier below
-    const int s = sr_node[ri];
+    // the region's record: node, partitions, mixing weights, and per partition its einsum item and nodes
+    const int32_t* rec = sr_rec + (size_t)ri * SR_REC_INTS;
+    const int s = rec[0], nparts = rec[1];
     const int k = sel[(size_t)s * B + b];
     if (k < 0) return;
-    const int mi = sr_mix[ri];
-    int c = 0;
-    if (mi >= 0) {
-        c = sample_partition(mi, s, k, b, m_cptr, m_child, m_voff, evidence, params, A, Off, u, num_partitions, B, K);
+    int item, left, right, woff, upart;
+    if (nparts <= SR_REC_PARTS) {
+        int c = 0;
+        if (nparts > 1) {
+            // partition c has weight v[k][c] * S^c[k] / S[k] given the evidence (App. B), v[k][c] without; every
+            // lane walks the few partitions and gets the same answer
+            const float* v = params + rec[2] + (size_t)k * nparts;
+            const size_t srow = (size_t)s * B + b;
+            float w[SR_REC_PARTS];
+#pragma unroll
+            for (int q = 0; q < SR_REC_PARTS; ++q) {
+                w[q] = 0.f;
+                if (q < nparts) {
+                    w[q] = v[q];
+                    if (evidence) {
+                        const size_t crow = (size_t)rec[4 + q * SR_REC_STRIDE + 5] * B + b;
+                        w[q] *= expf((float)(Off[crow] - Off[srow]) + A[crow * K + k] - A[srow * K + k]);
+                    }
+                }
+            }
+            float total = 0.f;
+#pragma unroll
+            for (int q = 0; q < SR_REC_PARTS; ++q)
+                if (q < nparts) total += w[q];
+            const float tau = u[(size_t)(num_partitions + s) * B + b] * total;
+            float run = 0.f;
+            int pick = -1, last = 0;
+#pragma unroll
+            for (int q = 0; q < SR_REC_PARTS; ++q)
+                if (q < nparts) {
+                    run += w[q];
+                    if (w[q] > 0.f) last = q;
+                    if (pick < 0 && run > tau) pick = q;
+                }
+            c = pick < 0 ? last : pick;                  // u so close to 1 that rounding ate the last interval
+            if (lane == 0) sel[(size_t)rec[4 + c * SR_REC_STRIDE + 5] * B + b] = k;
+        }
+        const int32_t* q = rec + 4 + c * SR_REC_STRIDE;
+        item = q[0], left = q[1], right = q[2], woff = q[3], upart = q[4];
+    } else {
+        const int mi = sr_mix[ri];
+        const int c = sample_partition(mi, s, k, b, m_cptr, m_child, m_voff, evidence, params, A, Off, u, num_partitions,
+                                       B, K);
         if (lane == 0) sel[(size_t)m_child[m_cptr[mi] + c] * B + b] = k;
+        item = sr_item[sr_pptr[ri] + c];
+        left = e_left[item], right = e_right[item], woff = e_woff[item], upart = e_part[item];
     }
-    const int item = sr_item[sr_pptr[ri] + c];       // einsum item of the chosen partition
     const int KK = K * K;
     float* wl = lds + wave * (sample_pos(KK) + 1 + 128);
     float* el = wl + sample_pos(KK) + 1;
     float* er = el + 64;
     if (evidence) {
         const float al = amax[(size_t)item * 2 * B + b], ar = amax[((size_t)item * 2 + 1) * B + b];
-        el[lane] = lane < K ? __expf(A[((size_t)e_left[item] * B + b) * K + lane] - al) : 0.f;
-        er[lane] = lane < K ? __expf(A[((size_t)e_right[item] * B + b) * K + lane] - ar) : 0.f;
+        el[lane] = lane < K ? __expf(A[((size_t)left * B + b) * K + lane] - al) : 0.f;
+        er[lane] = lane < K ? __expf(A[((size_t)right * B + b) * K + lane] - ar) : 0.f;
         __builtin_amdgcn_wave_barrier();
     }
-    const float* row = params + e_woff[item] + (size_t)k * KK;
+    const float* row = params + woff + (size_t)k * KK;
     for (int t = lane; t < KK; t += 64) {
         float w = row[t];
         if (evidence) {
@@ -107,7 +149,7 @@ __global__ __launch_bounds__(64 * SAMPLE_WAVES) void k_sample_regions(
         if (lane >= o) incl += up;
     }
     const float total = __shfl(incl, 63, 64);
-    const float tau = u[(size_t)e_part[item] * B + b] * total;
+    const float tau = u[(size_t)upart * B + b] * total;
     const unsigned long long hit = __ballot(incl > tau && t1 > t0);
     int pick = -1;
     if (hit != 0ull) {
@@ -135,8 +177,8 @@ __global__ __launch_bounds__(64 * SAMPLE_WAVES) void k_sample_regions(
     }
     if (lane == 0) {
         const int i = pick / K;
-        sel[(size_t)e_left[item] * B + b] = i;
-        sel[(size_t)e_right[item] * B + b] = pick - i * K;
+        sel[(size_t)left * B + b] = i;
+        sel[(size_t)right * B + b] = pick - i * K;
     }
 }
 
@@ -231,7 +273,7 @@ void launch_sample_regions(const DevTables& t, int first, int count, bool eviden
         attr_set = true;
     }
     hipLaunchKernelGGL(k_sample_regions, dim3(count, (d.B + SAMPLE_WAVES - 1) / SAMPLE_WAVES), dim3(64 * SAMPLE_WAVES),
-                       lds, s, t.sr_node + first, t.sr_pptr + first, t.sr_item, t.sr_mix + first, t.mix_cptr,
+                       lds, s, t.sr_rec + (size_t)first * SR_REC_INTS, t.sr_pptr + first, t.sr_item, t.sr_mix + first, t.mix_cptr,
                        t.mix_child, t.mix_voff, t.ein_left, t.ein_right, t.ein_woff, t.ein_part, evidence ? 1 : 0,
                        params, A, Off, amax, u, num_partitions, sel, d.B, d.K);
 }

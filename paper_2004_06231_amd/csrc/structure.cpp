@@ -309,6 +309,27 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param
         }
     }
 
+    // ---- one record per sampling item (see SR_REC_INTS)
+    p.sr_rec.assign(p.sr_node.size() * SR_REC_INTS, -1);
+    for (size_t i = 0; i < p.sr_node.size(); ++i) {
+        int32_t* rec = p.sr_rec.data() + i * SR_REC_INTS;
+        const int np_i = p.sr_pptr[i + 1] - p.sr_pptr[i];
+        rec[0] = p.sr_node[i];
+        rec[1] = np_i;
+        rec[2] = p.sr_mix[i] >= 0 ? p.mix_voff[p.sr_mix[i]] : -1;
+        if (np_i > SR_REC_PARTS) continue;
+        for (int c = 0; c < np_i; ++c) {
+            const int e = p.sr_item[p.sr_pptr[i] + c];
+            int32_t* q = rec + 4 + c * SR_REC_STRIDE;
+            q[0] = e;
+            q[1] = p.ein_left[e];
+            q[2] = p.ein_right[e];
+            q[3] = p.ein_woff[e];
+            q[4] = p.ein_part[e];
+            q[5] = p.ein_out[e] == p.sr_node[i] ? -1 : p.ein_out[e];
+        }
+    }
+
     // ---- leaves
     p.leaf_sptr.push_back(0);
     for (int s = 0; s < nr; ++s) {
