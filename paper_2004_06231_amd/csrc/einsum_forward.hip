@@ -65,14 +65,27 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
     const int n_btiles = (B + 15) >> 4;
     // stage W[4kt .. 4kt+3][.][.]
     if ((K & 3) == 0) {
-        for (int q = tid; q < 4 * KP * KQ; q += blockDim.x) {
-            const int j4 = q % KQ, i = (q / KQ) % KP, kl = q / (KQ * KP);
-            const int k = 4 * kt + kl;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k < kout && i < K) v = *reinterpret_cast<const float4*>(W + ((size_t)k * K + i) * K + 4 * j4);
-            float* dst = Wl + kl * SK + i * SJ + 4 * j4;
-            *reinterpret_cast<float2*>(dst) = make_float2(v.x, v.y);
-            *reinterpret_cast<float2*>(dst + 2) = make_float2(v.z, v.w);
+        // four 16-byte loads per thread in flight before the first goes to LDS
+        for (int q0 = tid; q0 < 4 * KP * KQ; q0 += 4 * blockDim.x) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = q0 + u * blockDim.x;
+                const int j4 = q % KQ, i = (q / KQ) % KP, kl = q / (KQ * KP);
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (q < 4 * KP * KQ && 4 * kt + kl < kout && i < K)
+                    v[u] = *reinterpret_cast<const float4*>(W + ((size_t)(4 * kt + kl) * K + i) * K + 4 * j4);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = q0 + u * blockDim.x;
+                if (q < 4 * KP * KQ) {
+                    const int j4 = q % KQ, i = (q / KQ) % KP, kl = q / (KQ * KP);
+                    float* dst = Wl + kl * SK + i * SJ + 4 * j4;
+                    *reinterpret_cast<float2*>(dst) = make_float2(v[u].x, v[u].y);
+                    *reinterpret_cast<float2*>(dst + 2) = make_float2(v[u].z, v[u].w);
+                }
+            }
         }
     } else {
         for (int q = tid; q < 4 * KP * KP; q += blockDim.x) {
