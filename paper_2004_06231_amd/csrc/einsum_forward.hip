@@ -88,12 +88,20 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
             }
         }
     } else {
-        for (int q = tid; q < 4 * KP * KP; q += blockDim.x) {
-            const int j = q % KP, i = (q / KP) % KP, kl = q / (KP * KP);
-            const int k = 4 * kt + kl;
-            float v = 0.f;
-            if (k < kout && i < K && j < K) v = W[((size_t)k * K + i) * K + j];
-            Wl[kl * SK + i * SJ + j] = v;
+        for (int q0 = tid; q0 < 4 * KP * KP; q0 += 8 * blockDim.x) {     // eight loads in flight, as above
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int q = q0 + u * blockDim.x;
+                const int j = q % KP, i = (q / KP) % KP, kl = q / (KP * KP);
+                v[u] = 0.f;
+                if (q < 4 * KP * KP && 4 * kt + kl < kout && i < K && j < K) v[u] = W[((size_t)(4 * kt + kl) * K + i) * K + j];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int q = q0 + u * blockDim.x;
+                if (q < 4 * KP * KP) Wl[(q / (KP * KP)) * SK + ((q / KP) % KP) * SJ + q % KP] = v[u];
+            }
         }
     }
     __syncthreads();

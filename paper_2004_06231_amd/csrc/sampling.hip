@@ -129,13 +129,21 @@ __global__ __launch_bounds__(64 * SAMPLE_WAVES) void k_sample_regions(
         __builtin_amdgcn_wave_barrier();
     }
     const float* row = params + woff + (size_t)k * KK;
-    for (int t = lane; t < KK; t += 64) {
-        float w = row[t];
-        if (evidence) {
-            const int i = t / K, j = t - i * K;
-            w *= el[i] * er[j];
+    for (int t0 = lane; t0 < KK; t0 += 8 * 64) {      // eight loads in flight per lane
+        float w[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) w[q] = t0 + 64 * q < KK ? row[t0 + 64 * q] : 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int t = t0 + 64 * q;
+            if (t < KK) {
+                if (evidence) {
+                    const int i = t / K, j = t - i * K;
+                    w[q] *= el[i] * er[j];
+                }
+                wl[sample_pos(t)] = w[q];
+            }
         }
-        wl[sample_pos(t)] = w;
     }
     __builtin_amdgcn_wave_barrier();                 // a wave reads back only its own part of LDS
     const int chunk = (KK + 63) >> 6;

@@ -182,7 +182,14 @@ __device__ __forceinline__ void leaf_backward_cells_body(
     for (int b0 = 0; b0 < d.B; b0 += CELL_BC) {
         const int nb = min(CELL_BC, d.B - b0);
         if (b0 > 0) __syncthreads();                  // readers of the previous pass are done
-        for (int i = tid; i < nb * d.K; i += 1024) Gs[i] = Gl[(size_t)b0 * d.K + i];
+        for (int i0 = tid; i0 < nb * d.K; i0 += 4 * 1024) {      // four loads in flight per thread
+            float gq[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) gq[q] = i0 + q * 1024 < nb * d.K ? Gl[(size_t)b0 * d.K + i0 + q * 1024] : 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (i0 + q * 1024 < nb * d.K) Gs[i0 + q * 1024] = gq[q];
+        }
 #pragma unroll 4
         for (int i = tid; i < nb * np; i += 1024) {
             const int bb = i / np, p = i - bb * np;
