@@ -521,6 +521,104 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
     }
 }
 
+// The same kernel in the form that needs at most 64 vector registers (values sample-major in LDS, read one by one,
+// one pair at a time), so that two workgroups share a compute unit: for launches of more workgroups than the chip
+// has room for at once, where occupancy counts for more than the shorter dependency chains of the kernel above.
+__global__ __launch_bounds__(1024, 8) void k_leaf_forward_wide1_lean(const int32_t* __restrict__ leaf_node,
+                                                            const int32_t* __restrict__ leaf_replica,
+                                                            const int32_t* __restrict__ leaf_sptr,
+                                                            const int32_t* __restrict__ leaf_var,
+                                                            const float* __restrict__ x,
+                                                            const uint8_t* __restrict__ mask, int mask_mode,
+                                                            const float* __restrict__ theta,
+                                                            const int32_t* __restrict__ logc, float* __restrict__ A,
+                                                            double* __restrict__ Off, int max_scope, Dims d) {
+    extern __shared__ double lds_d[];
+    const int leaf = blockIdx.x, b0 = blockIdx.y * LEAF_RED, tid = threadIdx.x;
+    const int nbs = min(LEAF_RED, d.B - b0);
+    const int r = leaf_replica[leaf];
+    const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0, np = nv * d.C;
+    const int nparts = 1024 / d.K;
+    double* val = lds_d;                                  // [LEAF_RED][K] finished entries
+    float* red = reinterpret_cast<float*>(val + LEAF_RED * d.K);   // [nparts][LEAF_RED][K]
+    float* xs = red + (size_t)nparts * LEAF_RED * d.K;     // [LEAF_RED][np] values, zeros where unused
+    float* ob = xs + (size_t)LEAF_RED * max_scope * d.C;   // [LEAF_RED][nv] 1 = observed
+    for (int idx = tid; idx < LEAF_RED * np; idx += 1024) {
+        const int b = idx / np, p = idx - b * np, v = p / d.C, c = p - v * d.C;
+        xs[idx] = b < nbs ? x[((size_t)(b0 + b) * d.D + leaf_var[s0 + v]) * d.C + c] : 0.f;
+    }
+    for (int idx = tid; idx < LEAF_RED * nv; idx += 1024) {
+        const int b = idx / nv, v = idx - b * nv;
+        float o = 1.f;
+        if (b < nbs && mask_mode == EINET_MASK_SHARED) o = mask[leaf_var[s0 + v]] ? 1.f : 0.f;
+        if (b < nbs && mask_mode == EINET_MASK_PER_SAMPLE) o = mask[(size_t)(b0 + b) * d.D + leaf_var[s0 + v]] ? 1.f : 0.f;
+        ob[idx] = o;
+    }
+    __syncthreads();
+    const int k = tid % d.K, part = tid / d.K;
+    const size_t tstride = (size_t)d.TD * d.K;
+    const bool base = d.family == EINET_LEAF_BINOMIAL && k == 0;   // this thread also sums the binomial coefficients
+    float acc[LEAF_RED], hacc[LEAF_RED];
+#pragma unroll
+    for (int b = 0; b < LEAF_RED; ++b) acc[b] = hacc[b] = 0.f;
+    if (part < nparts) {
+        for (int p = part; p < np; p += nparts) {
+            const int v = p / d.C, c = p - v * d.C;
+            const float* th = theta + ((size_t)(leaf_var[s0 + v] * d.C + c) * d.R + r) * tstride + k;
+            if (d.family == EINET_LEAF_GAUSSIAN) {
+                const float mu = th[0], c1 = th[d.K], c0 = th[2 * d.K];
+#pragma unroll
+                for (int b = 0; b < LEAF_RED; ++b) {
+                    const float diff = xs[b * np + p] - mu;
+                    acc[b] += ob[b * nv + v] * fmaf(c1 * diff, diff, c0);
+                }
+            } else if (d.family == EINET_LEAF_CATEGORICAL) {
+#pragma unroll
+                for (int b = 0; b < LEAF_RED; ++b)
+                    acc[b] += ob[b * nv + v] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + p], th, d.K, d.P);
+            } else {
+                const float lp = th[0], l1p = th[d.K], nf = (float)d.P;
+#pragma unroll
+                for (int b = 0; b < LEAF_RED; ++b) {
+                    const float xv = xs[b * np + p];
+                    acc[b] += ob[b * nv + v] * (xv * lp + (nf - xv) * l1p);
+                    if (base) hacc[b] += ob[b * nv + v] * leaf_base(logc, xv, d.P);
+                }
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < LEAF_RED; ++b) red[(part * LEAF_RED + b) * d.K + k] = acc[b];
+    }
+    __syncthreads();
+    const bool fin = tid < LEAF_RED * d.K;
+    const int fb = fin ? tid / d.K : 0, kk = tid - fb * d.K;
+    const int nact = min(nparts, np);                // parts beyond the number of pairs hold zeros
+    double sum = 0.0;
+    if (fin) {
+        for (int q = 0; q < nact; ++q) sum += (double)red[(q * LEAF_RED + fb) * d.K + kk];
+        val[fb * d.K + kk] = sum;
+    }
+    __syncthreads();
+    if (base && part < nparts) {                     // (after the barrier: the sums above have been read)
+#pragma unroll
+        for (int b = 0; b < LEAF_RED; ++b) red[(part * LEAF_RED + b) * d.K] = hacc[b];
+    }
+    if (d.family == EINET_LEAF_BINOMIAL) __syncthreads();
+    if (fin && fb < nbs) {
+        double m = -INFINITY;
+        for (int q = 0; q < d.K; ++q) m = fmax(m, val[fb * d.K + q]);
+        if (m == -INFINITY) m = 0.0;
+        const size_t row = (size_t)leaf_node[leaf] * d.B + b0 + fb;
+        A[row * d.K + kk] = (float)(sum - m);
+        if (kk == 0) {
+            double h = 0.0;
+            if (d.family == EINET_LEAF_BINOMIAL)
+                for (int q = 0; q < nact; ++q) h += (double)red[(q * LEAF_RED + fb) * d.K];
+            Off[row] = m + h;
+        }
+    }
+}
+
 }  // namespace
 
 void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream_t s) {
@@ -538,9 +636,16 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
         const bool multi = max_scope > leaf_chunk_vars(max_scope, d.C), masked = mask_mode != EINET_MASK_NONE;
         dim3 grid(n_leaves, (d.B + LEAF_RED - 1) / LEAF_RED);
         if (!multi) {
-            hipLaunchKernelGGL(k_leaf_forward_wide1, grid, dim3(1024), leaf_wide1_lds_bytes(max_scope, d.C, d.K), s,
-                               t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, x, mask, mask_mode, theta,
-                               t.leaf_logc, A, Off, max_scope, d);
+            // up to two workgroups per compute unit fit whatever their registers: the kernel with the batched loads
+            if ((size_t)grid.x * grid.y <= 512)
+                hipLaunchKernelGGL(k_leaf_forward_wide1, grid, dim3(1024), leaf_wide1_lds_bytes(max_scope, d.C, d.K), s,
+                                   t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, x, mask, mask_mode, theta,
+                                   t.leaf_logc, A, Off, max_scope, d);
+            else
+                hipLaunchKernelGGL(k_leaf_forward_wide1_lean, grid, dim3(1024),
+                                   leaf_wide1_lds_bytes(max_scope, d.C, d.K), s, t.leaf_node, t.leaf_replica,
+                                   t.leaf_sptr, t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off, max_scope,
+                                   d);
             return;
         }
         const size_t lds = leaf_wide_lds_bytes(max_scope, d.C, d.K, LEAF_RED);
