@@ -156,7 +156,11 @@ int einet_structure(const einet_t* h, einet_structure_view* view);
  * the index tables into the workspace on `stream`, synchronising once.  The
  * buffers stay owned by the caller and must outlive every later call.  The
  * parameter buffer may be uninitialised at this point; call einet_refresh
- * after writing it. */
+ * after writing it.  The statistics buffer is taken as it is (statistics to be
+ * continued), with one exception: binding again the very buffer that an
+ * einet_em_update on this handle has consumed keeps it logically zero.  A copy
+ * of such a buffer holds unspecified einsum-weight statistics (see
+ * einet_em_update): call einet_em_reset after binding it. */
 int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_dev, void* stream);
 
 /* Recomputes what the kernels derive from the parameters (per leaf entry:

@@ -84,10 +84,15 @@ def ef_log_density(family, x, phi, leaf_param=0):
             out = out + np.where(Tx[v] != 0, theta[v], 0.0)
         return out
     if family == BERNOULLI:
-        p = phi[0]
-        theta = np.log(p) - np.log1p(-p)        # natural parameter
-        A = -np.log1p(-p)                       # log-normaliser
-        return x * theta - A                    # h(x) = 1, T(x) = x
+        # h(x) = 1, T(x) = x, theta = log p - log(1-p), A = -log(1-p):  x theta - A = x log p + (1-x) log(1-p).
+        # Written in the second form so that the boundary of the parameter space (p = 0 or 1, where theta is
+        # infinite) gives the density p^x (1-p)^(1-x) itself: an exponent of 0 contributes log 1 = 0.
+        p = phi[0] + 0.0 * x
+        xx = x + 0.0 * p
+        with np.errstate(divide="ignore", invalid="ignore"):
+            a = np.where(xx != 0, xx * np.log(p), 0.0)
+            b = np.where(xx != 1, (1.0 - xx) * np.log1p(-p), 0.0)
+        return a + b
     if family == GAUSSIAN:
         mu = phi[0]
         var = phi[1] - phi[0] ** 2              # phi = (E[x], E[x^2])
@@ -193,7 +198,7 @@ class OracleEiNet:
                     for c in range(self.C):
                         e = ef_log_density(self.family, x[:, d, c][:, None],
                                            self.phi[d, c, r][:, None, :], self.leaf_param)      # [B, K]
-                        acc += m[:, d][:, None] * e
+                        acc += np.where(m[:, d][:, None] != 0, e, 0.0)      # marginalised: factor 1, whatever e is
                 N[s] = acc
                 continue
             simple = []

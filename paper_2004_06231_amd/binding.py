@@ -205,29 +205,41 @@ class EiNet:
     def _mask_args(self, mask, B):
         if mask is None:
             return None, MASK_NONE
+        D = int(self.structure()["num_vars"])
         assert mask.dtype == self._torch.uint8 and mask.is_cuda and mask.is_contiguous()
         if mask.dim() == 1:
+            assert tuple(mask.shape) == (D,), f"shared mask must have shape ({D},)"
             return C.c_void_p(mask.data_ptr()), MASK_SHARED
-        assert mask.shape[0] == B
+        assert tuple(mask.shape) == (B, D), f"per-sample mask must have shape ({B}, {D})"
         return C.c_void_p(mask.data_ptr()), MASK_PER_SAMPLE
+
+    def _batch_of(self, x):
+        """The C ABI sees pointers only: a tensor of another shape would be read out of bounds by the kernels."""
+        torch = self._torch
+        D = int(self.structure()["num_vars"])
+        assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous() and x.dim() == 3
+        assert tuple(x.shape[1:]) == (D, self.channels), f"x must have shape (B, {D}, {self.channels})"
+        return x.shape[0]
+
+    def _out_arg(self, t, n):
+        torch = self._torch
+        assert t.dtype == torch.float32 and t.is_cuda and t.is_contiguous() and t.numel() >= n
+        return C.c_void_p(t.data_ptr())
 
     def logp(self, x, mask=None, out=None):
         """x: cuda float32 [B, D, channels]; mask: cuda uint8 [D] or [B, D] (1 = observed) or None."""
         torch = self._torch
-        assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous() and x.dim() == 3
-        B = x.shape[0]
+        B = self._batch_of(x)
         if out is None:
             out = torch.empty(B, dtype=torch.float32, device=self.device)
         m, mode = self._mask_args(mask, B)
-        self._check(self._lib.einet_logp(self._h, x.data_ptr(), m, mode, B, out.data_ptr(), self._stream()))
+        self._check(self._lib.einet_logp(self._h, x.data_ptr(), m, mode, B, self._out_arg(out, B), self._stream()))
         return out
 
     def em_accumulate(self, x, mask=None, logp=None):
-        torch = self._torch
-        assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous() and x.dim() == 3
-        B = x.shape[0]
+        B = self._batch_of(x)
         m, mode = self._mask_args(mask, B)
-        lp = None if logp is None else C.c_void_p(logp.data_ptr())
+        lp = None if logp is None else self._out_arg(logp, B)
         self._check(self._lib.einet_em_accumulate(self._h, x.data_ptr(), m, mode, B, lp, self._stream()))
         return logp
 
@@ -239,11 +251,9 @@ class EiNet:
 
     def em_epoch(self, x, mask=None, batch=None, step=0.5, min_var=0.0, max_var=math.inf, w_floor=0.0, logp=None):
         """x: cuda float32 [N, D, channels], visited in mini-batches of `batch` (default max_batch) samples."""
-        torch = self._torch
-        assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous() and x.dim() == 3
-        N = x.shape[0]
+        N = self._batch_of(x)
         m, mode = self._mask_args(mask, N)
-        lp = None if logp is None else C.c_void_p(logp.data_ptr())
+        lp = None if logp is None else self._out_arg(logp, N)
         self._check(self._lib.einet_em_epoch(self._h, x.data_ptr(), m, mode, N, self.max_batch if batch is None else batch,
                                              step, min_var, max_var, w_floor, lp, self._stream()))
         return logp

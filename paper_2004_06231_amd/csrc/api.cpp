@@ -32,6 +32,7 @@ struct einet {
     bool profiling = false;
     struct Timed { int cls; hipEvent_t start, stop; };
     std::vector<Timed> timed;
+    int profile_dropped = 0;        // launches that could not be bracketed (event creation failed)
 
     // true while the einsum-weight statistics are logically zero: einet_em_update does not clear them,
     // the next einet_em_accumulate overwrites them instead of adding
@@ -128,6 +129,9 @@ void run(einet_t* h, int cls, hipStream_t s, F&& launch) {
     }
     einet::Timed t{cls, nullptr, nullptr};
     if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) {
+        (void)hipGetLastError();
+        if (t.start) (void)hipEventDestroy(t.start);
+        h->profile_dropped += 1;          // einet_profile_read reports it: the totals would be short
         launch();
         return;
     }
@@ -287,6 +291,9 @@ int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_
     hipError_t e = hipMemcpyAsync(workspace_dev, h->blob.data(), h->blob.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return fail(h, EINET_ERR_HIP, std::string("uploading index tables: ") + hipGetErrorString(e));
+    // Statistics that an M-step has consumed but not cleared in memory stay logically zero when the very same
+    // buffer is bound again; any other buffer is taken to hold statistics to be continued.
+    const bool same_stats = h->bound && h->stats == stats_dev;
     h->params = params_dev;
     h->stats = stats_dev;
     h->ws = static_cast<char*>(workspace_dev);
@@ -297,7 +304,7 @@ int einet_bind(einet_t* h, float* params_dev, float* stats_dev, void* workspace_
 #undef X
     h->bound = true;
     h->root_ones_batch = 0;
-    h->weight_stats_zero = false;   // the caller's buffer may hold statistics to be continued
+    h->weight_stats_zero = same_stats && h->weight_stats_zero;
     return EINET_OK;
 }
 
@@ -370,9 +377,12 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
                              (int)p.mix_node.size(), p.max_mix_children, x_dev, mask_dev,
                              mask_mode, h->params, A, Off, G, h->stats, p.phi_offset, p.den_offset, p.tot_offset, d, s);
     });
+    rc = check_hip(h, "einet_em_accumulate");
+    // (after a failed launch nothing is known about the arena or the statistics: the root's ones are written
+    // again next time, and the statistics are added to, never overwritten)
     h->weight_stats_zero = false;
-    h->root_ones_batch = B;
-    return check_hip(h, "einet_em_accumulate");
+    h->root_ones_batch = rc == EINET_OK ? B : 0;
+    return rc;
 }
 
 int einet_em_update(einet_t* h, float step, float min_var, float max_var, float w_floor, void* stream) {
@@ -386,16 +396,18 @@ int einet_em_update(einet_t* h, float step, float min_var, float max_var, float 
                          reinterpret_cast<float*>(h->ws + h->off_theta), p.phi_offset, p.den_offset, p.tot_offset,
                          step, min_var, max_var, w_floor, d, s);
     });
-    h->weight_stats_zero = true;
-    return check_hip(h, "einet_em_update");
+    rc = check_hip(h, "einet_em_update");
+    if (rc == EINET_OK) h->weight_stats_zero = true;
+    return rc;
 }
 
 int einet_em_reset(einet_t* h, void* stream) {
     if (!h) return EINET_ERR_INVALID_ARG;
     if (!h->bound) return fail(h, EINET_ERR_NOT_BOUND, "einet_bind has not been called");
     launch_fill(h->stats, 0.f, h->plan.n_stats, static_cast<hipStream_t>(stream));
-    h->weight_stats_zero = true;
-    return check_hip(h, "einet_em_reset");
+    const int rc = check_hip(h, "einet_em_reset");
+    h->weight_stats_zero = rc == EINET_OK;
+    return rc;
 }
 
 int einet_em_epoch(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int64_t N, int batch,
@@ -488,6 +500,10 @@ int einet_profile_read(einet_t* h, int capacity, int* n_classes, const char** na
         (void)hipEventDestroy(t.stop);
     }
     h->timed.clear();
+    if (h->profile_dropped > 0) {
+        rc = fail(h, EINET_ERR_HIP, std::to_string(h->profile_dropped) + " launches were not timed (event creation failed)");
+        h->profile_dropped = 0;
+    }
     *n_classes = KC_COUNT;
     for (int i = 0; i < KC_COUNT && i < capacity; ++i) {
         if (names) names[i] = kKernelClassNames[i];

@@ -36,6 +36,17 @@ __global__ void k_leaf_derive(const float* __restrict__ phi, float* __restrict__
 //   Gaussian      -1/(2 var) (x - mean)^2 - log(2 pi var)/2
 //   Bernoulli, binomial with P trials   x log p + (P - x) log(1 - p); the binomial coefficient goes to the offset
 //   categorical   log p[x]
+// Bernoulli / binomial term x log p + (P - x) log(1 - p).  A count of zero contributes log 1 = 0 also when the
+// probability is 0 or 1 (the density p^x (1-p)^(P-x) at the boundary); 0 * -inf would be NaN.
+__device__ __forceinline__ float count_term(float xv, float lp, float l1p, float nf) {
+    const float a = xv != 0.f ? xv * lp : 0.f;
+    const float b = nf != xv ? (nf - xv) * l1p : 0.f;
+    return a + b;
+}
+
+// A marginalised variable contributes 0 whatever its term is (also -inf).
+__device__ __forceinline__ float observed_term(float o, float term) { return o != 0.f ? term : 0.f; }
+
 template <int FAMILY>
 __device__ __forceinline__ float leaf_term(float xv, const float* __restrict__ th, int K, int P) {
     if constexpr (FAMILY == EINET_LEAF_GAUSSIAN) {
@@ -44,7 +55,7 @@ __device__ __forceinline__ float leaf_term(float xv, const float* __restrict__ t
     } else if constexpr (FAMILY == EINET_LEAF_CATEGORICAL) {
         return th[(size_t)min(max((int)xv, 0), P - 1) * K];
     } else {
-        return xv * th[0] + ((float)P - xv) * th[K];
+        return count_term(xv, th[0], th[K], (float)P);
     }
 }
 
@@ -286,7 +297,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
                         for (int b = 0; b < BS; ++b) {
                             const float diff = xs[b * np + pp[u]] - mu[u];
                             const float term = fmaf(c1[u] * diff, diff, c0[u]);
-                            t[b] += MASKED ? ob[b * cv + vv[u]] * term : term;
+                            t[b] += MASKED ? observed_term(ob[b * cv + vv[u]], term) : term;
                         }
                 } else if (d.family == EINET_LEAF_CATEGORICAL) {
 #pragma unroll
@@ -295,7 +306,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
 #pragma unroll
                         for (int b = 0; b < BS; ++b) {
                             const float term = leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + pp[u]], th[u], d.K, d.P);
-                            t[b] += MASKED ? ob[b * cv + vv[u]] * term : term;
+                            t[b] += MASKED ? observed_term(ob[b * cv + vv[u]], term) : term;
                         }
                 } else {
                     float lp[LEAF_U], l1p[LEAF_U];
@@ -311,8 +322,8 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
 #pragma unroll
                         for (int b = 0; b < BS; ++b) {
                             const float xv = xs[b * np + pp[u]];
-                            const float term = xv * lp[u] + (nf - xv) * l1p[u];
-                            t[b] += MASKED ? ob[b * cv + vv[u]] * term : term;
+                            const float term = count_term(xv, lp[u], l1p[u], nf);
+                            t[b] += MASKED ? observed_term(ob[b * cv + vv[u]], term) : term;
                             if (base)
                                 ht[b] += MASKED ? ob[b * cv + vv[u]] * leaf_base(logc, xv, d.P) : leaf_base(logc, xv, d.P);
                         }
@@ -427,7 +438,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
                 const float* th = theta + ((size_t)(vs[v] * d.C + c) * d.R + r) * tstride + k;
 #pragma unroll
                 for (int b = 0; b < LEAF_RED; ++b)
-                    acc[b] += ob[v * LEAF_RED + b] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[p * LEAF_RED + b], th, d.K, d.P);
+                    acc[b] += observed_term(ob[v * LEAF_RED + b], leaf_term<EINET_LEAF_CATEGORICAL>(xs[p * LEAF_RED + b], th, d.K, d.P));
             }
         } else {
             // Four pairs per round: their variable numbers are requested together, then their constants, so that
@@ -481,7 +492,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide1(const int32_t* __re
 #pragma unroll
                         for (int b = 0; b < LEAF_RED; ++b) {
                             // (nf * t1 is zero for a pair beyond the scope: both logarithms were set to zero)
-                            acc[b] += ov[b] * (xv[b] * t0[q] + (nf - xv[b]) * t1[q]);
+                            acc[b] += observed_term(ov[b], count_term(xv[b], t0[q], t1[q], nf));
                             if (base && p + q * nparts < np) hacc[b] += ov[b] * leaf_base(logc, xv[b], d.P);
                         }
                     }
@@ -575,13 +586,13 @@ __global__ __launch_bounds__(1024, 8) void k_leaf_forward_wide1_lean(const int32
             } else if (d.family == EINET_LEAF_CATEGORICAL) {
 #pragma unroll
                 for (int b = 0; b < LEAF_RED; ++b)
-                    acc[b] += ob[b * nv + v] * leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + p], th, d.K, d.P);
+                    acc[b] += observed_term(ob[b * nv + v], leaf_term<EINET_LEAF_CATEGORICAL>(xs[b * np + p], th, d.K, d.P));
             } else {
                 const float lp = th[0], l1p = th[d.K], nf = (float)d.P;
 #pragma unroll
                 for (int b = 0; b < LEAF_RED; ++b) {
                     const float xv = xs[b * np + p];
-                    acc[b] += ob[b * nv + v] * (xv * lp + (nf - xv) * l1p);
+                    acc[b] += observed_term(ob[b * nv + v], count_term(xv, lp, l1p, nf));
                     if (base) hacc[b] += ob[b * nv + v] * leaf_base(logc, xv, d.P);
                 }
             }

@@ -38,8 +38,16 @@ def test_fig3_corner_matches_oracle(point):
     num_got = got[lay.phi_off:lay.n_params].reshape(oracle.phi.shape)
     num_ref = ref_stats["num"]
     bound = ref_stats["den"][:, None, :, None, :] * np.abs(x).max()
-    tol = 1e-3 * np.abs(num_ref) + 1e-6 * np.abs(num_ref).max() + 1e-5 * bound
-    assert np.all(np.abs(num_got - num_ref) <= tol), float(np.max(np.abs(num_got - num_ref) - tol))
+    plain = 1e-3 * np.abs(num_ref) + 1e-6 * np.abs(num_ref).max()          # the tolerance every other tensor meets
+    tol = plain + 1e-5 * bound
+    d_num = np.abs(num_got - num_ref)
+    # how much of the extra slack is used: entries beyond the plain tolerance, and the worst of them in units of
+    # the slack (1 would be the limit)
+    over = d_num > plain
+    used = float(((d_num - plain) / np.maximum(1e-5 * bound, 1e-300))[over].max()) if over.any() else 0.0
+    print(f"  num: {int(over.sum())} of {over.size} entries beyond the plain tolerance, worst uses {used:.3f} of the "
+          f"signed-data slack; worst |d|/plain {float((d_num / plain).max()):.3f}", flush=True)
+    assert np.all(d_num <= tol), float(np.max(d_num - tol))
     # one stochastic-EM update with the paper's step size (Sec. 4.2) and the variance projection
     kw = dict(step=0.5, min_var=1e-6, max_var=10.0, w_floor=1e-9)
     m.em_update(**kw)
@@ -50,6 +58,11 @@ def test_fig3_corner_matches_oracle(point):
     err = np.abs(got_p - ref)
     # leaf means inherit the error of the signed sums above (divided by the posterior mass)
     tol_p = 1e-3 * np.abs(ref) + 1e-7
+    # weights and mixing weights are held to the plain parameter tolerance
+    assert np.all(err[:lay.phi_off] <= tol_p[:lay.phi_off]), float(np.max(err[:lay.phi_off] - tol_p[:lay.phi_off]))
+    over_p = err[lay.phi_off:] > tol_p[lay.phi_off:]
+    print(f"  leaf parameters: {int(over_p.sum())} of {over_p.size} beyond the plain tolerance, worst |d|/plain "
+          f"{float((err[lay.phi_off:] / tol_p[lay.phi_off:]).max()):.3f}", flush=True)
     tol_p[lay.phi_off:] += 1e-5 * np.abs(x).max() ** 2
     assert np.all(err <= tol_p), float(np.max(err - tol_p))
     m.close()

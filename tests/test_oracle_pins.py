@@ -386,3 +386,64 @@ def test_flat_round_trip_and_chunking():
     back = model.stats_from_flat(model.stats_to_flat(s1))
     np.testing.assert_array_equal(model.stats_to_flat(back), model.stats_to_flat(s1))
     np.testing.assert_array_equal(back["num"], s1["num"])
+
+
+# ----------------------------------------------------------------------------- impossible evidence (-inf)
+def _impossible_models():
+    """Bernoulli circuits in which variable 3 has p = 0 under every leaf entry of every replica: states with
+    x_3 = 1 have probability zero and the leaf vector that holds variable 3 is -inf in all of its entries."""
+    for spec, K in ((dict(kind="rat", D=6, depth=1, R=1), 3), (RAT_TINY, 4), (dict(kind="pd", H=2, W=4, deltas=[1]), 2)):
+        model, _, rng = make_oracle(spec, K, 1, BERNOULLI, seed=11)
+        normalise_exactly(model)
+        model.phi[3] = 0.0
+        yield spec, K, model, rng
+
+
+def test_impossible_evidence_gives_minus_inf_and_the_rest_stays_normalised():
+    """The shift of Eq. 4 when a whole input vector is -inf: the oracle's logsumexp takes shift 0 there.  Pinned by
+    what does not depend on that guard: the impossible states have log-density -inf exactly, the possible ones are
+    finite, and the density still sums to one over all 2^D states (so the possible states carry all the mass)."""
+    for spec, K, model, rng in _impossible_models():
+        D = model.g.num_vars
+        X = all_binary(D)
+        lp = model.logp(X)
+        bad = X[:, 3, 0] == 1
+        assert np.all(np.isneginf(lp[bad])) and np.all(np.isfinite(lp[~bad])), spec
+        assert abs(np.exp(lp).sum() - 1.0) < 1e-12, spec
+        # marginalising the impossible variable makes every state possible again, with P(x_rest) = P(x_rest, x_3 = 0)
+        m = np.ones(D); m[3] = 0
+        lp_m = model.logp(X, m)
+        assert np.all(np.isfinite(lp_m))
+        x0 = X.copy(); x0[:, 3, 0] = 0
+        np.testing.assert_allclose(lp_m, model.logp(x0), rtol=0, atol=1e-12)
+
+
+def test_impossible_evidence_against_an_explicit_mixture():
+    """Depth-1 tree, one replica: the circuit is a mixture of K^2 products of Bernoullis; its log-density,
+    written with scipy's logsumexp and the Bernoulli mass function evaluated as p^x (1-p)^(1-x), is -inf
+    for the impossible rows and agrees with the oracle on the others, in one mixed batch."""
+    spec, K, model, rng = next(_impossible_models())
+    D = model.g.num_vars
+    x = (rng.random((12, D, 1)) < 0.5).astype(float)
+    x[::3, 3, 0] = 1.0                                     # every third row is impossible
+    x[1::3, 3, 0] = 0.0
+    (_, left, right), = model.g.partitions
+    W = model.W[0][0]                                      # [K, K]
+    want = np.empty(12)
+    for b in range(12):
+        comp = np.empty((K, K))
+        for i in range(K):
+            for j in range(K):
+                pr = W[i, j]
+                for reg, k in ((left, i), (right, j)):
+                    for d in model.g.scopes[reg]:
+                        p = model.phi[d, 0, model.g.replica[reg], 0, k]
+                        pr *= p ** x[b, d, 0] * (1.0 - p) ** (1.0 - x[b, d, 0])     # 0 ** 0 = 1
+                comp[i, j] = pr
+        with np.errstate(divide="ignore"):
+            want[b] = scipy.special.logsumexp(np.log(comp.ravel()))
+    got = model.logp(x)
+    bad = x[:, 3, 0] == 1
+    assert bad.any() and (~bad).any()
+    assert np.all(np.isneginf(got[bad])) and np.all(np.isneginf(want[bad]))
+    np.testing.assert_allclose(got[~bad], want[~bad], rtol=1e-12)
