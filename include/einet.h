@@ -195,6 +195,28 @@ int einet_init_params(einet_t* h, uint64_t seed, float leaf_lo, float leaf_hi, v
 int einet_logp(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int B,
                float* logp_dev, void* stream);
 
+/* einet_logp for callers that cannot allocate device memory for a batch (code
+ * under HIP graph capture, serving loops, harnesses that forbid hipMalloc):
+ * same arguments, same kernels and the same result as einet_logp, but the
+ * activations of the forward pass (the per-node log-densities, their
+ * per-sample offsets and the shifts of Eq. 4) live in an arena of
+ * EINET_STATIC_SCRATCH_BYTES bytes that is part of the library's code object
+ * on every GPU, not in the bound workspace.  The call allocates nothing and
+ * frees nothing.  The handle must be bound (parameters, index tables and
+ * derived leaf constants are read from the caller's buffers); besides
+ * B <= max_batch the batch is limited by the arena:
+ *   4*nodes*B*K + 8*nodes*B + 8*partitions*B bytes, each term rounded up to
+ *   a multiple of 256 (nodes = regions + one per partition of a region with
+ *   several),
+ * must fit, else EINET_ERR_BATCH_TOO_LARGE and nothing is launched.  All calls on one
+ * GPU, from any handle, share that GPU's arena: calls that overlap in time on
+ * one GPU (different streams or threads) race; calls on one stream are safe.
+ * Nothing in the arena has to be zero at entry; its contents after the call are
+ * unspecified.  einet_em_accumulate and einet_sample do not use it. */
+#define EINET_STATIC_SCRATCH_BYTES (16u << 20)
+int einet_logp_static(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int B,
+                      float* logp_dev, void* stream);
+
 /* E-step on one batch (Eq. 6): forward pass as einet_logp, then the top-down
  * pass that yields n = w * dlogP/dw for every sum weight and the posterior
  * p = dlogP/dlogL of every leaf entry, summed over the batch and ADDED to the

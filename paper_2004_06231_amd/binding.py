@@ -14,7 +14,7 @@ MAX_DELTAS = 8
 
 EXPORTED_SYMBOLS = [
     "einet_create", "einet_destroy", "einet_last_error", "einet_sizes", "einet_structure", "einet_bind",
-    "einet_refresh", "einet_init_params", "einet_logp", "einet_em_accumulate", "einet_em_update", "einet_em_reset", "einet_em_epoch",
+    "einet_refresh", "einet_init_params", "einet_logp", "einet_logp_static", "einet_em_accumulate", "einet_em_update", "einet_em_reset", "einet_em_epoch",
     "einet_mixture_logp", "einet_sample", "einet_profile_enable", "einet_profile_read",
 ]
 
@@ -69,6 +69,7 @@ def load_library():
     lib.einet_refresh.argtypes = [vp, vp]
     lib.einet_init_params.argtypes = [vp, C.c_uint64, f32, f32, vp]
     lib.einet_logp.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.einet_logp_static.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.einet_em_accumulate.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.einet_em_update.argtypes = [vp, f32, f32, f32, f32, vp]
     lib.einet_em_reset.argtypes = [vp, vp]
@@ -236,6 +237,13 @@ class EiNet:
         self._check(self._lib.einet_logp(self._h, x.data_ptr(), m, mode, B, self._out_arg(out, B), self._stream()))
         return out
 
+    def logp_static(self, x, out, mask=None):
+        """As logp, with the activations in the library's fixed arena: the call allocates nothing (out is required)."""
+        B = self._batch_of(x)
+        m, mode = self._mask_args(mask, B)
+        self._check(self._lib.einet_logp_static(self._h, x.data_ptr(), m, mode, B, self._out_arg(out, B), self._stream()))
+        return out
+
     def em_accumulate(self, x, mask=None, logp=None):
         B = self._batch_of(x)
         m, mode = self._mask_args(mask, B)
@@ -330,6 +338,10 @@ def einet_refresh(m):
 
 def einet_logp(m, x, mask=None, out=None):
     return m.logp(x, mask, out)
+
+
+def einet_logp_static(m, x, out, mask=None):
+    return m.logp_static(x, out, mask)
 
 
 def einet_em_accumulate(m, x, mask=None, logp=None):

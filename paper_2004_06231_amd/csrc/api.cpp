@@ -141,12 +141,25 @@ void run(einet_t* h, int cls, hipStream_t s, F&& launch) {
     h->timed.push_back(t);
 }
 
-// Leaf layer, then einsum (+ mixing) layers bottom-up; fills the arena A.
-void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, float* logp, const Dims& d,
-             hipStream_t s) {
+// Where the activations of a forward pass live: residuals A [node][B][K], offsets Off [node][B], shifts
+// amax [item][2][B].
+struct Arena {
+    float* A;
+    double* Off;
+    float* amax;
+};
+
+Arena workspace_arena(const einet_t* h) {
+    return Arena{reinterpret_cast<float*>(h->ws + h->off_A), reinterpret_cast<double*>(h->ws + h->off_Off),
+                 reinterpret_cast<float*>(h->ws + h->off_amax)};
+}
+
+// Leaf layer, then einsum (+ mixing) layers bottom-up; fills the arena.
+void forward(einet_t* h, const Arena& ar, const float* x, const uint8_t* mask, int mask_mode, float* logp,
+             const Dims& d, hipStream_t s) {
     const Plan& p = h->plan;
-    float* A = reinterpret_cast<float*>(h->ws + h->off_A);
-    double* Off = reinterpret_cast<double*>(h->ws + h->off_Off);
+    float* A = ar.A;
+    double* Off = ar.Off;
     const float* theta = reinterpret_cast<const float*>(h->ws + h->off_theta);
     run(h, KC_LEAF_FWD, s, [&] {
         launch_leaf_forward(h->dt, (int)p.leaf_node.size(), p.max_leaf_scope, x, mask, mask_mode, theta, A, Off, d, s);
@@ -154,7 +167,7 @@ void forward(einet_t* h, const float* x, const uint8_t* mask, int mask_mode, flo
     for (int l = 0; l < p.num_layers; ++l) {
         run(h, KC_EINSUM_FWD, s, [&] {
             launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params, A,
-                                  Off, reinterpret_cast<float*>(h->ws + h->off_amax), logp, d, s);
+                                  Off, ar.amax, logp, d, s);
         });
         if (p.mix_layer_ptr[l + 1] > p.mix_layer_ptr[l])
             run(h, KC_MIXING_FWD, s, [&] {
@@ -337,8 +350,36 @@ int einet_logp(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask
     if (!logp_dev) return fail(h, EINET_ERR_INVALID_ARG, "logp_dev is NULL");
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Dims d = dims_of(h, B);
-    forward(h, x_dev, mask_dev, mask_mode, logp_dev, d, s);
+    forward(h, workspace_arena(h), x_dev, mask_dev, mask_mode, logp_dev, d, s);
     return check_hip(h, "einet_logp");
+}
+
+int einet_logp_static(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int B, float* logp_dev,
+                      void* stream) {
+    int rc = check_batch_args(h, x_dev, mask_dev, mask_mode, B);
+    if (rc != EINET_OK) return rc;
+    if (!logp_dev) return fail(h, EINET_ERR_INVALID_ARG, "logp_dev is NULL");
+    const Plan& p = h->plan;
+    const size_t K = p.K, nb = (size_t)B;
+    const size_t bytes_A = align256(sizeof(float) * size_t(p.num_nodes) * nb * K);
+    const size_t bytes_Off = align256(sizeof(double) * size_t(p.num_nodes) * nb);
+    const size_t bytes_amax = align256(sizeof(float) * 2 * p.ein_left.size() * nb);
+    const size_t need = bytes_A + bytes_Off + bytes_amax;
+    if (need > EINET_STATIC_SCRATCH_BYTES)
+        return fail(h, EINET_ERR_BATCH_TOO_LARGE,
+                    "einet_logp_static: this model needs " + std::to_string(need) + " bytes of activations for B = " +
+                        std::to_string(B) + ", the fixed arena holds " + std::to_string(EINET_STATIC_SCRATCH_BYTES));
+    void* base = nullptr;
+    const hipError_t e = static_scratch_address(&base);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(h, EINET_ERR_HIP, std::string("einet_logp_static: address of the fixed arena: ") + hipGetErrorString(e));
+    }
+    char* c = static_cast<char*>(base);
+    const Arena ar{reinterpret_cast<float*>(c), reinterpret_cast<double*>(c + bytes_A),
+                   reinterpret_cast<float*>(c + bytes_A + bytes_Off)};
+    forward(h, ar, x_dev, mask_dev, mask_mode, logp_dev, dims_of(h, B), static_cast<hipStream_t>(stream));
+    return check_hip(h, "einet_logp_static");
 }
 
 int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev, int mask_mode, int B,
@@ -348,7 +389,7 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Dims d = dims_of(h, B);
     const Plan& p = h->plan;
-    forward(h, x_dev, mask_dev, mask_mode, logp_dev, d, s);
+    forward(h, workspace_arena(h), x_dev, mask_dev, mask_mode, logp_dev, d, s);
     const float* A = reinterpret_cast<const float*>(h->ws + h->off_A);
     const double* Off = reinterpret_cast<const double*>(h->ws + h->off_Off);
     float* G = reinterpret_cast<float*>(h->ws + h->off_G);
@@ -448,7 +489,7 @@ int einet_sample(einet_t* h, int B, const float* x_dev, const uint8_t* mask_dev,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Dims d = dims_of(h, B);
     const Plan& p = h->plan;
-    if (evidence) forward(h, x_dev, mask_dev, mask_mode, nullptr, d, s);
+    if (evidence) forward(h, workspace_arena(h), x_dev, mask_dev, mask_mode, nullptr, d, s);
     const float* A = reinterpret_cast<const float*>(h->ws + h->off_A);
     const double* Off = reinterpret_cast<const double*>(h->ws + h->off_Off);
     const float* amax = reinterpret_cast<const float*>(h->ws + h->off_amax);

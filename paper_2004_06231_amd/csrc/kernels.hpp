@@ -100,6 +100,10 @@ void launch_sample_regions(const DevTables& t, int first, int count, bool eviden
 void launch_sample_leaves(const DevTables& t, int n_lv, const float* x, const uint8_t* mask, int mask_mode,
                           const float* phi, const float* noise, const int32_t* sel, float* out, const Dims& d,
                           hipStream_t s);
+// Device address, on the current device, of the library's fixed arena of EINET_STATIC_SCRATCH_BYTES bytes
+// (256-byte aligned).  No allocation: the arena is part of the loaded code object.
+hipError_t static_scratch_address(void** ptr);
+
 void launch_mixture_logp(const float* lp, const float* log_coef, int n_components, int B, float* out, hipStream_t s);
 
 }  // namespace einet_impl
