@@ -166,8 +166,8 @@ void forward(einet_t* h, const Arena& ar, const float* x, const uint8_t* mask, i
     });
     for (int l = 0; l < p.num_layers; ++l) {
         run(h, KC_EINSUM_FWD, s, [&] {
-            launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->params, A,
-                                  Off, ar.amax, logp, d, s);
+            launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
+                                  p.ein_layer_full[l] != 0, h->params, A, Off, ar.amax, logp, d, s);
         });
         if (p.mix_layer_ptr[l + 1] > p.mix_layer_ptr[l])
             run(h, KC_MIXING_FWD, s, [&] {
@@ -405,7 +405,7 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
             });
         run(h, KC_EINSUM_BWD, s, [&] {
             launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
-                                   !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp, d, s);
+                                   p.ein_layer_full[l] != 0, !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp, d, s);
         });
     }
     const int leaf_step = p.num_layers;

@@ -28,6 +28,9 @@ namespace einet_impl {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+constexpr int EINET_NUM_CUS = 256;        // compute units of an MI355X: workgroups of a one-per-unit launch
+constexpr int EINET_MAX_DEVICES = 16;     // per-device once-flags of the launchers
+
 // Raises the dynamic-LDS limit of a kernel.  A refusal is not kept as the thread's last error: the launch
 // that needs the memory then fails and reports it, instead of a later, unrelated call.
 template <class Kernel>

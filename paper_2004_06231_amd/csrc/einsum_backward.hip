@@ -2,6 +2,8 @@
 // posteriors of the children).
 #include "device_common.hpp"
 
+#include <mutex>
+
 namespace einet_impl {
 
 namespace {
@@ -432,6 +434,523 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     }
 }
 
+// ------------------------------------------------------------------ top-down pass, einsum items, K a multiple of 8 up to 40
+// The same two GEMMs on v_mfma_f32_32x32x2_f32 (the fp32 shape that issues at the full rate of the matrix pipe), as
+// one workgroup per compute unit that walks a run of (item, slice) pairs, a slice being four consecutive left
+// entries i.  Waves 0-3 only run the matrix pipe, waves 4-7 do everything else:
+//   producers   bring the W slice in (transposed on the way: four consecutive k of a row (il, j) in 16 bytes, rows
+//               swizzled so that neither their 16-byte stores nor the operand reads collide), stage eR^T, eL^T and
+//               Q^T of up to 128 samples per (item, chunk), and finish the tiles that the four matrix waves share;
+//   statistics  rows (k, il) in tiles of 32, columns j: one 32-column tile (K >= 32) on 32x32x2, the remaining
+//               columns on 16x16x4; a wave owns whole tiles (all samples) and takes its 32 samples of the tiles that
+//               are left over, whose shares meet in LDS;
+//   posteriors  rows (il, j) in K/8 tiles of 32, columns = this wave's 32 samples, contraction over k; both
+//               reductions are in-lane: the left child's entries are complete per slice, the right child's are kept
+//               in registers over the workgroup's slices of the item and written once, as a block of their own.
+// A vector instruction between two MFMAs of a wave stalls the matrix pipe for about 15 cycles, so operand products
+// are formed in batches ahead of the MFMAs that use them.
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+template <int K8>
+struct BwdSLayout {
+    static constexpr int K = 8 * K8;
+    static constexpr int NS = K / 4;                   // slices (four consecutive left entries i) per item
+    static constexpr int ST = 128 + 4;                 // row stride of the sample-major operand copies
+    static constexpr int SLICE = 4 * K * K;            // W[:, 4 it .. 4 it + 3, :] as [K/4 kq][4K rows (il, j), swizzled][4 kr]
+    static constexpr int OFF_R = 2 * SLICE;            // eR^T [K][ST]
+    static constexpr int OFF_Q = OFF_R + K * ST;       // Q^T  [K][ST]
+    static constexpr int OFF_L = OFF_Q + K * ST;       // eL^T [K][ST]
+    static constexpr int N32 = K / 32;                 // 32-column tiles of the statistics GEMM (K <= 40: 0 or 1)
+    static constexpr int N16C = (K % 32 + 15) / 16;    // 16-column tiles for the remaining columns
+    static constexpr int T32 = K8 * N32;               // 32x32 tiles of a slice (K8 row tiles of 32 rows (k, il))
+    static constexpr int O32 = T32 / 4, S32 = T32 % 4; // owned per matrix wave; shared (contraction split over the four waves)
+    static constexpr int T16 = (K / 4) * N16C;         // 16x16 tiles of a slice
+    static constexpr int O16 = T16 / 4, S16 = T16 % 4;
+    static constexpr int NPART = 16 * S32 + 4 * S16;   // registers per lane of a matrix wave that hold shared tiles
+    static constexpr int OFF_P = OFF_L + K * ST;       // [4 waves][NPART][64 lanes]
+    static constexpr int LDS_FLOATS = OFF_P + 4 * NPART * 64;
+    static constexpr int WITEMS = K * K / 4;           // work items of the slice copy: (kq, il, j4) -> 4 x 16 bytes
+    static constexpr int NWI = (WITEMS + 255) / 256;
+};
+
+template <int K8, bool ACCUM>
+__global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
+    const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_out,
+    const int32_t* __restrict__ e_reg, const int32_t* __restrict__ e_woff, const int32_t* __restrict__ e_voff,
+    const int32_t* __restrict__ e_vstr, const float* __restrict__ params, float* __restrict__ stats,
+    const float* __restrict__ A, const double* __restrict__ Off, const float* __restrict__ amax,
+    const float* __restrict__ G, float* __restrict__ Gp, int item0, int count, int B) {
+    using LY = BwdSLayout<K8>;
+    constexpr int K = LY::K, NS = LY::NS, ST = LY::ST, NB = 1 + NS;
+    extern __shared__ float lds[];
+    float* sR = lds + LY::OFF_R;
+    float* sQ = lds + LY::OFF_Q;
+    float* sL = lds + LY::OFF_L;
+    float* sP = lds + LY::OFF_P;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nchunks = (B + 127) >> 7;
+    const long long P = (long long)count * NS;
+    const int g = xcd_contiguous_block();
+    const int p0 = (int)((long long)g * P / gridDim.x), p1 = (int)((long long)(g + 1) * P / gridDim.x);
+    if (p0 >= p1) return;
+    const size_t blk = (size_t)B * K;
+
+    // position of a unit: item li, chunk, slice it; [s0, s1) are this workgroup's slices of the item
+    struct Pos { int li, chunk, it, s0, s1; };
+    auto seg = [&](Pos& q) {
+        q.s0 = max(p0 - q.li * NS, 0);
+        q.s1 = min(p1 - q.li * NS, NS);
+    };
+    auto advance = [&](Pos& q) {          // -> false past the end
+        if (++q.it < q.s1) return true;
+        if (++q.chunk < nchunks) { q.it = q.s0; return true; }
+        ++q.li; q.chunk = 0;
+        if (q.li * NS >= p1) return false;
+        seg(q); q.it = q.s0;
+        return true;
+    };
+    Pos pos;
+    pos.li = p0 / NS; pos.chunk = 0; seg(pos); pos.it = pos.s0;
+
+    if (wave >= 4) {
+        // ============================================================ producer waves
+        const int pt = tid - 256;
+        // ---- W slice of (li, it): 16 bytes at four consecutive k per work item, transposed in registers
+        floatx4 wv[LY::NWI][4];
+        auto fetch_w = [&](const Pos& q) {
+            const float* W = params + e_woff[q.li];
+#pragma unroll
+            for (int x = 0; x < LY::NWI; ++x) {
+                const int wi = min(pt + 256 * x, LY::WITEMS - 1);
+                const int j4 = wi % (K / 4), il = (wi / (K / 4)) & 3, kq = wi / K;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    wv[x][kk] = *reinterpret_cast<const floatx4*>(W + ((size_t)(4 * kq + kk) * K + 4 * q.it + il) * K + 4 * j4);
+            }
+        };
+        auto store_w = [&](float* buf) {
+#pragma unroll
+            for (int x = 0; x < LY::NWI; ++x) {
+                const int wi = pt + 256 * x;
+                const int j4 = wi % (K / 4), il = (wi / (K / 4)) & 3, kq = wi / K;
+                if (wi < LY::WITEMS) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int rho = il * K + 4 * j4 + c;
+                        const int ps = rho ^ ((rho >> 3) & 7);
+                        floatx4 o = {wv[x][0][c], wv[x][1][c], wv[x][2][c], wv[x][3][c]};
+                        *reinterpret_cast<floatx4*>(buf + ((size_t)kq * 4 * K + ps) * 4) = o;
+                    }
+                }
+            }
+        };
+        // ---- operands of (li, chunk): thread (b = pt / 2, half hh = pt % 2) holds K/2 entries of row b of R, L, G, A[s]
+        const int rb_ = pt >> 1, hh = pt & 1;
+        floatx4 r4[K8], l4[K8], g4[K8], a4[K8], v4[K8];
+        float arow = 0.f, alrow = 0.f, ddrow = 0.f;
+        bool rin = false;
+        auto fetch_rows = [&](const Pos& q) {
+            const int bg = q.chunk * 128 + rb_;
+            rin = bg < B;
+            const int bc = min(bg, B - 1);
+            const int item = item0 + q.li;
+            const size_t ro = (size_t)bc * K + 4 * hh * K8;
+            const float* Rp = A + (size_t)e_right[q.li] * blk + ro;
+            const float* Lp = A + (size_t)e_left[q.li] * blk + ro;
+            const float* Gs = G + (size_t)e_reg[q.li] * blk + ro;
+            const float* As = A + (size_t)e_reg[q.li] * blk + ro;
+#pragma unroll
+            for (int x = 0; x < K8; ++x) {
+                r4[x] = *reinterpret_cast<const floatx4*>(Rp + 4 * x);
+                l4[x] = *reinterpret_cast<const floatx4*>(Lp + 4 * x);
+                g4[x] = *reinterpret_cast<const floatx4*>(Gs + 4 * x);
+                a4[x] = *reinterpret_cast<const floatx4*>(As + 4 * x);
+            }
+            alrow = amax[(size_t)item * 2 * B + bc];
+            arow = amax[((size_t)item * 2 + 1) * B + bc];
+            ddrow = (float)(Off[(size_t)e_out[q.li] * B + bc] - Off[(size_t)e_reg[q.li] * B + bc]);
+            const int voff = e_voff[q.li], vstr = e_vstr[q.li];
+#pragma unroll
+            for (int x = 0; x < K8; ++x)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v4[x][c] = voff >= 0 ? params[voff + (4 * (hh * K8 + x) + c) * vstr] : 1.f;
+        };
+        auto stage_rows = [&]() {
+#pragma unroll
+            for (int x = 0; x < K8; ++x)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int k = 4 * (hh * K8 + x) + c;
+                    const float e = __expf(r4[x][c] - arow);
+                    const float l = __expf(l4[x][c] - alrow);
+                    const float qv = g4[x][c] * v4[x][c] * __expf(ddrow - a4[x][c]);
+                    sR[k * ST + rb_] = rin ? e : 0.f;
+                    sL[k * ST + rb_] = rin ? l : 0.f;
+                    sQ[k * ST + rb_] = (rin && g4[x][c] != 0.f) ? qv : 0.f;
+                }
+        };
+        // ---- shared tiles of a finished unit: sum the four waves' shares, then Nw (+)= W * sum.  The W entries (and the old
+        // statistics, when they are added to) are requested while the unit is still being computed.
+        float wred[LY::NPART / 4 > 0 ? LY::NPART / 4 : 1], nred[LY::NPART / 4 > 0 ? LY::NPART / 4 : 1];
+        auto shared_index = [&](int x, int& k, int& il, int& j) {
+            const int e = pt + 256 * x;
+            const int reg = e >> 6, ln = e & 63;
+            if (reg < 16 * LY::S32) {
+                const int m1 = 4 * LY::O32 + (reg >> 4), rr = reg & 15;
+                k = 8 * m1 + 2 * (rr >> 2) + (ln >> 5); il = rr & 3; j = ln & 31;
+            } else {
+                const int r2 = reg - 16 * LY::S32;
+                const int ptile = 4 * LY::O16 + (r2 >> 2);
+                const int rt = ptile / (LY::N16C > 0 ? LY::N16C : 1), ct = ptile % (LY::N16C > 0 ? LY::N16C : 1);
+                k = 4 * rt + (ln >> 4); il = r2 & 3; j = 32 * LY::N32 + 16 * ct + (ln & 15);
+            }
+        };
+        auto fetch_shared = [&](const Pos& q) {
+            if constexpr (LY::NPART > 0) {
+                const size_t wbase = (size_t)e_woff[q.li];
+#pragma unroll
+                for (int x = 0; x < LY::NPART / 4; ++x) {
+                    int k, il, j;
+                    shared_index(x, k, il, j);
+                    const size_t idx = wbase + ((size_t)k * K + 4 * q.it + il) * K + min(j, K - 1);
+                    wred[x] = params[idx];
+                    nred[x] = (ACCUM || q.chunk > 0) ? stats[idx] : 0.f;
+                }
+            }
+        };
+        auto reduce_shared = [&](const Pos& q) {
+            if constexpr (LY::NPART > 0) {
+                float* Nw = stats + (size_t)e_woff[q.li];
+#pragma unroll
+                for (int x = 0; x < LY::NPART / 4; ++x) {
+                    const int e = pt + 256 * x;
+                    const int reg = e >> 6, ln = e & 63;
+                    float s = 0.f;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) s += sP[(w * LY::NPART + reg) * 64 + ln];
+                    int k, il, j;
+                    shared_index(x, k, il, j);
+                    if (j < K) Nw[((size_t)k * K + 4 * q.it + il) * K + j] = nred[x] + wred[x] * s;
+                }
+            }
+        };
+
+        fetch_w(pos);
+        fetch_rows(pos);
+        store_w(lds);
+        stage_rows();
+        Pos npos = pos;
+        bool nvalid = advance(npos);
+        if (nvalid) fetch_w(npos);
+        __syncthreads();                                  // B0
+        Pos prev = pos;
+        int u = 0;
+        bool have_prev = false;
+        for (;;) {
+            // the matrix waves work on unit u = pos; slice npos is in registers
+            if (have_prev) reduce_shared(prev);
+            fetch_shared(pos);
+            if (nvalid) {
+                store_w(lds + ((u + 1) & 1) * LY::SLICE);
+                Pos nn = npos;
+                if (advance(nn)) fetch_w(nn);
+            }
+            const bool new_ops = nvalid && (npos.li != pos.li || npos.chunk != pos.chunk);
+            if (new_ops) fetch_rows(npos);
+            if constexpr (LY::NPART > 0) __syncthreads();  // M(u)
+            __syncthreads();                              // B(u+1)
+            prev = pos; have_prev = true;
+            if (!nvalid) break;
+            pos = npos;
+            nvalid = advance(npos);
+            ++u;
+            if (new_ops) {
+                stage_rows();
+                __syncthreads();                          // X(u)
+            }
+        }
+        reduce_shared(prev);
+    } else {
+        // ============================================================ matrix waves
+        const int n = lane & 31, h = lane >> 5;
+        const int c16 = lane & 15, kg = lane >> 4;
+        const int bl = 32 * wave + n;                     // sample of this lane within the chunk (posterior GEMM)
+        float q[4 * K8], er[4 * K8], gr[4 * K8];
+#pragma unroll
+        for (int x = 0; x < 4 * K8; ++x) gr[x] = 0.f;
+        // swizzled rows of the K8 tiles of the slice
+        int prow[K8];
+#pragma unroll
+        for (int m = 0; m < K8; ++m) {
+            const int rho = 32 * m + n;
+            prow[m] = (rho ^ ((rho >> 3) & 7)) * 4;
+        }
+        __syncthreads();                                  // B0
+        bool new_ops = true;
+        int u = 0;
+        for (;;) {
+            const int item = item0 + pos.li;
+            const int bg = pos.chunk * 128 + bl;
+            if (new_ops) {
+#pragma unroll
+                for (int t = 0; t < K8; ++t)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        q[4 * t + c] = sQ[(8 * t + 4 * h + c) * ST + bl];
+                        er[4 * t + c] = sR[(8 * t + 4 * h + c) * ST + bl];
+                    }
+            }
+            float el4[4];
+#pragma unroll
+            for (int il = 0; il < 4; ++il) el4[il] = sL[(4 * pos.it + il) * ST + bl];
+            const size_t wbase = (size_t)e_woff[pos.li];
+            float* Nw = stats + wbase;
+            const bool accum = ACCUM || pos.chunk > 0;
+
+            // ---- statistics GEMM: P[(k, il), j] = sum_b Q[b,k] eL[b, 4 it + il] eR[b,j] over the 128 staged samples
+            const float* wcur = lds + (u & 1) * LY::SLICE;      // W of the slice, for Nw (+)= W * P
+            // 32x32 tiles: lane (n, h) is row n of the tile as A operand: (k = 8 m1 + n / 4, il = n % 4); as B operand column j = n;
+            // group t contracts the samples 8 t + 4 h .. + 3.  Owned tiles first (all samples), then the shared ones (this wave's
+            // 32 samples); a tile's registers are free again before the next one starts.
+#pragma unroll
+            for (int o = 0; o < LY::O32 + LY::S32; ++o) {
+                const bool own = o < LY::O32;
+                const int m1 = own ? wave + 4 * o : 4 * LY::O32 + (o - LY::O32);
+                const int t0 = own ? 0 : 4 * wave;
+                const int nt = own ? 16 : 4;
+                float nold[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) nold[v] = 0.f;
+                if (own && accum) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        nold[v] = Nw[((size_t)(8 * m1 + 2 * (v >> 2) + h) * K + 4 * pos.it + (v & 3)) * K + n];
+                }
+                if constexpr (LY::NPART > 0) {
+                    if (o == LY::O32) __syncthreads();    // M(u): the shares of the previous unit have been read
+                }
+                const float* qp = sQ + (8 * m1 + (n >> 2)) * ST + 4 * h + 8 * t0;
+                const float* lp = sL + (4 * pos.it + (n & 3)) * ST + 4 * h + 8 * t0;
+                const float* rp = sR + n * ST + 4 * h + 8 * t0;
+                floatx16 acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+                // Batches of two groups (eight MFMAs): the products of a batch are formed before its first MFMA, because a vector
+                // instruction between two MFMAs of a wave costs about 15 cycles of the matrix pipe; operands are requested two
+                // batches ahead.
+                floatx4 qa[3][2], ea[3][2], rb[3][2];
+                constexpr int NBAT32 = 8;
+                const int nbat = nt / 2;
+#pragma unroll
+                for (int x = 0; x < 2; ++x)
+#pragma unroll
+                    for (int y = 0; y < 2; ++y) {
+                        qa[x][y] = *reinterpret_cast<const floatx4*>(qp + 8 * (2 * x + y));
+                        ea[x][y] = *reinterpret_cast<const floatx4*>(lp + 8 * (2 * x + y));
+                        rb[x][y] = *reinterpret_cast<const floatx4*>(rp + 8 * (2 * x + y));
+                    }
+#pragma unroll
+                for (int x = 0; x < NBAT32; ++x) {
+                    if (x < nbat) {
+                        if (x + 2 < nbat) {
+#pragma unroll
+                            for (int y = 0; y < 2; ++y) {
+                                qa[(x + 2) % 3][y] = *reinterpret_cast<const floatx4*>(qp + 8 * (2 * (x + 2) + y));
+                                ea[(x + 2) % 3][y] = *reinterpret_cast<const floatx4*>(lp + 8 * (2 * (x + 2) + y));
+                                rb[(x + 2) % 3][y] = *reinterpret_cast<const floatx4*>(rp + 8 * (2 * (x + 2) + y));
+                            }
+                        }
+                        float pr[8];
+#pragma unroll
+                        for (int y = 0; y < 2; ++y)
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) pr[4 * y + c] = qa[x % 3][y][c] * ea[x % 3][y][c];
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int y = 0; y < 2; ++y)
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pr[4 * y + c], rb[x % 3][y][c], acc, 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                if (own) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int k = 8 * m1 + 2 * (v >> 2) + h, rho = (v & 3) * K + n;
+                        const float wv_ = wcur[((k >> 2) * 4 * K + (rho ^ ((rho >> 3) & 7))) * 4 + (k & 3)];
+                        Nw[((size_t)k * K + 4 * pos.it + (v & 3)) * K + n] = nold[v] + wv_ * acc[v];
+                    }
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sP[(wave * LY::NPART + 16 * (o - LY::O32) + v) * 64 + lane] = acc[v];
+                }
+            }
+            if constexpr (LY::NPART > 0 && LY::S32 == 0) __syncthreads();   // M(u) when no 32x32 tile is shared
+            // 16x16 tiles: lane (c16, kg): A row c16 = (k = 4 rt + c16 / 4, il = c16 % 4), B column j = jb + c16; group t contracts
+            // the samples 16 t + 4 kg .. + 3
+            // (two tiles advance together where possible: a single chain of this shape does not keep the matrix pipe busy)
+#pragma unroll
+            for (int part = 0; part < 2; ++part)
+#pragma unroll
+            for (int o0 = 0; o0 < (part == 0 ? LY::O16 : LY::S16); o0 += 2) {
+                const bool own = part == 0;                 // owned tiles, then shared ones; a pair never mixes them
+                const int np = o0 + 1 < (own ? LY::O16 : LY::S16) ? 2 : 1;
+                const int t0 = own ? 0 : 2 * wave;
+                const int nt = own ? 8 : 2;
+                int rt[2], jj[2];
+                const float* qp[2];
+                const float* rp[2];
+                const float* lp = sL + (4 * pos.it + (c16 & 3)) * ST + 4 * kg + 16 * t0;
+                float nold[2][4];
+#pragma unroll
+                for (int z = 0; z < 2; ++z) {
+                    const int o = o0 + (z < np ? z : 0);
+                    const int ptile = own ? wave + 4 * o : 4 * LY::O16 + o;
+                    rt[z] = ptile / (LY::N16C > 0 ? LY::N16C : 1);
+                    jj[z] = 32 * LY::N32 + 16 * (ptile % (LY::N16C > 0 ? LY::N16C : 1)) + c16;
+                    qp[z] = sQ + (4 * rt[z] + (c16 >> 2)) * ST + 4 * kg + 16 * t0;
+                    rp[z] = sR + min(jj[z], K - 1) * ST + 4 * kg + 16 * t0;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) nold[z][c] = 0.f;
+                    if (own && accum && z < np) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) nold[z][c] = Nw[((size_t)(4 * rt[z] + kg) * K + 4 * pos.it + c) * K + min(jj[z], K - 1)];
+                    }
+                }
+                floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+                floatx4 qa[3][2], ea[3], rb[3][2];
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    ea[x] = *reinterpret_cast<const floatx4*>(lp + 16 * x);
+#pragma unroll
+                    for (int z = 0; z < 2; ++z) {
+                        if (z < np) {
+                            qa[x][z] = *reinterpret_cast<const floatx4*>(qp[z] + 16 * x);
+                            rb[x][z] = *reinterpret_cast<const floatx4*>(rp[z] + 16 * x);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    if (x < nt) {
+                        if (x + 2 < nt) {
+                            ea[(x + 2) % 3] = *reinterpret_cast<const floatx4*>(lp + 16 * (x + 2));
+#pragma unroll
+                            for (int z = 0; z < 2; ++z) {
+                                if (z < np) {
+                                    qa[(x + 2) % 3][z] = *reinterpret_cast<const floatx4*>(qp[z] + 16 * (x + 2));
+                                    rb[(x + 2) % 3][z] = *reinterpret_cast<const floatx4*>(rp[z] + 16 * (x + 2));
+                                }
+                            }
+                        }
+                        float pr[2][4];
+#pragma unroll
+                        for (int z = 0; z < 2; ++z)
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) pr[z][c] = z < np ? qa[x % 3][z][c] * ea[x % 3][c] : 0.f;
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+#pragma unroll
+                            for (int z = 0; z < 2; ++z)
+                                if (z < np) acc[z] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[z][c], rb[x % 3][z][c], acc[z], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+#pragma unroll
+                for (int z = 0; z < 2; ++z) {
+                    if (z < np) {
+                        if (own) {
+                            if (jj[z] < K) {
+#pragma unroll
+                                for (int c = 0; c < 4; ++c) {
+                                    const int k = 4 * rt[z] + kg, rho = c * K + jj[z];
+                                    const float wv_ = wcur[((k >> 2) * 4 * K + (rho ^ ((rho >> 3) & 7))) * 4 + (k & 3)];
+                                    Nw[((size_t)k * K + 4 * pos.it + c) * K + jj[z]] = nold[z][c] + wv_ * acc[z][c];
+                                }
+                            }
+                        } else {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                sP[(wave * LY::NPART + 16 * LY::S32 + 4 * (o0 + z) + c) * 64 + lane] = acc[z][c];
+                        }
+                    }
+                }
+            }
+            // ---- posterior GEMM: U[(il, j), b] = sum_k W[k, 4 it + il, j] Q[b, k]; tile m holds rows 32 m .. 32 m + 31 of (il, j)
+            const float* wsl = lds + (u & 1) * LY::SLICE + h * (4 * K * 4);
+            float gl[4] = {0.f, 0.f, 0.f, 0.f};
+            {
+                floatx4 a[2][K8];
+                floatx16 acc[2];
+#pragma unroll
+                for (int t = 0; t < K8; ++t) a[0][t] = *reinterpret_cast<const floatx4*>(wsl + 2 * t * (4 * K * 4) + prow[0]);
+#pragma unroll
+                for (int m = 0; m <= K8; ++m) {
+                    if (m + 1 < K8) {
+#pragma unroll
+                        for (int t = 0; t < K8; ++t)
+                            a[(m + 1) & 1][t] = *reinterpret_cast<const floatx4*>(wsl + 2 * t * (4 * K * 4) + prow[m + 1 < K8 ? m + 1 : 0]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (m < K8) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[m & 1][v] = 0.f;
+#pragma unroll
+                        for (int t = 0; t < K8; ++t)
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                acc[m & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[m & 1][t][c], q[4 * t + c], acc[m & 1], 0, 0, 0);
+                    }
+                    if (m > 0) {
+                        // acc[4 a + c]: row 8 a + 4 h + c of tile m - 1; group gg = 4 (m - 1) + a: il = gg / K8, j = 8 (gg % K8) + 4 h + c
+#pragma unroll
+                        for (int a4 = 0; a4 < 4; ++a4) {
+                            const int gg = 4 * (m - 1) + a4, il = gg / K8, uu = gg % K8;
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                const float v = acc[(m - 1) & 1][4 * a4 + c];
+                                gl[il] = fmaf(v, er[4 * uu + c], gl[il]);
+                                gr[4 * uu + c] = fmaf(v, el4[il], gr[4 * uu + c]);
+                            }
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int il = 0; il < 4; ++il) gl[il] += __shfl_xor(gl[il], 32, 64);
+            if (h == 0 && bg < B) {
+                floatx4 o = {gl[0] * el4[0], gl[1] * el4[1], gl[2] * el4[2], gl[3] * el4[3]};
+                *reinterpret_cast<floatx4*>(Gp + ((size_t)item * NB * B + bg) * K + 4 * pos.it) = o;
+            }
+            // next unit
+            Pos npos = pos;
+            const bool nvalid = advance(npos);
+            new_ops = !nvalid || npos.li != pos.li || npos.chunk != pos.chunk;
+            if (new_ops) {
+                // the right child's share of this workgroup's slices of (item, chunk)
+                const int grp = g - bwds_wg_of_pair((long long)pos.li * NS, P, gridDim.x);
+                if (bg < B) {
+                    float* right = Gp + ((size_t)(item * NB + 1 + grp) * B + bg) * K + 4 * h;
+#pragma unroll
+                    for (int t = 0; t < K8; ++t) {
+                        floatx4 o = {gr[4 * t] * er[4 * t], gr[4 * t + 1] * er[4 * t + 1], gr[4 * t + 2] * er[4 * t + 2], gr[4 * t + 3] * er[4 * t + 3]};
+                        *reinterpret_cast<floatx4*>(right + 8 * t) = o;
+                    }
+                }
+#pragma unroll
+                for (int x = 0; x < 4 * K8; ++x) gr[x] = 0.f;
+            }
+            __syncthreads();                              // B(u+1)
+            if (!nvalid) break;
+            pos = npos;
+            ++u;
+            if (new_ops) __syncthreads();                 // X(u): the next operands are staged
+        }
+    }
+}
+
 }  // namespace
 
 void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
@@ -447,13 +966,16 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
                                       const float* params, float* stats, const float* A, const double* Off,
                                       const float* amax, const float* G, float* Gp, const Dims& d, hipStream_t s) {
     const size_t lds = sizeof(float) * BwdLayout<KQ>::LDS_FLOATS;
-    static bool attr_set = false;
-    if (lds > 64 * 1024 && !attr_set) {
-        allow_dynamic_lds(&k_einsum_backward<KQ, true, true>, lds);
-        allow_dynamic_lds(&k_einsum_backward<KQ, false, true>, lds);
-        allow_dynamic_lds(&k_einsum_backward<KQ, true, false>, lds);
-        allow_dynamic_lds(&k_einsum_backward<KQ, false, false>, lds);
-        attr_set = true;
+    if (lds > 64 * 1024) {
+        static std::once_flag attr_set[EINET_MAX_DEVICES];
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] {
+            allow_dynamic_lds(&k_einsum_backward<KQ, true, true>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, false, true>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, true, false>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, false, false>, lds);
+        });
     }
     const int ngroups = bwd_groups_per_item(count, d.K);
 #define EINET_LAUNCH(V, ACC)                                                                                      \
@@ -471,10 +993,41 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
 #undef EINET_LAUNCH
 }
 
-void launch_einsum_backward(const DevTables& t, int first, int count, bool accumulate, const float* params,
-                            float* stats, const float* A, const double* Off, const float* amax, const float* G,
-                            float* Gp, const Dims& d, hipStream_t s) {
+template <int K8>
+static void launch_einsum_backward_k8(const DevTables& t, int first, int count, bool accumulate, const float* params,
+                                      float* stats, const float* A, const double* Off, const float* amax,
+                                      const float* G, float* Gp, const Dims& d, hipStream_t s) {
+    using LY = BwdSLayout<K8>;
+    const size_t lds = sizeof(float) * LY::LDS_FLOATS;
+    static std::once_flag attr_set[EINET_MAX_DEVICES];
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] {
+        allow_dynamic_lds(&k_einsum_backward_s<K8, true>, lds);
+        allow_dynamic_lds(&k_einsum_backward_s<K8, false>, lds);
+    });
+    const int grid = bwd_split_grid(count, d.K);
+#define EINET_LAUNCH(ACC)                                                                                         \
+    hipLaunchKernelGGL((k_einsum_backward_s<K8, ACC>), dim3(grid), dim3(512), lds, s, t.ein_left + first,          \
+                       t.ein_right + first, t.ein_out + first, t.ein_reg + first, t.ein_woff + first,             \
+                       t.ein_voff + first, t.ein_vstr + first, params, stats, A, Off, amax, G, Gp, first, count, d.B)
+    if (accumulate) EINET_LAUNCH(true);
+    else EINET_LAUNCH(false);
+#undef EINET_LAUNCH
+}
+
+void launch_einsum_backward(const DevTables& t, int first, int count, bool full_k, bool accumulate,
+                            const float* params, float* stats, const float* A, const double* Off, const float* amax,
+                            const float* G, float* Gp, const Dims& d, hipStream_t s) {
     if (count == 0) return;
+    if (bwd_uses_split_kernel(d.K, full_k)) {
+        switch (d.K / 8) {
+#define EINET_CASE(J) \
+        case J: launch_einsum_backward_k8<J>(t, first, count, accumulate, params, stats, A, Off, amax, G, Gp, d, s); return;
+            EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5)
+#undef EINET_CASE
+        }
+    }
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
     case J: launch_einsum_backward_kq<J>(t, first, count, accumulate, params, stats, A, Off, amax, G, Gp, d, s); break;

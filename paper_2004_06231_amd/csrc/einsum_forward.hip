@@ -1,6 +1,8 @@
 // Bottom-up pass: einsum layers (Eq. 3-5) and mixing layers (App. B).
 #include "device_common.hpp"
 
+#include <mutex>
+
 namespace einet_impl {
 
 namespace {
@@ -203,6 +205,224 @@ __global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __rest
     }
 }
 
+// ------------------------------------------------------------------ einsum layer, forward, K a multiple of 8
+// The same factorisation on v_mfma_f32_32x32x2_f32 (the fp32 shape that issues at the full rate of the matrix
+// pipe), as one workgroup per compute unit that walks a run of work units.  A tile of the product T has 32 rows
+// (k, i) and 32 samples; with i fastest, groups of 8 rows stay inside one k, and a lane holds four consecutive i of
+// four such groups, so the i-reduction is again in-lane: 16 FMAs per tile.  K / 8 tiles hold exactly four k.
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+template <int K8>
+struct FwdSLayout {
+    static constexpr int K = 8 * K8;
+    static constexpr int RS = K + 4;                 // row stride (floats): RS/4 odd -> 16-byte operand reads of 8 lanes hit 32 banks
+    static constexpr int SLICE = 4 * K * RS;         // W[4 k][K i][RS]
+    static constexpr int OFF_E = 2 * SLICE;          // eR, eL of the four sample tiles: [tile][2][K8][64 lanes][4]
+    static constexpr int OFF_S = OFF_E + 4 * 2 * K8 * 256;   // sums of a unit: [2 slots][tile][64 lanes][4]
+    static constexpr int LDS_FLOATS = OFF_S + 2 * 4 * 256;
+    static constexpr int NQ4 = 4 * K * (K / 4);      // float4 of a slice
+    static constexpr int NL = (NQ4 + 255) / 256;     // per producer thread
+};
+
+// A workgroup owns a run of units; a unit is (item, batch chunk of 128 samples, 4 outputs k) = K8 tiles of 32 rows
+// (k, i) of the product W[(k,i), j] eR[j, b].  Waves 0-3 only run the matrix pipe: wave w owns samples 32 w .. 32 w + 31
+// of the chunk, reads its operands from LDS and leaves four sums per lane in LDS.  Waves 4-7 do everything else: they
+// bring the W slices and the child rows in, form exp(x - max), and turn the sums of the previous unit into log values.
+template <int K8>
+__global__ __launch_bounds__(512, 1) void k_einsum_forward_s(const int32_t* __restrict__ e_left,
+                                                           const int32_t* __restrict__ e_right,
+                                                           const int32_t* __restrict__ e_out,
+                                                           const int32_t* __restrict__ e_woff,
+                                                           const float* __restrict__ params, float* __restrict__ A,
+                                                           double* __restrict__ Off, float* __restrict__ amax,
+                                                           int item0, int count, int B) {
+    using LY = FwdSLayout<K8>;
+    constexpr int K = LY::K, RS = LY::RS, NQ = K / 4, NL = LY::NL;
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int nt = wave & 3;                          // sample tile of this wave (both roles)
+    const int nchunks = (B + 127) >> 7;
+    const int U = count * nchunks * NQ;              // unit = (item, chunk, quad), quad fastest
+    const int g = xcd_contiguous_block();
+    const int u0 = (int)((long long)g * U / gridDim.x), u1 = (int)((long long)(g + 1) * U / gridDim.x);
+    if (u0 >= u1) return;
+    // position of the first unit
+    int quad = u0 % NQ, chunk = (u0 / NQ) % nchunks, li = u0 / (NQ * nchunks);
+    float* erl = lds + LY::OFF_E + nt * (2 * K8 * 256) + lane * 4;       // + (2 * which + t) * 256 ... see below
+
+    if (wave >= 4) {
+        // ------------------------------------------------------------ producer waves
+        const int pt = tid - 256;
+        floatx4 wv[NL];
+#define FETCH_W(li_, quad_)                                                                \
+    {                                                                                      \
+        const float* W_ = params + e_woff[li_] + (size_t)(quad_) * 4 * K * K;              \
+        _Pragma("unroll") for (int q = 0; q < NL; ++q) {                                   \
+            const int f = min(pt + 256 * q, LY::NQ4 - 1);                                  \
+            wv[q] = *reinterpret_cast<const floatx4*>(W_ + (size_t)4 * f);                 \
+        }                                                                                  \
+    }
+#define STORE_W(buf_)                                                                      \
+    {                                                                                      \
+        _Pragma("unroll") for (int q = 0; q < NL; ++q) {                                   \
+            const int f = pt + 256 * q;                                                    \
+            const int row = f / (K / 4), c4 = f - row * (K / 4);                           \
+            if (f < LY::NQ4) *reinterpret_cast<floatx4*>((buf_) + row * RS + 4 * c4) = wv[q]; \
+        }                                                                                  \
+    }
+        // rows of (item, chunk): lane (n, h) of tile nt takes entries 8 t + 4 h .. + 3 of sample 32 nt + n; exp(x - max)
+        // goes to LDS for the matrix wave of the same tile; the item's first unit also owns the offsets and shifts
+        auto rows = [&](int rli, int rchunk, bool owner) {
+            const int b = rchunk * 128 + nt * 32 + n;
+            const int bc = min(b, B - 1);              // rows beyond the batch read the last one again
+            const int left = e_left[rli], right = e_right[rli];
+            const float* Lp = A + ((size_t)left * B + bc) * K + 4 * h;
+            const float* Rp = A + ((size_t)right * B + bc) * K + 4 * h;
+            floatx4 rawR[K8], rawL[K8];
+#pragma unroll
+            for (int t = 0; t < K8; ++t) {
+                rawR[t] = *reinterpret_cast<const floatx4*>(Rp + 8 * t);
+                rawL[t] = *reinterpret_cast<const floatx4*>(Lp + 8 * t);
+            }
+            double off_children = 0.0;
+            if (owner && h == 0) off_children = Off[(size_t)left * B + bc] + Off[(size_t)right * B + bc];
+            float xr = -INFINITY, xl = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < K8; ++t) {
+                xr = fmaxf(fmaxf(xr, fmaxf(rawR[t][0], rawR[t][1])), fmaxf(rawR[t][2], rawR[t][3]));
+                xl = fmaxf(fmaxf(xl, fmaxf(rawL[t][0], rawL[t][1])), fmaxf(rawL[t][2], rawL[t][3]));
+            }
+            xr = fmaxf(xr, __shfl_xor(xr, 32, 64));
+            xl = fmaxf(xl, __shfl_xor(xl, 32, 64));
+            if (xr == -INFINITY) xr = 0.f;             // an all-zero input vector: exp(-inf) = 0, no NaN
+            if (xl == -INFINITY) xl = 0.f;
+#pragma unroll
+            for (int t = 0; t < K8; ++t) {
+                floatx4 er, el;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    er[c] = __expf(rawR[t][c] - xr);
+                    el[c] = __expf(rawL[t][c] - xl);
+                }
+                *reinterpret_cast<floatx4*>(erl + t * 256) = er;
+                *reinterpret_cast<floatx4*>(erl + (K8 + t) * 256) = el;
+            }
+            if (owner && h == 0 && b < B) {
+                const int out = e_out[rli];
+                Off[(size_t)out * B + b] = off_children + (double)xl + (double)xr;
+                amax[((size_t)(item0 + rli) * 2) * B + b] = xl;
+                amax[((size_t)(item0 + rli) * 2 + 1) * B + b] = xr;
+            }
+        };
+        // sums of a finished unit -> residuals log S~
+        auto finish = [&](int fli, int fchunk, int fquad, int slot) {
+            const float* sp = lds + LY::OFF_S + (slot * 4 + nt) * 256 + n * 4;
+            const floatx4 s0 = *reinterpret_cast<const floatx4*>(sp);
+            const floatx4 s1 = *reinterpret_cast<const floatx4*>(sp + 128);
+            const int b = fchunk * 128 + nt * 32 + n;
+            if (h == 0 && b < B) {
+                floatx4 r;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) r[c] = __logf(s0[c] + s1[c]);
+                *reinterpret_cast<floatx4*>(A + ((size_t)e_out[fli] * B + b) * K + 4 * fquad) = r;
+            }
+        };
+        FETCH_W(li, quad)
+        rows(li, chunk, quad == 0);
+        STORE_W(lds)
+        // position of the unit whose slice is in flight
+        int lq = quad, lc = chunk, lli = li;
+        auto advance = [&](int& q_, int& c_, int& i_) {
+            if (++q_ == NQ) { q_ = 0; if (++c_ == nchunks) { c_ = 0; ++i_; } }
+        };
+        advance(lq, lc, lli);
+        if (u0 + 1 < u1) FETCH_W(lli, lq)
+        __syncthreads();                                // B0: slice u0 and the first rows are in LDS
+        __syncthreads();                                // X: the matrix waves hold the rows in registers
+        int pq = quad, pc = chunk, pli = li;            // previous unit
+        for (int u = u0; u < u1; ++u) {
+            // the matrix waves work on unit u = (li, chunk, quad)
+            if (u + 1 < u1) {
+                STORE_W(lds + ((u + 1 - u0) & 1) * LY::SLICE)
+                int q2 = lq, c2 = lc, i2 = lli;
+                advance(q2, c2, i2);
+                if (u + 2 < u1) FETCH_W(i2, q2)
+            }
+            if (u > u0) finish(pli, pc, pq, (u - 1 - u0) & 1);
+            const bool new_rows = u + 1 < u1 && quad == NQ - 1;
+            if (new_rows) rows(lli, lc, true);
+            pq = quad; pc = chunk; pli = li;
+            quad = lq; chunk = lc; li = lli;
+            advance(lq, lc, lli);
+            __syncthreads();                            // B(u+1)
+            if (new_rows) __syncthreads();              // X
+        }
+        finish(pli, pc, pq, (u1 - 1 - u0) & 1);
+    } else {
+        // ------------------------------------------------------------ matrix waves
+        float er[4 * K8], el[K8][4];
+        const bool active = chunk * 128 + nt * 32 < B || nchunks > 1;     // (a tile beyond a short batch does nothing)
+        __syncthreads();                                // B0
+        bool load_rows = true;
+        for (int u = u0; u < u1; ++u) {
+            if (load_rows) {
+#pragma unroll
+                for (int t = 0; t < K8; ++t) {
+                    const floatx4 r = *reinterpret_cast<const floatx4*>(erl + t * 256);
+                    const floatx4 l = *reinterpret_cast<const floatx4*>(erl + (K8 + t) * 256);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) { er[4 * t + c] = r[c]; el[t][c] = l[c]; }
+                }
+                __syncthreads();                        // X
+            }
+            const float* wrow = lds + ((u - u0) & 1) * LY::SLICE + n * RS + 4 * h;
+            float sk[4] = {0.f, 0.f, 0.f, 0.f};
+            if (active) {
+                floatx4 a[2][K8];
+                floatx16 acc[2];
+#pragma unroll
+                for (int t = 0; t < K8; ++t) a[0][t] = *reinterpret_cast<const floatx4*>(wrow + 8 * t);
+#pragma unroll
+                for (int m = 0; m <= K8; ++m) {
+                    if (m + 1 < K8) {
+#pragma unroll
+                        for (int t = 0; t < K8; ++t)
+                            a[(m + 1) & 1][t] = *reinterpret_cast<const floatx4*>(wrow + 32 * (m + 1) * RS + 8 * t);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (m < K8) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[m & 1][r] = 0.f;
+#pragma unroll
+                        for (int t = 0; t < K8; ++t) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                acc[m & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[m & 1][t][c], er[4 * t + c], acc[m & 1], 0, 0, 0);
+                        }
+                    }
+                    if (m > 0) {
+                        // acc[4 a + c]: row 8 a + 4 h + c of tile m - 1; group g = 4 (m - 1) + a: k = g / K8, i = 8 (g % K8) + 4 h + c
+#pragma unroll
+                        for (int a4 = 0; a4 < 4; ++a4) {
+                            const int gg = 4 * (m - 1) + a4, kq = gg / K8, uu = gg % K8;
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) sk[kq] = fmaf(acc[(m - 1) & 1][4 * a4 + c], el[uu][c], sk[kq]);
+                        }
+                    }
+                }
+            }
+            floatx4 sv = {sk[0], sk[1], sk[2], sk[3]};
+            *reinterpret_cast<floatx4*>(lds + LY::OFF_S + (((u - u0) & 1) * 4 + nt) * 256 + lane * 4) = sv;
+            load_rows = u + 1 < u1 && quad == NQ - 1;
+            if (++quad == NQ) quad = 0;
+            __syncthreads();                            // B(u+1)
+        }
+    }
+#undef FETCH_W
+#undef STORE_W
+}
+
 // ------------------------------------------------------------------ mixing layer, forward (App. B)
 // Offset of the output: the largest offset of the children (their residuals are at most 0, so no term
 // exceeds its weight); residual: log sum_c v[c] exp((Off[c] - Off[out]) + A[c]).
@@ -297,18 +517,42 @@ static void launch_einsum_forward_kq(const DevTables& t, int first, int count, c
     const int n_btiles = (d.B + 15) / 16;
     const int nw = n_btiles < 8 ? n_btiles : 8;
     const size_t lds = sizeof(float) * FwdLayout<KQ>::LDS_FLOATS;
-    static bool attr_set = false;
-    if (lds > 64 * 1024 && !attr_set) {
-        allow_dynamic_lds(&k_einsum_forward<KQ>, lds);
-        attr_set = true;
+    if (lds > 64 * 1024) {
+        static std::once_flag attr_set[EINET_MAX_DEVICES];
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] { allow_dynamic_lds(&k_einsum_forward<KQ>, lds); });
     }
     hipLaunchKernelGGL(k_einsum_forward<KQ>, dim3(count * nkt), dim3(64 * nw), lds, s, t.ein_left + first,
                        t.ein_right + first, t.ein_out + first, t.ein_kout + first, t.ein_woff + first, params, A, Off,
                        amax, logp, first, d.B, d.K, nkt);
 }
 
-void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
-                           float* amax, float* logp, const Dims& d, hipStream_t s) {
+template <int K8>
+static void launch_einsum_forward_k8(const DevTables& t, int first, int count, const float* params, float* A,
+                                     double* Off, float* amax, const Dims& d, hipStream_t s) {
+    using LY = FwdSLayout<K8>;
+    const size_t lds = sizeof(float) * LY::LDS_FLOATS;
+    static std::once_flag attr_set[EINET_MAX_DEVICES];
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] { allow_dynamic_lds(&k_einsum_forward_s<K8>, lds); });
+    const int units = count * ((d.B + 127) / 128) * (LY::K / 4);
+    hipLaunchKernelGGL(k_einsum_forward_s<K8>, dim3(units < EINET_NUM_CUS ? units : EINET_NUM_CUS), dim3(512), lds, s,
+                       t.ein_left + first, t.ein_right + first, t.ein_out + first, t.ein_woff + first, params, A, Off,
+                       amax, first, count, d.B);
+}
+
+void launch_einsum_forward(const DevTables& t, int first, int count, bool full_k, const float* params, float* A,
+                           double* Off, float* amax, float* logp, const Dims& d, hipStream_t s) {
+    if (full_k && (d.K & 7) == 0 && d.K <= 48) {
+        switch (d.K / 8) {
+#define EINET_CASE(J) \
+        case J: launch_einsum_forward_k8<J>(t, first, count, params, A, Off, amax, d, s); return;
+            EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6)
+#undef EINET_CASE
+        }
+    }
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
     case J: launch_einsum_forward_kq<J>(t, first, count, params, A, Off, amax, logp, d, s); break;

@@ -34,9 +34,10 @@ void launch_leaf_derive(const float* phi, float* theta, const Dims& d, hipStream
 // A [node][B][K] float32 holds residuals, Off [node][B] float64 the offsets: log-density = Off + A
 void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const float* x, const uint8_t* mask,
                          int mask_mode, const float* theta, float* A, double* Off, const Dims& d, hipStream_t s);
-// logp (may be NULL): the launch that produces the root value also writes it there
-void launch_einsum_forward(const DevTables& t, int first, int count, const float* params, float* A, double* Off,
-                           float* amax, float* logp, const Dims& d, hipStream_t s);
+// logp (may be NULL): the launch that produces the root value also writes it there.  full_k: every item of the
+// launch has K output entries (all layers but the root's).
+void launch_einsum_forward(const DevTables& t, int first, int count, bool full_k, const float* params, float* A,
+                           double* Off, float* amax, float* logp, const Dims& d, hipStream_t s);
 // A mixing item with at most MIX_REC_CHILDREN partitions also has a record of MIX_REC_INTS ints in mix_rec:
 // node, entries, offset of its weights, number of partitions, then the nodes of the partitions.  The kernel gets
 // all of it with one request instead of walking three tables one after the other.
@@ -50,10 +51,11 @@ void launch_mixing_forward(const DevTables& t, int first, int count, int max_chi
 constexpr int RB_REC_INTS = 32, RB_REC_BLOCKS = 28;
 void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
                             const Dims& d, hipStream_t s);
-// accumulate = false: the weight statistics of these items are known to be zero and are overwritten
-void launch_einsum_backward(const DevTables& t, int first, int count, bool accumulate, const float* params,
-                            float* stats, const float* A, const double* Off, const float* amax, const float* G,
-                            float* Gp, const Dims& d, hipStream_t s);
+// accumulate = false: the weight statistics of these items are known to be zero and are overwritten.
+// full_k: every item of the launch has K output entries (all layers but the root's).
+void launch_einsum_backward(const DevTables& t, int first, int count, bool full_k, bool accumulate,
+                            const float* params, float* stats, const float* A, const double* Off, const float* amax,
+                            const float* G, float* Gp, const Dims& d, hipStream_t s);
 // posterior blocks ([B][K] floats each) reserved per einsum item in Gp: one for its left child, then up to
 // one per slice of four left entries for its right child
 inline int gp_blocks_per_item(int K) { return 1 + (K + 3) / 4; }
@@ -65,6 +67,26 @@ inline int bwd_groups_per_item(int count, int K) {
     const int kq = (K + 3) / 4;
     const int g = 256 / (count > 0 ? count : 1);
     return g < 1 ? 1 : (g > kq ? kq : g);
+}
+// Layers whose items all have K output entries, K a multiple of 8 up to 40, take the top-down kernel with
+// specialised waves: one workgroup per compute unit, the layer's count * K/4 (item, slice) pairs split evenly
+// over the workgroups in order, so that a workgroup's pairs touch one or two items.  Workgroup g owns the pairs
+// g * P / G .. (g + 1) * P / G - 1 and writes right-child block 1 + (g - first workgroup of the item).
+inline bool bwd_uses_split_kernel(int K, bool full_k) { return full_k && (K & 7) == 0 && K <= 40; }
+inline int bwd_split_grid(int count, int K) {
+    const int pairs = count * (K / 4);
+    return pairs < 256 ? pairs : 256;
+}
+// workgroup that owns pair x of P pairs split over G workgroups
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+inline int bwds_wg_of_pair(long long x, long long P, long long G) { return (int)(((x + 1) * G - 1) / P); }
+// right-child blocks that item li of a layer of `count` items writes (the workgroups that touch it)
+inline int bwd_blocks_of_item(int count, int K, bool full_k, int li) {
+    if (!bwd_uses_split_kernel(K, full_k)) return bwd_groups_per_item(count, K);
+    const long long ns = K / 4, P = (long long)count * ns, G = bwd_split_grid(count, K);
+    return bwds_wg_of_pair((li + 1) * ns - 1, P, G) - bwds_wg_of_pair(li * ns, P, G) + 1;
 }
 // leaf statistics and mixing statistics (independent of each other) in one launch
 void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_scope, int n_mix, int max_children,

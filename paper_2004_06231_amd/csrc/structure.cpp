@@ -260,6 +260,9 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param
             p.layer_partition.push_back(n);
             p.ein_part.push_back(n);
         }
+        bool full = true;
+        for (size_t e = (size_t)p.ein_layer_ptr.back(); e < p.ein_kout.size(); ++e) full = full && p.ein_kout[e] == K;
+        p.ein_layer_full.push_back(full ? 1 : 0);
         p.ein_layer_ptr.push_back((int32_t)p.ein_left.size());
         p.layer_ptr.push_back((int32_t)p.layer_partition.size());
     }
@@ -356,7 +359,8 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param
         for (int e = p.ein_layer_ptr[l]; e < p.ein_layer_ptr[l + 1]; ++e) layer_of_item[e] = l;
     for (int n = 0; n < np; ++n) {
         const int e = item_of[n], l = layer_of_item[e];
-        const int groups = bwd_groups_per_item(p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], K);
+        const int groups = bwd_blocks_of_item(p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], K, p.ein_layer_full[l] != 0,
+                                              e - p.ein_layer_ptr[l]);
         runs[g.partition[n][1]].push_back({e * nb, 1});
         runs[g.partition[n][2]].push_back({e * nb + 1, groups});
     }
