@@ -24,9 +24,22 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_FP32_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
 WORKLOAD = 4
-# HBM bytes per launch of the dominant kernel on the default workload, from two rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE; see profiles/hbm_traffic_cfg4.md): (31721 + 77890) KiB over six launches
-MEASURED_TRAFFIC = {(4, "einsum_backward"): 18.71e6}
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of a kernel class on a configuration, as the committed counter summary states it
+    (profiles/hbm_traffic_cfg<N>.md, line `traffic_bytes_per_launch <kernel class> <bytes>`, written from two
+    rocprofv3 --pmc runs); None when there is no such measurement."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_cfg{workload}.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                w = line.split()
+                if len(w) >= 3 and w[0] == "traffic_bytes_per_launch" and w[1] == kernel:
+                    return float(w[2])
+    except OSError:
+        pass
+    return None
 
 
 def algorithmic_work(st, K, C, R, T, TD, B, D):
@@ -102,6 +115,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the streaming-copy and register-resident MFMA loops")
     ap.add_argument("--workload", type=int, default=WORKLOAD, help="configuration to time (1-5); the default is the headline")
     ap.add_argument("--batch", type=int, default=0,
                     help="batch size instead of the configuration's own (for batch-scaling tables; not the headline)")
@@ -191,6 +205,7 @@ def main():
         em_step()
     torch.cuda.synchronize()
     prof = m.profile_read()
+    launch_list = m.profile_launches()
     m.profile_enable(False)
     work = algorithmic_work(st, K, C, R, T, TD, B, D)
     kernels = {}
@@ -217,8 +232,33 @@ def main():
                     frac=round(achieved / PEAK_HBM_GBS, 4))
     roof.update(kernel=dom, avg_launch_us=round(avg_launch_s * 1e6, 2), launches_per_step=n_launch,
                 algorithmic_flop_per_step=flop, algorithmic_bytes_per_step=byts,
-                traffic=MEASURED_TRAFFIC.get((wl, dom)) if B == cfg["B"] else None,
+                algorithmic_bytes_per_launch=round(byts / n_launch, 1),
+                traffic=measured_traffic(wl, dom) if B == cfg["B"] else None,
+                traffic_unit="HBM bytes per launch (rocprofv3 counters, profiles/hbm_traffic_cfg%d.md)" % wl,
                 timing="hip events around each launch, separate pass of the same steps")
+
+    # launch by launch: the einsum layers of one step, averaged over the steps of the profiled pass (the work tag of
+    # a launch is the number of output entries summed over its partitions)
+    ein = [l for l in launch_list if l[0] in ("einsum_forward", "einsum_backward")]
+    per_step = len(ein) // args.steps
+    layers = []
+    if per_step * args.steps == len(ein):
+        for pos in range(per_step):
+            name, _, wk = ein[pos]
+            us = 1e3 * sum(ein[s_ * per_step + pos][1] for s_ in range(args.steps)) / args.steps
+            fl = (2.0 if name == "einsum_forward" else 4.0) * B * K * K * wk
+            layers.append(dict(kernel=name, outputs=int(wk), partitions=int(wk // K) if wk % K == 0 else int(wk),
+                               us=round(us, 2), tflops=round(fl / us / 1e6, 2),
+                               frac=round(fl / us / 1e6 / PEAK_MFMA_FP32_TFLOPS, 4)))
+    roof["einsum_layers"] = layers
+
+    if not args.no_peaks:
+        pk = P.measure_peaks()
+        roof["measured_peaks"] = {k: round(v, 1) for k, v in pk.items()}
+        if roof["bound"] == "mfma":
+            roof["frac_of_measured_peak"] = round(roof["achieved"] / pk["mfma_f32_32x32x2_tflops"], 4)
+        else:
+            roof["frac_of_measured_peak"] = round(roof["achieved"] / pk["copy_gbs"], 4)
 
     out = {
         "metric": "EM samples/sec (fwd+bwd+M-step)", "value": round(B * args.steps / t_em, 1), "unit": "samples/s",

@@ -322,6 +322,28 @@ int einet_mixture_logp(const float* logp_dev, const float* log_coef_dev, int n_c
 int einet_profile_enable(einet_t* h, int enable);
 int einet_profile_read(einet_t* h, int capacity, int* n_classes, const char** names, double* total_ms,
                        int64_t* launches);
+/* The launches that the last einet_profile_read summed, one by one and in the order
+ * they were enqueued: cls[i] (index into the names of einet_profile_read),
+ * ms[i], and work[i]: for the launches of an einsum layer the number of output
+ * entries summed over the layer's partitions (K per partition, 1 for a
+ * partition of the root), so that the launch's algorithmic flop are
+ * 2 B K^2 work bottom-up and 4 B K^2 work top-down (Eq. 5, Eq. 6); 0 for the
+ * other classes.  Writes up to `capacity` entries; *n_launches receives their
+ * number.  All outputs: host. */
+int einet_profile_launches(einet_t* h, int64_t capacity, int64_t* n_launches, int32_t* cls, float* ms, int64_t* work);
+
+/* Achievable peaks of the current device, measured with plain kernels (no
+ * passage of the paper: measurement aid, needs no handle): out4[0] the rate
+ * of a streaming copy of `bytes` bytes from src_dev to dst_dev in GB/s (read
+ * plus written), out4[1] the rate of a register-resident loop of
+ * v_mfma_f32_32x32x2_f32 in TFLOP/s, out4[2] and out4[3] the same for
+ * v_mfma_f32_16x16x4_f32 with one and with four waves per SIMD; each the best
+ * of `reps` launches.  src_dev, dst_dev: device buffers of `bytes` bytes owned
+ * by the caller (bytes a multiple of 16, at least EINET_PEAKS_MIN_BYTES;
+ * dst_dev is overwritten); out4: host.  Synchronises `stream`.  Errors:
+ * EINET_ERR_INVALID_ARG, EINET_ERR_HIP (reason via einet_last_error(NULL)). */
+#define EINET_PEAKS_MIN_BYTES (4 * 1024 * 1024)
+int einet_measure_peaks(const void* src_dev, void* dst_dev, int64_t bytes, int reps, double* out4, void* stream);
 
 #ifdef __cplusplus
 }

@@ -15,7 +15,8 @@ MAX_DELTAS = 8
 EXPORTED_SYMBOLS = [
     "einet_create", "einet_destroy", "einet_last_error", "einet_sizes", "einet_structure", "einet_bind",
     "einet_refresh", "einet_init_params", "einet_logp", "einet_logp_static", "einet_em_accumulate", "einet_em_update", "einet_em_reset", "einet_em_epoch",
-    "einet_mixture_logp", "einet_sample", "einet_profile_enable", "einet_profile_read",
+    "einet_mixture_logp", "einet_sample", "einet_profile_enable", "einet_profile_read", "einet_profile_launches",
+    "einet_measure_peaks",
 ]
 
 
@@ -79,6 +80,9 @@ def load_library():
     lib.einet_profile_enable.argtypes = [vp, i32]
     lib.einet_profile_read.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                        C.POINTER(C.c_int64)]
+    lib.einet_profile_launches.argtypes = [vp, C.c_int64, C.POINTER(C.c_int64), C.POINTER(i32), C.POINTER(f32),
+                                           C.POINTER(C.c_int64)]
+    lib.einet_measure_peaks.argtypes = [vp, vp, C.c_int64, i32, C.POINTER(C.c_double), vp]
     _lib = lib
     return lib
 
@@ -300,7 +304,32 @@ class EiNet:
         n = C.c_int()
         names, ms, cnt = (C.c_char_p * cap)(), (C.c_double * cap)(), (C.c_int64 * cap)()
         self._check(self._lib.einet_profile_read(self._h, cap, C.byref(n), names, ms, cnt))
+        self._class_names = [names[i].decode() for i in range(min(n.value, cap))]
         return {names[i].decode(): (ms[i], cnt[i]) for i in range(min(n.value, cap))}
+
+    def profile_launches(self):
+        """[(kernel class, milliseconds, work tag)] of the launches the last profile_read summed, in order."""
+        n = C.c_int64()
+        self._check(self._lib.einet_profile_launches(self._h, 0, C.byref(n), None, None, None))
+        cap = n.value
+        cls, ms, work = (C.c_int32 * cap)(), (C.c_float * cap)(), (C.c_int64 * cap)()
+        self._check(self._lib.einet_profile_launches(self._h, cap, C.byref(n), cls, ms, work))
+        return [(self._class_names[cls[i]], ms[i], work[i]) for i in range(cap)]
+
+
+def measure_peaks(n_bytes=1 << 30, reps=5):
+    """Streaming-copy rate (GB/s, read + written) and register-resident fp32 MFMA rates (TFLOP/s) of cuda:0."""
+    import torch
+    lib = load_library()
+    src = torch.ones(n_bytes // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    out = (C.c_double * 4)()
+    rc = lib.einet_measure_peaks(src.data_ptr(), dst.data_ptr(), n_bytes, reps, out,
+                                 C.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if rc != 0:
+        raise EinetError(rc, lib.einet_last_error(None).decode())
+    return {"copy_gbs": out[0], "mfma_f32_32x32x2_tflops": out[1], "mfma_f32_16x16x4_tflops": out[2],
+            "mfma_f32_16x16x4_4waves_tflops": out[3]}
 
 
 # The C names, for callers who prefer the flat interface.

@@ -30,8 +30,10 @@ struct einet {
 
     // optional per-launch timing (einet_profile_*)
     bool profiling = false;
-    struct Timed { int cls; hipEvent_t start, stop; };
+    struct Timed { int cls; hipEvent_t start, stop; int64_t work; };
     std::vector<Timed> timed;
+    struct Launch { int cls; float ms; int64_t work; };
+    std::vector<Launch> last_launches;   // the launches of the last einet_profile_read, in order
     int profile_dropped = 0;        // launches that could not be bracketed (event creation failed)
 
     // true while the einsum-weight statistics are logically zero: einet_em_update does not clear them,
@@ -122,12 +124,12 @@ const char* const kKernelClassNames[KC_COUNT] = {"leaf_forward", "einsum_forward
 
 // Runs `launch` (which enqueues kernels on s); when profiling, brackets it with two events.
 template <class F>
-void run(einet_t* h, int cls, hipStream_t s, F&& launch) {
+void run(einet_t* h, int cls, hipStream_t s, F&& launch, int64_t work = 0) {
     if (!h->profiling) {
         launch();
         return;
     }
-    einet::Timed t{cls, nullptr, nullptr};
+    einet::Timed t{cls, nullptr, nullptr, work};
     if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) {
         (void)hipGetLastError();
         if (t.start) (void)hipEventDestroy(t.start);
@@ -154,6 +156,14 @@ Arena workspace_arena(const einet_t* h) {
                  reinterpret_cast<float*>(h->ws + h->off_amax)};
 }
 
+// Output entries of the einsum items of layer l, summed (the work tag of its launches in the profile: the
+// algorithmic flop of a launch are 2 B K^2 times this bottom-up and 4 B K^2 times this top-down).
+int64_t layer_outputs(const Plan& p, int l) {
+    int64_t n = 0;
+    for (int e = p.ein_layer_ptr[l]; e < p.ein_layer_ptr[l + 1]; ++e) n += p.ein_kout[e];
+    return n;
+}
+
 // Leaf layer, then einsum (+ mixing) layers bottom-up; fills the arena.
 void forward(einet_t* h, const Arena& ar, const float* x, const uint8_t* mask, int mask_mode, float* logp,
              const Dims& d, hipStream_t s) {
@@ -168,7 +178,7 @@ void forward(einet_t* h, const Arena& ar, const float* x, const uint8_t* mask, i
         run(h, KC_EINSUM_FWD, s, [&] {
             launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
                                   p.ein_layer_full[l] != 0, h->params, A, Off, ar.amax, logp, d, s);
-        });
+        }, layer_outputs(p, l));
         if (p.mix_layer_ptr[l + 1] > p.mix_layer_ptr[l])
             run(h, KC_MIXING_FWD, s, [&] {
                 int most = 0;                         // partitions of the widest region of this layer
@@ -406,7 +416,7 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
         run(h, KC_EINSUM_BWD, s, [&] {
             launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
                                    p.ein_layer_full[l] != 0, !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp, d, s);
-        });
+        }, layer_outputs(p, l));
     }
     const int leaf_step = p.num_layers;
     run(h, KC_REGION_BWD, s, [&] {
@@ -530,6 +540,7 @@ int einet_profile_read(einet_t* h, int capacity, int* n_classes, const char** na
     double ms[KC_COUNT] = {0};
     int64_t cnt[KC_COUNT] = {0};
     int rc = EINET_OK;
+    h->last_launches.clear();
     for (auto& t : h->timed) {
         float el = 0.f;
         hipError_t e = hipEventSynchronize(t.stop);
@@ -537,6 +548,7 @@ int einet_profile_read(einet_t* h, int capacity, int* n_classes, const char** na
         if (e != hipSuccess) rc = fail(h, EINET_ERR_HIP, std::string("reading profile events: ") + hipGetErrorString(e));
         ms[t.cls] += el;
         cnt[t.cls] += 1;
+        h->last_launches.push_back({t.cls, el, t.work});
         (void)hipEventDestroy(t.start);
         (void)hipEventDestroy(t.stop);
     }
@@ -552,6 +564,26 @@ int einet_profile_read(einet_t* h, int capacity, int* n_classes, const char** na
         if (launches) launches[i] = cnt[i];
     }
     return rc;
+}
+
+int einet_profile_launches(einet_t* h, int64_t capacity, int64_t* n_launches, int32_t* cls, float* ms, int64_t* work) {
+    if (!h || capacity < 0 || !n_launches) return EINET_ERR_INVALID_ARG;
+    *n_launches = (int64_t)h->last_launches.size();
+    for (int64_t i = 0; i < *n_launches && i < capacity; ++i) {
+        if (cls) cls[i] = h->last_launches[i].cls;
+        if (ms) ms[i] = h->last_launches[i].ms;
+        if (work) work[i] = h->last_launches[i].work;
+    }
+    return EINET_OK;
+}
+
+int einet_measure_peaks(const void* src_dev, void* dst_dev, int64_t bytes, int reps, double* out4, void* stream) {
+    if (!src_dev || !dst_dev || !out4 || reps < 1 || bytes < (int64_t)EINET_PEAKS_MIN_BYTES || bytes % 16 != 0)
+        return fail(nullptr, EINET_ERR_INVALID_ARG,
+                    "einet_measure_peaks: buffers of at least EINET_PEAKS_MIN_BYTES bytes, a multiple of 16, and reps >= 1");
+    if (measure_peaks(src_dev, dst_dev, (size_t)bytes, reps, out4, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return fail(nullptr, EINET_ERR_HIP, "einet_measure_peaks: a timed launch failed");
+    return check_hip(nullptr, "einet_measure_peaks");
 }
 
 }  // extern "C"

@@ -649,15 +649,15 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
         for (;;) {
             // the matrix waves work on unit u = pos; slice npos is in registers
             if (have_prev) reduce_shared(prev);
+            if (nvalid) store_w(lds + ((u + 1) & 1) * LY::SLICE);
+            if constexpr (LY::NPART > 0) __syncthreads();  // M(u)
             fetch_shared(pos);
             if (nvalid) {
-                store_w(lds + ((u + 1) & 1) * LY::SLICE);
                 Pos nn = npos;
                 if (advance(nn)) fetch_w(nn);
             }
             const bool new_ops = nvalid && (npos.li != pos.li || npos.chunk != pos.chunk);
             if (new_ops) fetch_rows(npos);
-            if constexpr (LY::NPART > 0) __syncthreads();  // M(u)
             __syncthreads();                              // B(u+1)
             prev = pos; have_prev = true;
             if (!nvalid) break;

@@ -126,6 +126,11 @@ void launch_sample_leaves(const DevTables& t, int n_lv, const float* x, const ui
 // (256-byte aligned).  No allocation: the arena is part of the loaded code object.
 hipError_t static_scratch_address(void** ptr);
 
+// Streaming-copy rate (GB/s, read + written) and register-resident fp32 MFMA rates (TFLOP/s: 32x32x2; 16x16x4 with one
+// and with four waves per SIMD) of the current device, best of `reps` launches each; dst also receives the loops'
+// results (it needs at least EINET_PEAKS_MIN_BYTES bytes).
+hipError_t measure_peaks(const void* src, void* dst, size_t bytes, int reps, double* out, hipStream_t s);
+
 void launch_mixture_logp(const float* lp, const float* log_coef, int n_components, int B, float* out, hipStream_t s);
 
 }  // namespace einet_impl
