@@ -70,6 +70,46 @@ def algorithmic_work(st, K, C, R, T, TD, B, D):
     return w
 
 
+def profiled_pass(m, em_step, steps, work):
+    """Runs `steps` EM steps with a HIP event pair around every launch (recorded on the stream the kernels run on;
+    a separate pass, since recording costs host time).  Returns the per-class table, the roofline of the class with
+    the largest device time, and the launches one by one."""
+    import torch
+    m.profile_enable(True)
+    for _ in range(steps):
+        em_step()
+    torch.cuda.synchronize()
+    prof = m.profile_read()
+    launch_list = m.profile_launches()
+    m.profile_enable(False)
+    kernels = {}
+    for name, (ms, launches) in prof.items():
+        if launches == 0:
+            continue
+        flop, byts = work[name]
+        per_step_us = 1e3 * ms / steps
+        kernels[name] = dict(us_per_step=round(per_step_us, 2), launches_per_step=launches // steps,
+                             tflops=round(flop / (per_step_us * 1e-6) / 1e12, 3),
+                             gbs=round(byts / (per_step_us * 1e-6) / 1e9, 1))
+    dom = max(kernels, key=lambda n: kernels[n]["us_per_step"])
+    flop, byts = work[dom]
+    n_launch = kernels[dom]["launches_per_step"]
+    avg_launch_s = kernels[dom]["us_per_step"] * 1e-6 / n_launch
+    # which roof binds the dominant kernel: the one that takes longer at peak
+    if flop / (PEAK_MFMA_FP32_TFLOPS * 1e12) >= byts / (PEAK_HBM_GBS * 1e9):
+        achieved = flop / n_launch / avg_launch_s / 1e12
+        roof = dict(bound="mfma", achieved=round(achieved, 3), peak=PEAK_MFMA_FP32_TFLOPS, unit="TFLOP/s",
+                    frac=round(achieved / PEAK_MFMA_FP32_TFLOPS, 4))
+    else:
+        achieved = byts / n_launch / avg_launch_s / 1e9
+        roof = dict(bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(achieved / PEAK_HBM_GBS, 4))
+    roof.update(kernel=dom, avg_launch_us=round(avg_launch_s * 1e6, 2), launches_per_step=n_launch,
+                algorithmic_flop_per_step=flop, algorithmic_bytes_per_step=byts,
+                algorithmic_bytes_per_launch=round(byts / n_launch, 1))
+    return kernels, roof, launch_list
+
+
 def time_config(i, steps, warmup):
     """EM-step and logP rates of configuration i (1-based) with its own seeded inputs."""
     import numpy as np
@@ -104,6 +144,12 @@ def time_config(i, steps, warmup):
         dt = (time.perf_counter() - t0) / steps
         res[name + "_samples_per_s"] = round(B / dt, 1)
         res[name + "_ms"] = round(1e3 * dt, 4)
+    TD = 3 if fam == P.GAUSSIAN else 2
+    work = algorithmic_work(st, K, C, R, T, TD, B, D)
+    kernels, roof, _ = profiled_pass(m, lambda: (m.em_accumulate(x, None, logp), m.em_update(**kw)), steps, work)
+    res["roofline"] = {k: roof[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "avg_launch_us",
+                                            "launches_per_step")}
+    res["kernels_us_per_step"] = {k: v["us_per_step"] for k, v in kernels.items()}
     m.close()
     return res
 
@@ -198,42 +244,10 @@ def main():
         sampling[name] = {"samples_per_s": round(B / dt, 1), "ms_per_call": round(1e3 * dt, 4)}
     assert bool(torch.isfinite(x_out).all())
 
-    # per-kernel device time: the same steps again with a HIP event pair around every launch,
-    # recorded on the stream the kernels run on (separate pass: recording costs host time)
-    m.profile_enable(True)
-    for _ in range(args.steps):
-        em_step()
-    torch.cuda.synchronize()
-    prof = m.profile_read()
-    launch_list = m.profile_launches()
-    m.profile_enable(False)
     work = algorithmic_work(st, K, C, R, T, TD, B, D)
-    kernels = {}
-    for name, (ms, launches) in prof.items():
-        if launches == 0:
-            continue
-        flop, byts = work[name]
-        per_step_us = 1e3 * ms / args.steps
-        kernels[name] = dict(us_per_step=round(per_step_us, 2), launches_per_step=launches // args.steps,
-                             tflops=round(flop / (per_step_us * 1e-6) / 1e12, 3),
-                             gbs=round(byts / (per_step_us * 1e-6) / 1e9, 1))
-    dom = max(kernels, key=lambda n: kernels[n]["us_per_step"])
-    flop, byts = work[dom]
-    n_launch = kernels[dom]["launches_per_step"]
-    avg_launch_s = kernels[dom]["us_per_step"] * 1e-6 / n_launch
-    # which roof binds the dominant kernel: the one that takes longer at peak
-    if flop / (PEAK_MFMA_FP32_TFLOPS * 1e12) >= byts / (PEAK_HBM_GBS * 1e9):
-        achieved = flop / n_launch / avg_launch_s / 1e12
-        roof = dict(bound="mfma", achieved=round(achieved, 3), peak=PEAK_MFMA_FP32_TFLOPS, unit="TFLOP/s",
-                    frac=round(achieved / PEAK_MFMA_FP32_TFLOPS, 4))
-    else:
-        achieved = byts / n_launch / avg_launch_s / 1e9
-        roof = dict(bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                    frac=round(achieved / PEAK_HBM_GBS, 4))
-    roof.update(kernel=dom, avg_launch_us=round(avg_launch_s * 1e6, 2), launches_per_step=n_launch,
-                algorithmic_flop_per_step=flop, algorithmic_bytes_per_step=byts,
-                algorithmic_bytes_per_launch=round(byts / n_launch, 1),
-                traffic=measured_traffic(wl, dom) if B == cfg["B"] else None,
+    kernels, roof, launch_list = profiled_pass(m, em_step, args.steps, work)
+    dom = roof["kernel"]
+    roof.update(traffic=measured_traffic(wl, dom) if B == cfg["B"] else None,
                 traffic_unit="HBM bytes per launch (rocprofv3 counters, profiles/hbm_traffic_cfg%d.md)" % wl,
                 timing="hip events around each launch, separate pass of the same steps")
 
@@ -244,12 +258,16 @@ def main():
     layers = []
     if per_step * args.steps == len(ein):
         for pos in range(per_step):
-            name, _, wk = ein[pos]
+            name, _, tag = ein[pos]
+            outs, parts = tag >> 24, tag & 0xFFFFFF
             us = 1e3 * sum(ein[s_ * per_step + pos][1] for s_ in range(args.steps)) / args.steps
-            fl = (2.0 if name == "einsum_forward" else 4.0) * B * K * K * wk
-            layers.append(dict(kernel=name, outputs=int(wk), partitions=int(wk // K) if wk % K == 0 else int(wk),
-                               us=round(us, 2), tflops=round(fl / us / 1e6, 2),
-                               frac=round(fl / us / 1e6 / PEAK_MFMA_FP32_TFLOPS, 4)))
+            fwd = name == "einsum_forward"
+            fl = (2.0 if fwd else 4.0) * B * K * K * outs
+            # W once (and Nw written once top-down); rows of the children, of the region and its posterior; outputs
+            by = (4.0 if fwd else 8.0) * K * K * outs + 4.0 * B * ((2 * K * parts + outs) if fwd else (4 * K * parts + 2 * outs))
+            layers.append(dict(kernel=name, outputs=int(outs), partitions=int(parts), us=round(us, 2),
+                               tflops=round(fl / us / 1e6, 2), frac=round(fl / us / 1e6 / PEAK_MFMA_FP32_TFLOPS, 4),
+                               gbs=round(by / us / 1e3, 1), frac_hbm=round(by / us / 1e3 / PEAK_HBM_GBS, 4)))
     roof["einsum_layers"] = layers
 
     if not args.no_peaks:

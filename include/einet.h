@@ -324,11 +324,11 @@ int einet_profile_read(einet_t* h, int capacity, int* n_classes, const char** na
                        int64_t* launches);
 /* The launches that the last einet_profile_read summed, one by one and in the order
  * they were enqueued: cls[i] (index into the names of einet_profile_read),
- * ms[i], and work[i]: for the launches of an einsum layer the number of output
- * entries summed over the layer's partitions (K per partition, 1 for a
- * partition of the root), so that the launch's algorithmic flop are
- * 2 B K^2 work bottom-up and 4 B K^2 work top-down (Eq. 5, Eq. 6); 0 for the
- * other classes.  Writes up to `capacity` entries; *n_launches receives their
+ * ms[i], and work[i]: for the launches of an einsum layer o * 2^24 + p, with p
+ * the layer's partitions and o their output entries summed (K per partition,
+ * 1 for a partition of the root), so that the launch's algorithmic flop are
+ * 2 B K^2 o bottom-up and 4 B K^2 o top-down (Eq. 5, Eq. 6); 0 for the other
+ * classes.  Writes up to `capacity` entries; *n_launches receives their
  * number.  All outputs: host. */
 int einet_profile_launches(einet_t* h, int64_t capacity, int64_t* n_launches, int32_t* cls, float* ms, int64_t* work);
 

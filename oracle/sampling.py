@@ -27,8 +27,12 @@ import numpy as np
 from .einet import BERNOULLI, GAUSSIAN, BINOMIAL, CATEGORICAL, ef_log_density
 
 
-def choose(w, u):
-    """(index, margin) of the inverse-CDF choice described in the module docstring."""
+def choose(w, u, other_side=False):
+    """(index, margin) of the inverse-CDF choice described in the module docstring.  other_side: instead of the
+    index whose interval holds u * total, its neighbour across the nearer boundary of that interval (the next
+    index with a non-zero weight on that side, if there is one): what an implementation in lower precision may
+    pick when the margin is tiny."""
+    w = np.asarray(w, dtype=np.float64)
     c = np.cumsum(w)
     total = c[-1]
     tau = u * total
@@ -37,10 +41,15 @@ def choose(w, u):
         t = int(np.nonzero(w)[0][-1])
     lo = c[t - 1] if t > 0 else 0.0
     margin = min(tau - lo, c[t] - tau) / total
+    if other_side:
+        nz = np.nonzero(w)[0]
+        side = nz[nz < t] if tau - lo <= c[t] - tau else nz[nz > t]
+        if len(side):
+            t = int(side[-1] if tau - lo <= c[t] - tau else side[0])
     return t, margin
 
 
-def sample(model, B, u, noise=None, x=None, mask=None):
+def sample(model, B, u, noise=None, x=None, mask=None, only=None, flip=None, tie_margin=0.0):
     """Draws B samples.
 
     u     : [num_partitions + num_regions, B] uniforms in [0, 1): row n decides the pair of
@@ -51,6 +60,12 @@ def sample(model, B, u, noise=None, x=None, mask=None):
             noise * (sum of all probabilities); None: the leaf means (E[x] of the chosen
             leaf entry, App. D)
     x, mask : evidence [B, D, C] and mask ([D] or [B, D], 1 = observed); None: no evidence
+
+    only  : the samples to draw (default all; the others keep x, margin inf and an empty path)
+    flip, tie_margin : flip = {b: j} takes, for sample b, the j-th (from 0, in the order the choices are made)
+            of its choices whose margin is below tie_margin on the other side of the nearer boundary
+            (`choose(..., other_side=True)`); the descent then continues from there.  For comparing
+            implementations that decide near-ties in another precision.
 
     Returns (samples [B, D, C] float64 with the observed entries copied from x,
              margin [B]: the smallest margin over the choices made for each sample,
@@ -71,6 +86,21 @@ def sample(model, B, u, noise=None, x=None, mask=None):
     paths = []
     for b in range(B):
         path = []
+        if only is not None and b not in only:
+            paths.append(path)
+            continue
+        ties = 0                                          # near-tie choices met so far
+        want = None if flip is None else flip.get(b)
+
+        def decide(w, ub):
+            nonlocal ties
+            t, mg = choose(w, ub)
+            if mg < tie_margin:
+                if want is not None and ties == want:
+                    t, _ = choose(w, ub, other_side=True)
+                ties += 1
+            return t, mg
+
         todo = [(0, 0)]
         while todo:
             s, k = todo.pop()
@@ -102,12 +132,12 @@ def sample(model, B, u, noise=None, x=None, mask=None):
                 n = parts[0]
             else:
                 w = np.array([model.v[s][k, ci] * np.exp(S[nn][b, k] - N[s][b, k]) for ci, nn in enumerate(parts)])
-                ci, mg = choose(w, u[P + s, b])
+                ci, mg = decide(w, u[P + s, b])
                 margins[b] = min(margins[b], mg)
                 n = parts[ci]
             _, left, right = g.partitions[n]
             w = model.W[n][k] * np.exp(N[left][b][:, None] + N[right][b][None, :] - S[n][b, k])
-            t, mg = choose(w.ravel(), u[n, b])
+            t, mg = decide(w.ravel(), u[n, b])
             margins[b] = min(margins[b], mg)
             i, j = divmod(t, K)
             path.append((n, i, j))

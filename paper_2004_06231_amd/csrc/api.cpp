@@ -156,12 +156,12 @@ Arena workspace_arena(const einet_t* h) {
                  reinterpret_cast<float*>(h->ws + h->off_amax)};
 }
 
-// Output entries of the einsum items of layer l, summed (the work tag of its launches in the profile: the
-// algorithmic flop of a launch are 2 B K^2 times this bottom-up and 4 B K^2 times this top-down).
+// Work tag of the launches of einsum layer l in the profile: output entries summed over its items (the algorithmic
+// flop of a launch are 2 B K^2 times this bottom-up and 4 B K^2 times this top-down) times 2^24, plus the items.
 int64_t layer_outputs(const Plan& p, int l) {
     int64_t n = 0;
     for (int e = p.ein_layer_ptr[l]; e < p.ein_layer_ptr[l + 1]; ++e) n += p.ein_kout[e];
-    return n;
+    return (n << 24) | (int64_t)(p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l]);
 }
 
 // Leaf layer, then einsum (+ mixing) layers bottom-up; fills the arena.

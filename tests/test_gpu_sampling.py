@@ -5,7 +5,9 @@ oracle in float64.  With K*K pairs to choose from, the interval of a pair is abo
 (6e-4 for K = 40), the float32 running sums are good to about 1e-6 of the total, so a small share of the choices
 can fall on the other side of a boundary.  Every sample whose choices all stayed at least MARGIN (relative to
 the total weight) away from the boundaries of their intervals must agree with the oracle entry by entry; of all
-samples at least `min_fraction` must agree; for the others validity is checked (finite values, evidence kept,
+samples at least `min_fraction` must agree; every other sample must be the one the oracle draws when one of its
+near-tie choices (margin below MARGIN) falls on the other side of the nearer boundary and the descent continues
+from there (`oracle.sampling.sample(..., flip=...)`), besides the validity checks (finite values, evidence kept,
 Bernoulli values in {0, 1})."""
 import numpy as np
 import pytest
@@ -58,6 +60,18 @@ def _compare(oracle, m, B, rng, x, mask, values, family, min_fraction=0.9):
     clear = margin >= MARGIN
     assert np.all(same[clear]), f"{int((~same[clear]).sum())} samples with clear-cut choices differ"
     assert same.mean() >= min_fraction, f"only {same.mean():.2f} of the samples agree"
+    # a sample that differs took the neighbouring interval at one near-tie: flip the near-ties of its reference
+    # descent one at a time until the oracle reproduces it
+    u64 = u.astype(np.float64)
+    n64 = None if noise is None else noise.astype(np.float64)
+    for b in np.nonzero(~same)[0]:
+        ok = False
+        for j in range(8):
+            alt, _, _ = sample(oracle, B, u64, n64, x, mask, only=[int(b)], flip={int(b): j}, tie_margin=MARGIN)
+            if np.all(np.abs(got[b] - alt[b]) <= 1e-5 * np.abs(alt[b]) + 1e-6):
+                ok = True
+                break
+        assert ok, f"sample {b} differs from the oracle and from every single near-tie alternative"
     return float(same.mean())
 
 

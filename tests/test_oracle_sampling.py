@@ -130,3 +130,25 @@ def test_conditional_samples_follow_eq1():
     cond = np.exp(model.logp(full) - model.logp(full[:1], mask)[0])
     assert abs(cond.sum() - 1.0) < 1e-12
     assert _chi_square(counts, cond) < 7 + 5 * 3.7
+
+
+def test_choose_other_side_and_flipped_descent():
+    """The near-tie helper used by the GPU comparison: the neighbour across the nearer boundary, by hand."""
+    from oracle.sampling import choose
+    w = [1.0, 1.0, 0.0, 2.0]                               # running sums 1, 2, 2, 4
+    assert choose(w, 0.2500001)[0] == 1 and choose(w, 0.2500001, other_side=True)[0] == 0
+    assert choose(w, 0.4999999)[0] == 1 and choose(w, 0.4999999, other_side=True)[0] == 3    # skips the zero weight
+    assert choose(w, 0.1)[0] == 0 and choose(w, 0.1, other_side=True)[0] == 0                # nothing below index 0
+    assert choose(w, 0.9)[0] == 3 and choose(w, 0.9, other_side=True)[0] == 3                # nothing above the last
+    # a flipped descent is the unflipped one up to the flipped choice, and a valid sample afterwards
+    model, _, rng = make_oracle(dict(kind="rat", D=8, depth=2, R=2), 3, 1, BERNOULLI, 11)
+    g = model.g
+    u = rng.random((g.num_partitions + g.num_regions, 4))
+    noise = rng.random((4, 8, 1))
+    ref, margin, paths = sample(model, 4, u, noise)
+    # with tie_margin = 1 every choice counts as a near-tie: flip number j changes choice j and keeps those before it
+    alt, _, apaths = sample(model, 4, u, noise, only=[2], flip={2: 1}, tie_margin=1.0)
+    assert apaths[0] == [] and apaths[2] != paths[2]
+    assert np.all((alt[2] == 0.0) | (alt[2] == 1.0))
+    same_again, _, p2 = sample(model, 4, u, noise, only=[2], flip={2: 99}, tie_margin=1.0)     # no such choice: unchanged
+    assert p2[2] == paths[2] and np.array_equal(same_again[2], ref[2])
