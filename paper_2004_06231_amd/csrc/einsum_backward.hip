@@ -549,7 +549,7 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
         floatx4 r4[K8], l4[K8], g4[K8], a4[K8], v4[K8];
         float arow = 0.f, alrow = 0.f, ddrow = 0.f;
         bool rin = false;
-        auto fetch_rows = [&](const Pos& q) {
+        auto fetch_rows = [&](const Pos& q, bool with_q) {
             const int bg = q.chunk * 128 + rb_;
             rin = bg < B;
             const int bc = min(bg, B - 1);
@@ -563,19 +563,23 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
             for (int x = 0; x < K8; ++x) {
                 r4[x] = *reinterpret_cast<const floatx4*>(Rp + 4 * x);
                 l4[x] = *reinterpret_cast<const floatx4*>(Lp + 4 * x);
-                g4[x] = *reinterpret_cast<const floatx4*>(Gs + 4 * x);
-                a4[x] = *reinterpret_cast<const floatx4*>(As + 4 * x);
+                if (with_q) {
+                    g4[x] = *reinterpret_cast<const floatx4*>(Gs + 4 * x);
+                    a4[x] = *reinterpret_cast<const floatx4*>(As + 4 * x);
+                }
             }
             alrow = amax[(size_t)item * 2 * B + bc];
             arow = amax[((size_t)item * 2 + 1) * B + bc];
-            ddrow = (float)(Off[(size_t)e_out[q.li] * B + bc] - Off[(size_t)e_reg[q.li] * B + bc]);
-            const int voff = e_voff[q.li], vstr = e_vstr[q.li];
+            if (with_q) {
+                ddrow = (float)(Off[(size_t)e_out[q.li] * B + bc] - Off[(size_t)e_reg[q.li] * B + bc]);
+                const int voff = e_voff[q.li], vstr = e_vstr[q.li];
 #pragma unroll
-            for (int x = 0; x < K8; ++x)
+                for (int x = 0; x < K8; ++x)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) v4[x][c] = voff >= 0 ? params[voff + (4 * (hh * K8 + x) + c) * vstr] : 1.f;
+                    for (int c = 0; c < 4; ++c) v4[x][c] = voff >= 0 ? params[voff + (4 * (hh * K8 + x) + c) * vstr] : 1.f;
+            }
         };
-        auto stage_rows = [&]() {
+        auto stage_rows = [&](bool with_q) {
 #pragma unroll
             for (int x = 0; x < K8; ++x)
 #pragma unroll
@@ -583,10 +587,12 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
                     const int k = 4 * (hh * K8 + x) + c;
                     const float e = __expf(r4[x][c] - arow);
                     const float l = __expf(l4[x][c] - alrow);
-                    const float qv = g4[x][c] * v4[x][c] * __expf(ddrow - a4[x][c]);
                     sR[k * ST + rb_] = rin ? e : 0.f;
                     sL[k * ST + rb_] = rin ? l : 0.f;
-                    sQ[k * ST + rb_] = (rin && g4[x][c] != 0.f) ? qv : 0.f;
+                    if (with_q) {
+                        const float qv = g4[x][c] * v4[x][c] * __expf(ddrow - a4[x][c]);
+                        sQ[k * ST + rb_] = (rin && g4[x][c] != 0.f) ? qv : 0.f;
+                    }
                 }
         };
         // ---- shared tiles of a finished unit: sum the four waves' shares, then Nw (+)= W * sum.  The W entries (and the old
@@ -636,9 +642,9 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
         };
 
         fetch_w(pos);
-        fetch_rows(pos);
+        fetch_rows(pos, false);             // (the matrix waves stage Q^T of the first operands themselves)
         store_w(lds);
-        stage_rows();
+        stage_rows(false);
         Pos npos = pos;
         bool nvalid = advance(npos);
         if (nvalid) fetch_w(npos);
@@ -657,7 +663,7 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
                 if (advance(nn)) fetch_w(nn);
             }
             const bool new_ops = nvalid && (npos.li != pos.li || npos.chunk != pos.chunk);
-            if (new_ops) fetch_rows(npos);
+            if (new_ops) fetch_rows(npos, true);
             __syncthreads();                              // B(u+1)
             prev = pos; have_prev = true;
             if (!nvalid) break;
@@ -665,7 +671,7 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
             nvalid = advance(npos);
             ++u;
             if (new_ops) {
-                stage_rows();
+                stage_rows(true);
                 __syncthreads();                          // X(u)
             }
         }
@@ -684,6 +690,33 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
         for (int m = 0; m < K8; ++m) {
             const int rho = 32 * m + n;
             prow[m] = (rho ^ ((rho >> 3) & 7)) * 4;
+        }
+        {
+            // Q^T of the first operands: thread (b = tid / 2, half = tid % 2), as the producers do it for the later ones
+            const int rb_ = tid >> 1, hh = tid & 1;
+            const int bgq = pos.chunk * 128 + rb_;
+            const bool rin = bgq < B;
+            const int bc = min(bgq, B - 1);
+            const size_t ro = (size_t)bc * K + 4 * hh * K8;
+            const float* Gs = G + (size_t)e_reg[pos.li] * blk + ro;
+            const float* As = A + (size_t)e_reg[pos.li] * blk + ro;
+            floatx4 g4[K8], a4[K8];
+#pragma unroll
+            for (int x = 0; x < K8; ++x) {
+                g4[x] = *reinterpret_cast<const floatx4*>(Gs + 4 * x);
+                a4[x] = *reinterpret_cast<const floatx4*>(As + 4 * x);
+            }
+            const float ddrow = (float)(Off[(size_t)e_out[pos.li] * B + bc] - Off[(size_t)e_reg[pos.li] * B + bc]);
+            const int voff = e_voff[pos.li], vstr = e_vstr[pos.li];
+#pragma unroll
+            for (int x = 0; x < K8; ++x)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int k = 4 * (hh * K8 + x) + c;
+                    const float vw = voff >= 0 ? params[voff + k * vstr] : 1.f;
+                    const float qv = g4[x][c] * vw * __expf(ddrow - a4[x][c]);
+                    sQ[k * ST + rb_] = (rin && g4[x][c] != 0.f) ? qv : 0.f;
+                }
         }
         __syncthreads();                                  // B0
         bool new_ops = true;
@@ -818,7 +851,9 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
                         for (int c = 0; c < 4; ++c) nold[z][c] = Nw[((size_t)(4 * rt[z] + kg) * K + 4 * pos.it + c) * K + min(jj[z], K - 1)];
                     }
                 }
-                floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+                // (a dependent chain of this shape issues every 42 cycles, four independent ones every 32: each tile keeps two
+                // accumulators, for the even and the odd groups)
+                floatx4 acc2[2][2] = {{{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}};
                 floatx4 qa[3][2], ea[3], rb[3][2];
 #pragma unroll
                 for (int x = 0; x < 2; ++x) {
@@ -854,10 +889,14 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
                         for (int c = 0; c < 4; ++c)
 #pragma unroll
                             for (int z = 0; z < 2; ++z)
-                                if (z < np) acc[z] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[z][c], rb[x % 3][z][c], acc[z], 0, 0, 0);
+                                if (z < np)
+                                    acc2[z][x & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[z][c], rb[x % 3][z][c], acc2[z][x & 1], 0, 0, 0);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
+                floatx4 acc[2];
+#pragma unroll
+                for (int z = 0; z < 2; ++z) acc[z] = acc2[z][0] + acc2[z][1];
 #pragma unroll
                 for (int z = 0; z < 2; ++z) {
                     if (z < np) {

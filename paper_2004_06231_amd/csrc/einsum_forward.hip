@@ -328,9 +328,7 @@ __global__ __launch_bounds__(512, 1) void k_einsum_forward_s(const int32_t* __re
                 *reinterpret_cast<floatx4*>(A + ((size_t)e_out[fli] * B + b) * K + 4 * fquad) = r;
             }
         };
-        FETCH_W(li, quad)
-        rows(li, chunk, quad == 0);
-        STORE_W(lds)
+        rows(li, chunk, quad == 0);                     // (the matrix waves bring the first slice in)
         // position of the unit whose slice is in flight
         int lq = quad, lc = chunk, lli = li;
         auto advance = [&](int& q_, int& c_, int& i_) {
@@ -363,6 +361,19 @@ __global__ __launch_bounds__(512, 1) void k_einsum_forward_s(const int32_t* __re
         // ------------------------------------------------------------ matrix waves
         float er[4 * K8], el[K8][4];
         const bool active = chunk * 128 + nt * 32 < B || nchunks > 1;     // (a tile beyond a short batch does nothing)
+        {
+            // the first W slice, while the producer waves fetch and shift the first rows
+            const float* W_ = params + e_woff[li] + (size_t)quad * 4 * K * K;
+            floatx4 w0[NL];
+#pragma unroll
+            for (int q = 0; q < NL; ++q) w0[q] = *reinterpret_cast<const floatx4*>(W_ + (size_t)4 * min(tid + 256 * q, LY::NQ4 - 1));
+#pragma unroll
+            for (int q = 0; q < NL; ++q) {
+                const int f = tid + 256 * q;
+                const int row = f / (K / 4), c4 = f - row * (K / 4);
+                if (f < LY::NQ4) *reinterpret_cast<floatx4*>(lds + row * RS + 4 * c4) = w0[q];
+            }
+        }
         __syncthreads();                                // B0
         bool load_rows = true;
         for (int u = u0; u < u1; ++u) {
