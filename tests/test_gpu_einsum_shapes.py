@@ -1,0 +1,66 @@
+"""GPU parity of the einsum kernels with specialised waves over every K they are instantiated for (multiples of 8:
+bottom-up to 48, top-down to 40; K = 48 takes the new kernel one way and the 16x16x4 kernel the other), with batches
+that span several chunks of 128 samples and a ragged last one, with statistics added to (two E-steps in a row),
+overwritten (E-step after an M-step) and mixing weights in play (regions with several partitions)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle.einet import BERNOULLI, GAUSSIAN
+from tests.common import make_oracle
+from tests.gpu_common import gpu_model, dev, assert_logp_close, assert_stats_close
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # spec, K, C, family, B
+    (dict(kind="rat", D=32, depth=3, R=2), 8, 1, BERNOULLI, 300),          # three chunks, the last ragged
+    (dict(kind="pd", H=8, W=4, deltas=[4, 2]), 16, 1, BERNOULLI, 129),     # one sample beyond a chunk
+    (dict(kind="pd", H=8, W=8, deltas=[4]), 24, 1, GAUSSIAN, 200),         # two 16-column statistics tiles, one half used
+    (dict(kind="pd", H=6, W=6, deltas=[2]), 32, 1, GAUSSIAN, 77),          # one 32-column tile, nothing left over
+    (dict(kind="rat", D=16, depth=2, R=2), 40, 2, GAUSSIAN, 1),            # a single sample
+    (dict(kind="pd", H=6, W=4, deltas=[2]), 40, 1, BERNOULLI, 260),        # K = 40 with chunks
+    (dict(kind="rat", D=24, depth=2, R=3), 48, 1, GAUSSIAN, 130),          # new kernel bottom-up, 16x16x4 kernel top-down
+]
+
+
+@pytest.mark.parametrize("spec,K,C,family,B", CASES)
+def test_einsum_kernels_for_every_tile_shape(spec, K, C, family, B):
+    print("einsum shape case", spec, K, C, family, B, flush=True)
+    seed = 4000 + K + B
+    oracle, flat, rng = make_oracle(spec, K, C, family, seed, leaf_range=(0.1, 0.9))
+    D = oracle.g.num_vars
+    x = workloads.draw_data(rng, dict(kind="bernoulli_iid", p=0.4) if family == BERNOULLI
+                            else dict(kind="gaussian_mixture", components=3, std=0.3), B, D, C)
+    m = gpu_model(spec, K, C, family, B, seed, flat)
+    ref_stats, ref_logp = oracle.em_accumulate(x, None)
+    ref_flat = oracle.stats_to_flat(ref_stats)
+    assert_logp_close(m.logp(dev(x)), ref_logp)
+    lp = torch.empty(B, device="cuda")
+    m.em_accumulate(dev(x), None, lp)
+    assert_logp_close(lp, ref_logp)
+    assert_stats_close(m.stats, ref_flat, oracle.layout, m.n_params)
+    # a second E-step adds to the statistics (the kernels read them back)
+    m.em_accumulate(dev(x), None, lp)
+    assert_stats_close(m.stats, 2.0 * ref_flat, oracle.layout, m.n_params)
+    # after an M-step the einsum-weight statistics are overwritten, not added to
+    kw = dict(step=0.5, min_var=1e-4, max_var=2.0, w_floor=1e-9) if family == GAUSSIAN else dict(step=0.5, w_floor=1e-9)
+    m.em_update(**kw)
+    oracle.em_update(oracle.stats_from_flat(2.0 * ref_flat), **kw)
+    ref_p = oracle.get_flat_params()
+    got_p = m.params.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got_p - ref_p) <= 1e-3 * np.abs(ref_p) + 1e-7)
+    m.set_params(ref_p)                                  # (both sides continue from the oracle's parameters)
+    oracle.set_flat_params(ref_p)
+    ref2, ref_logp2 = oracle.em_accumulate(x, None)
+    m.em_accumulate(dev(x), None, lp)
+    assert_logp_close(lp, ref_logp2)
+    assert_stats_close(m.stats, oracle.stats_to_flat(ref2), oracle.layout, m.n_params)
+    # a smaller batch on the same handle
+    nb = max(1, B // 3)
+    m.em_reset()
+    m.em_accumulate(dev(x[:nb]), None, lp[:nb])
+    ref3, _ = oracle.em_accumulate(x[:nb], None)
+    assert_stats_close(m.stats, oracle.stats_to_flat(ref3), oracle.layout, m.n_params)
+    m.close()
