@@ -1,6 +1,8 @@
 // Top-down sampling (Sec. 2, Sec. 4.2, App. D).
 #include "device_common.hpp"
 
+#include <mutex>
+
 namespace einet_impl {
 
 namespace {
@@ -275,10 +277,11 @@ void launch_sample_regions(const DevTables& t, int first, int count, bool eviden
     if (count == 0) return;
     const int KK = d.K * d.K;
     const size_t lds = sizeof(float) * SAMPLE_WAVES * (size_t)(KK + (KK >> 5) + 1 + 128);   // at most 68 KB (K = 64)
-    static bool attr_set = false;
-    if (lds > 64 * 1024 && !attr_set) {
-        allow_dynamic_lds(&k_sample_regions, 72 * 1024);
-        attr_set = true;
+    if (lds > 64 * 1024) {
+        static std::once_flag attr_set[EINET_MAX_DEVICES];
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] { allow_dynamic_lds(&k_sample_regions, 72 * 1024); });
     }
     hipLaunchKernelGGL(k_sample_regions, dim3(count, (d.B + SAMPLE_WAVES - 1) / SAMPLE_WAVES), dim3(64 * SAMPLE_WAVES),
                        lds, s, t.sr_rec + (size_t)first * SR_REC_INTS, t.sr_pptr + first, t.sr_item, t.sr_mix + first, t.mix_cptr,

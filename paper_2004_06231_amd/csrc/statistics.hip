@@ -1,6 +1,8 @@
 // End of the top-down pass: statistics of the mixing weights and of the leaves (Eq. 6-7).
 #include "device_common.hpp"
 
+#include <mutex>
+
 namespace einet_impl {
 
 namespace {
@@ -250,6 +252,159 @@ __device__ __forceinline__ void leaf_backward_cells_body(
     }
 }
 
+// The same statistics for very long scopes (strips of a large image: thousands of (variable, channel) pairs per leaf)
+// when nothing is marginalised: num[pair][k] = sum_b x[b][pair] p[b][k] (and the same with x^2) is a GEMM with the
+// batch as contraction, here on v_mfma_f32_32x32x2_f32: rows = 32 pairs (A operand: the values, staged per pass of 64
+// samples in LDS exactly as above), columns = 32 entries k (B operand: the leaf's posterior block, zero beyond K).
+// A workgroup of four waves takes one leaf and 128 of its pairs, a wave one row tile (three workgroups share a
+// compute unit, so that one stages while another multiplies); SQ adds the x^2 rows
+// (Gaussian leaves), NCT is the number of column tiles (K <= 32: one).  tot = den = sum_b p[b][k] is summed on the side.
+typedef float floatx16s __attribute__((ext_vector_type(16)));
+constexpr int LSM_BC = 64, LSM_PC = 128, LSM_XS = LSM_PC + 8;   // samples per pass, pairs per workgroup, row stride of the values
+__host__ __device__ inline size_t leaf_stats_mfma_lds_bytes() {
+    return sizeof(float) * ((size_t)LSM_BC * 64 + (size_t)LSM_BC * LSM_XS + 64) + sizeof(int) * (LSM_PC + 2);
+}
+
+template <bool SQ, int NCT>
+__global__ __launch_bounds__(256) void k_leaf_stats_mfma(
+    const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica, const int32_t* __restrict__ leaf_sptr,
+    const int32_t* __restrict__ leaf_var, const float* __restrict__ x, const float* __restrict__ G,
+    float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, int chunks_per_leaf, Dims d) {
+    extern __shared__ float lsm_lds[];
+    float* Gs = lsm_lds;                               // [LSM_BC][64], columns beyond K are zero
+    float* xs = Gs + LSM_BC * 64;                      // [LSM_BC][LSM_XS]
+    float* tots = xs + LSM_BC * LSM_XS;                // [64]
+    int* vsl = reinterpret_cast<int*>(tots + 64);      // variables of the chunk's pairs
+    const int leaf = blockIdx.x / chunks_per_leaf, chunk = blockIdx.x - leaf * chunks_per_leaf;
+    const int s0 = leaf_sptr[leaf], npairs = (leaf_sptr[leaf + 1] - s0) * d.C;
+    const int p0 = chunk * LSM_PC;
+    if (p0 >= npairs) return;                          // (whole workgroup) this leaf has fewer chunks
+    const int np = min(LSM_PC, npairs - p0);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K;
+    const int vfirst = p0 / d.C, vcount = (p0 + np - 1) / d.C - vfirst + 1;
+    for (int j = tid; j < vcount; j += 256) vsl[j] = leaf_var[s0 + vfirst + j];
+    floatx16s acc[1][SQ ? 2 : 1][NCT];
+#pragma unroll
+    for (int t = 0; t < 1; ++t)
+#pragma unroll
+        for (int q = 0; q < (SQ ? 2 : 1); ++q)
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[t][q][ct][v] = 0.f;
+    float tot = 0.f;                                   // thread k < K: sum_b p[b][k]
+    __syncthreads();
+    // thread (pair = tid % 128, half = tid / 128) stages the even or odd samples of its pair (half a column of xs) and 16
+    // entries of the posterior block per pass; the values of the next pass are requested before the MFMAs of the current
+    // one and go to LDS after them
+    size_t xoff = 0;
+    const int sp = tid & (LSM_PC - 1), sh = tid >> 7;
+    const bool pin = sp < np;
+    if (pin) {
+        const int pair = p0 + sp, vv = pair / d.C, c = pair - vv * d.C;
+        xoff = (size_t)vsl[vv - vfirst] * d.C + c;
+    }
+    const size_t xstride = (size_t)d.D * d.C;
+    float xr[LSM_BC / 2], gq[LSM_BC * 64 / 256];
+    auto fetch = [&](int b0) {
+        const int nb = min(LSM_BC, d.B - b0);
+#pragma unroll
+        for (int q = 0; q < LSM_BC / 2; ++q) {
+            const int bb = 2 * q + sh;
+            xr[q] = (pin && bb < nb) ? x[(size_t)(b0 + bb) * xstride + xoff] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < LSM_BC * 64 / 256; ++q) {
+            const int i = tid + 256 * q, bb = i >> 6, k = i & 63;
+            gq[q] = (bb < nb && k < d.K) ? Gl[(size_t)(b0 + bb) * d.K + k] : 0.f;
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int q = 0; q < LSM_BC / 2; ++q) xs[(2 * q + sh) * LSM_XS + sp] = xr[q];
+#pragma unroll
+        for (int q = 0; q < LSM_BC * 64 / 256; ++q) Gs[tid + 256 * q] = gq[q];
+    };
+    fetch(0);
+    for (int b0 = 0; b0 < d.B; b0 += LSM_BC) {
+        const int nb = min(LSM_BC, d.B - b0);
+        if (b0 > 0) __syncthreads();                   // readers of the previous pass are done
+        stage();
+        __syncthreads();
+        if (b0 + LSM_BC < d.B) fetch(b0 + LSM_BC);
+        __builtin_amdgcn_sched_barrier(0);             // (the requests stay ahead of the MFMA loop)
+        if (tid < d.K) {
+            float t4[4] = {0.f, 0.f, 0.f, 0.f};        // (rows beyond nb are zero)
+#pragma unroll
+            for (int bb = 0; bb < LSM_BC; ++bb) t4[bb & 3] += Gs[bb * 64 + tid];
+            tot += (t4[0] + t4[1]) + (t4[2] + t4[3]);
+        }
+        const float* xa = xs + h * LSM_XS + 32 * wave + n;       // + 2 s LSM_XS
+        const float* pb = Gs + h * 64 + n;                        // + 2 s 64 + 32 ct
+        // operands of the next step are requested before the MFMAs of the current one; the squares are formed ahead of
+        // the MFMAs, not between them
+        float a[2][1], b[2][NCT];
+#pragma unroll
+        for (int t = 0; t < 1; ++t) a[0][t] = xa[32 * t];
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) b[0][ct] = pb[32 * ct];
+#pragma unroll
+        for (int s = 0; s < LSM_BC / 2; ++s) {
+            const int cur = s & 1, nxt = cur ^ 1;
+            if (s + 1 < LSM_BC / 2) {
+#pragma unroll
+                for (int t = 0; t < 1; ++t) a[nxt][t] = xa[2 * (s + 1) * LSM_XS + 32 * t];
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) b[nxt][ct] = pb[2 * (s + 1) * 64 + 32 * ct];
+            }
+            float a2[1];
+#pragma unroll
+            for (int t = 0; t < 1; ++t) a2[t] = a[cur][t] * a[cur][t];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < 1; ++t)
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) {
+                    acc[t][0][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][t], b[cur][ct], acc[t][0][ct], 0, 0, 0);
+                    if (SQ) acc[t][SQ ? 1 : 0][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[t], b[cur][ct], acc[t][SQ ? 1 : 0][ct], 0, 0, 0);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    // acc[0][q][ct][v]: pair = 32 wave + 8 (v / 4) + 4 h + v % 4 of the chunk, entry k = 32 ct + n
+    const int r = leaf_replica[leaf];
+#pragma unroll
+    for (int t = 0; t < 1; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int p = 32 * wave + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (p < np) {
+                const int pair = p0 + p, vv = pair / d.C, c = pair - vv * d.C;
+                const size_t ph = phi_off + ((size_t)(vsl[vv - vfirst] * d.C + c) * d.R + r) * d.T * d.K;
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) {
+                    const int k = 32 * ct + n;
+                    if (k < d.K) {
+                        stats[ph + k] += acc[t][0][ct][v];
+                        if (SQ) stats[ph + d.K + k] += acc[t][SQ ? 1 : 0][ct][v];
+                    }
+                }
+            }
+        }
+    // den = tot for every variable whose first channel lies in this chunk
+    if (tid < 64) tots[tid] = tid < d.K ? tot : 0.f;
+    __syncthreads();
+    const int vlo = (p0 + d.C - 1) / d.C, vhi = (p0 + np - 1) / d.C;      // variables with pair (v, 0) in [p0, p0 + np)
+    for (int i = tid; i < (vhi - vlo + 1) * d.K; i += 256) {
+        const int vv = vlo + i / d.K, k = i % d.K;
+        const size_t o = ((size_t)vsl[vv - vfirst] * d.R + r) * d.K + k;
+        stats[den_off + o] += tots[k];
+        stats[tot_off + o] += tots[k];
+    }
+}
+
 // Last launch of the top-down pass: leaf statistics in the first n_leaf_blocks workgroups, mixing
 // statistics in the others (item = idx / max_children, child = idx % max_children).  NCH = 0 selects the
 // kernel body for long scopes (chunks_per_leaf workgroups per leaf, PPT pairs per thread).
@@ -290,6 +445,31 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
         hipLaunchKernelGGL(k_leaf_backward_categorical, dim3(n_lv * d.C), dim3(64), sizeof(float) * d.P * d.K, s,
                            t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, x, mask, mask_mode, G, stats, phi_off,
                            den_off, tot_off, d);
+    // very long scopes, nothing marginalised: the statistics as a GEMM over the batch on the matrix pipe, the mixing
+    // statistics in a launch of their own
+    bool leaves_done = categorical;
+    if (!categorical && mask_mode == EINET_MASK_NONE && max_scope * d.C >= 1024 && d.K <= 64) {
+        const size_t lds_m = leaf_stats_mfma_lds_bytes();
+        static std::once_flag attr_m[EINET_MAX_DEVICES];
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        std::call_once(attr_m[dev % EINET_MAX_DEVICES], [&] {
+            allow_dynamic_lds(&k_leaf_stats_mfma<true, 1>, lds_m);
+            allow_dynamic_lds(&k_leaf_stats_mfma<true, 2>, lds_m);
+            allow_dynamic_lds(&k_leaf_stats_mfma<false, 1>, lds_m);
+            allow_dynamic_lds(&k_leaf_stats_mfma<false, 2>, lds_m);
+        });
+        const int cpl = (max_scope * d.C + LSM_PC - 1) / LSM_PC;
+#define EINET_LSM(SQ, NCT)                                                                                        \
+    hipLaunchKernelGGL((k_leaf_stats_mfma<SQ, NCT>), dim3(n_leaves * cpl), dim3(256), lds_m, s, t.leaf_node,      \
+                       t.leaf_replica, t.leaf_sptr, t.leaf_var, x, G, stats, phi_off, den_off, tot_off, cpl, d)
+        if (d.T == 2 && d.K > 32) EINET_LSM(true, 2);
+        else if (d.T == 2) EINET_LSM(true, 1);
+        else if (d.K > 32) EINET_LSM(false, 2);
+        else EINET_LSM(false, 1);
+#undef EINET_LSM
+        leaves_done = true;
+    }
     // long scopes: posterior block and values through LDS; short ones: straight from memory
     const int pc1 = cell_pairs_per_group(d.K);
     const int chunks1 = (max_scope * d.C + pc1 - 1) / pc1;
@@ -299,15 +479,18 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
     const int ppt = cells && n_leaves * chunks1 >= 1024 && pc1 * 4 <= 128 ? 4 : 1;
     const int nch = cells ? 0 : (d.B >= 16 ? 4 : 1);
     const int chunks_per_leaf = cells ? (max_scope * d.C + pc1 * ppt - 1) / (pc1 * ppt) : 1;
-    const int n_leaf_blocks = categorical ? 0 : (cells ? n_leaves * chunks_per_leaf : (total + 1024 / nch - 1) / (1024 / nch));
+    const int n_leaf_blocks = leaves_done ? 0 : (cells ? n_leaves * chunks_per_leaf : (total + 1024 / nch - 1) / (1024 / nch));
     const int blocks = n_leaf_blocks + n_mix * max_children;
     if (blocks == 0) return;
     const size_t lds = cells ? cell_lds_bytes(d.K, ppt) : 0;
-    static bool attr_set = false;
-    if (cells && !attr_set) {
-        allow_dynamic_lds(&k_tail_backward<0, 1>, 64 * 1024);
-        allow_dynamic_lds(&k_tail_backward<0, 4>, 128 * 1024);
-        attr_set = true;
+    if (cells) {
+        static std::once_flag attr_set[EINET_MAX_DEVICES];
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] {
+            allow_dynamic_lds(&k_tail_backward<0, 1>, 64 * 1024);
+            allow_dynamic_lds(&k_tail_backward<0, 4>, 128 * 1024);
+        });
     }
 #define EINET_LAUNCH(N, P)                                                                                           \
     hipLaunchKernelGGL((k_tail_backward<N, P>), dim3(blocks), dim3(1024), lds, s, n_leaf_blocks,                      \

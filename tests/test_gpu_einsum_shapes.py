@@ -64,3 +64,38 @@ def test_einsum_kernels_for_every_tile_shape(spec, K, C, family, B):
     ref3, _ = oracle.em_accumulate(x[:nb], None)
     assert_stats_close(m.stats, oracle.stats_to_flat(ref3), oracle.layout, m.n_params)
     m.close()
+
+
+LONG_SCOPES = [
+    # spec, K, C, family, B: leaves with at least 1024 (variable, channel) pairs take the statistics kernel on the matrix
+    # pipe when nothing is marginalised
+    (dict(kind="rat", D=2500, depth=1, R=2), 5, 1, BERNOULLI, 70),         # one statistic, one column tile, ragged pairs
+    (dict(kind="pd", H=48, W=44, deltas=[24]), 33, 3, GAUSSIAN, 130),      # two statistics, two column tiles, three passes
+    (dict(kind="pd", H=32, W=40, deltas=[20], axes=2), 8, 1, GAUSSIAN, 64),   # strips of 640 and 640 pixels: below the limit
+]
+
+
+@pytest.mark.parametrize("spec,K,C,family,B", LONG_SCOPES)
+def test_leaf_statistics_of_very_long_scopes(spec, K, C, family, B):
+    print("long scope case", spec, K, C, family, B, flush=True)
+    seed = 5000 + K + B
+    oracle, flat, rng = make_oracle(spec, K, C, family, seed, leaf_range=(0.2, 0.8))
+    D = oracle.g.num_vars
+    x = workloads.draw_data(rng, dict(kind="bernoulli_iid", p=0.4) if family == BERNOULLI
+                            else dict(kind="gaussian_mixture", components=3, std=0.3), B, D, C)
+    m = gpu_model(spec, K, C, family, B, seed, flat)
+    ref_stats, ref_logp = oracle.em_accumulate(x, None)
+    ref_flat = oracle.stats_to_flat(ref_stats)
+    lp = torch.empty(B, device="cuda")
+    m.em_accumulate(dev(x), None, lp)
+    assert_logp_close(lp, ref_logp)
+    assert_stats_close(m.stats, ref_flat, oracle.layout, m.n_params)
+    m.em_accumulate(dev(x), None, lp)                    # added to, not overwritten
+    assert_stats_close(m.stats, 2.0 * ref_flat, oracle.layout, m.n_params)
+    # with a mask the element-wise kernel runs; both must agree with the oracle
+    mask = workloads.draw_mask(rng, dict(kind="shared", observed_fraction=0.7), B, D)
+    ref_m, _ = oracle.em_accumulate(x, mask)
+    m.em_reset()
+    m.em_accumulate(dev(x), dev(mask), lp)
+    assert_stats_close(m.stats, oracle.stats_to_flat(ref_m), oracle.layout, m.n_params)
+    m.close()
