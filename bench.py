@@ -53,13 +53,20 @@ def algorithmic_work(st, K, C, R, T, TD, B, D):
     mix = {s: c for s, c in n_children.items() if c > 1}
     n_leaf = int((st["region_replica"] >= 0).sum())
     w = {}
-    w["einsum_forward"] = (sum(2.0 * B * ko * K * K for ko in kout),
-                           sum(4.0 * ko * K * K + 4.0 * B * (2 * K + ko) for ko in kout))
+    # the root's partitions (one output entry each) and the root's mixture run in launches of their own
+    inner = [ko for ko in kout if ko != 1] if K != 1 else kout
+    top = [ko for ko in kout if ko == 1] if K != 1 else []
+    w["einsum_forward"] = (sum(2.0 * B * ko * K * K for ko in inner),
+                           sum(4.0 * ko * K * K + 4.0 * B * (2 * K + ko) for ko in inner))
     # backward: W read, Nw written (after an M-step the statistics start from zero, so the benchmark loop
     # never has to read them back); L, R, A_out, G_out read; two posterior blocks written
-    w["einsum_backward"] = (sum(4.0 * B * ko * K * K for ko in kout),
-                            sum(8.0 * ko * K * K + 4.0 * B * (4 * K + 2 * ko) for ko in kout))
-    w["mixing_forward"] = (0.0, sum(4.0 * (c + 1) * B * (1 if s == 0 else K) for s, c in mix.items()))
+    w["einsum_backward"] = (sum(4.0 * B * ko * K * K for ko in inner),
+                            sum(8.0 * ko * K * K + 4.0 * B * (4 * K + 2 * ko) for ko in inner))
+    w["root_forward"] = (sum(2.0 * B * K * K for _ in top),
+                         sum(4.0 * K * K + 4.0 * B * (2 * K + 1) for _ in top) + 4.0 * B)
+    w["root_backward"] = (sum(4.0 * B * K * K for _ in top),
+                          sum(8.0 * K * K + 4.0 * B * (4 * K + 2) for _ in top))
+    w["mixing_forward"] = (0.0, sum(4.0 * (c + 1) * B * K for s, c in mix.items() if s != 0))
     w["leaf_forward"] = (0.0, 4.0 * B * D * C + 4.0 * D * C * R * TD * K + 4.0 * n_leaf * B * K)
     w["leaf_mixing_backward"] = (0.0, 4.0 * B * D * C + 4.0 * n_leaf * B * K + 8.0 * (D * C * R * T * K + 2 * D * R * K)
                                  + sum(4.0 * (c + 2) * B * (1 if s == 0 else K) for s, c in mix.items()))

@@ -5,7 +5,7 @@ import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libeinet.so")
-SOURCES = ["csrc/leaf_forward.hip", "csrc/einsum_forward.hip", "csrc/einsum_backward.hip", "csrc/statistics.hip",
+SOURCES = ["csrc/leaf_forward.hip", "csrc/einsum_forward.hip", "csrc/einsum_backward.hip", "csrc/root_layer.hip", "csrc/statistics.hip",
            "csrc/update.hip", "csrc/sampling.hip", "csrc/static_scratch.hip", "csrc/peaks.hip", "csrc/api.cpp", "csrc/structure.cpp"]
 # -packed-fp32-ops is switched off for all device code (a target feature of the device compiler only;
 # the host pass warns that it does not know it)

@@ -107,7 +107,8 @@ int check_batch_args(einet_t* h, const float* x, const uint8_t* mask, int mask_m
 }
 
 enum KernelClass {
-    KC_LEAF_FWD, KC_EINSUM_FWD, KC_MIXING_FWD, KC_REGION_BWD, KC_EINSUM_BWD, KC_LEAF_BWD, KC_UPDATE, KC_SAMPLE, KC_COUNT
+    KC_LEAF_FWD, KC_EINSUM_FWD, KC_MIXING_FWD, KC_REGION_BWD, KC_EINSUM_BWD, KC_LEAF_BWD, KC_UPDATE, KC_SAMPLE, KC_ROOT_FWD,
+    KC_ROOT_BWD, KC_COUNT
 };
 int check_update_args(einet_t* h, float step, float min_var, float max_var, float w_floor) {
     if (!h) return EINET_ERR_INVALID_ARG;
@@ -120,7 +121,7 @@ int check_update_args(einet_t* h, float step, float min_var, float max_var, floa
 
 const char* const kKernelClassNames[KC_COUNT] = {"leaf_forward", "einsum_forward", "mixing_forward", "region_backward",
                                                  "einsum_backward", "leaf_mixing_backward", "em_update",
-                                                 "sampling"};
+                                                 "sampling", "root_forward", "root_backward"};
 
 // Runs `launch` (which enqueues kernels on s); when profiling, brackets it with two events.
 template <class F>
@@ -175,6 +176,13 @@ void forward(einet_t* h, const Arena& ar, const float* x, const uint8_t* mask, i
         launch_leaf_forward(h->dt, (int)p.leaf_node.size(), p.max_leaf_scope, x, mask, mask_mode, theta, A, Off, d, s);
     });
     for (int l = 0; l < p.num_layers; ++l) {
+        const int count = p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l];
+        if (l == p.num_layers - 1 && root_kernels_apply(count, p.K)) {
+            // the root's partitions and the root's mixture in one launch
+            run(h, KC_ROOT_FWD, s, [&] { launch_root_forward(h->dt, count, h->params, A, Off, ar.amax, logp, d, s); },
+                layer_outputs(p, l));
+            break;
+        }
         run(h, KC_EINSUM_FWD, s, [&] {
             launch_einsum_forward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
                                   p.ein_layer_full[l] != 0, h->params, A, Off, ar.amax, logp, d, s);
@@ -413,7 +421,9 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
                 launch_region_assemble(h->dt, p.rb_layer_ptr[step], p.rb_layer_ptr[step + 1] - p.rb_layer_ptr[step],
                                        step == 0, G, Gp, d, s);
             });
-        run(h, KC_EINSUM_BWD, s, [&] {
+        // (the root's partitions have one output entry each: their launch is a chain of memory requests with next to
+        // no arithmetic and is timed as a class of its own)
+        run(h, step == 0 ? KC_ROOT_BWD : KC_EINSUM_BWD, s, [&] {
             launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
                                    p.ein_layer_full[l] != 0, !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp, d, s);
         }, layer_outputs(p, l));

@@ -17,7 +17,7 @@ namespace einet_impl {
     X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff) X(mix_rec)                                \
     X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
     X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len) X(leaf_logc)                         \
-    X(sr_node) X(sr_pptr) X(sr_item) X(sr_mix) X(rb_rec) X(sr_rec)
+    X(sr_node) X(sr_pptr) X(sr_item) X(sr_mix) X(rb_rec) X(sr_rec) X(root_rec)
 
 struct DevTables {
 #define X(name) const int32_t* name;
@@ -45,6 +45,38 @@ constexpr int MIX_REC_CHILDREN = 8, MIX_REC_INTS = 16;
 // max_children: the largest number of partitions of a region of these items
 void launch_mixing_forward(const DevTables& t, int first, int count, int max_children, const float* params, float* A,
                            double* Off, float* logp, const Dims& d, hipStream_t s);
+
+// The top of the circuit bottom-up in one launch.  The top einsum layer holds exactly the partitions of the root (a
+// single output entry each); root_rec lists them: number of partitions, the root's node, the offset of its mixing
+// weights (-1: one partition), unused, then ROOT_REC_STRIDE ints per partition: einsum item, left node, right node,
+// node of the partition's own output (the root's node when it is the only one), offset of W, position among the
+// root's mixing weights.
+constexpr int ROOT_REC_STRIDE = 6;
+// Row stride (floats) of the LDS copies of these kernels: a multiple of 4 whose quarter is odd, so that 16-byte reads
+// of eight consecutive rows fall into different banks.
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+inline int root_row_stride(int K) {
+    const int k4 = (K + 3) & ~3;
+    return ((k4 >> 2) & 1) ? k4 : k4 + 4;
+}
+// LDS of the bottom-up kernel: per wave a copy of W [K][stride] and of eR [samples][stride], then offset (float64) and
+// residual of every partition for the workgroup's samples, and the mixing weight of every partition.
+constexpr int ROOT_FWD_WAVES = 8, ROOT_FWD_SAMPLES = 4;
+inline size_t root_forward_lds_bytes(int K, int n_partitions) {
+    const size_t ks = (size_t)root_row_stride(K);
+    return sizeof(float) * ROOT_FWD_WAVES * (K * ks + ROOT_FWD_SAMPLES * ks) +
+           (sizeof(double) + sizeof(float)) * (size_t)n_partitions * ROOT_FWD_SAMPLES + sizeof(float) * (size_t)n_partitions;
+}
+// The kernel serves the top layer whenever it fits the 160 KB of LDS of a compute unit (a few
+// hundred partitions at K = 64); beyond that the general einsum and mixing kernels run.
+inline bool root_kernels_apply(int n_partitions, int K) {
+    return n_partitions > 0 && root_forward_lds_bytes(K, n_partitions) <= 160 * 1024;
+}
+// Bottom-up: S~, shifts and offsets of every partition (Eq. 3-5), then the root's mixture (App. B) and log P.
+void launch_root_forward(const DevTables& t, int n_partitions, const float* params, float* A, double* Off, float* amax,
+                         float* logp, const Dims& d, hipStream_t s);
 
 // Every top-down region also has a record of RB_REC_INTS ints in rb_rec: node, entries, number of parent blocks,
 // position of its list in rb_pblk, then the first RB_REC_BLOCKS block numbers (the rest, if any, only in the list).

@@ -256,63 +256,67 @@ __device__ __forceinline__ void leaf_backward_cells_body(
 // when nothing is marginalised: num[pair][k] = sum_b x[b][pair] p[b][k] (and the same with x^2) is a GEMM with the
 // batch as contraction, here on v_mfma_f32_32x32x2_f32: rows = 32 pairs (A operand: the values, staged per pass of 64
 // samples in LDS exactly as above), columns = 32 entries k (B operand: the leaf's posterior block, zero beyond K).
-// A workgroup of four waves takes one leaf and 128 of its pairs, a wave one row tile (three workgroups share a
-// compute unit, so that one stages while another multiplies); SQ adds the x^2 rows
-// (Gaussian leaves), NCT is the number of column tiles (K <= 32: one).  tot = den = sum_b p[b][k] is summed on the side.
+// A workgroup of four waves takes one leaf and 128 / NCT of its pairs, NCT being the number of column tiles (K <= 32:
+// one); a wave takes one tile of 32 pairs x 32 entries, so that every wave of a launch carries the same number of
+// MFMAs whatever K is.  Three workgroups share a compute unit (one stages while another multiplies); SQ adds the
+// x^2 rows (Gaussian leaves).  tot = den = sum_b p[b][k] is summed on the side.
 typedef float floatx16s __attribute__((ext_vector_type(16)));
-constexpr int LSM_BC = 64, LSM_PC = 128, LSM_XS = LSM_PC + 8;   // samples per pass, pairs per workgroup, row stride of the values
-__host__ __device__ inline size_t leaf_stats_mfma_lds_bytes() {
-    return sizeof(float) * ((size_t)LSM_BC * 64 + (size_t)LSM_BC * LSM_XS + 64) + sizeof(int) * (LSM_PC + 2);
-}
+constexpr int LSM_BC = 64;                             // samples per pass
+template <int NCT>
+struct LsmLayout {
+    static constexpr int PC = 128 / NCT;               // pairs per workgroup
+    static constexpr int XS = PC + 8;                  // row stride of the values
+    static constexpr int PH = 256 / PC;                // threads per pair while staging: thread takes every PH-th sample
+    static constexpr size_t LDS_BYTES = sizeof(float) * ((size_t)LSM_BC * 64 + (size_t)LSM_BC * XS + 64) + sizeof(int) * (PC + 2);
+};
 
 template <bool SQ, int NCT>
 __global__ __launch_bounds__(256) void k_leaf_stats_mfma(
     const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica, const int32_t* __restrict__ leaf_sptr,
     const int32_t* __restrict__ leaf_var, const float* __restrict__ x, const float* __restrict__ G,
     float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, int chunks_per_leaf, Dims d) {
+    using LY = LsmLayout<NCT>;
+    constexpr int PC = LY::PC, XS = LY::XS, PH = LY::PH, NX = LSM_BC / PH;
     extern __shared__ float lsm_lds[];
     float* Gs = lsm_lds;                               // [LSM_BC][64], columns beyond K are zero
-    float* xs = Gs + LSM_BC * 64;                      // [LSM_BC][LSM_XS]
-    float* tots = xs + LSM_BC * LSM_XS;                // [64]
+    float* xs = Gs + LSM_BC * 64;                      // [LSM_BC][XS]
+    float* tots = xs + LSM_BC * XS;                    // [64]
     int* vsl = reinterpret_cast<int*>(tots + 64);      // variables of the chunk's pairs
     const int leaf = blockIdx.x / chunks_per_leaf, chunk = blockIdx.x - leaf * chunks_per_leaf;
     const int s0 = leaf_sptr[leaf], npairs = (leaf_sptr[leaf + 1] - s0) * d.C;
-    const int p0 = chunk * LSM_PC;
+    const int p0 = chunk * PC;
     if (p0 >= npairs) return;                          // (whole workgroup) this leaf has fewer chunks
-    const int np = min(LSM_PC, npairs - p0);
+    const int np = min(PC, npairs - p0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rt = wave % (4 / NCT), ct = wave / (4 / NCT);   // this wave's tile: pairs 32 rt .., entries 32 ct ..
     const int n = lane & 31, h = lane >> 5;
     const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K;
     const int vfirst = p0 / d.C, vcount = (p0 + np - 1) / d.C - vfirst + 1;
     for (int j = tid; j < vcount; j += 256) vsl[j] = leaf_var[s0 + vfirst + j];
-    floatx16s acc[1][SQ ? 2 : 1][NCT];
+    floatx16s acc[SQ ? 2 : 1];
 #pragma unroll
-    for (int t = 0; t < 1; ++t)
+    for (int q = 0; q < (SQ ? 2 : 1); ++q)
 #pragma unroll
-        for (int q = 0; q < (SQ ? 2 : 1); ++q)
-#pragma unroll
-            for (int ct = 0; ct < NCT; ++ct)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[t][q][ct][v] = 0.f;
-    float tot = 0.f;                                   // thread k < K: sum_b p[b][k]
+        for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
+    float tot = 0.f;                                   // thread (k, quarter): its share of sum_b p[b][k]
     __syncthreads();
-    // thread (pair = tid % 128, half = tid / 128) stages the even or odd samples of its pair (half a column of xs) and 16
+    // thread (pair = tid % PC, phase = tid / PC) stages every PH-th sample of its pair (part of a column of xs) and 16
     // entries of the posterior block per pass; the values of the next pass are requested before the MFMAs of the current
     // one and go to LDS after them
     size_t xoff = 0;
-    const int sp = tid & (LSM_PC - 1), sh = tid >> 7;
+    const int sp = tid & (PC - 1), sh = tid / PC;
     const bool pin = sp < np;
     if (pin) {
         const int pair = p0 + sp, vv = pair / d.C, c = pair - vv * d.C;
         xoff = (size_t)vsl[vv - vfirst] * d.C + c;
     }
     const size_t xstride = (size_t)d.D * d.C;
-    float xr[LSM_BC / 2], gq[LSM_BC * 64 / 256];
+    float xr[NX], gq[LSM_BC * 64 / 256];
     auto fetch = [&](int b0) {
         const int nb = min(LSM_BC, d.B - b0);
 #pragma unroll
-        for (int q = 0; q < LSM_BC / 2; ++q) {
-            const int bb = 2 * q + sh;
+        for (int q = 0; q < NX; ++q) {
+            const int bb = PH * q + sh;
             xr[q] = (pin && bb < nb) ? x[(size_t)(b0 + bb) * xstride + xoff] : 0.f;
         }
 #pragma unroll
@@ -323,85 +327,70 @@ __global__ __launch_bounds__(256) void k_leaf_stats_mfma(
     };
     auto stage = [&]() {
 #pragma unroll
-        for (int q = 0; q < LSM_BC / 2; ++q) xs[(2 * q + sh) * LSM_XS + sp] = xr[q];
+        for (int q = 0; q < NX; ++q) xs[(PH * q + sh) * XS + sp] = xr[q];
 #pragma unroll
         for (int q = 0; q < LSM_BC * 64 / 256; ++q) Gs[tid + 256 * q] = gq[q];
     };
     fetch(0);
     for (int b0 = 0; b0 < d.B; b0 += LSM_BC) {
-        const int nb = min(LSM_BC, d.B - b0);
         if (b0 > 0) __syncthreads();                   // readers of the previous pass are done
         stage();
         __syncthreads();
         if (b0 + LSM_BC < d.B) fetch(b0 + LSM_BC);
         __builtin_amdgcn_sched_barrier(0);             // (the requests stay ahead of the MFMA loop)
-        if (tid < d.K) {
-            float t4[4] = {0.f, 0.f, 0.f, 0.f};        // (rows beyond nb are zero)
+        {
+            // thread (k = tid % 64, quarter = tid / 64) sums a quarter of the pass (rows beyond the batch are zero)
+            float t4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int bb = 0; bb < LSM_BC; ++bb) t4[bb & 3] += Gs[bb * 64 + tid];
+            for (int bb = 0; bb < LSM_BC / 4; ++bb) t4[bb & 3] += Gs[(16 * wave + bb) * 64 + lane];
             tot += (t4[0] + t4[1]) + (t4[2] + t4[3]);
         }
-        const float* xa = xs + h * LSM_XS + 32 * wave + n;       // + 2 s LSM_XS
-        const float* pb = Gs + h * 64 + n;                        // + 2 s 64 + 32 ct
+        const float* xa = xs + h * XS + 32 * rt + n;   // + 2 s XS
+        const float* pb = Gs + h * 64 + 32 * ct + n;   // + 2 s 64
         // operands of the next step are requested before the MFMAs of the current one; the squares are formed ahead of
         // the MFMAs, not between them
-        float a[2][1], b[2][NCT];
-#pragma unroll
-        for (int t = 0; t < 1; ++t) a[0][t] = xa[32 * t];
-#pragma unroll
-        for (int ct = 0; ct < NCT; ++ct) b[0][ct] = pb[32 * ct];
+        float a[2], b[2];
+        a[0] = xa[0];
+        b[0] = pb[0];
 #pragma unroll
         for (int s = 0; s < LSM_BC / 2; ++s) {
             const int cur = s & 1, nxt = cur ^ 1;
             if (s + 1 < LSM_BC / 2) {
-#pragma unroll
-                for (int t = 0; t < 1; ++t) a[nxt][t] = xa[2 * (s + 1) * LSM_XS + 32 * t];
-#pragma unroll
-                for (int ct = 0; ct < NCT; ++ct) b[nxt][ct] = pb[2 * (s + 1) * 64 + 32 * ct];
+                a[nxt] = xa[2 * (s + 1) * XS];
+                b[nxt] = pb[2 * (s + 1) * 64];
             }
-            float a2[1];
-#pragma unroll
-            for (int t = 0; t < 1; ++t) a2[t] = a[cur][t] * a[cur][t];
+            const float a2 = a[cur] * a[cur];
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int t = 0; t < 1; ++t)
-#pragma unroll
-                for (int ct = 0; ct < NCT; ++ct) {
-                    acc[t][0][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][t], b[cur][ct], acc[t][0][ct], 0, 0, 0);
-                    if (SQ) acc[t][SQ ? 1 : 0][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[t], b[cur][ct], acc[t][SQ ? 1 : 0][ct], 0, 0, 0);
-                }
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur], b[cur], acc[0], 0, 0, 0);
+            if (SQ) acc[SQ ? 1 : 0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2, b[cur], acc[SQ ? 1 : 0], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    // acc[0][q][ct][v]: pair = 32 wave + 8 (v / 4) + 4 h + v % 4 of the chunk, entry k = 32 ct + n
+    // acc[q][v]: pair = 32 rt + 8 (v / 4) + 4 h + v % 4 of the chunk, entry k = 32 ct + n
     const int r = leaf_replica[leaf];
+    const int k = 32 * ct + n;
 #pragma unroll
-    for (int t = 0; t < 1; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int p = 32 * wave + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (p < np) {
-                const int pair = p0 + p, vv = pair / d.C, c = pair - vv * d.C;
-                const size_t ph = phi_off + ((size_t)(vsl[vv - vfirst] * d.C + c) * d.R + r) * d.T * d.K;
-#pragma unroll
-                for (int ct = 0; ct < NCT; ++ct) {
-                    const int k = 32 * ct + n;
-                    if (k < d.K) {
-                        stats[ph + k] += acc[t][0][ct][v];
-                        if (SQ) stats[ph + d.K + k] += acc[t][SQ ? 1 : 0][ct][v];
-                    }
-                }
-            }
+    for (int v = 0; v < 16; ++v) {
+        const int p = 32 * rt + 8 * (v >> 2) + 4 * h + (v & 3);
+        if (p < np && k < d.K) {
+            const int pair = p0 + p, vv = pair / d.C, c = pair - vv * d.C;
+            const size_t ph = phi_off + ((size_t)(vsl[vv - vfirst] * d.C + c) * d.R + r) * d.T * d.K;
+            stats[ph + k] += acc[0][v];
+            if (SQ) stats[ph + d.K + k] += acc[SQ ? 1 : 0][v];
         }
+    }
     // den = tot for every variable whose first channel lies in this chunk
-    if (tid < 64) tots[tid] = tid < d.K ? tot : 0.f;
+    __syncthreads();                                   // (the last pass has been read: Gs is free)
+    Gs[tid] = tot;
+    __syncthreads();
+    if (tid < 64) tots[tid] = tid < d.K ? (Gs[tid] + Gs[64 + tid]) + (Gs[128 + tid] + Gs[192 + tid]) : 0.f;
     __syncthreads();
     const int vlo = (p0 + d.C - 1) / d.C, vhi = (p0 + np - 1) / d.C;      // variables with pair (v, 0) in [p0, p0 + np)
     for (int i = tid; i < (vhi - vlo + 1) * d.K; i += 256) {
-        const int vv = vlo + i / d.K, k = i % d.K;
-        const size_t o = ((size_t)vsl[vv - vfirst] * d.R + r) * d.K + k;
-        stats[den_off + o] += tots[k];
-        stats[tot_off + o] += tots[k];
+        const int vv = vlo + i / d.K, kk = i % d.K;
+        const size_t o = ((size_t)vsl[vv - vfirst] * d.R + r) * d.K + kk;
+        stats[den_off + o] += tots[kk];
+        stats[tot_off + o] += tots[kk];
     }
 }
 
@@ -449,24 +438,26 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
     // statistics in a launch of their own
     bool leaves_done = categorical;
     if (!categorical && mask_mode == EINET_MASK_NONE && max_scope * d.C >= 1024 && d.K <= 64) {
-        const size_t lds_m = leaf_stats_mfma_lds_bytes();
         static std::once_flag attr_m[EINET_MAX_DEVICES];
         int dev = 0;
         (void)hipGetDevice(&dev);
         std::call_once(attr_m[dev % EINET_MAX_DEVICES], [&] {
-            allow_dynamic_lds(&k_leaf_stats_mfma<true, 1>, lds_m);
-            allow_dynamic_lds(&k_leaf_stats_mfma<true, 2>, lds_m);
-            allow_dynamic_lds(&k_leaf_stats_mfma<false, 1>, lds_m);
-            allow_dynamic_lds(&k_leaf_stats_mfma<false, 2>, lds_m);
+            allow_dynamic_lds(&k_leaf_stats_mfma<true, 1>, LsmLayout<1>::LDS_BYTES);
+            allow_dynamic_lds(&k_leaf_stats_mfma<true, 2>, LsmLayout<2>::LDS_BYTES);
+            allow_dynamic_lds(&k_leaf_stats_mfma<false, 1>, LsmLayout<1>::LDS_BYTES);
+            allow_dynamic_lds(&k_leaf_stats_mfma<false, 2>, LsmLayout<2>::LDS_BYTES);
         });
-        const int cpl = (max_scope * d.C + LSM_PC - 1) / LSM_PC;
-#define EINET_LSM(SQ, NCT)                                                                                        \
-    hipLaunchKernelGGL((k_leaf_stats_mfma<SQ, NCT>), dim3(n_leaves * cpl), dim3(256), lds_m, s, t.leaf_node,      \
-                       t.leaf_replica, t.leaf_sptr, t.leaf_var, x, G, stats, phi_off, den_off, tot_off, cpl, d)
-        if (d.T == 2 && d.K > 32) EINET_LSM(true, 2);
-        else if (d.T == 2) EINET_LSM(true, 1);
-        else if (d.K > 32) EINET_LSM(false, 2);
-        else EINET_LSM(false, 1);
+#define EINET_LSM(SQ, NCT)                                                                                       \
+    {                                                                                                            \
+        const int cpl = (max_scope * d.C + LsmLayout<NCT>::PC - 1) / LsmLayout<NCT>::PC;                         \
+        hipLaunchKernelGGL((k_leaf_stats_mfma<SQ, NCT>), dim3(n_leaves * cpl), dim3(256), LsmLayout<NCT>::LDS_BYTES, \
+                           s, t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, x, G, stats, phi_off, den_off,   \
+                           tot_off, cpl, d);                                                                     \
+    }
+        if (d.T == 2 && d.K > 32) EINET_LSM(true, 2)
+        else if (d.T == 2) EINET_LSM(true, 1)
+        else if (d.K > 32) EINET_LSM(false, 2)
+        else EINET_LSM(false, 1)
 #undef EINET_LSM
         leaves_done = true;
     }

@@ -295,6 +295,27 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param
         for (int c = 0; c < nc && c < MIX_REC_CHILDREN; ++c) rec[4 + c] = p.mix_child[p.mix_cptr[i] + c];
     }
 
+    // ---- the root's partitions (see ROOT_REC_STRIDE): the items of the top einsum layer
+    if (p.num_layers > 0) {
+        const int e0 = p.ein_layer_ptr[p.num_layers - 1], e1 = p.ein_layer_ptr[p.num_layers];
+        const auto& sib = g.parts_of[0];
+        p.root_rec.assign(4 + (size_t)(e1 - e0) * ROOT_REC_STRIDE, 0);
+        p.root_rec[0] = e1 - e0;
+        p.root_rec[1] = 0;
+        p.root_rec[2] = (int32_t)p.v_offset[0];
+        for (int e = e0; e < e1; ++e) {
+            int32_t* q = p.root_rec.data() + 4 + (size_t)(e - e0) * ROOT_REC_STRIDE;
+            q[0] = e;
+            q[1] = p.ein_left[e];
+            q[2] = p.ein_right[e];
+            q[3] = p.ein_out[e];
+            q[4] = p.ein_woff[e];
+            q[5] = int(std::find(sib.begin(), sib.end(), p.ein_part[e]) - sib.begin());
+        }
+    } else {
+        p.root_rec.assign(4, 0);
+    }
+
     // ---- sampling items: the sum regions layer by layer, each with the einsum items of its partitions
     {
         std::vector<int> mix_of(nr, -1);
