@@ -260,7 +260,9 @@ def main():
 
     # launch by launch: the einsum layers of one step, averaged over the steps of the profiled pass (the work tag of
     # a launch is the number of output entries summed over its partitions)
-    ein = [l for l in launch_list if l[0] in ("einsum_forward", "einsum_backward")]
+    # (the root's partitions, one output entry each, have launches of their own: root_forward, which also forms the
+    # root's mixture, and root_backward)
+    ein = [l for l in launch_list if l[0] in ("einsum_forward", "einsum_backward", "root_forward", "root_backward")]
     per_step = len(ein) // args.steps
     layers = []
     if per_step * args.steps == len(ein):
@@ -268,7 +270,7 @@ def main():
             name, _, tag = ein[pos]
             outs, parts = tag >> 24, tag & 0xFFFFFF
             us = 1e3 * sum(ein[s_ * per_step + pos][1] for s_ in range(args.steps)) / args.steps
-            fwd = name == "einsum_forward"
+            fwd = name.endswith("_forward")
             fl = (2.0 if fwd else 4.0) * B * K * K * outs
             # W once (and Nw written once top-down); rows of the children, of the region and its posterior; outputs
             by = (4.0 if fwd else 8.0) * K * K * outs + 4.0 * B * ((2 * K * parts + outs) if fwd else (4 * K * parts + 2 * outs))

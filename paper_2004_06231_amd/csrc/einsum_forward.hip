@@ -526,7 +526,8 @@ static void launch_einsum_forward_kq(const DevTables& t, int first, int count, c
                                      double* Off, float* amax, float* logp, const Dims& d, hipStream_t s) {
     const int nkt = (d.K + 3) / 4;
     const int n_btiles = (d.B + 15) / 16;
-    const int nw = n_btiles < 8 ? n_btiles : 8;
+    const int nw_max = count * nkt >= 1024 ? 4 : 8;    // many small workgroups: more of them per compute unit
+    const int nw = n_btiles < nw_max ? n_btiles : nw_max;
     const size_t lds = sizeof(float) * FwdLayout<KQ>::LDS_FLOATS;
     if (lds > 64 * 1024) {
         static std::once_flag attr_set[EINET_MAX_DEVICES];
