@@ -99,3 +99,37 @@ def test_leaf_statistics_of_very_long_scopes(spec, K, C, family, B):
     m.em_accumulate(dev(x), dev(mask), lp)
     assert_stats_close(m.stats, oracle.stats_to_flat(ref_m), oracle.layout, m.n_params)
     m.close()
+
+
+ROOT_CASES = [
+    # spec, K, C, family, B: the top of the circuit (the root's partitions and the root's mixture in one launch)
+    (dict(kind="rat", D=8, depth=1, R=1), 64, 1, BERNOULLI, 5),            # one partition, no mixture, widest K, B below a tile
+    (dict(kind="rat", D=8, depth=1, R=40), 64, 1, BERNOULLI, 33),          # widest K and many partitions: more than 64 KB of LDS
+    (dict(kind="rat", D=8, depth=2, R=3), 7, 2, GAUSSIAN, 130),            # K not a multiple of 4
+    (dict(kind="rat", D=6, depth=1, R=300), 64, 1, BERNOULLI, 9),          # just within the 160 KB of LDS
+    (dict(kind="rat", D=6, depth=1, R=320), 64, 1, BERNOULLI, 9),          # too many partitions for the LDS: general kernels
+    (dict(kind="pd", H=4, W=4, deltas=[2]), 1, 1, GAUSSIAN, 70),           # K = 1
+]
+
+
+@pytest.mark.parametrize("spec,K,C,family,B", ROOT_CASES)
+def test_root_of_the_circuit(spec, K, C, family, B):
+    print("root case", spec, K, C, family, B, flush=True)
+    seed = 6000 + K + B
+    oracle, flat, rng = make_oracle(spec, K, C, family, seed, leaf_range=(0.1, 0.9))
+    D = oracle.g.num_vars
+    x = workloads.draw_data(rng, dict(kind="bernoulli_iid", p=0.4) if family == BERNOULLI
+                            else dict(kind="gaussian_mixture", components=3, std=0.3), B, D, C)
+    m = gpu_model(spec, K, C, family, B, seed, flat)
+    ref_stats, ref_logp = oracle.em_accumulate(x, None)
+    assert_logp_close(m.logp(dev(x)), ref_logp)
+    lp = torch.empty(B, device="cuda")
+    m.em_accumulate(dev(x), None, lp)
+    assert_logp_close(lp, ref_logp)
+    assert_stats_close(m.stats, oracle.stats_to_flat(ref_stats), oracle.layout, m.n_params)
+    # a marginalised batch, then a smaller one on the same handle
+    mask = workloads.draw_mask(rng, dict(kind="per_sample", observed_fraction=0.5), B, D)
+    assert_logp_close(m.logp(dev(x), dev(mask)), oracle.logp(x, mask))
+    nb = max(1, B // 2)
+    assert_logp_close(m.logp(dev(x[:nb])), ref_logp[:nb])
+    m.close()
