@@ -421,9 +421,16 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
                 launch_region_assemble(h->dt, p.rb_layer_ptr[step], p.rb_layer_ptr[step + 1] - p.rb_layer_ptr[step],
                                        step == 0, G, Gp, d, s);
             });
-        // (the root's partitions have one output entry each: their launch is a chain of memory requests with next to
-        // no arithmetic and is timed as a class of its own)
-        run(h, step == 0 ? KC_ROOT_BWD : KC_EINSUM_BWD, s, [&] {
+        if (step == 0) {
+            // the root's partitions (one output entry each; the root's posterior is 1, its block in G is read by the
+            // mixing statistics only): a launch of their own kind, timed as a class of its own
+            run(h, KC_ROOT_BWD, s, [&] {
+                launch_root_backward(h->dt, p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], !h->weight_stats_zero, h->params,
+                                     h->stats, A, Off, amax, Gp, d, s);
+            }, layer_outputs(p, l));
+            continue;
+        }
+        run(h, KC_EINSUM_BWD, s, [&] {
             launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
                                    p.ein_layer_full[l] != 0, !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp, d, s);
         }, layer_outputs(p, l));

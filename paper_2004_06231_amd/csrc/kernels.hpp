@@ -46,7 +46,7 @@ constexpr int MIX_REC_CHILDREN = 8, MIX_REC_INTS = 16;
 void launch_mixing_forward(const DevTables& t, int first, int count, int max_children, const float* params, float* A,
                            double* Off, float* logp, const Dims& d, hipStream_t s);
 
-// The top of the circuit bottom-up in one launch.  The top einsum layer holds exactly the partitions of the root (a
+// The top of the circuit in one launch each way.  The top einsum layer holds exactly the partitions of the root (a
 // single output entry each); root_rec lists them: number of partitions, the root's node, the offset of its mixing
 // weights (-1: one partition), unused, then ROOT_REC_STRIDE ints per partition: einsum item, left node, right node,
 // node of the partition's own output (the root's node when it is the only one), offset of W, position among the
@@ -77,6 +77,11 @@ inline bool root_kernels_apply(int n_partitions, int K) {
 // Bottom-up: S~, shifts and offsets of every partition (Eq. 3-5), then the root's mixture (App. B) and log P.
 void launch_root_forward(const DevTables& t, int n_partitions, const float* params, float* A, double* Off, float* amax,
                          float* logp, const Dims& d, hipStream_t s);
+// Top-down: weight statistics (Eq. 6) and child posteriors of the root's partitions; the root's posterior is 1 and its
+// mixing step is folded in.  Writes the posterior blocks that launch_einsum_backward writes for a layer of
+// n_partitions items with one output entry each (bwd_groups_per_item workgroups and right-child blocks per item).
+void launch_root_backward(const DevTables& t, int n_partitions, bool accumulate, const float* params, float* stats,
+                          const float* A, const double* Off, const float* amax, float* Gp, const Dims& d, hipStream_t s);
 
 // Every top-down region also has a record of RB_REC_INTS ints in rb_rec: node, entries, number of parent blocks,
 // position of its list in rb_pblk, then the first RB_REC_BLOCKS block numbers (the rest, if any, only in the list).

@@ -1,7 +1,8 @@
-// The top of the circuit bottom-up, in one launch.  The partitions of the root are einsum items with a single output
-// entry (Eq. 3-5): K^2 multiply-adds per sample, far too little for the matrix pipe to matter, so this launch is a
-// chain of dependent memory requests.  The kernel reads one record (all indices of all partitions), requests rows,
-// offsets and weights together, works on the vector ALU, and forms the root's mixture (App. B) and log P itself.
+// The top of the circuit, one launch each way.  The partitions of the root are einsum items with a single output
+// entry (Eq. 3-5): K^2 multiply-adds per sample, far too little for the matrix pipe to matter, so these launches are
+// chains of dependent memory requests.  Both kernels read one record (all indices of all partitions), request rows,
+// offsets and weights together, and work on the vector ALU; bottom-up the root's mixture (App. B) and log P are formed
+// in the same launch, top-down the mixing step of the root is folded into the posterior weight (Eq. 6).
 #include "device_common.hpp"
 
 #include <mutex>
@@ -166,6 +167,210 @@ __global__ __launch_bounds__(64 * RF_WAVES) void k_root_forward(const int32_t* _
     }
 }
 
+// ------------------------------------------------------------------ top-down
+// With one output entry the posterior weight of a sample is a scalar,
+//     q[b] = v exp((Off[out][b] - Off[root][b]) - A[root][b])            (v = 1, Off[out] = Off[root] for one partition;
+// the root's own posterior is 1), and with QL[b][i] = q[b] eL[b][i]:
+//     Nw[i][j]      += W[i][j] sum_b QL[b][i] eR[b][j]
+//     Gp_left[b][i]  = QL[b][i] sum_j W[i][j] eR[b][j]
+//     Gp_right[b][j] = eR[b][j] sum_i W[i][j] QL[b][i].
+// A workgroup takes one partition and a run of slices (four consecutive left entries i each), the same split and the
+// same posterior blocks as the general top-down kernel: the left block is complete per slice, the right block of the
+// workgroup holds the sum over its slices.  Per slice and pass of RB_BC samples everything is requested at once (the
+// right rows, the slice's four left entries, offsets, shifts, the four W rows) and staged in LDS: eR both sample-major
+// (statistics and left posterior: lanes along the batch) and row-major (right posterior: lanes along j, stores
+// coalesced), QL likewise, W transposed [j][4].
+constexpr int RB_BC = 128, RB_ST = RB_BC + 4, RB_THREADS = 512;
+
+template <int KQ>
+struct RootBwdLayout {
+    static constexpr int K4 = 4 * KQ, KS = (KQ & 1) ? K4 : K4 + 4;
+    static constexpr int OFF_RT = 0;                         // eR^T [K4][RB_ST]
+    static constexpr int OFF_R = OFF_RT + K4 * RB_ST;        // eR   [RB_BC][KS]
+    static constexpr int OFF_QT = OFF_R + RB_BC * KS;        // QL^T [4][RB_ST]
+    static constexpr int OFF_Q = OFF_QT + 4 * RB_ST;         // QL   [RB_BC][4]
+    static constexpr int OFF_WT = OFF_Q + 4 * RB_BC;         // W^T  [K4][4] of the slice
+    static constexpr int LDS_FLOATS = OFF_WT + 4 * K4;
+};
+
+template <int KQ>
+__global__ __launch_bounds__(RB_THREADS) void k_root_backward(const int32_t* __restrict__ rec, const float* __restrict__ params,
+                                                       float* __restrict__ stats, const float* __restrict__ A,
+                                                       const double* __restrict__ Off, const float* __restrict__ amax,
+                                                       float* __restrict__ Gp, int ngroups, int accumulate, int B, int K) {
+    using LY = RootBwdLayout<KQ>;
+    constexpr int K4 = LY::K4, KS = LY::KS;
+    extern __shared__ float lds[];
+    float* sRT = lds + LY::OFF_RT;
+    float* sR = lds + LY::OFF_R;
+    float* sQT = lds + LY::OFF_QT;
+    float* sQ = lds + LY::OFF_Q;
+    float* sWT = lds + LY::OFF_WT;
+    const int root = rec[1], voff = rec[2];
+    const int p = blockIdx.x / ngroups, grp = blockIdx.x - p * ngroups;
+    const int32_t* q = rec + 4 + p * ROOT_REC_STRIDE;
+    const int item = q[0], left = q[1], right = q[2], out = q[3], woff = q[4];
+    const int it0 = grp * KQ / ngroups, it1 = (grp + 1) * KQ / ngroups;
+    const int tid = threadIdx.x;
+    const size_t blk = (size_t)B * K;
+    const float* Lp = A + (size_t)left * blk;
+    const float* Rp = A + (size_t)right * blk;
+    const float* As = A + (size_t)root * blk;
+    const double* Oo = Off + (size_t)out * B;
+    const double* Os = Off + (size_t)root * B;
+    const float* aL = amax + (size_t)item * 2 * B;
+    const float* aR = aL + B;
+    const float* W = params + woff;
+    float* Nw = stats + woff;
+    const int nblk = 1 + KQ;
+    float* gleft = Gp + (size_t)item * nblk * blk;
+    float* gright = Gp + ((size_t)item * nblk + 1 + grp) * blk;
+    const bool vec = (K & 3) == 0;
+    // Roles within a pass (they run side by side): threads 0 .. 127 stage QL and take the left child (one sample each),
+    // threads 128 .. 128 + 4K - 1 take the statistics (entry (il, j) each; the first K4 of them also bring the W rows in),
+    // everybody stages eR and shares the right child.
+    const int st = tid - 128;
+    const int sil = st >= 0 ? st / K : 0, sj = st - sil * K;
+    for (int it = it0; it < it1; ++it) {
+        const bool sact = st >= 0 && st < 4 * K && 4 * it + sil < K;
+        float acc = 0.f;
+        // (this thread's weight and old statistic are requested with the first pass, not after the last)
+        const size_t sidx = sact ? (size_t)(4 * it + sil) * K + sj : 0;
+        const float wown = sact ? W[sidx] : 0.f;
+        const float nold = sact && accumulate ? Nw[sidx] : 0.f;
+        for (int b0 = 0; b0 < B; b0 += RB_BC) {
+            const int nb = min(RB_BC, B - b0), nb4 = (nb + 3) & ~3;
+            // ---- requests: everything this pass needs, before the first value is used
+            float vq = 1.f, lq[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, alq = 0.f, asq = 0.f;
+            double ddq = 0.0;
+            if (tid < nb) {
+                const int b = b0 + tid;
+                if (voff >= 0) vq = params[voff + q[5]];
+                ddq = Oo[b] - Os[b];
+                asq = As[(size_t)b * K];
+                alq = aL[b];
+                if (vec) {
+                    const float4 l4 = *reinterpret_cast<const float4*>(Lp + (size_t)b * K + 4 * it);
+                    lq[0] = l4.x, lq[1] = l4.y, lq[2] = l4.z, lq[3] = l4.w;
+                } else {
+#pragma unroll
+                    for (int il = 0; il < 4; ++il)
+                        if (4 * it + il < K) lq[il] = Lp[(size_t)b * K + 4 * it + il];
+                }
+            }
+            float wq[4] = {0.f, 0.f, 0.f, 0.f};            // thread j < K4: column j of the slice's four W rows
+            if (tid >= 128 && tid < 128 + K4) {
+                const int j = tid - 128;
+#pragma unroll
+                for (int il = 0; il < 4; ++il)
+                    if (4 * it + il < K && j < K) wq[il] = W[(size_t)(4 * it + il) * K + j];
+            }
+            constexpr int NF = (RB_BC * KQ + RB_THREADS - 1) / RB_THREADS;   // 16-byte pieces of the right rows per thread
+            float4 r4[NF];
+            float ar[NF];
+#pragma unroll
+            for (int n = 0; n < NF; ++n) {
+                const int f = min(tid + RB_THREADS * n, nb * KQ - 1), row = f / KQ, k4 = f - row * KQ;
+                ar[n] = aR[b0 + row];
+                if (vec) {
+                    r4[n] = *reinterpret_cast<const float4*>(Rp + (size_t)(b0 + row) * K + 4 * k4);
+                } else {
+                    const float* src = Rp + (size_t)(b0 + row) * K + 4 * k4;
+                    r4[n].x = 4 * k4 + 0 < K ? src[0] : -INFINITY;
+                    r4[n].y = 4 * k4 + 1 < K ? src[1] : -INFINITY;
+                    r4[n].z = 4 * k4 + 2 < K ? src[2] : -INFINITY;
+                    r4[n].w = 4 * k4 + 3 < K ? src[3] : -INFINITY;
+                }
+            }
+            __syncthreads();                               // the previous pass (or slice) has been read
+            // ---- staging
+            if (tid < nb4) {
+                const float qv = tid < nb ? vq * __expf((float)ddq - asq) : 0.f;
+                float4 ql;
+                ql.x = tid < nb ? qv * __expf(lq[0] - alq) : 0.f;     // (entries beyond K: exp(-inf) = 0)
+                ql.y = tid < nb ? qv * __expf(lq[1] - alq) : 0.f;
+                ql.z = tid < nb ? qv * __expf(lq[2] - alq) : 0.f;
+                ql.w = tid < nb ? qv * __expf(lq[3] - alq) : 0.f;
+                *reinterpret_cast<float4*>(sQ + 4 * tid) = ql;
+                sQT[tid] = ql.x, sQT[RB_ST + tid] = ql.y, sQT[2 * RB_ST + tid] = ql.z, sQT[3 * RB_ST + tid] = ql.w;
+            }
+            if (tid >= 128 && tid < 128 + K4)
+                *reinterpret_cast<float4*>(sWT + 4 * (tid - 128)) = make_float4(wq[0], wq[1], wq[2], wq[3]);
+#pragma unroll
+            for (int n = 0; n < NF; ++n) {
+                const int f = tid + RB_THREADS * n, row = f / KQ, k4 = f - row * KQ;
+                if (f < nb4 * KQ) {
+                    const bool in = row < nb;              // rows nb .. nb4 - 1 are zeros: the loops below run over whole fours
+                    float4 e;
+                    e.x = in ? __expf(r4[n].x - ar[n]) : 0.f;
+                    e.y = in ? __expf(r4[n].y - ar[n]) : 0.f;
+                    e.z = in ? __expf(r4[n].z - ar[n]) : 0.f;
+                    e.w = in ? __expf(r4[n].w - ar[n]) : 0.f;
+                    *reinterpret_cast<float4*>(sR + row * KS + 4 * k4) = e;
+                    sRT[(4 * k4 + 0) * RB_ST + row] = e.x;
+                    sRT[(4 * k4 + 1) * RB_ST + row] = e.y;
+                    sRT[(4 * k4 + 2) * RB_ST + row] = e.z;
+                    sRT[(4 * k4 + 3) * RB_ST + row] = e.w;
+                }
+            }
+            __syncthreads();
+            // ---- statistics: thread (il, j) contracts the batch, four samples per 16-byte read
+            if (sact) {
+                const float* qp = sQT + sil * RB_ST;
+                const float* rp = sRT + sj * RB_ST;
+                float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll 4
+                for (int m = 0; m < nb4; m += 4) {
+                    const float4 qq = *reinterpret_cast<const float4*>(qp + m);
+                    const float4 rr = *reinterpret_cast<const float4*>(rp + m);
+                    a0 = fmaf(qq.x, rr.x, a0);
+                    a1 = fmaf(qq.y, rr.y, a1);
+                    a2 = fmaf(qq.z, rr.z, a2);
+                    a3 = fmaf(qq.w, rr.w, a3);
+                }
+                acc += (a0 + a1) + (a2 + a3);
+            }
+            // ---- left child: thread b takes the four entries of the slice
+            if (tid < nb) {
+                float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
+#pragma unroll 4
+                for (int j = 0; j < K4; ++j) {
+                    const float4 w = *reinterpret_cast<const float4*>(sWT + 4 * j);
+                    const float r = sRT[j * RB_ST + tid];
+                    d0 = fmaf(w.x, r, d0);
+                    d1 = fmaf(w.y, r, d1);
+                    d2 = fmaf(w.z, r, d2);
+                    d3 = fmaf(w.w, r, d3);
+                }
+                const float4 ql = *reinterpret_cast<const float4*>(sQ + 4 * tid);
+                float* dst = gleft + (size_t)(b0 + tid) * K + 4 * it;
+                if (vec) {
+                    *reinterpret_cast<float4*>(dst) = make_float4(ql.x * d0, ql.y * d1, ql.z * d2, ql.w * d3);
+                } else {
+                    if (4 * it + 0 < K) dst[0] = ql.x * d0;
+                    if (4 * it + 1 < K) dst[1] = ql.y * d1;
+                    if (4 * it + 2 < K) dst[2] = ql.z * d2;
+                    if (4 * it + 3 < K) dst[3] = ql.w * d3;
+                }
+            }
+            // ---- right child: lanes along j, the workgroup's slices summed in place (the same thread owns an entry in
+            // every slice)
+#pragma unroll 4
+            for (int e = tid; e < nb * K4; e += RB_THREADS) {
+                const int bl = e / K4, j = e - bl * K4;    // (K4 is a constant: no division)
+                const float4 ql = *reinterpret_cast<const float4*>(sQ + 4 * bl);
+                const float4 w = *reinterpret_cast<const float4*>(sWT + 4 * j);
+                const float tsum = fmaf(w.x, ql.x, fmaf(w.y, ql.y, fmaf(w.z, ql.z, w.w * ql.w)));
+                if (j < K) {
+                    float* dst = gright + (size_t)(b0 + bl) * K + j;
+                    *dst = sR[bl * KS + j] * tsum + (it > it0 ? *dst : 0.f);
+                }
+            }
+        }
+        if (sact) Nw[sidx] = wown * acc + nold;
+    }
+}
+
 template <int KQ>
 void launch_root_forward_kq(const DevTables& t, int n_partitions, const float* params, float* A, double* Off, float* amax,
                             float* logp, const Dims& d, hipStream_t s) {
@@ -180,6 +385,22 @@ void launch_root_forward_kq(const DevTables& t, int n_partitions, const float* p
                        A, Off, amax, logp, d.B, d.K);
 }
 
+template <int KQ>
+void launch_root_backward_kq(const DevTables& t, int n_partitions, bool accumulate, const float* params, float* stats,
+                             const float* A, const double* Off, const float* amax, float* Gp, const Dims& d,
+                             hipStream_t s) {
+    const size_t lds = sizeof(float) * RootBwdLayout<KQ>::LDS_FLOATS;
+    if (lds > 64 * 1024) {
+        static std::once_flag attr_set[EINET_MAX_DEVICES];
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] { allow_dynamic_lds(&k_root_backward<KQ>, lds); });
+    }
+    const int ngroups = bwd_groups_per_item(n_partitions, d.K);
+    hipLaunchKernelGGL(k_root_backward<KQ>, dim3(n_partitions * ngroups), dim3(RB_THREADS), lds, s, t.root_rec, params, stats, A,
+                       Off, amax, Gp, ngroups, accumulate ? 1 : 0, d.B, d.K);
+}
+
 }  // namespace
 
 void launch_root_forward(const DevTables& t, int n_partitions, const float* params, float* A, double* Off, float* amax,
@@ -187,6 +408,18 @@ void launch_root_forward(const DevTables& t, int n_partitions, const float* para
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
     case J: launch_root_forward_kq<J>(t, n_partitions, params, A, Off, amax, logp, d, s); break;
+        EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
+        EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
+        EINET_CASE(16)
+#undef EINET_CASE
+    }
+}
+
+void launch_root_backward(const DevTables& t, int n_partitions, bool accumulate, const float* params, float* stats,
+                          const float* A, const double* Off, const float* amax, float* Gp, const Dims& d, hipStream_t s) {
+    switch ((d.K + 3) / 4) {
+#define EINET_CASE(J) \
+    case J: launch_root_backward_kq<J>(t, n_partitions, accumulate, params, stats, A, Off, amax, Gp, d, s); break;
         EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
         EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
         EINET_CASE(16)
