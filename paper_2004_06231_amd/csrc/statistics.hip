@@ -9,40 +9,73 @@ namespace {
 
 // Statistics of the mixing weights (App. B, Eq. 6): Nv[s,k,c] += v[s,k,c] * sum_b G[s][b,k] * S^c[b,k] / S[b,k].
 // One workgroup per (mixing item, child); a reduction over the batch through LDS.  Runs in the same
-// launch as the leaf statistics (k_tail_backward): the two are independent.
-__device__ __forceinline__ void mixing_stats_body(int item, int c, const int32_t* __restrict__ m_node,
-                                                  const int32_t* __restrict__ m_kout,
+// launch as the leaf statistics (k_tail_backward): the two are independent.  The workgroup is a chain of memory
+// requests: the item's record (node, entries, weight offset, partitions: one request instead of four tables one after the
+// other), then the rows of four samples per thread at once together with the weight and its old statistic.
+template <int TPB>
+__device__ __forceinline__ void mixing_stats_body(int item, int c, const int32_t* __restrict__ m_rec,
                                                   const int32_t* __restrict__ m_cptr,
-                                                  const int32_t* __restrict__ m_child,
-                                                  const int32_t* __restrict__ m_voff, const float* __restrict__ params,
+                                                  const int32_t* __restrict__ m_child, const float* __restrict__ params,
                                                   float* __restrict__ stats, const float* __restrict__ A,
                                                   const double* __restrict__ Off, const float* __restrict__ G, int B,
                                                   int K) {
-    __shared__ float red[1024];
+    __shared__ float red[TPB];
     const int tid = threadIdx.x;
-    const int c0 = m_cptr[item], nc = m_cptr[item + 1] - c0;
+    const int32_t* rec = m_rec + (size_t)item * MIX_REC_INTS;
+    const int node = rec[0], kout = rec[1], voff = rec[2], nc = rec[3];
     if (c >= nc) return;
-    const int kout = m_kout[item];
-    const int nbl = 1024 / kout, k = tid % kout, bl = tid / kout;
-    const float* As = A + (size_t)m_node[item] * B * K;
-    const float* Ac = A + (size_t)m_child[c0 + c] * B * K;
-    const float* Gs = G + (size_t)m_node[item] * B * K;
-    const double* Os = Off + (size_t)m_node[item] * B;
-    const double* Oc = Off + (size_t)m_child[c0 + c] * B;
+    const int child = c < MIX_REC_CHILDREN ? rec[4 + c] : m_child[m_cptr[item] + c];
+    const int nbl = TPB / kout, k = tid % kout, bl = tid / kout;
+    const float* As = A + (size_t)node * B * K;
+    const float* Ac = A + (size_t)child * B * K;
+    const float* Gs = G + (size_t)node * B * K;
+    const double* Os = Off + (size_t)node * B;
+    const double* Oc = Off + (size_t)child * B;
+    const size_t so = (size_t)voff + (size_t)min(tid, kout - 1) * nc + c;
+    const float pv = params[so], sv = stats[so];       // (used by the first kout threads at the end)
     float part = 0.f;
     if (bl < nbl)
-        for (int b = bl; b < B; b += nbl) {
-            const size_t o = (size_t)b * K + k;
-            const float g = Gs[o];
-            if (g != 0.f) part += g * expf((float)(Oc[b] - Os[b]) + Ac[o] - As[o]);
+        for (int b0 = bl; b0 < B; b0 += 4 * nbl) {
+            float g[4], ac[4], as[4];
+            double dd[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int b = min(b0 + u * nbl, B - 1);
+                const size_t o = (size_t)b * K + k;
+                g[u] = Gs[o];
+                ac[u] = Ac[o];
+                as[u] = As[o];
+                dd[u] = Oc[b] - Os[b];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (b0 + u * nbl < B && g[u] != 0.f) part += g[u] * expf((float)dd[u] + ac[u] - as[u]);
         }
     red[tid] = part;
     __syncthreads();
+    // A sum with few entries (the root has one) has hundreds of sample groups: 32 threads per entry first add every 32nd
+    // group, so that no thread walks more than a few dozen values.
+    int ngr = nbl;
+    if (nbl > 64) {
+        constexpr int J = 32;
+        float t = 0.f;
+        const int kk = tid % kout, j = tid / kout;
+        if (j < J)
+            for (int l = j; l < nbl; l += J) t += red[l * kout + kk];
+        __syncthreads();
+        if (j < J) red[j * kout + kk] = t;
+        __syncthreads();
+        ngr = J;
+    }
     if (tid < kout) {
-        float tot = 0.f;
-        for (int l = 0; l < nbl; ++l) tot += red[l * kout + tid];
-        const size_t o = (size_t)m_voff[item] + (size_t)tid * nc + c;
-        stats[o] += params[o] * tot;
+        float t4[4] = {0.f, 0.f, 0.f, 0.f};
+        int l = 0;
+        for (; l + 4 <= ngr; l += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t4[u] += red[(l + u) * kout + tid];
+        }
+        for (; l < ngr; ++l) t4[0] += red[l * kout + tid];
+        stats[so] = sv + pv * ((t4[0] + t4[1]) + (t4[2] + t4[3]));
     }
 }
 
@@ -402,11 +435,10 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
     int n_leaf_blocks, int max_children, const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var,
     const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica, int n_lv,
     const float* __restrict__ x, const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G,
-    float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const int32_t* __restrict__ m_node,
-    const int32_t* __restrict__ m_kout, const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child,
-    const int32_t* __restrict__ m_voff, const float* __restrict__ params, const float* __restrict__ A,
-    const double* __restrict__ Off, const int32_t* __restrict__ leaf_sptr, const int32_t* __restrict__ leaf_var,
-    int chunks_per_leaf, Dims d) {
+    float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const int32_t* __restrict__ m_rec,
+    const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child, const float* __restrict__ params,
+    const float* __restrict__ A, const double* __restrict__ Off, const int32_t* __restrict__ leaf_sptr,
+    const int32_t* __restrict__ leaf_var, int chunks_per_leaf, Dims d) {
     const int blk = blockIdx.x;
     if (blk < n_leaf_blocks) {
         if constexpr (NCH == 0)
@@ -417,8 +449,8 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
                                     phi_off, den_off, tot_off, d);
     } else {
         const int idx = blk - n_leaf_blocks;
-        mixing_stats_body(idx / max_children, idx % max_children, m_node, m_kout, m_cptr, m_child, m_voff, params,
-                          stats, A, Off, G, d.B, d.K);
+        mixing_stats_body<1024>(idx / max_children, idx % max_children, m_rec, m_cptr, m_child, params, stats, A, Off, G,
+                                d.B, d.K);
     }
 }
 
@@ -486,8 +518,8 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
 #define EINET_LAUNCH(N, P)                                                                                           \
     hipLaunchKernelGGL((k_tail_backward<N, P>), dim3(blocks), dim3(1024), lds, s, n_leaf_blocks,                      \
                        max_children > 0 ? max_children : 1, t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, n_lv, x, \
-                       mask, mask_mode, G, stats, phi_off, den_off, tot_off, t.mix_node, t.mix_kout, t.mix_cptr,      \
-                       t.mix_child, t.mix_voff, params, A, Off, t.leaf_sptr, t.leaf_var, chunks_per_leaf, d)
+                       mask, mask_mode, G, stats, phi_off, den_off, tot_off, t.mix_rec, t.mix_cptr, t.mix_child,      \
+                       params, A, Off, t.leaf_sptr, t.leaf_var, chunks_per_leaf, d)
     if (nch == 0 && ppt == 4) EINET_LAUNCH(0, 4);
     else if (nch == 0) EINET_LAUNCH(0, 1);
     else if (nch == 4) EINET_LAUNCH(4, 1);
