@@ -304,7 +304,7 @@ struct LsmLayout {
 };
 
 template <bool SQ, int NCT>
-__global__ __launch_bounds__(256) void k_leaf_stats_mfma(
+__global__ __launch_bounds__(256, NCT == 2 ? 3 : 2) void k_leaf_stats_mfma(
     const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica, const int32_t* __restrict__ leaf_sptr,
     const int32_t* __restrict__ leaf_var, const float* __restrict__ x, const float* __restrict__ G,
     float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, int chunks_per_leaf, Dims d) {
