@@ -647,8 +647,9 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
         const bool multi = max_scope > leaf_chunk_vars(max_scope, d.C), masked = mask_mode != EINET_MASK_NONE;
         dim3 grid(n_leaves, (d.B + LEAF_RED - 1) / LEAF_RED);
         if (!multi) {
-            // up to two workgroups per compute unit fit whatever their registers: the kernel with the batched loads
-            if ((size_t)grid.x * grid.y <= 512)
+            // the kernel with the batched loads needs 122 registers, one workgroup of 1024 threads per compute unit: it
+            // serves launches of one round; beyond that the 64-register form, two workgroups per compute unit
+            if ((size_t)grid.x * grid.y <= EINET_NUM_CUS)
                 hipLaunchKernelGGL(k_leaf_forward_wide1, grid, dim3(1024), leaf_wide1_lds_bytes(max_scope, d.C, d.K), s,
                                    t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, x, mask, mask_mode, theta,
                                    t.leaf_logc, A, Off, max_scope, d);
