@@ -41,7 +41,7 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 template <int KQ>
-__global__ __launch_bounds__(512, 4) void k_einsum_forward(const int32_t* __restrict__ e_left,
+__global__ __launch_bounds__(512, KQ >= 14 ? 2 : 4) void k_einsum_forward(const int32_t* __restrict__ e_left,
                                                         const int32_t* __restrict__ e_right,
                                                         const int32_t* __restrict__ e_out,
                                                         const int32_t* __restrict__ e_kout,
