@@ -1,6 +1,7 @@
 // Leaf layer (Sec. 3.4): constants derived from the expectation parameters, log-densities of the leaves.
 #include "device_common.hpp"
 
+#include <mutex>
 #include <type_traits>
 
 namespace einet_impl {
@@ -377,6 +378,274 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
     }
 }
 
+// Leaves of several chunks whose entries have two or three constants (Gaussian, Bernoulli, binomial): the same
+// decomposition as above (a workgroup per leaf and LL_BS samples, thread (k, part), values staged chunk by chunk),
+// arranged so that no wave waits for memory in front of its arithmetic.  The last of the sixteen waves does nothing
+// but stage: while the others work on chunk c it gathers the values of chunk c+1 into the other half of a double
+// buffer and the rows of the constants' table for chunk c+2 (every lane owns the same LL_SLOTS pairs of every
+// chunk, so its divisions are done once and what it needs of the next chunk stays in its registers).  The other
+// waves take LL_U pairs per round with the constants of the next round, also across the end of a chunk, requested
+// before the arithmetic of this one; values are pair-major in LDS and read sixteen bytes at a time; the row of a
+// pair comes from LDS, so there is no division in the loop.  One barrier per chunk.
+constexpr int LL_BS = 8;                  // samples per workgroup
+constexpr int LL_U = 8;                   // pairs per round (half as many for the families with count terms)
+constexpr int LL_COMPUTE = 960;           // threads of the fifteen waves that do arithmetic
+constexpr int LL_SLOTS = LEAF_CHUNK / 64; // pairs of a chunk per lane of the staging wave
+static_assert(LEAF_CHUNK % 64 == 0 && LL_BS == 8, "a lane stages whole pairs, two 16-byte stores each");
+
+// bytes of LDS: finished entries (float64), partial sums of the parts, two buffers of values, (two of observation
+// flags), three of rows
+__host__ __device__ inline size_t leaf_long_lds_bytes(int max_scope, int C, int K, bool masked) {
+    const size_t chp = (size_t)leaf_chunk_vars(max_scope, C) * C;
+    return sizeof(double) * ((size_t)LL_BS * K) +
+           sizeof(float) * ((size_t)(LL_COMPUTE / K) * LL_BS * K + (masked ? 4 : 2) * chp * LL_BS + 3 * chp);
+}
+
+// constants of an entry with which every term is zero (never written): what a pair beyond its chunk reads
+__device__ float leaf_zero_consts[3 * 64];
+
+template <bool MASKED, bool GAUSS>
+__global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __restrict__ leaf_node,
+                                                            const int32_t* __restrict__ leaf_replica,
+                                                            const int32_t* __restrict__ leaf_sptr,
+                                                            const int32_t* __restrict__ leaf_var,
+                                                            const float* __restrict__ x,
+                                                            const uint8_t* __restrict__ mask, int mask_mode,
+                                                            const float* __restrict__ theta,
+                                                            const int32_t* __restrict__ logc, float* __restrict__ A,
+                                                            double* __restrict__ Off, int max_scope, Dims d) {
+    extern __shared__ double lds_d[];
+    constexpr int U = GAUSS ? LL_U : LL_U / 2;               // pairs per round
+    const int leaf = blockIdx.x, b0 = blockIdx.y * LL_BS, tid = threadIdx.x;
+    const int nbs = min(LL_BS, d.B - b0);
+    const int r = leaf_replica[leaf];
+    const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0;
+    const int nparts = LL_COMPUTE / d.K;
+    const int vch = leaf_chunk_vars(max_scope, d.C), chp = vch * d.C;   // variables, pairs of a full chunk
+    const int nchunks = (nv + vch - 1) / vch;
+    double* val = lds_d;                                       // [LL_BS][K] finished entries
+    float* red = reinterpret_cast<float*>(val + LL_BS * d.K);  // partial sums of the parts
+    double* redd = reinterpret_cast<double*>(red);             // the same memory as [nparts][LL_BS/2][K] float64
+    float* xs = red + (size_t)nparts * LL_BS * d.K;            // [2][chp][LL_BS] values
+    float* ob = xs + (size_t)2 * chp * LL_BS;                  // [2][chp][LL_BS] 1 = observed (MASKED)
+    int* rows = reinterpret_cast<int*>(ob + (MASKED ? (size_t)2 * chp * LL_BS : 0));   // [3][chp] variable * C + channel
+    const int k = tid % d.K, part = tid / d.K;
+    const bool stager = tid >= LL_COMPUTE, comp = !stager && part < nparts;
+    const bool base = !GAUSS && d.family == EINET_LEAF_BINOMIAL && k == 0;   // also sums the binomial coefficients
+    auto pairs_of = [&](int c) { return min(vch, nv - c * vch) * d.C; };
+
+    double acc[LL_BS], hacc[LL_BS];
+#pragma unroll
+    for (int b = 0; b < LL_BS; ++b) acc[b] = hacc[b] = 0.0;
+    // The two roles are two separate pieces of code, so that neither holds the other's registers; each passes the
+    // same barriers, one before the first chunk and one after every chunk.  Loads are never conditional: an index
+    // that does not exist is replaced by one that does and the value is dropped, which keeps every load a single
+    // instruction with nothing to wait for in front of it.
+    if (stager) {
+        const int sl = tid - LL_COMPUTE;
+        int vj[LL_SLOTS], cj[LL_SLOTS];                        // variable (within a chunk) and channel of lane's pairs
+        unsigned row[LL_SLOTS], var[LL_SLOTS];                 // of the chunk whose values are staged next
+#pragma unroll
+        for (int j = 0; j < LL_SLOTS; ++j) {
+            vj[j] = (sl + 64 * j) / d.C;
+            cj[j] = sl + 64 * j - vj[j] * d.C;
+        }
+        const float* xrow[LL_BS];                              // the samples' rows of x (the last one repeated)
+        const uint8_t* mrow[LL_BS];
+#pragma unroll
+        for (int b = 0; b < LL_BS; ++b) {
+            const size_t bb = (size_t)(b0 + min(b, nbs - 1));
+            xrow[b] = x + bb * d.D * d.C;
+            mrow[b] = MASKED ? (mask_mode == EINET_MASK_SHARED ? mask : mask + bb * d.D) : nullptr;
+        }
+        auto stage_rows = [&](int c) {
+            const int np = pairs_of(c);
+            const int32_t* lv = leaf_var + s0 + c * vch;
+#pragma unroll
+            for (int j = 0; j < LL_SLOTS; ++j) var[j] = (unsigned)lv[sl + 64 * j < np ? vj[j] : 0];
+#pragma unroll
+            for (int j = 0; j < LL_SLOTS; ++j) {
+                row[j] = var[j] * d.C + cj[j];
+                if (sl + 64 * j < np) rows[(c % 3) * chp + sl + 64 * j] = (int)row[j];
+                else row[j] = var[j] * d.C;                    // (a pair that exists; its values are not stored)
+            }
+        };
+        auto stage_values = [&](int c) {
+            const int np = pairs_of(c);
+            float* xb = xs + (size_t)(c & 1) * chp * LL_BS;
+            float xv[LL_SLOTS][LL_BS];
+#pragma unroll
+            for (int j = 0; j < LL_SLOTS; ++j)
+#pragma unroll
+                for (int b = 0; b < LL_BS; ++b) xv[j][b] = xrow[b][row[j]];
+#pragma unroll
+            for (int j = 0; j < LL_SLOTS; ++j)
+                if (sl + 64 * j < np) {
+                    float4* dst = reinterpret_cast<float4*>(xb + (size_t)(sl + 64 * j) * LL_BS);
+                    dst[0] = make_float4(xv[j][0], xv[j][1], xv[j][2], xv[j][3]);
+                    dst[1] = make_float4(xv[j][4], xv[j][5], xv[j][6], xv[j][7]);
+                }
+            if constexpr (MASKED) {
+                float* obb = ob + (size_t)(c & 1) * chp * LL_BS;
+                uint8_t mv[LL_SLOTS][LL_BS];
+#pragma unroll
+                for (int j = 0; j < LL_SLOTS; ++j)
+#pragma unroll
+                    for (int b = 0; b < LL_BS; ++b) mv[j][b] = mrow[b][var[j]];
+#pragma unroll
+                for (int j = 0; j < LL_SLOTS; ++j)
+                    if (sl + 64 * j < np) {
+                        float o[LL_BS];
+#pragma unroll
+                        for (int b = 0; b < LL_BS; ++b) o[b] = mv[j][b] ? 1.f : 0.f;
+                        float4* dst = reinterpret_cast<float4*>(obb + (size_t)(sl + 64 * j) * LL_BS);
+                        dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+                        dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+                    }
+            }
+        };
+        stage_rows(0);
+        stage_values(0);
+        if (nchunks > 1) stage_rows(1);
+        __syncthreads();
+        for (int c = 0; c < nchunks; ++c) {
+            if (c + 1 < nchunks) stage_values(c + 1);          // (with the rows of chunk c+1, still in registers)
+            if (c + 2 < nchunks) stage_rows(c + 2);
+            __syncthreads();
+        }
+    } else {
+        const int rpc = (chp + nparts * U - 1) / (nparts * U);   // rounds per chunk
+        const unsigned tstride = (unsigned)(d.TD * d.K);         // (the launcher checks that the table has < 2^30 floats)
+        // the constants of round rr of chunk c; a pair beyond the chunk reads zeros, with which its terms are zero
+        // (no load is conditional and nothing is done to the values here, so nothing waits for them before their use)
+        auto request = [&](int c, int rr, float (&t0)[U], float (&t1)[U], float (&t2)[U]) {
+            const int np = pairs_of(c);
+            const int* rw = rows + (c % 3) * chp;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int p = part + (rr * U + u) * nparts;
+                const bool in = p < np;
+                const unsigned e = ((unsigned)rw[in ? p : 0] * d.R + r) * tstride + k;
+                const float* th = in ? theta + e : leaf_zero_consts + k;
+                t0[u] = th[0];
+                t1[u] = th[d.K];
+                if constexpr (GAUSS) t2[u] = th[2 * d.K];
+            }
+        };
+        auto compute = [&](int c, int rr, const float (&t0)[U], const float (&t1)[U], const float (&t2)[U]) {
+            const int np = pairs_of(c);
+            const float* xb = xs + (size_t)(c & 1) * chp * LL_BS;
+            const float* obb = ob + (size_t)(c & 1) * chp * LL_BS;
+            const float nf = (float)d.P;
+            float t[LL_BS];
+#pragma unroll
+            for (int b = 0; b < LL_BS; ++b) t[b] = 0.f;
+            float csum = 0.f;                                    // Gaussian, nothing marginalised: the terms' constants
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int p = part + (rr * U + u) * nparts;
+                const bool in = p < np;
+                const int pc = in ? p : 0;                       // (a pair that exists: finite values)
+                const float4 xa = *reinterpret_cast<const float4*>(xb + (size_t)pc * LL_BS);
+                const float4 xc = *reinterpret_cast<const float4*>(xb + (size_t)pc * LL_BS + 4);
+                const float xv[LL_BS] = {xa.x, xa.y, xa.z, xa.w, xc.x, xc.y, xc.z, xc.w};
+                float ov[LL_BS];
+                if constexpr (MASKED) {
+                    const float4 oa = *reinterpret_cast<const float4*>(obb + (size_t)pc * LL_BS);
+                    const float4 oc = *reinterpret_cast<const float4*>(obb + (size_t)pc * LL_BS + 4);
+                    ov[0] = oa.x; ov[1] = oa.y; ov[2] = oa.z; ov[3] = oa.w;
+                    ov[4] = oc.x; ov[5] = oc.y; ov[6] = oc.z; ov[7] = oc.w;
+                }
+                if constexpr (GAUSS && !MASKED) csum += t2[u];
+#pragma unroll
+                for (int b = 0; b < LL_BS; ++b) {
+                    if constexpr (GAUSS && !MASKED) {
+                        const float diff = xv[b] - t0[u];
+                        t[b] = fmaf(t1[u] * diff, diff, t[b]);
+                    } else if constexpr (GAUSS) {
+                        const float diff = xv[b] - t0[u];
+                        t[b] += observed_term(ov[b], fmaf(t1[u] * diff, diff, t2[u]));
+                    } else {
+                        const float term = count_term(xv[b], t0[u], t1[u], nf);
+                        t[b] += MASKED ? observed_term(ov[b], term) : term;
+                    }
+                }
+                if constexpr (!GAUSS)
+                    if (base && in) {                            // (one thread in K: straight to float64)
+#pragma unroll
+                        for (int b = 0; b < LL_BS; ++b) {
+                            const float hb = leaf_base(logc, xv[b], d.P);
+                            hacc[b] += (double)(MASKED ? ov[b] * hb : hb);
+                        }
+                    }
+            }
+#pragma unroll
+            for (int b = 0; b < LL_BS; ++b) acc[b] += (double)(t[b] + csum);
+        };
+        // Two sets of constants, used in turn; the loop is written out for two rounds so that each set keeps its
+        // registers.  (c, rr) is the round at hand, (cn, rn) the one after it; a chunk's last round ends at the barrier.
+        float a0[U], a1[U], a2[U], e0[U], e1[U], e2[U];
+        __syncthreads();
+        if (comp) request(0, 0, a0, a1, a2);
+        int c = 0, rr = 0;
+        while (c < nchunks) {
+            int rn = rr + 1 == rpc ? 0 : rr + 1, cn = rn == 0 ? c + 1 : c;
+            if (comp) {
+                if (cn < nchunks) request(cn, rn, e0, e1, e2);
+                compute(c, rr, a0, a1, a2);
+            }
+            if (cn != c) __syncthreads();
+            c = cn, rr = rn;
+            if (c >= nchunks) break;
+            rn = rr + 1 == rpc ? 0 : rr + 1, cn = rn == 0 ? c + 1 : c;
+            if (comp) {
+                if (cn < nchunks) request(cn, rn, a0, a1, a2);
+                compute(c, rr, e0, e1, e2);
+            }
+            if (cn != c) __syncthreads();
+            c = cn, rr = rn;
+        }
+    }
+
+    // ---- the parts meet: float64 partial sums, half of the samples at a time (the same LDS bytes)
+    const bool fin = tid < LL_BS * d.K;
+    const int fb = fin ? tid / d.K : 0, kk = tid - fb * d.K;
+    const int nact = min(nparts, min(nv, vch) * d.C);             // parts beyond the pairs of a chunk hold zeros
+    double sum = 0.0, h = 0.0;
+    constexpr int HB = LL_BS / 2;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        if (half) __syncthreads();                                // the previous half has been read
+        if (comp) {
+#pragma unroll
+            for (int b = 0; b < HB; ++b) redd[(part * HB + b) * d.K + k] = acc[half * HB + b];
+        }
+        __syncthreads();
+        if (fin && fb / HB == half)
+            for (int qq = 0; qq < nact; ++qq) sum += redd[(qq * HB + (fb - half * HB)) * d.K + kk];
+        if (!GAUSS && d.family == EINET_LEAF_BINOMIAL) {
+            __syncthreads();
+            if (base && comp) {
+#pragma unroll
+                for (int b = 0; b < HB; ++b) redd[(part * HB + b) * d.K] = hacc[half * HB + b];
+            }
+            __syncthreads();
+            if (fin && kk == 0 && fb / HB == half)
+                for (int qq = 0; qq < nact; ++qq) h += redd[(qq * HB + (fb - half * HB)) * d.K];
+        }
+    }
+    if (fin) val[fb * d.K + kk] = sum;
+    __syncthreads();
+    if (fin && fb < nbs) {
+        double m = -INFINITY;
+        for (int qq = 0; qq < d.K; ++qq) m = fmax(m, val[fb * d.K + qq]);
+        if (m == -INFINITY) m = 0.0;
+        const size_t rowo = (size_t)leaf_node[leaf] * d.B + b0 + fb;
+        A[rowo * d.K + kk] = (float)(sum - m);
+        if (kk == 0) Off[rowo] = m + h;
+    }
+}
+
 // The same for leaves whose scope fits one chunk (the image cells of the benchmark configurations): one
 // staging step, float32 sums per part (a part sums only a handful of terms), float64 across the parts.  A
 // workgroup of 1024 threads takes one leaf and LEAF_RED samples.  The samples' values are staged in LDS with coalesced reads of x; thread
@@ -658,6 +927,27 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
                                    leaf_wide1_lds_bytes(max_scope, d.C, d.K), s, t.leaf_node, t.leaf_replica,
                                    t.leaf_sptr, t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off, max_scope,
                                    d);
+            return;
+        }
+        if (d.family != EINET_LEAF_CATEGORICAL && (int64_t)d.D * d.C * d.R * d.TD * d.K < (int64_t(1) << 30)) {
+            // two or three constants per entry: the kernel with a staging wave and constants requested a round ahead
+            static std::once_flag attr_set[EINET_MAX_DEVICES];
+            int dev = 0;
+            (void)hipGetDevice(&dev);
+            std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] {
+                allow_dynamic_lds(&k_leaf_forward_long<false, false>, 160 * 1024);
+                allow_dynamic_lds(&k_leaf_forward_long<false, true>, 160 * 1024);
+                allow_dynamic_lds(&k_leaf_forward_long<true, false>, 160 * 1024);
+                allow_dynamic_lds(&k_leaf_forward_long<true, true>, 160 * 1024);
+            });
+            const size_t ll = leaf_long_lds_bytes(max_scope, d.C, d.K, masked);
+            const bool gauss = d.family == EINET_LEAF_GAUSSIAN;
+#define EINET_LONG(M, G)                                                                                              \
+    hipLaunchKernelGGL((k_leaf_forward_long<M, G>), grid, dim3(1024), ll, s, t.leaf_node, t.leaf_replica, t.leaf_sptr, \
+                       t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off, max_scope, d)
+            if (masked) { if (gauss) EINET_LONG(true, true); else EINET_LONG(true, false); }
+            else { if (gauss) EINET_LONG(false, true); else EINET_LONG(false, false); }
+#undef EINET_LONG
             return;
         }
         const size_t lds = leaf_wide_lds_bytes(max_scope, d.C, d.K, LEAF_RED);
