@@ -380,28 +380,47 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_wide(const int32_t* __res
 
 // Leaves of several chunks whose entries have two or three constants (Gaussian, Bernoulli, binomial): the same
 // decomposition as above (a workgroup per leaf and LL_BS samples, thread (k, part), values staged chunk by chunk),
-// arranged so that no wave waits for memory in front of its arithmetic.  The last of the sixteen waves does nothing
-// but stage: while the others work on chunk c it gathers the values of chunk c+1 into the other half of a double
-// buffer and the rows of the constants' table for chunk c+2 (every lane owns the same LL_SLOTS pairs of every
-// chunk, so its divisions are done once and what it needs of the next chunk stays in its registers).  The other
-// waves take LL_U pairs per round with the constants of the next round, also across the end of a chunk, requested
-// before the arithmetic of this one; values are pair-major in LDS and read sixteen bytes at a time; the row of a
-// pair comes from LDS, so there is no division in the loop.  One barrier per chunk.
+// arranged so that no wave waits for memory in front of its arithmetic and the arithmetic waves issue little
+// besides it.  The last of the sixteen waves does nothing but stage: while the others work on chunk c it gathers
+// the values of chunk c+1 into the other half of a double buffer and, for chunk c+2, where each pair's constants
+// are (every lane owns the same LL_SLOTS pairs of every chunk, so its divisions are done once and
+// what it needs of the next chunk stays in its registers).  The other waves take U pairs per round with the
+// constants of the next round, also across the end of a chunk, requested before the arithmetic of this one; values
+// are pair-major in LDS and read sixteen bytes at a time.  A round may reach beyond the pairs of its chunk: such a
+// slot is sent to an entry of zeros, with which every term is zero whatever finite value the slot holds, so the loop
+// has no bounds check, no division and no conditional load.  One barrier per chunk.
 constexpr int LL_BS = 8;                  // samples per workgroup
 constexpr int LL_U = 8;                   // pairs per round (half as many for the families with count terms)
 constexpr int LL_COMPUTE = 960;           // threads of the fifteen waves that do arithmetic
 constexpr int LL_SLOTS = LEAF_CHUNK / 64; // pairs of a chunk per lane of the staging wave
 static_assert(LEAF_CHUNK % 64 == 0 && LL_BS == 8, "a lane stages whole pairs, two 16-byte stores each");
 
+// How a workgroup divides a chunk: parts (threads with the same k are `parts` pairs apart), rounds per chunk and
+// the slots the rounds of a chunk reach (at least the pairs of a full chunk).
+struct LeafLongShape {
+    int vch, chp, parts, rpc, cap;
+};
+__host__ __device__ inline LeafLongShape leaf_long_shape(int max_scope, int C, int K, bool gauss) {
+    const int U = gauss ? LL_U : LL_U / 2;
+    LeafLongShape s;
+    s.vch = leaf_chunk_vars(max_scope, C);
+    s.chp = s.vch * C;
+    const int fit = LL_COMPUTE / K, need = (s.chp + U - 1) / U;   // more parts than pairs per round would idle
+    s.parts = fit < need ? fit : need;
+    s.rpc = (s.chp + s.parts * U - 1) / (s.parts * U);
+    s.cap = s.rpc * U * s.parts;
+    return s;
+}
 // bytes of LDS: finished entries (float64), partial sums of the parts, two buffers of values, (two of observation
-// flags), three of rows
-__host__ __device__ inline size_t leaf_long_lds_bytes(int max_scope, int C, int K, bool masked) {
-    const size_t chp = (size_t)leaf_chunk_vars(max_scope, C) * C;
+// flags), three of offsets into the table of constants
+__host__ __device__ inline size_t leaf_long_lds_bytes(int max_scope, int C, int K, bool masked, bool gauss) {
+    const LeafLongShape s = leaf_long_shape(max_scope, C, K, gauss);
     return sizeof(double) * ((size_t)LL_BS * K) +
-           sizeof(float) * ((size_t)(LL_COMPUTE / K) * LL_BS * K + (masked ? 4 : 2) * chp * LL_BS + 3 * chp);
+           sizeof(float) * ((size_t)s.parts * LL_BS * K + (masked ? 4 : 2) * (size_t)s.cap * LL_BS) +
+           sizeof(long long) * 3 * (size_t)s.cap;
 }
 
-// constants of an entry with which every term is zero (never written): what a pair beyond its chunk reads
+// constants of an entry with which every term is zero (never written): what a slot beyond its chunk reads
 __device__ float leaf_zero_consts[3 * 64];
 
 template <bool MASKED, bool GAUSS>
@@ -415,32 +434,38 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
                                                             const int32_t* __restrict__ logc, float* __restrict__ A,
                                                             double* __restrict__ Off, int max_scope, Dims d) {
     extern __shared__ double lds_d[];
-    constexpr int U = GAUSS ? LL_U : LL_U / 2;               // pairs per round
+    constexpr int U = GAUSS ? LL_U : LL_U / 2;                 // pairs per round
     const int leaf = blockIdx.x, b0 = blockIdx.y * LL_BS, tid = threadIdx.x;
     const int nbs = min(LL_BS, d.B - b0);
     const int r = leaf_replica[leaf];
     const int s0 = leaf_sptr[leaf], nv = leaf_sptr[leaf + 1] - s0;
-    const int nparts = LL_COMPUTE / d.K;
-    const int vch = leaf_chunk_vars(max_scope, d.C), chp = vch * d.C;   // variables, pairs of a full chunk
+    const LeafLongShape sh = leaf_long_shape(max_scope, d.C, d.K, GAUSS);
+    const int nparts = sh.parts, vch = sh.vch, chp = sh.chp, rpc = sh.rpc, cap = sh.cap;
     const int nchunks = (nv + vch - 1) / vch;
     double* val = lds_d;                                       // [LL_BS][K] finished entries
     float* red = reinterpret_cast<float*>(val + LL_BS * d.K);  // partial sums of the parts
     double* redd = reinterpret_cast<double*>(red);             // the same memory as [nparts][LL_BS/2][K] float64
-    float* xs = red + (size_t)nparts * LL_BS * d.K;            // [2][chp][LL_BS] values
-    float* ob = xs + (size_t)2 * chp * LL_BS;                  // [2][chp][LL_BS] 1 = observed (MASKED)
-    int* rows = reinterpret_cast<int*>(ob + (MASKED ? (size_t)2 * chp * LL_BS : 0));   // [3][chp] variable * C + channel
+    float* xs = red + (size_t)nparts * LL_BS * d.K;            // [2][cap][LL_BS] values
+    float* ob = xs + (size_t)2 * cap * LL_BS;                  // [2][cap][LL_BS] 1 = observed (MASKED)
+    // [3][cap] where a pair's constants are, in bytes from the table's start (as offsets from a kernel argument the
+    // loads stay loads from global memory; a pointer read from LDS would make them loads from any address space)
+    long long* ptrs = reinterpret_cast<long long*>(ob + (MASKED ? (size_t)2 * cap * LL_BS : 0));
+    const long long zeros_at = reinterpret_cast<const char*>(leaf_zero_consts) - reinterpret_cast<const char*>(theta);
     const int k = tid % d.K, part = tid / d.K;
     const bool stager = tid >= LL_COMPUTE, comp = !stager && part < nparts;
     const bool base = !GAUSS && d.family == EINET_LEAF_BINOMIAL && k == 0;   // also sums the binomial coefficients
     auto pairs_of = [&](int c) { return min(vch, nv - c * vch) * d.C; };
-
     double acc[LL_BS], hacc[LL_BS];
 #pragma unroll
     for (int b = 0; b < LL_BS; ++b) acc[b] = hacc[b] = 0.0;
+    // every slot starts with finite values and is sent to the zeros
+    for (int i = tid; i < 2 * cap * LL_BS; i += 1024) xs[i] = 0.f;
+    for (int i = tid; i < 3 * cap; i += 1024) ptrs[i] = zeros_at;
+    __syncthreads();
     // The two roles are two separate pieces of code, so that neither holds the other's registers; each passes the
-    // same barriers, one before the first chunk and one after every chunk.  Loads are never conditional: an index
-    // that does not exist is replaced by one that does and the value is dropped, which keeps every load a single
-    // instruction with nothing to wait for in front of it.
+    // same barriers, one before the first chunk and one after every chunk.  The stager's loads are never
+    // conditional: an index that does not exist is replaced by one that does and the value is dropped, which keeps
+    // every load a single instruction with nothing to wait for in front of it.
     if (stager) {
         const int sl = tid - LL_COMPUTE;
         int vj[LL_SLOTS], cj[LL_SLOTS];                        // variable (within a chunk) and channel of lane's pairs
@@ -458,6 +483,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
             xrow[b] = x + bb * d.D * d.C;
             mrow[b] = MASKED ? (mask_mode == EINET_MASK_SHARED ? mask : mask + bb * d.D) : nullptr;
         }
+        const size_t tstride = (size_t)d.TD * d.K;
         auto stage_rows = [&](int c) {
             const int np = pairs_of(c);
             const int32_t* lv = leaf_var + s0 + c * vch;
@@ -465,14 +491,16 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
             for (int j = 0; j < LL_SLOTS; ++j) var[j] = (unsigned)lv[sl + 64 * j < np ? vj[j] : 0];
 #pragma unroll
             for (int j = 0; j < LL_SLOTS; ++j) {
-                row[j] = var[j] * d.C + cj[j];
-                if (sl + 64 * j < np) rows[(c % 3) * chp + sl + 64 * j] = (int)row[j];
-                else row[j] = var[j] * d.C;                    // (a pair that exists; its values are not stored)
+                const bool in = sl + 64 * j < np;
+                row[j] = var[j] * d.C + (in ? cj[j] : 0);      // (always a pair that exists)
+                if (sl + 64 * j < chp)
+                    ptrs[(c % 3) * cap + sl + 64 * j] =
+                        in ? (long long)(sizeof(float) * ((size_t)row[j] * d.R + r) * tstride) : zeros_at;
             }
         };
         auto stage_values = [&](int c) {
             const int np = pairs_of(c);
-            float* xb = xs + (size_t)(c & 1) * chp * LL_BS;
+            float* xb = xs + (size_t)(c & 1) * cap * LL_BS;
             float xv[LL_SLOTS][LL_BS];
 #pragma unroll
             for (int j = 0; j < LL_SLOTS; ++j)
@@ -486,7 +514,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
                     dst[1] = make_float4(xv[j][4], xv[j][5], xv[j][6], xv[j][7]);
                 }
             if constexpr (MASKED) {
-                float* obb = ob + (size_t)(c & 1) * chp * LL_BS;
+                float* obb = ob + (size_t)(c & 1) * cap * LL_BS;
                 uint8_t mv[LL_SLOTS][LL_BS];
 #pragma unroll
                 for (int j = 0; j < LL_SLOTS; ++j)
@@ -514,19 +542,12 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
             __syncthreads();
         }
     } else {
-        const int rpc = (chp + nparts * U - 1) / (nparts * U);   // rounds per chunk
-        const unsigned tstride = (unsigned)(d.TD * d.K);         // (the launcher checks that the table has < 2^30 floats)
-        // the constants of round rr of chunk c; a pair beyond the chunk reads zeros, with which its terms are zero
-        // (no load is conditional and nothing is done to the values here, so nothing waits for them before their use)
+        // the constants of round rr of chunk c (nothing is done to the values here, so nothing waits for them)
         auto request = [&](int c, int rr, float (&t0)[U], float (&t1)[U], float (&t2)[U]) {
-            const int np = pairs_of(c);
-            const int* rw = rows + (c % 3) * chp;
+            const long long* pt = ptrs + (size_t)(c % 3) * cap + rr * U * nparts + part;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int p = part + (rr * U + u) * nparts;
-                const bool in = p < np;
-                const unsigned e = ((unsigned)rw[in ? p : 0] * d.R + r) * tstride + k;
-                const float* th = in ? theta + e : leaf_zero_consts + k;
+                const float* th = reinterpret_cast<const float*>(reinterpret_cast<const char*>(theta) + pt[u * nparts]) + k;
                 t0[u] = th[0];
                 t1[u] = th[d.K];
                 if constexpr (GAUSS) t2[u] = th[2 * d.K];
@@ -534,8 +555,8 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
         };
         auto compute = [&](int c, int rr, const float (&t0)[U], const float (&t1)[U], const float (&t2)[U]) {
             const int np = pairs_of(c);
-            const float* xb = xs + (size_t)(c & 1) * chp * LL_BS;
-            const float* obb = ob + (size_t)(c & 1) * chp * LL_BS;
+            const float* xb = xs + ((size_t)(c & 1) * cap + rr * U * nparts + part) * LL_BS;
+            const float* obb = ob + ((size_t)(c & 1) * cap + rr * U * nparts + part) * LL_BS;
             const float nf = (float)d.P;
             float t[LL_BS];
 #pragma unroll
@@ -543,16 +564,13 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
             float csum = 0.f;                                    // Gaussian, nothing marginalised: the terms' constants
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int p = part + (rr * U + u) * nparts;
-                const bool in = p < np;
-                const int pc = in ? p : 0;                       // (a pair that exists: finite values)
-                const float4 xa = *reinterpret_cast<const float4*>(xb + (size_t)pc * LL_BS);
-                const float4 xc = *reinterpret_cast<const float4*>(xb + (size_t)pc * LL_BS + 4);
+                const float4 xa = *reinterpret_cast<const float4*>(xb + (size_t)u * nparts * LL_BS);
+                const float4 xc = *reinterpret_cast<const float4*>(xb + (size_t)u * nparts * LL_BS + 4);
                 const float xv[LL_BS] = {xa.x, xa.y, xa.z, xa.w, xc.x, xc.y, xc.z, xc.w};
                 float ov[LL_BS];
                 if constexpr (MASKED) {
-                    const float4 oa = *reinterpret_cast<const float4*>(obb + (size_t)pc * LL_BS);
-                    const float4 oc = *reinterpret_cast<const float4*>(obb + (size_t)pc * LL_BS + 4);
+                    const float4 oa = *reinterpret_cast<const float4*>(obb + (size_t)u * nparts * LL_BS);
+                    const float4 oc = *reinterpret_cast<const float4*>(obb + (size_t)u * nparts * LL_BS + 4);
                     ov[0] = oa.x; ov[1] = oa.y; ov[2] = oa.z; ov[3] = oa.w;
                     ov[4] = oc.x; ov[5] = oc.y; ov[6] = oc.z; ov[7] = oc.w;
                 }
@@ -571,7 +589,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
                     }
                 }
                 if constexpr (!GAUSS)
-                    if (base && in) {                            // (one thread in K: straight to float64)
+                    if (base && part + (rr * U + u) * nparts < np) {     // (one thread in K: straight to float64)
 #pragma unroll
                         for (int b = 0; b < LL_BS; ++b) {
                             const float hb = leaf_base(logc, xv[b], d.P);
@@ -584,6 +602,9 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
         };
         // Two sets of constants, used in turn; the loop is written out for two rounds so that each set keeps its
         // registers.  (c, rr) is the round at hand, (cn, rn) the one after it; a chunk's last round ends at the barrier.
+        // The request is not conditional: with a branch around it the compiler must assume at every use of the set
+        // at hand that no younger loads are in flight, and waits for the new ones too.  After the last round it
+        // re-reads what the offsets of an earlier chunk (or the zeros) name, and the values are dropped.
         float a0[U], a1[U], a2[U], e0[U], e1[U], e2[U];
         __syncthreads();
         if (comp) request(0, 0, a0, a1, a2);
@@ -591,7 +612,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
         while (c < nchunks) {
             int rn = rr + 1 == rpc ? 0 : rr + 1, cn = rn == 0 ? c + 1 : c;
             if (comp) {
-                if (cn < nchunks) request(cn, rn, e0, e1, e2);
+                request(cn, rn, e0, e1, e2);
                 compute(c, rr, a0, a1, a2);
             }
             if (cn != c) __syncthreads();
@@ -599,7 +620,7 @@ __global__ __launch_bounds__(1024) void k_leaf_forward_long(const int32_t* __res
             if (c >= nchunks) break;
             rn = rr + 1 == rpc ? 0 : rr + 1, cn = rn == 0 ? c + 1 : c;
             if (comp) {
-                if (cn < nchunks) request(cn, rn, a0, a1, a2);
+                request(cn, rn, a0, a1, a2);
                 compute(c, rr, e0, e1, e2);
             }
             if (cn != c) __syncthreads();
@@ -929,7 +950,8 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
                                    d);
             return;
         }
-        if (d.family != EINET_LEAF_CATEGORICAL && (int64_t)d.D * d.C * d.R * d.TD * d.K < (int64_t(1) << 30)) {
+        if (d.family != EINET_LEAF_CATEGORICAL &&
+            leaf_long_lds_bytes(max_scope, d.C, d.K, masked, d.family == EINET_LEAF_GAUSSIAN) <= 160 * 1024) {
             // two or three constants per entry: the kernel with a staging wave and constants requested a round ahead
             static std::once_flag attr_set[EINET_MAX_DEVICES];
             int dev = 0;
@@ -940,8 +962,8 @@ void launch_leaf_forward(const DevTables& t, int n_leaves, int max_scope, const 
                 allow_dynamic_lds(&k_leaf_forward_long<true, false>, 160 * 1024);
                 allow_dynamic_lds(&k_leaf_forward_long<true, true>, 160 * 1024);
             });
-            const size_t ll = leaf_long_lds_bytes(max_scope, d.C, d.K, masked);
             const bool gauss = d.family == EINET_LEAF_GAUSSIAN;
+            const size_t ll = leaf_long_lds_bytes(max_scope, d.C, d.K, masked, gauss);
 #define EINET_LONG(M, G)                                                                                              \
     hipLaunchKernelGGL((k_leaf_forward_long<M, G>), grid, dim3(1024), ll, s, t.leaf_node, t.leaf_replica, t.leaf_sptr, \
                        t.leaf_var, x, mask, mask_mode, theta, t.leaf_logc, A, Off, max_scope, d)
