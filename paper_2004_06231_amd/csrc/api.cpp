@@ -21,7 +21,8 @@ struct einet {
 
     // workspace layout (bytes from the start of the workspace)
     std::vector<int32_t> blob;      // all index tables, concatenated
-    size_t off_theta = 0, off_A = 0, off_Off = 0, off_amax = 0, off_G = 0, off_Gp = 0, ws_bytes = 0;
+    size_t off_theta = 0, off_A = 0, off_Off = 0, off_amax = 0, off_G = 0, off_Gp = 0, off_part = 0, ws_bytes = 0;
+    bool has_part = false;    // scratch for the statistics of virtual items (see bwd_virtual_items)
     struct TableOffsets {
 #define X(name) size_t name;
         EINET_TABLES(X)
@@ -263,6 +264,14 @@ int einet_create(const einet_spec* spec, einet_t** out) {
     off = align256(off + sizeof(float) * size_t(p.num_nodes) * mb * K);
     h->off_Gp = off;
     off = align256(off + sizeof(float) * gp_blocks_per_item(p.K) * p.ein_left.size() * mb * K);
+    for (int l = 0; l + 1 < p.num_layers; ++l)       // (the root's layer has a kernel of its own)
+        if (bwd_uses_split_kernel(p.K, p.ein_layer_full[l] != 0) &&
+            bwd_virtual_items(p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], p.K, (int)mb) > 1)
+            h->has_part = true;
+    if (h->has_part) {
+        h->off_part = off;
+        off = align256(off + sizeof(float) * bwd_partial_floats(p.K));
+    }
     h->ws_bytes = off;
     *out = h;
     return EINET_OK;
@@ -432,7 +441,8 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
         }
         run(h, KC_EINSUM_BWD, s, [&] {
             launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
-                                   p.ein_layer_full[l] != 0, !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp, d, s);
+                                   p.ein_layer_full[l] != 0, !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp,
+                                   h->has_part ? reinterpret_cast<float*>(h->ws + h->off_part) : nullptr, d, s);
         }, layer_outputs(p, l));
     }
     const int leaf_step = p.num_layers;

@@ -479,7 +479,8 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
     const int32_t* __restrict__ e_reg, const int32_t* __restrict__ e_woff, const int32_t* __restrict__ e_voff,
     const int32_t* __restrict__ e_vstr, const float* __restrict__ params, float* __restrict__ stats,
     const float* __restrict__ A, const double* __restrict__ Off, const float* __restrict__ amax,
-    const float* __restrict__ G, float* __restrict__ Gp, int item0, int count, int B) {
+    const float* __restrict__ G, float* __restrict__ Gp, int item0, int count, int B, int vper, int cpv,
+    float* __restrict__ part) {
     using LY = BwdSLayout<K8>;
     constexpr int K = LY::K, NS = LY::NS, ST = LY::ST, NB = 1 + NS;
     extern __shared__ float lds[];
@@ -489,28 +490,42 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
     float* sP = lds + LY::OFF_P;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nchunks = (B + 127) >> 7;
-    const long long P = (long long)count * NS;
+    // A layer of few items and several chunks is launched with every item as vper virtual items, each with cpv of the
+    // chunks: their statistics go to blocks of their own in `part` ([vper][count][K^3], summed into the statistics by
+    // the launch that follows), so that the chunks of an item run side by side.  vper = 1: the items as they are.
+    const long long P = (long long)count * vper * NS;
     const int g = xcd_contiguous_block();
     const int p0 = (int)((long long)g * P / gridDim.x), p1 = (int)((long long)(g + 1) * P / gridDim.x);
     if (p0 >= p1) return;
     const size_t blk = (size_t)B * K;
 
-    // position of a unit: item li, chunk, slice it; [s0, s1) are this workgroup's slices of the item
-    struct Pos { int li, chunk, it, s0, s1; };
+    // position of a unit: virtual item vi = item li with chunks [c0, c1), chunk, slice it; [s0, s1) are this
+    // workgroup's slices of the virtual item
+    struct Pos { int vi, li, c0, c1, chunk, it, s0, s1; };
     auto seg = [&](Pos& q) {
-        q.s0 = max(p0 - q.li * NS, 0);
-        q.s1 = min(p1 - q.li * NS, NS);
+        q.s0 = max(p0 - q.vi * NS, 0);
+        q.s1 = min(p1 - q.vi * NS, NS);
+        q.li = q.vi / vper;
+        q.c0 = (q.vi - q.li * vper) * cpv;
+        q.c1 = min(q.c0 + cpv, nchunks);
+        q.chunk = q.c0;
     };
     auto advance = [&](Pos& q) {          // -> false past the end
         if (++q.it < q.s1) return true;
-        if (++q.chunk < nchunks) { q.it = q.s0; return true; }
-        ++q.li; q.chunk = 0;
-        if (q.li * NS >= p1) return false;
+        if (++q.chunk < q.c1) { q.it = q.s0; return true; }
+        ++q.vi;
+        if (q.vi * NS >= p1) return false;
         seg(q); q.it = q.s0;
         return true;
     };
     Pos pos;
-    pos.li = p0 / NS; pos.chunk = 0; seg(pos); pos.it = pos.s0;
+    pos.vi = p0 / NS; seg(pos); pos.it = pos.s0;
+    // where the statistics of a unit's item are, and whether the unit adds to them
+    auto stat_base = [&](const Pos& q) -> float* {
+        return vper > 1 ? part + ((size_t)(q.vi - q.li * vper) * count + q.li) * ((size_t)K * K * K)
+                        : stats + (size_t)e_woff[q.li];
+    };
+    auto stat_adds = [&](const Pos& q) { return ACCUM || q.chunk > q.c0; };
 
     if (wave >= 4) {
         // ============================================================ producer waves
@@ -618,15 +633,15 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
                 for (int x = 0; x < LY::NPART / 4; ++x) {
                     int k, il, j;
                     shared_index(x, k, il, j);
-                    const size_t idx = wbase + ((size_t)k * K + 4 * q.it + il) * K + min(j, K - 1);
-                    wred[x] = params[idx];
-                    nred[x] = (ACCUM || q.chunk > 0) ? stats[idx] : 0.f;
+                    const size_t idx = ((size_t)k * K + 4 * q.it + il) * K + min(j, K - 1);
+                    wred[x] = params[wbase + idx];
+                    nred[x] = stat_adds(q) ? stat_base(q)[idx] : 0.f;
                 }
             }
         };
         auto reduce_shared = [&](const Pos& q) {
             if constexpr (LY::NPART > 0) {
-                float* Nw = stats + (size_t)e_woff[q.li];
+                float* Nw = stat_base(q);
 #pragma unroll
                 for (int x = 0; x < LY::NPART / 4; ++x) {
                     const int e = pt + 256 * x;
@@ -737,8 +752,8 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
 #pragma unroll
             for (int il = 0; il < 4; ++il) el4[il] = sL[(4 * pos.it + il) * ST + bl];
             const size_t wbase = (size_t)e_woff[pos.li];
-            float* Nw = stats + wbase;
-            const bool accum = ACCUM || pos.chunk > 0;
+            float* Nw = stat_base(pos);
+            const bool accum = stat_adds(pos);
 
             // ---- statistics GEMM: P[(k, il), j] = sum_b Q[b,k] eL[b, 4 it + il] eR[b,j] over the 128 staged samples
             const float* wcur = lds + (u & 1) * LY::SLICE;      // W of the slice, for Nw (+)= W * P
@@ -969,7 +984,7 @@ __global__ __launch_bounds__(512, 1) void k_einsum_backward_s(
             new_ops = !nvalid || npos.li != pos.li || npos.chunk != pos.chunk;
             if (new_ops) {
                 // the right child's share of this workgroup's slices of (item, chunk)
-                const int grp = g - bwds_wg_of_pair((long long)pos.li * NS, P, gridDim.x);
+                const int grp = g - bwds_wg_of_pair((long long)pos.vi * NS, P, gridDim.x);
                 if (bg < B) {
                     float* right = Gp + ((size_t)(item * NB + 1 + grp) * B + bg) * K + 4 * h;
 #pragma unroll
@@ -1032,10 +1047,23 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
 #undef EINET_LAUNCH
 }
 
+// stats[item][r] (+)= sum over the vper blocks of part[.][item][r]: the launch after a top-down launch with virtual items
+__global__ void k_sum_partial_stats(const int32_t* __restrict__ e_woff, const float* __restrict__ part,
+                                    float* __restrict__ stats, int count, int vper, int k3, int accumulate) {
+    const size_t n = (size_t)count * k3;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const int li = (int)(i / k3);
+        float* dst = stats + (size_t)e_woff[li] + (i - (size_t)li * k3);
+        float sum = accumulate ? *dst : 0.f;
+        for (int v = 0; v < vper; ++v) sum += part[(size_t)v * n + i];
+        *dst = sum;
+    }
+}
+
 template <int K8>
 static void launch_einsum_backward_k8(const DevTables& t, int first, int count, bool accumulate, const float* params,
                                       float* stats, const float* A, const double* Off, const float* amax,
-                                      const float* G, float* Gp, const Dims& d, hipStream_t s) {
+                                      const float* G, float* Gp, float* part, const Dims& d, hipStream_t s) {
     using LY = BwdSLayout<K8>;
     const size_t lds = sizeof(float) * LY::LDS_FLOATS;
     static std::once_flag attr_set[EINET_MAX_DEVICES];
@@ -1045,24 +1073,33 @@ static void launch_einsum_backward_k8(const DevTables& t, int first, int count, 
         allow_dynamic_lds(&k_einsum_backward_s<K8, true>, lds);
         allow_dynamic_lds(&k_einsum_backward_s<K8, false>, lds);
     });
-    const int grid = bwd_split_grid(count, d.K);
+    const int vper = part ? bwd_virtual_items(count, d.K, d.B) : 1;
+    const int nchunks = (d.B + 127) / 128, cpv = (nchunks + vper - 1) / vper;
+    const int grid = vper > 1 ? count * vper * (d.K / 4) : bwd_split_grid(count, d.K);
 #define EINET_LAUNCH(ACC)                                                                                         \
     hipLaunchKernelGGL((k_einsum_backward_s<K8, ACC>), dim3(grid), dim3(512), lds, s, t.ein_left + first,          \
                        t.ein_right + first, t.ein_out + first, t.ein_reg + first, t.ein_woff + first,             \
-                       t.ein_voff + first, t.ein_vstr + first, params, stats, A, Off, amax, G, Gp, first, count, d.B)
-    if (accumulate) EINET_LAUNCH(true);
+                       t.ein_voff + first, t.ein_vstr + first, params, stats, A, Off, amax, G, Gp, first, count, d.B, \
+                       vper, cpv, part)
+    if (vper > 1) {
+        // (the blocks are written, not added to; the sum that follows adds to the statistics or overwrites them)
+        EINET_LAUNCH(false);
+        const int k3 = d.K * d.K * d.K, n = count * k3;
+        hipLaunchKernelGGL(k_sum_partial_stats, dim3((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024), dim3(256), 0, s,
+                           t.ein_woff + first, part, stats, count, vper, k3, accumulate ? 1 : 0);
+    } else if (accumulate) EINET_LAUNCH(true);
     else EINET_LAUNCH(false);
 #undef EINET_LAUNCH
 }
 
 void launch_einsum_backward(const DevTables& t, int first, int count, bool full_k, bool accumulate,
                             const float* params, float* stats, const float* A, const double* Off, const float* amax,
-                            const float* G, float* Gp, const Dims& d, hipStream_t s) {
+                            const float* G, float* Gp, float* part, const Dims& d, hipStream_t s) {
     if (count == 0) return;
     if (bwd_uses_split_kernel(d.K, full_k)) {
         switch (d.K / 8) {
 #define EINET_CASE(J) \
-        case J: launch_einsum_backward_k8<J>(t, first, count, accumulate, params, stats, A, Off, amax, G, Gp, d, s); return;
+        case J: launch_einsum_backward_k8<J>(t, first, count, accumulate, params, stats, A, Off, amax, G, Gp, part, d, s); return;
             EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5)
 #undef EINET_CASE
         }

@@ -90,9 +90,10 @@ void launch_region_assemble(const DevTables& t, int first, int count, bool is_ro
                             const Dims& d, hipStream_t s);
 // accumulate = false: the weight statistics of these items are known to be zero and are overwritten.
 // full_k: every item of the launch has K output entries (all layers but the root's).
+// part: bwd_partial_floats(K) floats of scratch, or null (then the chunks of an item are always walked in turn).
 void launch_einsum_backward(const DevTables& t, int first, int count, bool full_k, bool accumulate,
                             const float* params, float* stats, const float* A, const double* Off, const float* amax,
-                            const float* G, float* Gp, const Dims& d, hipStream_t s);
+                            const float* G, float* Gp, float* part, const Dims& d, hipStream_t s);
 // posterior blocks ([B][K] floats each) reserved per einsum item in Gp: one for its left child, then up to
 // one per slice of four left entries for its right child
 inline int gp_blocks_per_item(int K) { return 1 + (K + 3) / 4; }
@@ -114,6 +115,19 @@ inline int bwd_split_grid(int count, int K) {
     const int pairs = count * (K / 4);
     return pairs < 256 ? pairs : 256;
 }
+// A layer of so few items that its pairs leave more than half of the compute units idle, with a batch of several
+// chunks of 128 samples: every item is launched as this many virtual items, each with a share of the chunks, one
+// workgroup per (virtual item, slice), at most 256 in all.  The virtual items of an item write their statistics to
+// blocks of their own (at most bwd_partial_floats(K) floats together), which a second launch adds up in a fixed order.
+inline int bwd_virtual_items(int count, int K, int B) {
+    const int pairs = count * (K / 4), nchunks = (B + 127) / 128;
+    if (pairs <= 0 || pairs > 128 || nchunks < 2) return 1;
+    int v = 256 / pairs;
+    if (v > nchunks) v = nchunks;
+    const int cpv = (nchunks + v - 1) / v;
+    return (nchunks + cpv - 1) / cpv;
+}
+inline size_t bwd_partial_floats(int K) { return (size_t)1024 * K * K; }   // >= (256 / pairs) * count * K^3
 // workgroup that owns pair x of P pairs split over G workgroups
 #if defined(__HIPCC__)
 __host__ __device__

@@ -34,7 +34,7 @@ void launch_root_backward(const DevTables&, int, bool, const float*, float*, con
                           float*, const Dims&, hipStream_t) {}
 void launch_region_assemble(const DevTables&, int, int, bool, float*, const float*, const Dims&, hipStream_t) {}
 void launch_einsum_backward(const DevTables&, int, int, bool, bool, const float*, float*, const float*, const double*,
-                            const float*, const float*, float*, const Dims&, hipStream_t) {}
+                            const float*, const float*, float*, float*, const Dims&, hipStream_t) {}
 void launch_tail_backward(const DevTables&, int, int, int, int, int, const float*, const uint8_t*, int, const float*,
                           const float*, const double*, const float*, float*, int64_t, int64_t, int64_t, const Dims&,
                           hipStream_t) {}
