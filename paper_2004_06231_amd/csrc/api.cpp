@@ -22,7 +22,8 @@ struct einet {
     // workspace layout (bytes from the start of the workspace)
     std::vector<int32_t> blob;      // all index tables, concatenated
     size_t off_theta = 0, off_A = 0, off_Off = 0, off_amax = 0, off_G = 0, off_Gp = 0, off_part = 0, ws_bytes = 0;
-    bool has_part = false;    // scratch for the statistics of virtual items (see bwd_virtual_items)
+    bool has_part = false;    // scratch for the statistics of virtual items and batch groups (bwd_virtual_items, leaf_stats_groups)
+    size_t part_floats = 0;
     struct TableOffsets {
 #define X(name) size_t name;
         EINET_TABLES(X)
@@ -268,9 +269,18 @@ int einet_create(const einet_spec* spec, einet_t** out) {
         if (bwd_uses_split_kernel(p.K, p.ein_layer_full[l] != 0) &&
             bwd_virtual_items(p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], p.K, (int)mb) > 1)
             h->has_part = true;
+    if (h->has_part) h->part_floats = bwd_partial_floats(p.K);
+    {
+        const int lg = leaf_stats_groups_max((int)p.leaf_node.size(), p.max_leaf_scope, p.C, (int)p.K, (int)mb);
+        if (lg > 1 && p.family != EINET_LEAF_CATEGORICAL) {
+            h->has_part = true;
+            const size_t need = (size_t)lg * (size_t)(p.n_stats - p.phi_offset);
+            if (need > h->part_floats) h->part_floats = need;
+        }
+    }
     if (h->has_part) {
         h->off_part = off;
-        off = align256(off + sizeof(float) * bwd_partial_floats(p.K));
+        off = align256(off + sizeof(float) * h->part_floats);
     }
     h->ws_bytes = off;
     *out = h;
@@ -453,7 +463,8 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
     run(h, KC_LEAF_BWD, s, [&] {
         launch_tail_backward(h->dt, (int)p.lv_leaf.size(), (int)p.leaf_node.size(), p.max_leaf_scope,
                              (int)p.mix_node.size(), p.max_mix_children, x_dev, mask_dev,
-                             mask_mode, h->params, A, Off, G, h->stats, p.phi_offset, p.den_offset, p.tot_offset, d, s);
+                             mask_mode, h->params, A, Off, G, h->stats, p.phi_offset, p.den_offset, p.tot_offset, p.n_stats,
+                             h->has_part ? reinterpret_cast<float*>(h->ws + h->off_part) : nullptr, h->part_floats, d, s);
     });
     rc = check_hip(h, "einet_em_accumulate");
     // (after a failed launch nothing is known about the arena or the statistics: the root's ones are written

@@ -139,11 +139,31 @@ inline int bwd_blocks_of_item(int count, int K, bool full_k, int li) {
     const long long ns = K / 4, P = (long long)count * ns, G = bwd_split_grid(count, K);
     return bwds_wg_of_pair((li + 1) * ns - 1, P, G) - bwds_wg_of_pair(li * ns, P, G) + 1;
 }
+// Leaf statistics on the matrix pipe (nothing marginalised, scopes of at least 512 (variable, channel) pairs): with
+// so few leaves that the workgroups of the launch (one per leaf and 64 or 128 pairs) leave half of the compute units
+// idle, the batch is split into this many groups of passes of 64 samples (at least two passes each), every group
+// with workgroups of its own that write to a block of their own; a second launch adds the blocks to the statistics.
+inline int leaf_stats_pairs_per_group(int K) { return K > 32 ? 64 : 128; }
+// (most groups any batch of up to B samples is split into)
+inline int leaf_stats_groups_max(int n_leaves, int max_scope, int C, int K, int B) {
+    const int pc = leaf_stats_pairs_per_group(K), wgs = n_leaves * ((max_scope * C + pc - 1) / pc), passes = (B + 63) / 64;
+    if (max_scope * C < 512 || wgs > 128 || passes < 4) return 1;
+    const int v = 256 / wgs;
+    return v > passes / 2 ? passes / 2 : v;
+}
+inline int leaf_stats_groups(int n_leaves, int max_scope, int C, int K, int B) {
+    const int v = leaf_stats_groups_max(n_leaves, max_scope, C, K, B), passes = (B + 63) / 64;
+    if (v <= 1) return 1;
+    const int ppv = (passes + v - 1) / v;
+    return (passes + ppv - 1) / ppv;
+}
 // leaf statistics and mixing statistics (independent of each other) in one launch
+// part: part_floats floats of scratch for the blocks of the batch groups above, or null; n_stats: length of stats.
 void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_scope, int n_mix, int max_children,
                           const float* x, const uint8_t* mask, int mask_mode, const float* params, const float* A,
                           const double* Off, const float* G, float* stats, int64_t phi_off, int64_t den_off,
-                          int64_t tot_off, const Dims& d, hipStream_t s);
+                          int64_t tot_off, int64_t n_stats, float* part, size_t part_floats, const Dims& d,
+                          hipStream_t s);
 // the whole M-step in one launch; the statistics of the first n_lazy_rows weight rows are left as they
 // are (the next E-step overwrites them); when no E-step has run since they were last consumed
 // (lazy_rows_are_zero) those rows count as zero and their weights are kept

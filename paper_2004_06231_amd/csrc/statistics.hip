@@ -307,7 +307,8 @@ template <bool SQ, int NCT>
 __global__ __launch_bounds__(256, NCT == 2 ? 3 : 2) void k_leaf_stats_mfma(
     const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica, const int32_t* __restrict__ leaf_sptr,
     const int32_t* __restrict__ leaf_var, const float* __restrict__ x, const float* __restrict__ G,
-    float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, int chunks_per_leaf, Dims d) {
+    float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, int chunks_per_leaf, int groups,
+    int group_samples, float* __restrict__ part, int64_t part_stride, Dims d) {
     using LY = LsmLayout<NCT>;
     constexpr int PC = LY::PC, XS = LY::XS, PH = LY::PH, NX = LSM_BC / PH;
     extern __shared__ float lsm_lds[];
@@ -315,7 +316,13 @@ __global__ __launch_bounds__(256, NCT == 2 ? 3 : 2) void k_leaf_stats_mfma(
     float* xs = Gs + LSM_BC * 64;                      // [LSM_BC][XS]
     float* tots = xs + LSM_BC * XS;                    // [64]
     int* vsl = reinterpret_cast<int*>(tots + 64);      // variables of the chunk's pairs
-    const int leaf = blockIdx.x / chunks_per_leaf, chunk = blockIdx.x - leaf * chunks_per_leaf;
+    // groups > 1: workgroup (leaf, chunk, group) takes the samples [bfirst, bend) and writes (not adds) its sums to
+    // block `group` of part, which is laid out like the leaf part of the statistics (from phi_off on)
+    const int lc = blockIdx.x / groups, group = blockIdx.x - lc * groups;
+    const int leaf = lc / chunks_per_leaf, chunk = lc - leaf * chunks_per_leaf;
+    const int bfirst = group * group_samples, bend = min(d.B, bfirst + group_samples);
+    float* dst = groups > 1 ? part + (size_t)group * part_stride - phi_off : stats;
+    const bool adds = groups == 1;
     const int s0 = leaf_sptr[leaf], npairs = (leaf_sptr[leaf + 1] - s0) * d.C;
     const int p0 = chunk * PC;
     if (p0 >= npairs) return;                          // (whole workgroup) this leaf has fewer chunks
@@ -346,7 +353,7 @@ __global__ __launch_bounds__(256, NCT == 2 ? 3 : 2) void k_leaf_stats_mfma(
     const size_t xstride = (size_t)d.D * d.C;
     float xr[NX], gq[LSM_BC * 64 / 256];
     auto fetch = [&](int b0) {
-        const int nb = min(LSM_BC, d.B - b0);
+        const int nb = min(LSM_BC, bend - b0);
 #pragma unroll
         for (int q = 0; q < NX; ++q) {
             const int bb = PH * q + sh;
@@ -364,12 +371,12 @@ __global__ __launch_bounds__(256, NCT == 2 ? 3 : 2) void k_leaf_stats_mfma(
 #pragma unroll
         for (int q = 0; q < LSM_BC * 64 / 256; ++q) Gs[tid + 256 * q] = gq[q];
     };
-    fetch(0);
-    for (int b0 = 0; b0 < d.B; b0 += LSM_BC) {
-        if (b0 > 0) __syncthreads();                   // readers of the previous pass are done
+    fetch(bfirst);
+    for (int b0 = bfirst; b0 < bend; b0 += LSM_BC) {
+        if (b0 > bfirst) __syncthreads();              // readers of the previous pass are done
         stage();
         __syncthreads();
-        if (b0 + LSM_BC < d.B) fetch(b0 + LSM_BC);
+        if (b0 + LSM_BC < bend) fetch(b0 + LSM_BC);
         __builtin_amdgcn_sched_barrier(0);             // (the requests stay ahead of the MFMA loop)
         {
             // thread (k = tid % 64, quarter = tid / 64) sums a quarter of the pass (rows beyond the batch are zero)
@@ -408,8 +415,8 @@ __global__ __launch_bounds__(256, NCT == 2 ? 3 : 2) void k_leaf_stats_mfma(
         if (p < np && k < d.K) {
             const int pair = p0 + p, vv = pair / d.C, c = pair - vv * d.C;
             const size_t ph = phi_off + ((size_t)(vsl[vv - vfirst] * d.C + c) * d.R + r) * d.T * d.K;
-            stats[ph + k] += acc[0][v];
-            if (SQ) stats[ph + d.K + k] += acc[SQ ? 1 : 0][v];
+            dst[ph + k] = (adds ? dst[ph + k] : 0.f) + acc[0][v];
+            if (SQ) dst[ph + d.K + k] = (adds ? dst[ph + d.K + k] : 0.f) + acc[SQ ? 1 : 0][v];
         }
     }
     // den = tot for every variable whose first channel lies in this chunk
@@ -422,14 +429,27 @@ __global__ __launch_bounds__(256, NCT == 2 ? 3 : 2) void k_leaf_stats_mfma(
     for (int i = tid; i < (vhi - vlo + 1) * d.K; i += 256) {
         const int vv = vlo + i / d.K, kk = i % d.K;
         const size_t o = ((size_t)vsl[vv - vfirst] * d.R + r) * d.K + kk;
-        stats[den_off + o] += tots[kk];
-        stats[tot_off + o] += tots[kk];
+        dst[den_off + o] = (adds ? dst[den_off + o] : 0.f) + tots[kk];
+        dst[tot_off + o] = (adds ? dst[tot_off + o] : 0.f) + tots[kk];
+    }
+}
+
+// stats[i] += sum over the blocks of part[.][i], i over the n floats of the leaf part of the statistics (what follows
+// k_leaf_stats_mfma with several batch groups): workgroup blk of n_blocks, in the launch of the mixing statistics
+__device__ __forceinline__ void sum_leaf_blocks_body(int blk, int n_blocks, const float* __restrict__ part,
+                                                     float* __restrict__ stats, int64_t n, int groups) {
+    for (int64_t i = (int64_t)blk * blockDim.x + threadIdx.x; i < n; i += (int64_t)n_blocks * blockDim.x) {
+        float sum = stats[i];
+        for (int v = 0; v < groups; ++v) sum += part[v * n + i];
+        stats[i] = sum;
     }
 }
 
 // Last launch of the top-down pass: leaf statistics in the first n_leaf_blocks workgroups, mixing
 // statistics in the others (item = idx / max_children, child = idx % max_children).  NCH = 0 selects the
-// kernel body for long scopes (chunks_per_leaf workgroups per leaf, PPT pairs per thread).
+// kernel body for long scopes (chunks_per_leaf workgroups per leaf, PPT pairs per thread), NCH = TAIL_SUMS the sum of
+// the blocks that the batch groups of k_leaf_stats_mfma left in part.
+constexpr int TAIL_SUMS = 8;
 template <int NCH, int PPT>
 __global__ __launch_bounds__(1024) void k_tail_backward(
     int n_leaf_blocks, int max_children, const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var,
@@ -438,10 +458,13 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
     float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const int32_t* __restrict__ m_rec,
     const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child, const float* __restrict__ params,
     const float* __restrict__ A, const double* __restrict__ Off, const int32_t* __restrict__ leaf_sptr,
-    const int32_t* __restrict__ leaf_var, int chunks_per_leaf, Dims d) {
+    const int32_t* __restrict__ leaf_var, int chunks_per_leaf, const float* __restrict__ part, int64_t part_n,
+    int groups, Dims d) {
     const int blk = blockIdx.x;
     if (blk < n_leaf_blocks) {
-        if constexpr (NCH == 0)
+        if constexpr (NCH == TAIL_SUMS)
+            sum_leaf_blocks_body(blk, n_leaf_blocks, part, stats + phi_off, part_n, groups);
+        else if constexpr (NCH == 0)
             leaf_backward_cells_body<PPT>(blk, chunks_per_leaf, leaf_node, leaf_replica, leaf_sptr, leaf_var, x, mask,
                                           mask_mode, G, stats, phi_off, den_off, tot_off, d);
         else
@@ -459,7 +482,8 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
 void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_scope, int n_mix, int max_children,
                           const float* x, const uint8_t* mask, int mask_mode, const float* params, const float* A,
                           const double* Off, const float* G, float* stats, int64_t phi_off, int64_t den_off,
-                          int64_t tot_off, const Dims& d, hipStream_t s) {
+                          int64_t tot_off, int64_t n_stats, float* part, size_t part_floats, const Dims& d,
+                          hipStream_t s) {
     const int total = n_lv * d.C * d.K;
     const bool categorical = d.family == EINET_LEAF_CATEGORICAL;
     if (categorical)     // indicator statistics: a histogram kernel of its own (at most 256 x 64 floats of LDS)
@@ -469,7 +493,10 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
     // very long scopes, nothing marginalised: the statistics as a GEMM over the batch on the matrix pipe, the mixing
     // statistics in a launch of their own
     bool leaves_done = categorical;
-    if (!categorical && mask_mode == EINET_MASK_NONE && max_scope * d.C >= 1024 && d.K <= 64) {
+    const int64_t n_leaf_stats = n_stats - phi_off;
+    int groups = part ? leaf_stats_groups(n_leaves, max_scope, d.C, d.K, d.B) : 1;
+    if ((size_t)groups * (size_t)n_leaf_stats > part_floats) groups = 1;
+    if (!categorical && mask_mode == EINET_MASK_NONE && (max_scope * d.C >= 1024 || groups > 1) && d.K <= 64) {
         static std::once_flag attr_m[EINET_MAX_DEVICES];
         int dev = 0;
         (void)hipGetDevice(&dev);
@@ -481,11 +508,14 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
         });
 #define EINET_LSM(SQ, NCT)                                                                                       \
     {                                                                                                            \
+        static_assert(LsmLayout<NCT>::PC == (NCT == 2 ? 64 : 128), "leaf_stats_pairs_per_group");                \
         const int cpl = (max_scope * d.C + LsmLayout<NCT>::PC - 1) / LsmLayout<NCT>::PC;                         \
-        hipLaunchKernelGGL((k_leaf_stats_mfma<SQ, NCT>), dim3(n_leaves * cpl), dim3(256), LsmLayout<NCT>::LDS_BYTES, \
-                           s, t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, x, G, stats, phi_off, den_off,   \
-                           tot_off, cpl, d);                                                                     \
+        hipLaunchKernelGGL((k_leaf_stats_mfma<SQ, NCT>), dim3(n_leaves * cpl * groups), dim3(256),               \
+                           LsmLayout<NCT>::LDS_BYTES, s, t.leaf_node, t.leaf_replica, t.leaf_sptr, t.leaf_var, x, G, \
+                           stats, phi_off, den_off, tot_off, cpl, groups, group_samples, part, n_leaf_stats, d);   \
     }
+        const int passes = (d.B + LSM_BC - 1) / LSM_BC;
+        const int group_samples = groups > 1 ? LSM_BC * ((passes + groups - 1) / groups) : d.B;
         if (d.T == 2 && d.K > 32) EINET_LSM(true, 2)
         else if (d.T == 2) EINET_LSM(true, 1)
         else if (d.K > 32) EINET_LSM(false, 2)
@@ -502,11 +532,15 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
     const int ppt = cells && n_leaves * chunks1 >= 1024 && pc1 * 4 <= 128 ? 4 : 1;
     const int nch = cells ? 0 : (d.B >= 16 ? 4 : 1);
     const int chunks_per_leaf = cells ? (max_scope * d.C + pc1 * ppt - 1) / (pc1 * ppt) : 1;
-    const int n_leaf_blocks = leaves_done ? 0 : (cells ? n_leaves * chunks_per_leaf : (total + 1024 / nch - 1) / (1024 / nch));
+    // (after the matrix kernel with batch groups: the leaf workgroups of this launch add the groups' blocks up)
+    const bool sums = leaves_done && !categorical && groups > 1;
+    const int sum_blocks = (int)((n_leaf_stats + 4095) / 4096 < 256 ? (n_leaf_stats + 4095) / 4096 : 256);
+    const int n_leaf_blocks = sums ? sum_blocks
+                              : leaves_done ? 0 : (cells ? n_leaves * chunks_per_leaf : (total + 1024 / nch - 1) / (1024 / nch));
     const int blocks = n_leaf_blocks + n_mix * max_children;
     if (blocks == 0) return;
-    const size_t lds = cells ? cell_lds_bytes(d.K, ppt) : 0;
-    if (cells) {
+    const size_t lds = cells && !sums ? cell_lds_bytes(d.K, ppt) : 0;
+    if (cells && !sums) {
         static std::once_flag attr_set[EINET_MAX_DEVICES];
         int dev = 0;
         (void)hipGetDevice(&dev);
@@ -519,8 +553,9 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
     hipLaunchKernelGGL((k_tail_backward<N, P>), dim3(blocks), dim3(1024), lds, s, n_leaf_blocks,                      \
                        max_children > 0 ? max_children : 1, t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, n_lv, x, \
                        mask, mask_mode, G, stats, phi_off, den_off, tot_off, t.mix_rec, t.mix_cptr, t.mix_child,      \
-                       params, A, Off, t.leaf_sptr, t.leaf_var, chunks_per_leaf, d)
-    if (nch == 0 && ppt == 4) EINET_LAUNCH(0, 4);
+                       params, A, Off, t.leaf_sptr, t.leaf_var, chunks_per_leaf, part, n_leaf_stats, groups, d)
+    if (sums) EINET_LAUNCH(TAIL_SUMS, 1);
+    else if (nch == 0 && ppt == 4) EINET_LAUNCH(0, 4);
     else if (nch == 0) EINET_LAUNCH(0, 1);
     else if (nch == 4) EINET_LAUNCH(4, 1);
     else EINET_LAUNCH(1, 1);

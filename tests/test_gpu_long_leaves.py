@@ -22,6 +22,11 @@ CASES = [
     (BINOMIAL, 31, dict(kind="rat", D=1600, depth=1, R=1), 12, 2, 33, "shared"),              # chunks of 192 variables
     (BINOMIAL, 255, dict(kind="pd", H=32, W=32, deltas=[16], axes=2), 10, 3, 20, None),       # 8-bit pixels
     (CATEGORICAL, 4, dict(kind="rat", D=1000, depth=1, R=1), 8, 1, 20, "per_sample"),         # constants indexed by the value
+    # few leaves, scopes of 512 to 1023 pairs, several passes of 64 samples: statistics per batch group, then summed
+    (GAUSSIAN, 0, dict(kind="pd", H=32, W=32, deltas=[8], axes=2), 40, 3, 300, None),         # two groups, the second ragged
+    (BERNOULLI, 0, dict(kind="rat", D=1100, depth=1, R=1), 40, 1, 500, None),                 # four groups of two passes
+    (GAUSSIAN, 0, dict(kind="rat", D=1800, depth=1, R=2), 5, 1, 260, None),                   # one column tile, two groups
+    (BINOMIAL, 31, dict(kind="rat", D=1200, depth=1, R=1), 12, 1, 450, None),                 # one statistic, four groups
 ]
 
 
@@ -47,7 +52,10 @@ def test_leaves_with_long_scopes_match_oracle(family, param, spec, K, C, B, mask
     lp = torch.empty(B, device="cuda")
     m.em_accumulate(dev(x), dev(mask), lp)
     assert_logp_close(lp, ref_logp)
-    assert_stats_close(m.stats, oracle.stats_to_flat(ref_stats), oracle.layout, m.n_params)
+    ref_flat = oracle.stats_to_flat(ref_stats)
+    assert_stats_close(m.stats, ref_flat, oracle.layout, m.n_params)
+    m.em_accumulate(dev(x), dev(mask), lp)               # added to, not overwritten
+    assert_stats_close(m.stats, 2.0 * ref_flat, oracle.layout, m.n_params)
     # fewer samples on the same handle: a last group of fewer than eight
     nb = max(1, B - 3)
     mk = None if mask is None else (mask if mask.ndim == 1 else mask[:nb])
