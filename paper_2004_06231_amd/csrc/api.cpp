@@ -269,7 +269,10 @@ int einet_create(const einet_spec* spec, einet_t** out) {
         if (bwd_uses_split_kernel(p.K, p.ein_layer_full[l] != 0) &&
             bwd_virtual_items(p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], p.K, (int)mb) > 1)
             h->has_part = true;
-    if (h->has_part) h->part_floats = bwd_partial_floats(p.K);
+    if (p.num_layers > 0 &&
+        root_bwd_virtual_items(p.ein_layer_ptr[p.num_layers] - p.ein_layer_ptr[p.num_layers - 1], (int)p.K, (int)mb) > 1)
+        h->has_part = true;
+    if (h->has_part) h->part_floats = bwd_partial_floats(p.K);   // (the root's layer needs at most 256 K^2 of them)
     {
         const int lg = leaf_stats_groups_max((int)p.leaf_node.size(), p.max_leaf_scope, p.C, (int)p.K, (int)mb);
         if (lg > 1 && p.family != EINET_LEAF_CATEGORICAL) {
@@ -444,8 +447,9 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
             // the root's partitions (one output entry each; the root's posterior is 1, its block in G is read by the
             // mixing statistics only): a launch of their own kind, timed as a class of its own
             run(h, KC_ROOT_BWD, s, [&] {
-                launch_root_backward(h->dt, p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], !h->weight_stats_zero, h->params,
-                                     h->stats, A, Off, amax, Gp, d, s);
+                launch_root_backward(h->dt, p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->dt.ein_woff + p.ein_layer_ptr[l],
+                                     h->has_part ? reinterpret_cast<float*>(h->ws + h->off_part) : nullptr,
+                                     !h->weight_stats_zero, h->params, h->stats, A, Off, amax, Gp, d, s);
             }, layer_outputs(p, l));
             continue;
         }

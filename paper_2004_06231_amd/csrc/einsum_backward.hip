@@ -1048,6 +1048,7 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
 }
 
 // stats[item][r] (+)= sum over the vper blocks of part[.][item][r]: the launch after a top-down launch with virtual items
+namespace {
 __global__ void k_sum_partial_stats(const int32_t* __restrict__ e_woff, const float* __restrict__ part,
                                     float* __restrict__ stats, int count, int vper, int k3, int accumulate) {
     const size_t n = (size_t)count * k3;
@@ -1058,6 +1059,14 @@ __global__ void k_sum_partial_stats(const int32_t* __restrict__ e_woff, const fl
         for (int v = 0; v < vper; ++v) sum += part[(size_t)v * n + i];
         *dst = sum;
     }
+}
+}  // namespace
+
+void launch_sum_partial_stats(const int32_t* e_woff, const float* part, float* stats, int count, int vper, int block,
+                              bool accumulate, hipStream_t s) {
+    const int n = count * block;
+    hipLaunchKernelGGL(k_sum_partial_stats, dim3((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024), dim3(256), 0, s, e_woff,
+                       part, stats, count, vper, block, accumulate ? 1 : 0);
 }
 
 template <int K8>
@@ -1084,9 +1093,7 @@ static void launch_einsum_backward_k8(const DevTables& t, int first, int count, 
     if (vper > 1) {
         // (the blocks are written, not added to; the sum that follows adds to the statistics or overwrites them)
         EINET_LAUNCH(false);
-        const int k3 = d.K * d.K * d.K, n = count * k3;
-        hipLaunchKernelGGL(k_sum_partial_stats, dim3((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024), dim3(256), 0, s,
-                           t.ein_woff + first, part, stats, count, vper, k3, accumulate ? 1 : 0);
+        launch_sum_partial_stats(t.ein_woff + first, part, stats, count, vper, d.K * d.K * d.K, accumulate, s);
     } else if (accumulate) EINET_LAUNCH(true);
     else EINET_LAUNCH(false);
 #undef EINET_LAUNCH

@@ -80,7 +80,9 @@ void launch_root_forward(const DevTables& t, int n_partitions, const float* para
 // Top-down: weight statistics (Eq. 6) and child posteriors of the root's partitions; the root's posterior is 1 and its
 // mixing step is folded in.  Writes the posterior blocks that launch_einsum_backward writes for a layer of
 // n_partitions items with one output entry each (bwd_groups_per_item workgroups and right-child blocks per item).
-void launch_root_backward(const DevTables& t, int n_partitions, bool accumulate, const float* params, float* stats,
+// e_woff: the weight offsets of the layer's items in order (for the sum of the virtual items' blocks); part as for
+// launch_einsum_backward (at least 256 K^2 floats), or null.
+void launch_root_backward(const DevTables& t, int n_partitions, const int32_t* e_woff, float* part, bool accumulate, const float* params, float* stats,
                           const float* A, const double* Off, const float* amax, float* Gp, const Dims& d, hipStream_t s);
 
 // Every top-down region also has a record of RB_REC_INTS ints in rb_rec: node, entries, number of parent blocks,
@@ -128,6 +130,19 @@ inline int bwd_virtual_items(int count, int K, int B) {
     return (nchunks + cpv - 1) / cpv;
 }
 inline size_t bwd_partial_floats(int K) { return (size_t)1024 * K * K; }   // >= (256 / pairs) * count * K^3
+// stats[e_woff[item] + r] (+)= sum over v < vper of part[(v * count + item) * block + r], r < block
+void launch_sum_partial_stats(const int32_t* e_woff, const float* part, float* stats, int count, int vper, int block,
+                              bool accumulate, hipStream_t s);
+// The same for the root's layer (n_partitions items of K^2 weights, bwd_groups_per_item workgroups each): shares of
+// the chunks of 128 samples per workgroup when the launch would leave half of the compute units idle.
+inline int root_bwd_virtual_items(int n_partitions, int K, int B) {
+    const int wgs = n_partitions * bwd_groups_per_item(n_partitions, K), nchunks = (B + 127) / 128;
+    if (wgs <= 0 || wgs > 128 || nchunks < 2) return 1;
+    int v = 256 / wgs;
+    if (v > nchunks) v = nchunks;
+    const int cpv = (nchunks + v - 1) / v;
+    return (nchunks + cpv - 1) / cpv;
+}
 // workgroup that owns pair x of P pairs split over G workgroups
 #if defined(__HIPCC__)
 __host__ __device__

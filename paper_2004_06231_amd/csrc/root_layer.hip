@@ -197,7 +197,8 @@ template <int KQ>
 __global__ __launch_bounds__(RB_THREADS) void k_root_backward(const int32_t* __restrict__ rec, const float* __restrict__ params,
                                                        float* __restrict__ stats, const float* __restrict__ A,
                                                        const double* __restrict__ Off, const float* __restrict__ amax,
-                                                       float* __restrict__ Gp, int ngroups, int accumulate, int B, int K) {
+                                                       float* __restrict__ Gp, int ngroups, int accumulate, int B, int K,
+                                                       int vper, int cpv, float* __restrict__ part, int n_partitions) {
     using LY = RootBwdLayout<KQ>;
     constexpr int K4 = LY::K4, KS = LY::KS;
     extern __shared__ float lds[];
@@ -207,7 +208,11 @@ __global__ __launch_bounds__(RB_THREADS) void k_root_backward(const int32_t* __r
     float* sQ = lds + LY::OFF_Q;
     float* sWT = lds + LY::OFF_WT;
     const int root = rec[1], voff = rec[2];
-    const int p = blockIdx.x / ngroups, grp = blockIdx.x - p * ngroups;
+    // vper > 1: workgroup (partition, group of slices, share vg of the chunks) takes the samples [bfirst, bend) and
+    // writes its statistics to block (vg, partition) of part; a launch that follows adds the blocks up
+    const int pg = blockIdx.x / vper, vg = blockIdx.x - pg * vper;
+    const int p = pg / ngroups, grp = pg - p * ngroups;
+    const int bfirst = vg * cpv * RB_BC, bend = min(B, bfirst + cpv * RB_BC);
     const int32_t* q = rec + 4 + p * ROOT_REC_STRIDE;
     const int item = q[0], left = q[1], right = q[2], out = q[3], woff = q[4];
     const int it0 = grp * KQ / ngroups, it1 = (grp + 1) * KQ / ngroups;
@@ -221,7 +226,7 @@ __global__ __launch_bounds__(RB_THREADS) void k_root_backward(const int32_t* __r
     const float* aL = amax + (size_t)item * 2 * B;
     const float* aR = aL + B;
     const float* W = params + woff;
-    float* Nw = stats + woff;
+    float* Nw = vper > 1 ? part + ((size_t)vg * n_partitions + p) * ((size_t)K * K) : stats + woff;
     const int nblk = 1 + KQ;
     float* gleft = Gp + (size_t)item * nblk * blk;
     float* gright = Gp + ((size_t)item * nblk + 1 + grp) * blk;
@@ -238,8 +243,8 @@ __global__ __launch_bounds__(RB_THREADS) void k_root_backward(const int32_t* __r
         const size_t sidx = sact ? (size_t)(4 * it + sil) * K + sj : 0;
         const float wown = sact ? W[sidx] : 0.f;
         const float nold = sact && accumulate ? Nw[sidx] : 0.f;
-        for (int b0 = 0; b0 < B; b0 += RB_BC) {
-            const int nb = min(RB_BC, B - b0), nb4 = (nb + 3) & ~3;
+        for (int b0 = bfirst; b0 < bend; b0 += RB_BC) {
+            const int nb = min(RB_BC, bend - b0), nb4 = (nb + 3) & ~3;
             // ---- requests: everything this pass needs, before the first value is used
             float vq = 1.f, lq[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, alq = 0.f, asq = 0.f;
             double ddq = 0.0;
@@ -386,9 +391,9 @@ void launch_root_forward_kq(const DevTables& t, int n_partitions, const float* p
 }
 
 template <int KQ>
-void launch_root_backward_kq(const DevTables& t, int n_partitions, bool accumulate, const float* params, float* stats,
-                             const float* A, const double* Off, const float* amax, float* Gp, const Dims& d,
-                             hipStream_t s) {
+void launch_root_backward_kq(const DevTables& t, int n_partitions, const int32_t* e_woff, float* part, bool accumulate,
+                             const float* params, float* stats, const float* A, const double* Off, const float* amax,
+                             float* Gp, const Dims& d, hipStream_t s) {
     const size_t lds = sizeof(float) * RootBwdLayout<KQ>::LDS_FLOATS;
     if (lds > 64 * 1024) {
         static std::once_flag attr_set[EINET_MAX_DEVICES];
@@ -397,8 +402,13 @@ void launch_root_backward_kq(const DevTables& t, int n_partitions, bool accumula
         std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] { allow_dynamic_lds(&k_root_backward<KQ>, lds); });
     }
     const int ngroups = bwd_groups_per_item(n_partitions, d.K);
-    hipLaunchKernelGGL(k_root_backward<KQ>, dim3(n_partitions * ngroups), dim3(RB_THREADS), lds, s, t.root_rec, params, stats, A,
-                       Off, amax, Gp, ngroups, accumulate ? 1 : 0, d.B, d.K);
+    const int vper = part ? root_bwd_virtual_items(n_partitions, d.K, d.B) : 1;
+    const int nchunks = (d.B + RB_BC - 1) / RB_BC, cpv = (nchunks + vper - 1) / vper;
+    // (with virtual items the blocks are written, never added to; the sum adds to the statistics or overwrites them)
+    hipLaunchKernelGGL(k_root_backward<KQ>, dim3(n_partitions * ngroups * vper), dim3(RB_THREADS), lds, s, t.root_rec, params,
+                       stats, A, Off, amax, Gp, ngroups, vper > 1 ? 0 : (accumulate ? 1 : 0), d.B, d.K, vper, cpv, part,
+                       n_partitions);
+    if (vper > 1) launch_sum_partial_stats(e_woff, part, stats, n_partitions, vper, d.K * d.K, accumulate, s);
 }
 
 }  // namespace
@@ -415,11 +425,12 @@ void launch_root_forward(const DevTables& t, int n_partitions, const float* para
     }
 }
 
-void launch_root_backward(const DevTables& t, int n_partitions, bool accumulate, const float* params, float* stats,
+void launch_root_backward(const DevTables& t, int n_partitions, const int32_t* e_woff, float* part, bool accumulate,
+                          const float* params, float* stats,
                           const float* A, const double* Off, const float* amax, float* Gp, const Dims& d, hipStream_t s) {
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
-    case J: launch_root_backward_kq<J>(t, n_partitions, accumulate, params, stats, A, Off, amax, Gp, d, s); break;
+    case J: launch_root_backward_kq<J>(t, n_partitions, e_woff, part, accumulate, params, stats, A, Off, amax, Gp, d, s); break;
         EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
         EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
         EINET_CASE(16)

@@ -30,8 +30,9 @@ void launch_einsum_forward(const DevTables&, int, int, bool, const float*, float
 void launch_mixing_forward(const DevTables&, int, int, int, const float*, float*, double*, float*, const Dims&,
                            hipStream_t) {}
 void launch_root_forward(const DevTables&, int, const float*, float*, double*, float*, float*, const Dims&, hipStream_t) {}
-void launch_root_backward(const DevTables&, int, bool, const float*, float*, const float*, const double*, const float*,
-                          float*, const Dims&, hipStream_t) {}
+void launch_root_backward(const DevTables&, int, const int32_t*, float*, bool, const float*, float*, const float*,
+                          const double*, const float*, float*, const Dims&, hipStream_t) {}
+void launch_sum_partial_stats(const int32_t*, const float*, float*, int, int, int, bool, hipStream_t) {}
 void launch_region_assemble(const DevTables&, int, int, bool, float*, const float*, const Dims&, hipStream_t) {}
 void launch_einsum_backward(const DevTables&, int, int, bool, bool, const float*, float*, const float*, const double*,
                             const float*, const float*, float*, float*, const Dims&, hipStream_t) {}
