@@ -143,7 +143,9 @@ const char* einet_last_error(const einet_t* h);
 /* Sizes the caller must allocate on the device: n_params and n_stats in
  * float32 elements, workspace in bytes (index tables, derived leaf constants,
  * activation arena with its per-sample offsets and posterior arenas for
- * max_batch samples).  All outputs: host. */
+ * max_batch samples and, for models with so few einsum items or leaves that
+ * the chunks of a large batch are processed side by side, blocks for their
+ * partial statistics).  All outputs: host. */
 int einet_sizes(const einet_t* h, size_t* n_params, size_t* n_stats, size_t* workspace_bytes);
 
 /* Fills *view (host) with pointers into the handle's host tables. */
