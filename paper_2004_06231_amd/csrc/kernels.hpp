@@ -121,12 +121,18 @@ inline int bwd_split_grid(int count, int K) {
 // chunks of 128 samples: every item is launched as this many virtual items, each with a share of the chunks, one
 // workgroup per (virtual item, slice), at most 256 in all.  The virtual items of an item write their statistics to
 // blocks of their own (at most bwd_partial_floats(K) floats together), which a second launch adds up in a fixed order.
+// The second launch costs about 4 us, so the split is taken only where the chunks a workgroup no longer walks are worth
+// twice that: a workgroup spends roughly bwd_unit_us(K) on one chunk of one slice (10 us at K = 40, measured; the
+// work grows with K^2), half of that in the root's layer.
+constexpr float BWD_SPLIT_PAYS_US = 8.f;
+inline float bwd_unit_us(int K) { return 1.f + 9.f * (float)(K * K) / 1600.f; }
 inline int bwd_virtual_items(int count, int K, int B) {
     const int pairs = count * (K / 4), nchunks = (B + 127) / 128;
     if (pairs <= 0 || pairs > 128 || nchunks < 2) return 1;
     int v = 256 / pairs;
     if (v > nchunks) v = nchunks;
     const int cpv = (nchunks + v - 1) / v;
+    if ((float)(nchunks - cpv) * bwd_unit_us(K) < BWD_SPLIT_PAYS_US) return 1;
     return (nchunks + cpv - 1) / cpv;
 }
 inline size_t bwd_partial_floats(int K) { return (size_t)1024 * K * K; }   // >= (256 / pairs) * count * K^3
@@ -136,11 +142,13 @@ void launch_sum_partial_stats(const int32_t* e_woff, const float* part, float* s
 // The same for the root's layer (n_partitions items of K^2 weights, bwd_groups_per_item workgroups each): shares of
 // the chunks of 128 samples per workgroup when the launch would leave half of the compute units idle.
 inline int root_bwd_virtual_items(int n_partitions, int K, int B) {
-    const int wgs = n_partitions * bwd_groups_per_item(n_partitions, K), nchunks = (B + 127) / 128;
+    const int groups = bwd_groups_per_item(n_partitions, K), wgs = n_partitions * groups, nchunks = (B + 127) / 128;
     if (wgs <= 0 || wgs > 128 || nchunks < 2) return 1;
     int v = 256 / wgs;
     if (v > nchunks) v = nchunks;
     const int cpv = (nchunks + v - 1) / v;
+    const int slices = ((K + 3) / 4 + groups - 1) / groups;      // per workgroup
+    if ((float)((nchunks - cpv) * slices) * 0.5f * bwd_unit_us(K) < BWD_SPLIT_PAYS_US) return 1;
     return (nchunks + cpv - 1) / cpv;
 }
 // workgroup that owns pair x of P pairs split over G workgroups

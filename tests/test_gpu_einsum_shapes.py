@@ -22,6 +22,9 @@ CASES = [
     (dict(kind="rat", D=16, depth=2, R=2), 40, 2, GAUSSIAN, 1),            # a single sample
     (dict(kind="pd", H=6, W=4, deltas=[2]), 40, 1, BERNOULLI, 260),        # K = 40 with chunks
     (dict(kind="rat", D=24, depth=2, R=3), 48, 1, GAUSSIAN, 130),          # new kernel bottom-up, 16x16x4 kernel top-down
+    # few items and many chunks: the chunks of an item side by side, statistics blocks summed by a second launch
+    (dict(kind="rat", D=16, depth=2, R=2), 16, 1, BERNOULLI, 1100),        # nine shares of one chunk each
+    (dict(kind="pd", H=6, W=6, deltas=[2]), 24, 1, GAUSSIAN, 520),         # three shares of two, two and one chunk
 ]
 
 
