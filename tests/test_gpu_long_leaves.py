@@ -22,6 +22,8 @@ CASES = [
     (BINOMIAL, 31, dict(kind="rat", D=1600, depth=1, R=1), 12, 2, 33, "shared"),              # chunks of 192 variables
     (BINOMIAL, 255, dict(kind="pd", H=32, W=32, deltas=[16], axes=2), 10, 3, 20, None),       # 8-bit pixels
     (CATEGORICAL, 4, dict(kind="rat", D=1000, depth=1, R=1), 8, 1, 20, "per_sample"),         # constants indexed by the value
+    (GAUSSIAN, 0, dict(kind="rat", D=771, depth=1, R=1), 40, 1, 20, "shared"),                # second chunks of one and two variables
+    (GAUSSIAN, 0, dict(kind="rat", D=2000, depth=1, R=1), 1, 1, 10, None),                    # K = 1
     # few leaves, scopes of 512 to 1023 pairs, several passes of 64 samples: statistics per batch group, then summed
     (GAUSSIAN, 0, dict(kind="pd", H=32, W=32, deltas=[8], axes=2), 40, 3, 300, None),         # two groups, the second ragged
     (BERNOULLI, 0, dict(kind="rat", D=1100, depth=1, R=1), 40, 1, 500, None),                 # four groups of two passes
