@@ -22,8 +22,13 @@ struct einet {
     // workspace layout (bytes from the start of the workspace)
     std::vector<int32_t> blob;      // all index tables, concatenated
     size_t off_theta = 0, off_A = 0, off_Off = 0, off_amax = 0, off_G = 0, off_Gp = 0, off_part = 0, ws_bytes = 0;
-    bool has_part = false;    // scratch for the statistics of virtual items and batch groups (bwd_virtual_items, leaf_stats_groups)
+    // Scratch for the statistics blocks of virtual items (bwd_virtual_items: a region per layer, since the blocks
+    // of a top-down pass are summed at its end) and, after that sum, of the leaf statistics' batch groups
+    // (leaf_stats_groups), which share the memory.
+    bool has_part = false;
     size_t part_floats = 0;
+    static constexpr size_t NO_PART = ~size_t(0);
+    std::vector<size_t> part_off;   // per einsum layer: floats from off_part to its region, or NO_PART
     struct TableOffsets {
 #define X(name) size_t name;
         EINET_TABLES(X)
@@ -265,14 +270,16 @@ int einet_create(const einet_spec* spec, einet_t** out) {
     off = align256(off + sizeof(float) * size_t(p.num_nodes) * mb * K);
     h->off_Gp = off;
     off = align256(off + sizeof(float) * gp_blocks_per_item(p.K) * p.ein_left.size() * mb * K);
-    for (int l = 0; l + 1 < p.num_layers; ++l)       // (the root's layer has a kernel of its own)
-        if (bwd_uses_split_kernel(p.K, p.ein_layer_full[l] != 0) &&
-            bwd_virtual_items(p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], p.K, (int)mb) > 1)
-            h->has_part = true;
-    if (p.num_layers > 0 &&
-        root_bwd_virtual_items(p.ein_layer_ptr[p.num_layers] - p.ein_layer_ptr[p.num_layers - 1], (int)p.K, (int)mb) > 1)
+    h->part_off.assign(p.num_layers, einet::NO_PART);
+    for (int l = 0; l < p.num_layers; ++l) {         // (the root's layer, the last, has a kernel of its own)
+        const int count = p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l];
+        const size_t need = l + 1 < p.num_layers ? bwd_partial_bound(count, (int)p.K, (int)mb, p.ein_layer_full[l] != 0)
+                                                 : root_bwd_partial_bound(count, (int)p.K, (int)mb);
+        if (need == 0) continue;
         h->has_part = true;
-    if (h->has_part) h->part_floats = bwd_partial_floats(p.K);   // (the root's layer needs at most 256 K^2 of them)
+        h->part_off[l] = h->part_floats;
+        h->part_floats += (need + 63) & ~size_t(63);
+    }
     {
         const int lg = leaf_stats_groups_max((int)p.leaf_node.size(), p.max_leaf_scope, p.C, (int)p.K, (int)mb);
         if (lg > 1 && p.family != EINET_LEAF_CATEGORICAL) {
@@ -436,6 +443,11 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
     float* Gp = reinterpret_cast<float*>(h->ws + h->off_Gp);
     // top-down: posteriors of the regions of sum layer l (root first), then the einsum items below them
     const float* amax = reinterpret_cast<const float*>(h->ws + h->off_amax);
+    PartialSumList sums;
+    auto layer_part = [&](int l) -> float* {
+        return h->part_off[l] == einet::NO_PART ? nullptr
+                                                : reinterpret_cast<float*>(h->ws + h->off_part) + h->part_off[l];
+    };
     for (int l = p.num_layers - 1, step = 0; l >= 0; --l, ++step) {
         // (the top sum layer is the root alone: nothing to launch when its ones are still in place)
         if (step > 0 || B > h->root_ones_batch)
@@ -448,15 +460,19 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
             // mixing statistics only): a launch of their own kind, timed as a class of its own
             run(h, KC_ROOT_BWD, s, [&] {
                 launch_root_backward(h->dt, p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l], h->dt.ein_woff + p.ein_layer_ptr[l],
-                                     h->has_part ? reinterpret_cast<float*>(h->ws + h->off_part) : nullptr,
+                                     layer_part(l), &sums,
                                      !h->weight_stats_zero, h->params, h->stats, A, Off, amax, Gp, d, s);
+                if (l == 0) launch_sum_partial_stats(sums, h->stats, !h->weight_stats_zero, s);
             }, layer_outputs(p, l));
             continue;
         }
         run(h, KC_EINSUM_BWD, s, [&] {
             launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
                                    p.ein_layer_full[l] != 0, !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp,
-                                   h->has_part ? reinterpret_cast<float*>(h->ws + h->off_part) : nullptr, d, s);
+                                   layer_part(l), &sums, d, s);
+            // after the last layer: the statistics blocks of the launches that ran virtual items, all layers in one
+            // launch (before the leaf statistics, whose batch groups use the same scratch)
+            if (l == 0) launch_sum_partial_stats(sums, h->stats, !h->weight_stats_zero, s);
         }, layer_outputs(p, l));
     }
     const int leaf_step = p.num_layers;

@@ -1047,32 +1047,35 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
 #undef EINET_LAUNCH
 }
 
-// stats[item][r] (+)= sum over the vper blocks of part[.][item][r]: the launch after a top-down launch with virtual items
+// stats[item][r] (+)= sum over the vper blocks of part[.][item][r], job blockIdx.y of the list: the launch at the end of
+// a top-down pass whose launches ran virtual items
 namespace {
-__global__ void k_sum_partial_stats(const int32_t* __restrict__ e_woff, const float* __restrict__ part,
-                                    float* __restrict__ stats, int count, int vper, int k3, int accumulate) {
-    const size_t n = (size_t)count * k3;
+__global__ void k_sum_partial_stats(PartialSumList jobs, float* __restrict__ stats, int accumulate) {
+    const PartialSumJob& j = jobs.job[blockIdx.y];
+    const size_t n = (size_t)j.count * j.block;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-        const int li = (int)(i / k3);
-        float* dst = stats + (size_t)e_woff[li] + (i - (size_t)li * k3);
+        const int li = (int)(i / j.block);
+        float* dst = stats + (size_t)j.e_woff[li] + (i - (size_t)li * j.block);
         float sum = accumulate ? *dst : 0.f;
-        for (int v = 0; v < vper; ++v) sum += part[(size_t)v * n + i];
+        for (int v = 0; v < j.vper; ++v) sum += j.part[(size_t)v * n + i];
         *dst = sum;
     }
 }
 }  // namespace
 
-void launch_sum_partial_stats(const int32_t* e_woff, const float* part, float* stats, int count, int vper, int block,
-                              bool accumulate, hipStream_t s) {
-    const int n = count * block;
-    hipLaunchKernelGGL(k_sum_partial_stats, dim3((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024), dim3(256), 0, s, e_woff,
-                       part, stats, count, vper, block, accumulate ? 1 : 0);
+void launch_sum_partial_stats(const PartialSumList& jobs, float* stats, bool accumulate, hipStream_t s) {
+    if (jobs.n == 0) return;
+    size_t most = 0;
+    for (int i = 0; i < jobs.n; ++i) most = std::max(most, (size_t)jobs.job[i].count * jobs.job[i].block);
+    const unsigned bx = (unsigned)std::min<size_t>((most + 255) / 256, 1024);
+    hipLaunchKernelGGL(k_sum_partial_stats, dim3(bx, jobs.n), dim3(256), 0, s, jobs, stats, accumulate ? 1 : 0);
 }
 
 template <int K8>
 static void launch_einsum_backward_k8(const DevTables& t, int first, int count, bool accumulate, const float* params,
                                       float* stats, const float* A, const double* Off, const float* amax,
-                                      const float* G, float* Gp, float* part, const Dims& d, hipStream_t s) {
+                                      const float* G, float* Gp, float* part, PartialSumList* jobs, const Dims& d,
+                                      hipStream_t s) {
     using LY = BwdSLayout<K8>;
     const size_t lds = sizeof(float) * LY::LDS_FLOATS;
     static std::once_flag attr_set[EINET_MAX_DEVICES];
@@ -1082,7 +1085,7 @@ static void launch_einsum_backward_k8(const DevTables& t, int first, int count, 
         allow_dynamic_lds(&k_einsum_backward_s<K8, true>, lds);
         allow_dynamic_lds(&k_einsum_backward_s<K8, false>, lds);
     });
-    const int vper = part ? bwd_virtual_items(count, d.K, d.B) : 1;
+    const int vper = part && jobs && jobs->n < PARTIAL_SUM_JOBS ? bwd_virtual_items(count, d.K, d.B) : 1;
     const int nchunks = (d.B + 127) / 128, cpv = (nchunks + vper - 1) / vper;
     const int grid = vper > 1 ? count * vper * (d.K / 4) : bwd_split_grid(count, d.K);
 #define EINET_LAUNCH(ACC)                                                                                         \
@@ -1091,9 +1094,9 @@ static void launch_einsum_backward_k8(const DevTables& t, int first, int count, 
                        t.ein_voff + first, t.ein_vstr + first, params, stats, A, Off, amax, G, Gp, first, count, d.B, \
                        vper, cpv, part)
     if (vper > 1) {
-        // (the blocks are written, not added to; the sum that follows adds to the statistics or overwrites them)
+        // (the blocks are written, not added to; their sum, later, adds to the statistics or overwrites them)
         EINET_LAUNCH(false);
-        launch_sum_partial_stats(t.ein_woff + first, part, stats, count, vper, d.K * d.K * d.K, accumulate, s);
+        jobs->job[jobs->n++] = PartialSumJob{t.ein_woff + first, part, count, vper, d.K * d.K * d.K};
     } else if (accumulate) EINET_LAUNCH(true);
     else EINET_LAUNCH(false);
 #undef EINET_LAUNCH
@@ -1101,12 +1104,12 @@ static void launch_einsum_backward_k8(const DevTables& t, int first, int count, 
 
 void launch_einsum_backward(const DevTables& t, int first, int count, bool full_k, bool accumulate,
                             const float* params, float* stats, const float* A, const double* Off, const float* amax,
-                            const float* G, float* Gp, float* part, const Dims& d, hipStream_t s) {
+                            const float* G, float* Gp, float* part, PartialSumList* jobs, const Dims& d, hipStream_t s) {
     if (count == 0) return;
     if (bwd_uses_split_kernel(d.K, full_k)) {
         switch (d.K / 8) {
 #define EINET_CASE(J) \
-        case J: launch_einsum_backward_k8<J>(t, first, count, accumulate, params, stats, A, Off, amax, G, Gp, part, d, s); return;
+        case J: launch_einsum_backward_k8<J>(t, first, count, accumulate, params, stats, A, Off, amax, G, Gp, part, jobs, d, s); return;
             EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5)
 #undef EINET_CASE
         }

@@ -77,12 +77,14 @@ inline bool root_kernels_apply(int n_partitions, int K) {
 // Bottom-up: S~, shifts and offsets of every partition (Eq. 3-5), then the root's mixture (App. B) and log P.
 void launch_root_forward(const DevTables& t, int n_partitions, const float* params, float* A, double* Off, float* amax,
                          float* logp, const Dims& d, hipStream_t s);
+struct PartialSumList;   // sums of statistics blocks left for the end of a top-down pass (below)
 // Top-down: weight statistics (Eq. 6) and child posteriors of the root's partitions; the root's posterior is 1 and its
 // mixing step is folded in.  Writes the posterior blocks that launch_einsum_backward writes for a layer of
 // n_partitions items with one output entry each (bwd_groups_per_item workgroups and right-child blocks per item).
-// e_woff: the weight offsets of the layer's items in order (for the sum of the virtual items' blocks); part as for
-// launch_einsum_backward (at least 256 K^2 floats), or null.
-void launch_root_backward(const DevTables& t, int n_partitions, const int32_t* e_woff, float* part, bool accumulate, const float* params, float* stats,
+// e_woff: the weight offsets of the layer's items in order (for the sum of the virtual items' blocks); part, jobs as
+// for launch_einsum_backward (root_bwd_partial_bound floats), or null.
+void launch_root_backward(const DevTables& t, int n_partitions, const int32_t* e_woff, float* part, PartialSumList* jobs,
+                          bool accumulate, const float* params, float* stats,
                           const float* A, const double* Off, const float* amax, float* Gp, const Dims& d, hipStream_t s);
 
 // Every top-down region also has a record of RB_REC_INTS ints in rb_rec: node, entries, number of parent blocks,
@@ -92,10 +94,11 @@ void launch_region_assemble(const DevTables& t, int first, int count, bool is_ro
                             const Dims& d, hipStream_t s);
 // accumulate = false: the weight statistics of these items are known to be zero and are overwritten.
 // full_k: every item of the launch has K output entries (all layers but the root's).
-// part: bwd_partial_floats(K) floats of scratch, or null (then the chunks of an item are always walked in turn).
+// part: bwd_partial_bound floats of scratch for the blocks of virtual items, or null (then the chunks of an item are
+// always walked in turn); with virtual items the sum of the blocks is appended to *jobs, not launched.
 void launch_einsum_backward(const DevTables& t, int first, int count, bool full_k, bool accumulate,
                             const float* params, float* stats, const float* A, const double* Off, const float* amax,
-                            const float* G, float* Gp, float* part, const Dims& d, hipStream_t s);
+                            const float* G, float* Gp, float* part, PartialSumList* jobs, const Dims& d, hipStream_t s);
 // posterior blocks ([B][K] floats each) reserved per einsum item in Gp: one for its left child, then up to
 // one per slice of four left entries for its right child
 inline int gp_blocks_per_item(int K) { return 1 + (K + 3) / 4; }
@@ -120,9 +123,9 @@ inline int bwd_split_grid(int count, int K) {
 // A layer of so few items that its pairs leave more than half of the compute units idle, with a batch of several
 // chunks of 128 samples: every item is launched as this many virtual items, each with a share of the chunks, one
 // workgroup per (virtual item, slice), at most 256 in all.  The virtual items of an item write their statistics to
-// blocks of their own (at most bwd_partial_floats(K) floats together), which a second launch adds up in a fixed order.
-// The second launch costs about 4 us, so the split is taken only where the chunks a workgroup no longer walks are worth
-// twice that: a workgroup spends roughly bwd_unit_us(K) on one chunk of one slice (10 us at K = 40, measured; the
+// blocks of their own (bwd_partial_bound floats together), which a later launch adds up in a fixed order.
+// That launch costs about 4 us (one for all layers of a pass), so the split is taken only where the chunks a workgroup
+// no longer walks are worth twice that: a workgroup spends roughly bwd_unit_us(K) on one chunk of one slice (10 us at K = 40, measured; the
 // work grows with K^2), half of that in the root's layer.
 constexpr float BWD_SPLIT_PAYS_US = 8.f;
 inline float bwd_unit_us(int K) { return 1.f + 9.f * (float)(K * K) / 1600.f; }
@@ -135,10 +138,23 @@ inline int bwd_virtual_items(int count, int K, int B) {
     if ((float)(nchunks - cpv) * bwd_unit_us(K) < BWD_SPLIT_PAYS_US) return 1;
     return (nchunks + cpv - 1) / cpv;
 }
-inline size_t bwd_partial_floats(int K) { return (size_t)1024 * K * K; }   // >= (256 / pairs) * count * K^3
-// stats[e_woff[item] + r] (+)= sum over v < vper of part[(v * count + item) * block + r], r < block
-void launch_sum_partial_stats(const int32_t* e_woff, const float* part, float* stats, int count, int vper, int block,
-                              bool accumulate, hipStream_t s);
+// The sums of the blocks are not needed before the M-step, so the launches of a top-down pass only note them down
+// and one launch at the end of the pass does them all: per job,
+//   stats[e_woff[item] + r] (+)= sum over v < vper of part[(v * count + item) * block + r], r < block.
+constexpr int PARTIAL_SUM_JOBS = 8;
+struct PartialSumJob {
+    const int32_t* e_woff;
+    const float* part;
+    int count, vper, block;
+};
+struct PartialSumList {
+    int n = 0;
+    PartialSumJob job[PARTIAL_SUM_JOBS];
+};
+void launch_sum_partial_stats(const PartialSumList& jobs, float* stats, bool accumulate, hipStream_t s);
+// floats of scratch that a layer's launch needs for its blocks with any batch up to max_B (0: never virtual items)
+inline size_t bwd_partial_bound(int count, int K, int max_B, bool full_k);
+inline size_t root_bwd_partial_bound(int n_partitions, int K, int max_B);
 // The same for the root's layer (n_partitions items of K^2 weights, bwd_groups_per_item workgroups each): shares of
 // the chunks of 128 samples per workgroup when the launch would leave half of the compute units idle.
 inline int root_bwd_virtual_items(int n_partitions, int K, int B) {
@@ -161,6 +177,18 @@ inline int bwd_blocks_of_item(int count, int K, bool full_k, int li) {
     if (!bwd_uses_split_kernel(K, full_k)) return bwd_groups_per_item(count, K);
     const long long ns = K / 4, P = (long long)count * ns, G = bwd_split_grid(count, K);
     return bwds_wg_of_pair((li + 1) * ns - 1, P, G) - bwds_wg_of_pair(li * ns, P, G) + 1;
+}
+inline size_t bwd_partial_bound(int count, int K, int max_B, bool full_k) {
+    const int pairs = count * (K / 4), nchunks = (max_B + 127) / 128;
+    if (!bwd_uses_split_kernel(K, full_k) || pairs <= 0 || pairs > 128 || nchunks < 2) return 0;
+    const int v = 256 / pairs < nchunks ? 256 / pairs : nchunks;
+    return (size_t)v * count * K * K * K;
+}
+inline size_t root_bwd_partial_bound(int n_partitions, int K, int max_B) {
+    const int wgs = n_partitions * bwd_groups_per_item(n_partitions, K), nchunks = (max_B + 127) / 128;
+    if (wgs <= 0 || wgs > 128 || nchunks < 2) return 0;
+    const int v = 256 / wgs < nchunks ? 256 / wgs : nchunks;
+    return (size_t)v * n_partitions * K * K;
 }
 // Leaf statistics on the matrix pipe (nothing marginalised, scopes of at least 512 (variable, channel) pairs): with
 // so few leaves that the workgroups of the launch (one per leaf and 64 or 128 pairs) leave half of the compute units

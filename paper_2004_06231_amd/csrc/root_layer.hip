@@ -391,9 +391,9 @@ void launch_root_forward_kq(const DevTables& t, int n_partitions, const float* p
 }
 
 template <int KQ>
-void launch_root_backward_kq(const DevTables& t, int n_partitions, const int32_t* e_woff, float* part, bool accumulate,
-                             const float* params, float* stats, const float* A, const double* Off, const float* amax,
-                             float* Gp, const Dims& d, hipStream_t s) {
+void launch_root_backward_kq(const DevTables& t, int n_partitions, const int32_t* e_woff, float* part,
+                             PartialSumList* jobs, bool accumulate, const float* params, float* stats, const float* A,
+                             const double* Off, const float* amax, float* Gp, const Dims& d, hipStream_t s) {
     const size_t lds = sizeof(float) * RootBwdLayout<KQ>::LDS_FLOATS;
     if (lds > 64 * 1024) {
         static std::once_flag attr_set[EINET_MAX_DEVICES];
@@ -402,13 +402,13 @@ void launch_root_backward_kq(const DevTables& t, int n_partitions, const int32_t
         std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] { allow_dynamic_lds(&k_root_backward<KQ>, lds); });
     }
     const int ngroups = bwd_groups_per_item(n_partitions, d.K);
-    const int vper = part ? root_bwd_virtual_items(n_partitions, d.K, d.B) : 1;
+    const int vper = part && jobs && jobs->n < PARTIAL_SUM_JOBS ? root_bwd_virtual_items(n_partitions, d.K, d.B) : 1;
     const int nchunks = (d.B + RB_BC - 1) / RB_BC, cpv = (nchunks + vper - 1) / vper;
-    // (with virtual items the blocks are written, never added to; the sum adds to the statistics or overwrites them)
+    // (with virtual items the blocks are written, never added to; their sum, later, adds to the statistics or overwrites them)
     hipLaunchKernelGGL(k_root_backward<KQ>, dim3(n_partitions * ngroups * vper), dim3(RB_THREADS), lds, s, t.root_rec, params,
                        stats, A, Off, amax, Gp, ngroups, vper > 1 ? 0 : (accumulate ? 1 : 0), d.B, d.K, vper, cpv, part,
                        n_partitions);
-    if (vper > 1) launch_sum_partial_stats(e_woff, part, stats, n_partitions, vper, d.K * d.K, accumulate, s);
+    if (vper > 1) jobs->job[jobs->n++] = PartialSumJob{e_woff, part, n_partitions, vper, d.K * d.K};
 }
 
 }  // namespace
@@ -425,12 +425,12 @@ void launch_root_forward(const DevTables& t, int n_partitions, const float* para
     }
 }
 
-void launch_root_backward(const DevTables& t, int n_partitions, const int32_t* e_woff, float* part, bool accumulate,
-                          const float* params, float* stats,
+void launch_root_backward(const DevTables& t, int n_partitions, const int32_t* e_woff, float* part, PartialSumList* jobs,
+                          bool accumulate, const float* params, float* stats,
                           const float* A, const double* Off, const float* amax, float* Gp, const Dims& d, hipStream_t s) {
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
-    case J: launch_root_backward_kq<J>(t, n_partitions, e_woff, part, accumulate, params, stats, A, Off, amax, Gp, d, s); break;
+    case J: launch_root_backward_kq<J>(t, n_partitions, e_woff, part, jobs, accumulate, params, stats, A, Off, amax, Gp, d, s); break;
         EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
         EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
         EINET_CASE(16)

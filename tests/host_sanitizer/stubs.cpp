@@ -30,12 +30,12 @@ void launch_einsum_forward(const DevTables&, int, int, bool, const float*, float
 void launch_mixing_forward(const DevTables&, int, int, int, const float*, float*, double*, float*, const Dims&,
                            hipStream_t) {}
 void launch_root_forward(const DevTables&, int, const float*, float*, double*, float*, float*, const Dims&, hipStream_t) {}
-void launch_root_backward(const DevTables&, int, const int32_t*, float*, bool, const float*, float*, const float*,
-                          const double*, const float*, float*, const Dims&, hipStream_t) {}
-void launch_sum_partial_stats(const int32_t*, const float*, float*, int, int, int, bool, hipStream_t) {}
+void launch_root_backward(const DevTables&, int, const int32_t*, float*, PartialSumList*, bool, const float*, float*,
+                          const float*, const double*, const float*, float*, const Dims&, hipStream_t) {}
+void launch_sum_partial_stats(const PartialSumList&, float*, bool, hipStream_t) {}
 void launch_region_assemble(const DevTables&, int, int, bool, float*, const float*, const Dims&, hipStream_t) {}
 void launch_einsum_backward(const DevTables&, int, int, bool, bool, const float*, float*, const float*, const double*,
-                            const float*, const float*, float*, float*, const Dims&, hipStream_t) {}
+                            const float*, const float*, float*, float*, PartialSumList*, const Dims&, hipStream_t) {}
 void launch_tail_backward(const DevTables&, int, int, int, int, int, const float*, const uint8_t*, int, const float*,
                           const float*, const double*, const float*, float*, int64_t, int64_t, int64_t, int64_t, float*,
                           size_t, const Dims&, hipStream_t) {}
