@@ -449,8 +449,10 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
                                                 : reinterpret_cast<float*>(h->ws + h->off_part) + h->part_off[l];
     };
     for (int l = p.num_layers - 1, step = 0; l >= 0; --l, ++step) {
-        // (the top sum layer is the root alone: nothing to launch when its ones are still in place)
-        if (step > 0 || B > h->root_ones_batch)
+        // (the top sum layer is the root alone: nothing to launch when its ones are still in place; nor for a layer
+        // whose einsum kernel adds up the parents' blocks itself)
+        const bool direct = p.ein_layer_direct[l] != 0;
+        if (!direct && (step > 0 || B > h->root_ones_batch))
             run(h, KC_REGION_BWD, s, [&] {
                 launch_region_assemble(h->dt, p.rb_layer_ptr[step], p.rb_layer_ptr[step + 1] - p.rb_layer_ptr[step],
                                        step == 0, G, Gp, d, s);
@@ -469,7 +471,7 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
         run(h, KC_EINSUM_BWD, s, [&] {
             launch_einsum_backward(h->dt, p.ein_layer_ptr[l], p.ein_layer_ptr[l + 1] - p.ein_layer_ptr[l],
                                    p.ein_layer_full[l] != 0, !h->weight_stats_zero, h->params, h->stats, A, Off, amax, G, Gp,
-                                   layer_part(l), &sums, d, s);
+                                   layer_part(l), &sums, direct, d, s);
             // after the last layer: the statistics blocks of the launches that ran virtual items, all layers in one
             // launch (before the leaf statistics, whose batch groups use the same scratch)
             if (l == 0) launch_sum_partial_stats(sums, h->stats, !h->weight_stats_zero, s);

@@ -133,14 +133,14 @@ __device__ __forceinline__ void bwd_gemm1(floatx4* acc1, const float* const* qco
     }
 }
 
-template <int KQ, bool VEC, bool ACCUM>
+template <int KQ, bool VEC, bool ACCUM, bool DIRECT>
 __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     const int32_t* __restrict__ e_left, const int32_t* __restrict__ e_right, const int32_t* __restrict__ e_out,
     const int32_t* __restrict__ e_reg, const int32_t* __restrict__ e_kout, const int32_t* __restrict__ e_woff,
-    const int32_t* __restrict__ e_voff, const int32_t* __restrict__ e_vstr, const float* __restrict__ params,
-    float* __restrict__ stats, const float* __restrict__ A, const double* __restrict__ Off,
-    const float* __restrict__ amax, const float* __restrict__ G, float* __restrict__ Gp, int item0, int ngroups, int B,
-    int K) {
+    const int32_t* __restrict__ e_voff, const int32_t* __restrict__ e_vstr, const int32_t* __restrict__ e_gsrc,
+    const float* __restrict__ params, float* __restrict__ stats, const float* __restrict__ A,
+    const double* __restrict__ Off, const float* __restrict__ amax, const float* __restrict__ G, float* __restrict__ Gp,
+    int item0, int ngroups, int B, int K) {
     using LY = BwdLayout<KQ>;
     constexpr int KP = LY::KP, SI = LY::SI, S = LY::S, ST = LY::ST, BC = LY::BC, MAXU = LY::MAXU;
     extern __shared__ float lds[];
@@ -160,7 +160,10 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
     const float* Lp = A + (size_t)e_left[li] * blk;
     const float* Rp = A + (size_t)e_right[li] * blk;
     const float* As = A + (size_t)e_reg[li] * blk;
-    const float* Gs = G + (size_t)e_reg[li] * blk;
+    // posterior of the item's region: assembled in G, or (DIRECT) the sum of gcnt consecutive blocks that the
+    // region's only parent wrote to Gp, added up in the order the assembly launch would take
+    const int gsrc = DIRECT ? e_gsrc[li] : 0, gcnt = gsrc & 7;
+    const float* Gs = DIRECT ? Gp + (size_t)(gsrc >> 3) * blk : G + (size_t)e_reg[li] * blk;
     const float* W = params + e_woff[li];
     const size_t wbase = (size_t)e_woff[li];
     const int voff = e_voff[li], vstr = e_vstr[li];
@@ -254,6 +257,21 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
                 const int row = f / KQ, k4 = f - row * KQ;
                 r4[n] = *reinterpret_cast<const float4*>(Rp + (size_t)(b0 + row) * K + 4 * k4);
                 g4[n] = *reinterpret_cast<const float4*>(Gs + (size_t)(b0 + row) * K + 4 * k4);
+                if (DIRECT && gcnt > 1) {
+                    float4 gx[GSRC_MAX_BLOCKS - 1];
+#pragma unroll
+                    for (int x = 1; x < GSRC_MAX_BLOCKS; ++x)
+                        gx[x - 1] = *reinterpret_cast<const float4*>(Gs + (x < gcnt ? x : 0) * blk +
+                                                                      (size_t)(b0 + row) * K + 4 * k4);
+#pragma unroll
+                    for (int x = 1; x < GSRC_MAX_BLOCKS; ++x)
+                        if (x < gcnt) {
+                            g4[n].x += gx[x - 1].x;
+                            g4[n].y += gx[x - 1].y;
+                            g4[n].z += gx[x - 1].z;
+                            g4[n].w += gx[x - 1].w;
+                        }
+                }
                 a4[n] = *reinterpret_cast<const float4*>(As + (size_t)(b0 + row) * K + 4 * k4);
                 arn[n] = aR[b0 + row];
                 ddn[n] = (float)(Oo[b0 + row] - Os[b0 + row]);
@@ -298,6 +316,14 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
                 const int kc = min(k, K - 1);
                 rv[u] = Rp[ro + kc];
                 gv[u] = Gs[ro + min(kc, kout - 1)];
+                if (DIRECT && gcnt > 1) {
+                    float gx[GSRC_MAX_BLOCKS - 1];
+#pragma unroll
+                    for (int x = 1; x < GSRC_MAX_BLOCKS; ++x) gx[x - 1] = Gs[(x < gcnt ? x : 0) * blk + ro + min(kc, kout - 1)];
+#pragma unroll
+                    for (int x = 1; x < GSRC_MAX_BLOCKS; ++x)
+                        if (x < gcnt) gv[u] += gx[x - 1];
+                }
                 av[u] = As[ro + min(kc, kout - 1)];
             }
 #pragma unroll
@@ -1018,25 +1044,35 @@ void launch_region_assemble(const DevTables& t, int first, int count, bool is_ro
 template <int KQ>
 static void launch_einsum_backward_kq(const DevTables& t, int first, int count, bool accumulate,
                                       const float* params, float* stats, const float* A, const double* Off,
-                                      const float* amax, const float* G, float* Gp, const Dims& d, hipStream_t s) {
+                                      const float* amax, const float* G, float* Gp, bool direct, const Dims& d,
+                                      hipStream_t s) {
     const size_t lds = sizeof(float) * BwdLayout<KQ>::LDS_FLOATS;
     if (lds > 64 * 1024) {
         static std::once_flag attr_set[EINET_MAX_DEVICES];
         int dev = 0;
         (void)hipGetDevice(&dev);
         std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] {
-            allow_dynamic_lds(&k_einsum_backward<KQ, true, true>, lds);
-            allow_dynamic_lds(&k_einsum_backward<KQ, false, true>, lds);
-            allow_dynamic_lds(&k_einsum_backward<KQ, true, false>, lds);
-            allow_dynamic_lds(&k_einsum_backward<KQ, false, false>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, true, true, false>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, false, true, false>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, true, false, false>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, false, false, false>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, true, true, true>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, false, true, true>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, true, false, true>, lds);
+            allow_dynamic_lds(&k_einsum_backward<KQ, false, false, true>, lds);
         });
     }
     const int ngroups = bwd_groups_per_item(count, d.K);
-#define EINET_LAUNCH(V, ACC)                                                                                      \
-    hipLaunchKernelGGL((k_einsum_backward<KQ, V, ACC>), dim3(count * ngroups), dim3(512), lds, s, t.ein_left + first,  \
+#define EINET_LAUNCH_D(V, ACC, DIR)                                                                               \
+    hipLaunchKernelGGL((k_einsum_backward<KQ, V, ACC, DIR>), dim3(count * ngroups), dim3(512), lds, s, t.ein_left + first,  \
                        t.ein_right + first, t.ein_out + first, t.ein_reg + first, t.ein_kout + first,                 \
-                       t.ein_woff + first, t.ein_voff + first, t.ein_vstr + first, params, stats, A, Off, amax, G, Gp,  \
-                       first, ngroups, d.B, d.K)
+                       t.ein_woff + first, t.ein_voff + first, t.ein_vstr + first,                                    \
+                       t.ein_gsrc + first, params, stats, A, Off, amax, G, Gp, first, ngroups, d.B, d.K)
+#define EINET_LAUNCH(V, ACC)                   \
+    do {                                       \
+        if (direct) EINET_LAUNCH_D(V, ACC, true); \
+        else EINET_LAUNCH_D(V, ACC, false);    \
+    } while (0)
     if ((d.K & 3) == 0) {
         if (accumulate) EINET_LAUNCH(true, true);
         else EINET_LAUNCH(true, false);
@@ -1045,6 +1081,7 @@ static void launch_einsum_backward_kq(const DevTables& t, int first, int count, 
         else EINET_LAUNCH(false, false);
     }
 #undef EINET_LAUNCH
+#undef EINET_LAUNCH_D
 }
 
 // stats[item][r] (+)= sum over the vper blocks of part[.][item][r], job blockIdx.y of the list: the launch at the end of
@@ -1104,7 +1141,8 @@ static void launch_einsum_backward_k8(const DevTables& t, int first, int count, 
 
 void launch_einsum_backward(const DevTables& t, int first, int count, bool full_k, bool accumulate,
                             const float* params, float* stats, const float* A, const double* Off, const float* amax,
-                            const float* G, float* Gp, float* part, PartialSumList* jobs, const Dims& d, hipStream_t s) {
+                            const float* G, float* Gp, float* part, PartialSumList* jobs, bool direct, const Dims& d,
+                            hipStream_t s) {
     if (count == 0) return;
     if (bwd_uses_split_kernel(d.K, full_k)) {
         switch (d.K / 8) {
@@ -1116,7 +1154,7 @@ void launch_einsum_backward(const DevTables& t, int first, int count, bool full_
     }
     switch ((d.K + 3) / 4) {
 #define EINET_CASE(J) \
-    case J: launch_einsum_backward_kq<J>(t, first, count, accumulate, params, stats, A, Off, amax, G, Gp, d, s); break;
+    case J: launch_einsum_backward_kq<J>(t, first, count, accumulate, params, stats, A, Off, amax, G, Gp, direct, d, s); break;
         EINET_CASE(1) EINET_CASE(2) EINET_CASE(3) EINET_CASE(4) EINET_CASE(5) EINET_CASE(6) EINET_CASE(7) EINET_CASE(8)
         EINET_CASE(9) EINET_CASE(10) EINET_CASE(11) EINET_CASE(12) EINET_CASE(13) EINET_CASE(14) EINET_CASE(15)
         EINET_CASE(16)

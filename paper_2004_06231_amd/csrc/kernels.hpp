@@ -14,6 +14,7 @@ namespace einet_impl {
 // the float32 bit patterns of log C(N, v), v = 0..N, for binomial leaves.
 #define EINET_TABLES(X)                                                                                    \
     X(ein_left) X(ein_right) X(ein_out) X(ein_reg) X(ein_kout) X(ein_woff) X(ein_voff) X(ein_vstr) X(ein_part) \
+    X(ein_gsrc)                                                                                            \
     X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff) X(mix_rec)                                \
     X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
     X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len) X(leaf_logc)                         \
@@ -93,12 +94,20 @@ constexpr int RB_REC_INTS = 32, RB_REC_BLOCKS = 28;
 void launch_region_assemble(const DevTables& t, int first, int count, bool is_root_layer, float* G, const float* Gp,
                             const Dims& d, hipStream_t s);
 // accumulate = false: the weight statistics of these items are known to be zero and are overwritten.
+// direct: the posterior of every item's region is not in G; the kernel adds up the parent's blocks itself, as
+// ein_gsrc says (only layers with Plan::ein_layer_direct set; then no launch_region_assemble for their regions).
 // full_k: every item of the launch has K output entries (all layers but the root's).
 // part: bwd_partial_bound floats of scratch for the blocks of virtual items, or null (then the chunks of an item are
 // always walked in turn); with virtual items the sum of the blocks is appended to *jobs, not launched.
 void launch_einsum_backward(const DevTables& t, int first, int count, bool full_k, bool accumulate,
                             const float* params, float* stats, const float* A, const double* Off, const float* amax,
-                            const float* G, float* Gp, float* part, PartialSumList* jobs, const Dims& d, hipStream_t s);
+                            const float* G, float* Gp, float* part, PartialSumList* jobs, bool direct, const Dims& d,
+                            hipStream_t s);
+// A region with one partition and one parent partition (every inner region of a random binary tree) has its
+// posterior in at most GSRC_MAX_BLOCKS consecutive blocks of Gp, written by that parent.  The top-down einsum kernel
+// of its partition can add them up while it stages its operands, which saves the launch that would assemble G for
+// the layer.  ein_gsrc[item] = (first block << 3) | number of blocks, 0 when the region does not qualify.
+constexpr int GSRC_MAX_BLOCKS = 6;
 // posterior blocks ([B][K] floats each) reserved per einsum item in Gp: one for its left child, then up to
 // one per slice of four left entries for its right child
 inline int gp_blocks_per_item(int K) { return 1 + (K + 3) / 4; }

@@ -385,6 +385,22 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param
         runs[g.partition[n][1]].push_back({e * nb, 1});
         runs[g.partition[n][2]].push_back({e * nb + 1, groups});
     }
+    // ---- layers whose regions need no assembled posterior (see GSRC_MAX_BLOCKS)
+    p.ein_gsrc.assign(np, 0);
+    p.ein_layer_direct.assign(p.num_layers, 0);
+    for (int l = 0; l + 1 < p.num_layers; ++l) {       // (the root's layer has a kernel of its own)
+        bool all = !bwd_uses_split_kernel(K, p.ein_layer_full[l] != 0);
+        for (int e = p.ein_layer_ptr[l]; e < p.ein_layer_ptr[l + 1]; ++e) {
+            const int s = g.partition[p.ein_part[e]][0];
+            if (g.parts_of[s].size() == 1 && runs[s].size() == 1 && runs[s][0].second <= GSRC_MAX_BLOCKS)
+                p.ein_gsrc[e] = (runs[s][0].first << 3) | runs[s][0].second;
+            else
+                all = false;
+        }
+        p.ein_layer_direct[l] = all ? 1 : 0;
+        if (!all)
+            for (int e = p.ein_layer_ptr[l]; e < p.ein_layer_ptr[l + 1]; ++e) p.ein_gsrc[e] = 0;
+    }
     p.rb_layer_ptr.push_back(0);
     p.rb_pptr.push_back(0);
     auto push_region = [&](int s) {

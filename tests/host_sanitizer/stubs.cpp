@@ -35,7 +35,7 @@ void launch_root_backward(const DevTables&, int, const int32_t*, float*, Partial
 void launch_sum_partial_stats(const PartialSumList&, float*, bool, hipStream_t) {}
 void launch_region_assemble(const DevTables&, int, int, bool, float*, const float*, const Dims&, hipStream_t) {}
 void launch_einsum_backward(const DevTables&, int, int, bool, bool, const float*, float*, const float*, const double*,
-                            const float*, const float*, float*, float*, PartialSumList*, const Dims&, hipStream_t) {}
+                            const float*, const float*, float*, float*, PartialSumList*, bool, const Dims&, hipStream_t) {}
 void launch_tail_backward(const DevTables&, int, int, int, int, int, const float*, const uint8_t*, int, const float*,
                           const float*, const double*, const float*, float*, int64_t, int64_t, int64_t, int64_t, float*,
                           size_t, const Dims&, hipStream_t) {}
