@@ -478,14 +478,16 @@ int einet_em_accumulate(einet_t* h, const float* x_dev, const uint8_t* mask_dev,
         }, layer_outputs(p, l));
     }
     const int leaf_step = p.num_layers;
-    run(h, KC_REGION_BWD, s, [&] {
-        launch_region_assemble(h->dt, p.rb_layer_ptr[leaf_step],
-                               p.rb_layer_ptr[leaf_step + 1] - p.rb_layer_ptr[leaf_step], false, G, Gp, d, s);
-    });
+    if (!p.leaves_direct)
+        run(h, KC_REGION_BWD, s, [&] {
+            launch_region_assemble(h->dt, p.rb_layer_ptr[leaf_step],
+                                   p.rb_layer_ptr[leaf_step + 1] - p.rb_layer_ptr[leaf_step], false, G, Gp, d, s);
+        });
     run(h, KC_LEAF_BWD, s, [&] {
         launch_tail_backward(h->dt, (int)p.lv_leaf.size(), (int)p.leaf_node.size(), p.max_leaf_scope,
                              (int)p.mix_node.size(), p.max_mix_children, x_dev, mask_dev,
-                             mask_mode, h->params, A, Off, G, h->stats, p.phi_offset, p.den_offset, p.tot_offset, p.n_stats,
+                             mask_mode, h->params, A, Off, G, Gp, p.leaves_direct, h->stats, p.phi_offset, p.den_offset,
+                             p.tot_offset, p.n_stats,
                              h->has_part ? reinterpret_cast<float*>(h->ws + h->off_part) : nullptr, h->part_floats, d, s);
     });
     rc = check_hip(h, "einet_em_accumulate");

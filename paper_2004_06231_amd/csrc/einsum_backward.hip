@@ -261,8 +261,8 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
                     float4 gx[GSRC_MAX_BLOCKS - 1];
 #pragma unroll
                     for (int x = 1; x < GSRC_MAX_BLOCKS; ++x)
-                        gx[x - 1] = *reinterpret_cast<const float4*>(Gs + (x < gcnt ? x : 0) * blk +
-                                                                      (size_t)(b0 + row) * K + 4 * k4);
+                        gx[x - 1] = x < gcnt ? *reinterpret_cast<const float4*>(Gs + x * blk + (size_t)(b0 + row) * K + 4 * k4)
+                                             : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
                     for (int x = 1; x < GSRC_MAX_BLOCKS; ++x)
                         if (x < gcnt) {
@@ -319,7 +319,7 @@ __global__ __launch_bounds__(512, 2) void k_einsum_backward(
                 if (DIRECT && gcnt > 1) {
                     float gx[GSRC_MAX_BLOCKS - 1];
 #pragma unroll
-                    for (int x = 1; x < GSRC_MAX_BLOCKS; ++x) gx[x - 1] = Gs[(x < gcnt ? x : 0) * blk + ro + min(kc, kout - 1)];
+                    for (int x = 1; x < GSRC_MAX_BLOCKS; ++x) gx[x - 1] = x < gcnt ? Gs[x * blk + ro + min(kc, kout - 1)] : 0.f;
 #pragma unroll
                     for (int x = 1; x < GSRC_MAX_BLOCKS; ++x)
                         if (x < gcnt) gv[u] += gx[x - 1];

@@ -14,7 +14,7 @@ namespace einet_impl {
 // the float32 bit patterns of log C(N, v), v = 0..N, for binomial leaves.
 #define EINET_TABLES(X)                                                                                    \
     X(ein_left) X(ein_right) X(ein_out) X(ein_reg) X(ein_kout) X(ein_woff) X(ein_voff) X(ein_vstr) X(ein_part) \
-    X(ein_gsrc)                                                                                            \
+    X(ein_gsrc) X(leaf_gsrc)                                                                               \
     X(mix_node) X(mix_kout) X(mix_cptr) X(mix_child) X(mix_voff) X(mix_rec)                                \
     X(leaf_node) X(leaf_replica) X(leaf_sptr) X(leaf_var) X(lv_leaf) X(lv_var)                             \
     X(rb_node) X(rb_kout) X(rb_pptr) X(rb_pblk) X(row_off) X(row_len) X(leaf_logc)                         \
@@ -219,11 +219,14 @@ inline int leaf_stats_groups(int n_leaves, int max_scope, int C, int K, int B) {
 }
 // leaf statistics and mixing statistics (independent of each other) in one launch
 // part: part_floats floats of scratch for the blocks of the batch groups above, or null; n_stats: length of stats.
+// direct: the leaves' posteriors are not in G; the element-wise forms of the leaf statistics add up the parents'
+// blocks of Gp themselves, as leaf_gsrc says (only with Plan::leaves_direct, which also keeps the scopes below the
+// 512 pairs from which the matrix-pipe form, which reads G, can be chosen).
 void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_scope, int n_mix, int max_children,
                           const float* x, const uint8_t* mask, int mask_mode, const float* params, const float* A,
-                          const double* Off, const float* G, float* stats, int64_t phi_off, int64_t den_off,
-                          int64_t tot_off, int64_t n_stats, float* part, size_t part_floats, const Dims& d,
-                          hipStream_t s);
+                          const double* Off, const float* G, const float* Gp, bool direct, float* stats,
+                          int64_t phi_off, int64_t den_off, int64_t tot_off, int64_t n_stats, float* part,
+                          size_t part_floats, const Dims& d, hipStream_t s);
 // the whole M-step in one launch; the statistics of the first n_lazy_rows weight rows are left as they
 // are (the next E-step overwrites them); when no E-step has run since they were last consumed
 // (lazy_rows_are_zero) those rows count as zero and their weights are kept

@@ -83,11 +83,14 @@ __device__ __forceinline__ void mixing_stats_body(int item, int c, const int32_t
 // Posterior-weighted sufficient statistics (Eq. 6-7).  A workgroup of 1024 threads
 // owns 1024/NCH consecutive statistics entries (leaf variable, channel, k); its NCH
 // parts each walk every NCH-th sample and the partial sums meet in LDS.
-template <int NCH>
+// DIRECT: the leaf's posterior is not in G; it is the sum of the blocks of Gp that leaf_gsrc names (first block << 3 |
+// number of blocks, see GSRC_MAX_BLOCKS), added up in the order the assembly launch would take.
+template <int NCH, bool DIRECT>
 __device__ __forceinline__ void leaf_backward_body(
     int block, const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var, const int32_t* __restrict__ leaf_node,
     const int32_t* __restrict__ leaf_replica, int n_lv, const float* __restrict__ x,
-    const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, float* __restrict__ stats,
+    const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, const float* __restrict__ Gp,
+    const int32_t* __restrict__ leaf_gsrc, float* __restrict__ stats,
     int64_t phi_off, int64_t den_off, int64_t tot_off, Dims d) {
     constexpr int NO = 1024 / NCH;
     __shared__ float red[NCH][4][NO];
@@ -96,13 +99,23 @@ __device__ __forceinline__ void leaf_backward_body(
     const bool valid = idx < n_lv * d.C * d.K;
     const int k = valid ? idx % d.K : 0, c = valid ? (idx / d.K) % d.C : 0, e = valid ? idx / (d.K * d.C) : 0;
     const int leaf = lv_leaf[e], var = lv_var[e], r = leaf_replica[leaf];
-    const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K + k;
+    const size_t gblk = (size_t)d.B * d.K;
+    const int gsrc = DIRECT ? leaf_gsrc[leaf] : 0, gcnt = gsrc & 7;
+    const float* Gl = (DIRECT ? Gp + (size_t)(gsrc >> 3) * gblk : G + (size_t)leaf_node[leaf] * gblk) + k;
     const float* xp = x + (size_t)var * d.C + c;
     const bool shared_obs = mask_mode != EINET_MASK_SHARED || mask[var] != 0;
     float n1 = 0.f, n2 = 0.f, den = 0.f, tot = 0.f;
 #pragma unroll 4
     for (int b = part_id; b < d.B; b += NCH) {
-        const float p = Gl[(size_t)b * d.K];
+        float p = Gl[(size_t)b * d.K];
+        if (DIRECT && gcnt > 1) {
+            float px[GSRC_MAX_BLOCKS - 1];
+#pragma unroll
+            for (int q = 1; q < GSRC_MAX_BLOCKS; ++q) px[q - 1] = q < gcnt ? Gl[q * gblk + (size_t)b * d.K] : 0.f;
+#pragma unroll
+            for (int q = 1; q < GSRC_MAX_BLOCKS; ++q)
+                if (q < gcnt) p += px[q - 1];
+        }
         bool obs = shared_obs;
         if (mask_mode == EINET_MASK_PER_SAMPLE) obs = mask[(size_t)b * d.D + var] != 0;
         const float xv = xp[(size_t)b * d.D * d.C];
@@ -187,11 +200,12 @@ __host__ __device__ inline size_t cell_lds_bytes(int K, int PPT) {
            (size_t)CELL_BC * cell_pairs_per_group(K) * PPT;
 }
 
-template <int PPT>
+template <int PPT, bool DIRECT>
 __device__ __forceinline__ void leaf_backward_cells_body(
     int block, int chunks_per_leaf, const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica,
     const int32_t* __restrict__ leaf_sptr, const int32_t* __restrict__ leaf_var, const float* __restrict__ x,
-    const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, float* __restrict__ stats,
+    const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G, const float* __restrict__ Gp,
+    const int32_t* __restrict__ leaf_gsrc, float* __restrict__ stats,
     int64_t phi_off, int64_t den_off, int64_t tot_off, Dims d) {
     extern __shared__ float cell_lds[];
     const int pc = cell_pairs_per_group(d.K) * PPT;   // pairs per workgroup
@@ -206,7 +220,9 @@ __device__ __forceinline__ void leaf_backward_cells_body(
     const int np = min(pc, npairs - p0);
     const int tid = threadIdx.x;
     const int pl = (tid / d.K) * PPT, k = tid % d.K;  // this thread's first pair and its entry
-    const float* Gl = G + (size_t)leaf_node[leaf] * d.B * d.K;
+    const size_t gblk = (size_t)d.B * d.K;
+    const int gsrc = DIRECT ? leaf_gsrc[leaf] : 0, gcnt = gsrc & 7;
+    const float* Gl = DIRECT ? Gp + (size_t)(gsrc >> 3) * gblk : G + (size_t)leaf_node[leaf] * gblk;
     // the variable numbers go to LDS once, so that the loads of the values do not each wait for one
     const int vfirst = p0 / d.C, vcount = (p0 + np - 1) / d.C - vfirst + 1;
     for (int j = tid; j < vcount; j += 1024) vsl[j] = leaf_var[s0 + vfirst + j];
@@ -221,6 +237,16 @@ __device__ __forceinline__ void leaf_backward_cells_body(
             float gq[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) gq[q] = i0 + q * 1024 < nb * d.K ? Gl[(size_t)b0 * d.K + i0 + q * 1024] : 0.f;
+            if (DIRECT && gcnt > 1) {
+                for (int y = 1; y < gcnt; ++y) {       // (the same element of the next block, all four together)
+                    float gy[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        gy[q] = i0 + q * 1024 < nb * d.K ? Gl[y * gblk + (size_t)b0 * d.K + i0 + q * 1024] : 0.f;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) gq[q] += gy[q];
+                }
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 if (i0 + q * 1024 < nb * d.K) Gs[i0 + q * 1024] = gq[q];
@@ -450,11 +476,12 @@ __device__ __forceinline__ void sum_leaf_blocks_body(int blk, int n_blocks, cons
 // kernel body for long scopes (chunks_per_leaf workgroups per leaf, PPT pairs per thread), NCH = TAIL_SUMS the sum of
 // the blocks that the batch groups of k_leaf_stats_mfma left in part.
 constexpr int TAIL_SUMS = 8;
-template <int NCH, int PPT>
+template <int NCH, int PPT, bool DIRECT>
 __global__ __launch_bounds__(1024) void k_tail_backward(
     int n_leaf_blocks, int max_children, const int32_t* __restrict__ lv_leaf, const int32_t* __restrict__ lv_var,
     const int32_t* __restrict__ leaf_node, const int32_t* __restrict__ leaf_replica, int n_lv,
     const float* __restrict__ x, const uint8_t* __restrict__ mask, int mask_mode, const float* __restrict__ G,
+    const float* __restrict__ Gp, const int32_t* __restrict__ leaf_gsrc,
     float* __restrict__ stats, int64_t phi_off, int64_t den_off, int64_t tot_off, const int32_t* __restrict__ m_rec,
     const int32_t* __restrict__ m_cptr, const int32_t* __restrict__ m_child, const float* __restrict__ params,
     const float* __restrict__ A, const double* __restrict__ Off, const int32_t* __restrict__ leaf_sptr,
@@ -465,11 +492,11 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
         if constexpr (NCH == TAIL_SUMS)
             sum_leaf_blocks_body(blk, n_leaf_blocks, part, stats + phi_off, part_n, groups);
         else if constexpr (NCH == 0)
-            leaf_backward_cells_body<PPT>(blk, chunks_per_leaf, leaf_node, leaf_replica, leaf_sptr, leaf_var, x, mask,
-                                          mask_mode, G, stats, phi_off, den_off, tot_off, d);
+            leaf_backward_cells_body<PPT, DIRECT>(blk, chunks_per_leaf, leaf_node, leaf_replica, leaf_sptr, leaf_var, x,
+                                                  mask, mask_mode, G, Gp, leaf_gsrc, stats, phi_off, den_off, tot_off, d);
         else
-            leaf_backward_body<NCH>(blk, lv_leaf, lv_var, leaf_node, leaf_replica, n_lv, x, mask, mask_mode, G, stats,
-                                    phi_off, den_off, tot_off, d);
+            leaf_backward_body<NCH, DIRECT>(blk, lv_leaf, lv_var, leaf_node, leaf_replica, n_lv, x, mask, mask_mode, G, Gp,
+                                            leaf_gsrc, stats, phi_off, den_off, tot_off, d);
     } else {
         const int idx = blk - n_leaf_blocks;
         mixing_stats_body<1024>(idx / max_children, idx % max_children, m_rec, m_cptr, m_child, params, stats, A, Off, G,
@@ -481,9 +508,9 @@ __global__ __launch_bounds__(1024) void k_tail_backward(
 
 void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_scope, int n_mix, int max_children,
                           const float* x, const uint8_t* mask, int mask_mode, const float* params, const float* A,
-                          const double* Off, const float* G, float* stats, int64_t phi_off, int64_t den_off,
-                          int64_t tot_off, int64_t n_stats, float* part, size_t part_floats, const Dims& d,
-                          hipStream_t s) {
+                          const double* Off, const float* G, const float* Gp, bool direct, float* stats,
+                          int64_t phi_off, int64_t den_off, int64_t tot_off, int64_t n_stats, float* part,
+                          size_t part_floats, const Dims& d, hipStream_t s) {
     const int total = n_lv * d.C * d.K;
     const bool categorical = d.family == EINET_LEAF_CATEGORICAL;
     if (categorical)     // indicator statistics: a histogram kernel of its own (at most 256 x 64 floats of LDS)
@@ -545,21 +572,30 @@ void launch_tail_backward(const DevTables& t, int n_lv, int n_leaves, int max_sc
         int dev = 0;
         (void)hipGetDevice(&dev);
         std::call_once(attr_set[dev % EINET_MAX_DEVICES], [&] {
-            allow_dynamic_lds(&k_tail_backward<0, 1>, 64 * 1024);
-            allow_dynamic_lds(&k_tail_backward<0, 4>, 128 * 1024);
+            allow_dynamic_lds(&k_tail_backward<0, 1, false>, 64 * 1024);
+            allow_dynamic_lds(&k_tail_backward<0, 4, false>, 128 * 1024);
+            allow_dynamic_lds(&k_tail_backward<0, 1, true>, 64 * 1024);
+            allow_dynamic_lds(&k_tail_backward<0, 4, true>, 128 * 1024);
         });
     }
-#define EINET_LAUNCH(N, P)                                                                                           \
-    hipLaunchKernelGGL((k_tail_backward<N, P>), dim3(blocks), dim3(1024), lds, s, n_leaf_blocks,                      \
+#define EINET_LAUNCH_D(N, P, DIR)                                                                                    \
+    hipLaunchKernelGGL((k_tail_backward<N, P, DIR>), dim3(blocks), dim3(1024), lds, s, n_leaf_blocks,                 \
                        max_children > 0 ? max_children : 1, t.lv_leaf, t.lv_var, t.leaf_node, t.leaf_replica, n_lv, x, \
-                       mask, mask_mode, G, stats, phi_off, den_off, tot_off, t.mix_rec, t.mix_cptr, t.mix_child,      \
-                       params, A, Off, t.leaf_sptr, t.leaf_var, chunks_per_leaf, part, n_leaf_stats, groups, d)
-    if (sums) EINET_LAUNCH(TAIL_SUMS, 1);
+                       mask, mask_mode, G, Gp, t.leaf_gsrc, stats, phi_off, den_off, tot_off, t.mix_rec, t.mix_cptr,  \
+                       t.mix_child, params, A, Off, t.leaf_sptr, t.leaf_var, chunks_per_leaf, part, n_leaf_stats,     \
+                       groups, d)
+#define EINET_LAUNCH(N, P)                       \
+    do {                                         \
+        if (direct) EINET_LAUNCH_D(N, P, true);  \
+        else EINET_LAUNCH_D(N, P, false);        \
+    } while (0)
+    if (sums) EINET_LAUNCH_D(TAIL_SUMS, 1, false);
     else if (nch == 0 && ppt == 4) EINET_LAUNCH(0, 4);
     else if (nch == 0) EINET_LAUNCH(0, 1);
     else if (nch == 4) EINET_LAUNCH(4, 1);
     else EINET_LAUNCH(1, 1);
 #undef EINET_LAUNCH
+#undef EINET_LAUNCH_D
 }
 
 }  // namespace einet_impl

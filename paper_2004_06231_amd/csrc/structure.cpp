@@ -401,6 +401,18 @@ bool compile_plan(const RegionGraph& g, int K, int C, int family, int leaf_param
         if (!all)
             for (int e = p.ein_layer_ptr[l]; e < p.ein_layer_ptr[l + 1]; ++e) p.ein_gsrc[e] = 0;
     }
+    // the same for the leaves (element-wise statistics kernels only: no categorical leaves, scopes below the 512
+    // pairs from which the matrix-pipe kernel may be chosen)
+    p.leaf_gsrc.assign(p.leaf_node.size(), 0);
+    p.leaves_direct = family != EINET_LEAF_CATEGORICAL && p.max_leaf_scope * C < 512 && !p.leaf_node.empty();
+    for (size_t i = 0; i < p.leaf_node.size() && p.leaves_direct; ++i) {
+        const int s = p.leaf_node[i];
+        if (runs[s].size() == 1 && runs[s][0].second <= GSRC_MAX_BLOCKS)
+            p.leaf_gsrc[i] = (runs[s][0].first << 3) | runs[s][0].second;
+        else
+            p.leaves_direct = false;
+    }
+    if (!p.leaves_direct) p.leaf_gsrc.assign(p.leaf_node.size(), 0);
     p.rb_layer_ptr.push_back(0);
     p.rb_pptr.push_back(0);
     auto push_region = [&](int s) {

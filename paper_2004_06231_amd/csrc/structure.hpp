@@ -52,6 +52,8 @@ struct Plan {
     std::vector<uint8_t> ein_layer_full;            // [num_layers]: every item of the layer has K output entries
     std::vector<uint8_t> ein_layer_direct;          // [num_layers]: the layer's top-down kernel reads its regions'
                                                     // posteriors from the parents' blocks (ein_gsrc), G is not assembled
+    bool leaves_direct = false;                     // the leaf statistics read the leaves' posteriors from the
+                                                    // parents' blocks (leaf_gsrc); G of the leaves is not assembled
     std::vector<int32_t> mix_layer_ptr;             // [num_layers+1]
     std::vector<int32_t> rb_layer_ptr;              // [num_layers+2]
     std::vector<int32_t> sr_layer_ptr;              // [num_layers+1]: sampling items (sum regions) per layer, bottom-up

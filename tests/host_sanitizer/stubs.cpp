@@ -37,8 +37,8 @@ void launch_region_assemble(const DevTables&, int, int, bool, float*, const floa
 void launch_einsum_backward(const DevTables&, int, int, bool, bool, const float*, float*, const float*, const double*,
                             const float*, const float*, float*, float*, PartialSumList*, bool, const Dims&, hipStream_t) {}
 void launch_tail_backward(const DevTables&, int, int, int, int, int, const float*, const uint8_t*, int, const float*,
-                          const float*, const double*, const float*, float*, int64_t, int64_t, int64_t, int64_t, float*,
-                          size_t, const Dims&, hipStream_t) {}
+                          const float*, const double*, const float*, const float*, bool, float*, int64_t, int64_t, int64_t,
+                          int64_t, float*, size_t, const Dims&, hipStream_t) {}
 void launch_em_update(const DevTables&, int, int, bool, float*, float*, float*, int64_t, int64_t, int64_t, float, float,
                       float, float, const Dims&, hipStream_t) {}
 void launch_fill(float*, float, int64_t, hipStream_t) {}
