@@ -1,7 +1,9 @@
 """GPU parity of the einsum kernels with specialised waves over every K they are instantiated for (multiples of 8:
 bottom-up to 48, top-down to 40; K = 48 takes the new kernel one way and the 16x16x4 kernel the other), with batches
 that span several chunks of 128 samples and a ragged last one, with statistics added to (two E-steps in a row),
-overwritten (E-step after an M-step) and mixing weights in play (regions with several partitions)."""
+overwritten (E-step after an M-step) and mixing weights in play (regions with several partitions); and of the
+top-down kernels that add up the posterior blocks of a region's only parent themselves (random binary trees), with
+the number of posterior-assembly launches each case should still need."""
 import numpy as np
 import pytest
 import torch
@@ -135,4 +137,59 @@ def test_root_of_the_circuit(spec, K, C, family, B):
     assert_logp_close(m.logp(dev(x), dev(mask)), oracle.logp(x, mask))
     nb = max(1, B // 2)
     assert_logp_close(m.logp(dev(x[:nb])), ref_logp[:nb])
+    m.close()
+
+
+TREES = [
+    # spec, K, C, family, B, mask kind, posterior-assembly launches expected per E-step.  In a random binary tree every
+    # region has one partition and one parent partition: the 16x16x4 top-down kernel and the element-wise leaf statistics
+    # take the posterior from the parent's blocks, and nothing is assembled by a launch of its own.
+    (dict(kind="rat", D=40, depth=3, R=3), 10, 1, BERNOULLI, 100, None, 0),        # K not a multiple of 4, three blocks
+    (dict(kind="rat", D=40, depth=3, R=3), 7, 2, GAUSSIAN, 130, "per_sample", 0),  # two chunks of the batch, masks
+    (dict(kind="rat", D=64, depth=4, R=2), 20, 1, GAUSSIAN, 96, "shared", 0),      # 16-byte loads, up to five blocks
+    (dict(kind="rat", D=300, depth=2, R=8), 12, 1, GAUSSIAN, 70, None, 0),         # leaves of 75 variables: cell form
+    (dict(kind="rat", D=12, depth=1, R=3), 5, 1, BERNOULLI, 33, None, 0),          # leaves right under the root
+    (dict(kind="rat", D=40, depth=3, R=3), 28, 1, BERNOULLI, 64, None, 3),         # seven blocks per right child: assembled
+    (dict(kind="rat", D=40, depth=3, R=3), 16, 1, BERNOULLI, 64, None, 2),         # kernel with specialised waves: inner layers assembled
+    (dict(kind="rat", D=40, depth=3, R=3), 6, 1, 3, 50, None, 1),                  # categorical leaves read the assembled posterior
+]
+
+
+@pytest.mark.parametrize("spec,K,C,family,B,mask_kind,assemblies", TREES)
+def test_trees_take_posteriors_from_the_parents_blocks(spec, K, C, family, B, mask_kind, assemblies):
+    print("tree case", spec, K, C, family, B, mask_kind, flush=True)
+    seed = 5100 + K + B
+    leaf_param = 4 if family == 3 else 0
+    oracle, flat, rng = make_oracle(spec, K, C, family, seed, leaf_range=(0.1, 0.9), leaf_param=leaf_param)
+    D = oracle.g.num_vars
+    data = (dict(kind="bernoulli_iid", p=0.4) if family == BERNOULLI else
+            dict(kind="categorical_mixture", components=3, values=4) if family == 3 else dict(kind="gaussian_mixture", components=3, std=0.3))
+    x = workloads.draw_data(rng, data, B, D, C)
+    mask = workloads.draw_mask(rng, None if mask_kind is None else dict(kind=mask_kind, observed_fraction=0.7), B, D)
+    m = gpu_model(spec, K, C, family, B, seed, flat, leaf_param=leaf_param)
+    ref_stats, ref_logp = oracle.em_accumulate(x, mask)
+    ref_flat = oracle.stats_to_flat(ref_stats)
+    lp = torch.empty(B, device="cuda")
+    m.em_accumulate(dev(x), dev(mask), lp)          # (the first E-step also writes the root's ones)
+    assert_logp_close(lp, ref_logp)
+    assert_stats_close(m.stats, ref_flat, oracle.layout, m.n_params)
+    m.profile_enable(True)
+    m.em_accumulate(dev(x), dev(mask), lp)          # adds to the statistics
+    torch.cuda.synchronize()
+    prof = m.profile_read()
+    m.profile_enable(False)
+    assert_stats_close(m.stats, 2.0 * ref_flat, oracle.layout, m.n_params)
+    assert prof.get("region_backward", (0.0, 0))[1] == assemblies, prof
+    # a smaller batch on the same handle, statistics overwritten after an M-step
+    kw = dict(step=0.5, min_var=1e-4, max_var=2.0, w_floor=1e-9) if family == GAUSSIAN else dict(step=0.5, w_floor=1e-9)
+    m.em_update(**kw)
+    oracle.em_update(oracle.stats_from_flat(2.0 * ref_flat), **kw)
+    m.set_params(oracle.get_flat_params())
+    nb = max(1, B // 3)
+    m.em_reset()
+    mask3 = mask if mask is None or mask.ndim == 1 else mask[:nb]
+    m.em_accumulate(dev(x[:nb]), dev(mask3), lp[:nb])
+    ref3, ref_logp3 = oracle.em_accumulate(x[:nb], mask3)
+    assert_logp_close(lp[:nb], ref_logp3)
+    assert_stats_close(m.stats, oracle.stats_to_flat(ref3), oracle.layout, m.n_params)
     m.close()
