@@ -27,6 +27,9 @@ CASES = [
     # few items and many chunks: the chunks of an item side by side, statistics blocks summed by a second launch
     (dict(kind="rat", D=16, depth=2, R=2), 16, 1, BERNOULLI, 1100),        # nine shares of one chunk each
     (dict(kind="pd", H=6, W=6, deltas=[2]), 24, 1, GAUSSIAN, 520),         # three shares of two, two and one chunk
+    # twelve strips: ten layers of 11 to 36 items below the root that all split their nine chunks, more than the eight whose sums the
+    # launch at the end of the pass takes; the two bottom layers walk their chunks in turn
+    (dict(kind="pd", H=2, W=24, deltas=[2], axes=2), 8, 1, BERNOULLI, 1100),
 ]
 
 
